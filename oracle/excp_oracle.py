@@ -1,0 +1,420 @@
+"""Plain CPU oracle of the ExCP per-tensor compress / reconstruct step.
+
+TEST INFRASTRUCTURE ONLY -- never on the product path, shares no code with the
+HIP library, and is deliberately slow and literal so that every line can be
+checked against the paper by eye.
+
+Naming.  The paper's symbols for the two Adam moments are swapped relative to
+standard Adam (Sec. 3: the "first-order and second-order moments v_t, m_t").
+Here, as in the C ABI, ``m`` is the FIRST moment (signed EMA of the gradient)
+and ``v`` is the SECOND moment (EMA of the squared gradient, non-negative):
+
+    paper m_t (under the square root of Eq. "r_w")  ->  v  here
+    paper v_t (the indicator of Eq. "r_o")          ->  m  here
+
+All "fp32" arithmetic below is IEEE-754 binary32, round-to-nearest-even, one
+rounding per operation (numpy float32 scalars/arrays), denormals preserved.
+
+Pins.  Every function below is pinned by tests that do not re-use its own
+formula: full-sort / counting invariants for the median, rational arithmetic
+for the mean, element-by-element pure-Python brute force for the masks,
+exhaustive nearest-centre search and a monotone objective for Lloyd, textbook
+Lloyd-Max levels, uniform-data fixed points, byte-level hand-built blobs and
+the size identities of the paper's result tables.  The paper does not specify
+k-means initialisation, iteration count, tie handling or empty-cluster
+handling (Sec. 3.3 says only "K-means algorithm"): the choices made in
+``kmeans_init`` / ``lloyd`` are this build's reading, so the *values* of the
+codebooks are "parity unpinned" by the paper itself; they are pinned only by
+the mathematical properties listed above.
+"""
+from __future__ import annotations
+
+import math
+import struct
+from dataclasses import dataclass, field
+
+import numpy as np
+
+__all__ = [
+    "MAGIC", "VERSION", "HEADER_BYTES",
+    "residual", "lower_median_abs", "exact_mean_abs", "weight_mask",
+    "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
+    "pack_bitmap", "pack_codes", "unpack_bitmap", "unpack_codes",
+    "blob_size", "build_blob", "parse_blob", "compress_step",
+    "decompress_step", "CompressResult", "BlobError", "NonFiniteError",
+]
+
+MAGIC = 0x50435845          # bytes "EXCP" read as a little-endian u32
+VERSION = 1
+HEADER_BYTES = 80
+
+f32 = np.float32
+
+
+class BlobError(ValueError):
+    """The byte string is not a well-formed compressed tensor."""
+
+
+class NonFiniteError(ValueError):
+    """An input array holds NaN or Inf."""
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1, Eq. "ckpt_res"; Alg. 1 step 1
+# --------------------------------------------------------------------------
+def residual(W_prev: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """d = W_t - W_hat_{t-1}, one fp32 subtraction per element."""
+    return (W.astype(f32, copy=False) - W_prev.astype(f32, copy=False)).astype(f32)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2, Eq. "r_w": median(W), read as the median of |residual| of this
+# tensor; an even-length tensor takes the LOWER middle element so that the
+# result is one exact order statistic.
+# --------------------------------------------------------------------------
+def lower_median_abs(d: np.ndarray) -> np.float32:
+    a = np.sort(np.abs(d.astype(f32, copy=False)), kind="stable")
+    return f32(a[(a.size - 1) // 2])
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2, Eq. "r_o": mean(v_t), read as mean(|first moment|) over all n
+# elements.  The sum is the exact real-number sum, rounded once to fp64, so
+# the value does not depend on the order of summation.
+# --------------------------------------------------------------------------
+def exact_mean_abs(m: np.ndarray) -> tuple[float, np.float32]:
+    a = np.abs(m.astype(f32, copy=False)).astype(np.float64)   # exact widening
+    S = math.fsum(a.tolist())               # correctly rounded exact sum
+    mean64 = S / float(a.size)
+    return S, f32(mean64)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2, Eq. "r_w": r_w(i) = alpha / sqrt(second moment_i) * median ;
+# M_w(i) = [ |d_i| > r_w(i) ]  ("prune the residual ... by magnitude").
+# Evaluation order fixed as (alpha*med) / sqrt(v_i), three fp32 roundings.
+# v_i == 0 -> r = +inf -> pruned.  v_i < 0 -> sqrt = NaN -> comparison false.
+# --------------------------------------------------------------------------
+def weight_mask(d: np.ndarray, v: np.ndarray, alpha, med) -> tuple[np.ndarray, np.float32]:
+    t_w = f32(f32(alpha) * f32(med))
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore", under="ignore"):
+        root = np.sqrt(v.astype(f32, copy=False)).astype(f32)
+        r = (t_w / root).astype(f32)
+        Mw = np.abs(d.astype(f32, copy=False)) > r
+    return Mw, t_w
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.2, Eq. "r_o": r_o = beta * mean ; M_o(i) = [ |m_i| > r_o and M_w(i) ].
+# --------------------------------------------------------------------------
+def momentum_mask(m: np.ndarray, Mw: np.ndarray, beta, mean32) -> tuple[np.ndarray, np.float32]:
+    r_o = f32(f32(beta) * f32(mean32))
+    Mo = Mw & (np.abs(m.astype(f32, copy=False)) > r_o)
+    return Mo, r_o
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.3: k-means of the surviving values into 2^n - 1 centres.
+# Initialisation (paper silent): the K order statistics at ranks
+# ((2k+1) * len(x)) // (2K), k = 0..K-1 -- deterministic, sorted, no RNG.
+# --------------------------------------------------------------------------
+def kmeans_init(x: np.ndarray, K: int) -> np.ndarray:
+    n = int(x.size)
+    if n == 0:
+        return np.zeros(K, dtype=f32)
+    xs = np.sort(x.astype(f32, copy=False), kind="stable")
+    idx = [((2 * k + 1) * n) // (2 * K) for k in range(K)]
+    return xs[idx].astype(f32)
+
+
+def nearest_centre(x: np.ndarray, C: np.ndarray, chunk: int = 1 << 18) -> np.ndarray:
+    """a[j] = argmin_k (x_j - C_k)^2, all K distances evaluated in fp64
+    (difference rounded once, square rounded once), ties -> smallest k."""
+    C64 = C.astype(np.float64)
+    out = np.empty(x.size, dtype=np.int64)
+    for s in range(0, x.size, chunk):
+        xc = x[s:s + chunk].astype(np.float64)
+        diff = xc[:, None] - C64[None, :]
+        out[s:s + chunk] = np.argmin(diff * diff, axis=1)   # first minimum
+    return out
+
+
+def objective(x: np.ndarray, C: np.ndarray, a: np.ndarray) -> float:
+    """Sum over j of (x_j - C[a_j])^2, each term in fp64, exact summation."""
+    if x.size == 0:
+        return 0.0
+    diff = x.astype(np.float64) - C.astype(np.float64)[a]
+    return math.fsum((diff * diff).tolist())
+
+
+def lloyd(x: np.ndarray, K: int, iters: int, history: list | None = None):
+    """Exactly ``iters`` Lloyd updates from the quantile initialisation.
+
+    update: C_k = fp32( exact sum of the members (rounded once to fp64) / count )
+    for every non-empty cluster; an empty cluster keeps its centre.
+    Returns (C fp32[K], a int64[len(x)]) where a is the assignment to the FINAL
+    centres.  If ``history`` is a list, the objective before each update and
+    after the last one is appended to it.
+    """
+    x = x.astype(f32, copy=False)
+    C = kmeans_init(x, K)
+    if x.size == 0:
+        return C, np.empty(0, dtype=np.int64)
+    x64 = x.astype(np.float64)
+    for _ in range(iters):
+        a = nearest_centre(x, C)
+        if history is not None:
+            history.append(objective(x, C, a))
+        newC = C.copy()
+        order = np.argsort(a, kind="stable")
+        counts = np.bincount(a, minlength=K)
+        pos = 0
+        xsorted = x64[order]
+        for k in range(K):
+            c = int(counts[k])
+            if c:
+                S = math.fsum(xsorted[pos:pos + c].tolist())
+                newC[k] = f32(S / float(c))
+            pos += c
+        C = newC
+    a = nearest_centre(x, C)
+    if history is not None:
+        history.append(objective(x, C, a))
+    return C, a
+
+
+# --------------------------------------------------------------------------
+# Packed representations (Sec. 4.2: "combine two int4 number into one int8").
+# Bit i&63 of word i>>6 holds mask[i]; code j occupies bits
+# [j*nbits, (j+1)*nbits) of the little-endian bit stream (earlier element in
+# the lower bits), stored as little-endian u64 words.
+# --------------------------------------------------------------------------
+def _bits_to_words(bits: np.ndarray) -> np.ndarray:
+    """Little-endian bit stream (bit j of the stream = bits[j]) -> u64 words."""
+    nwords = (bits.size + 63) // 64
+    padded = np.zeros(nwords * 64, dtype=np.uint8)
+    padded[:bits.size] = bits
+    return np.packbits(padded, bitorder="little").view("<u8").astype(np.uint64)
+
+
+def _words_to_bits(words: np.ndarray, nbits_total: int) -> np.ndarray:
+    raw = np.ascontiguousarray(words.astype("<u8")).view(np.uint8)
+    return np.unpackbits(raw, bitorder="little")[:nbits_total]
+
+
+def pack_bitmap(mask: np.ndarray) -> np.ndarray:
+    return _bits_to_words(mask.astype(np.uint8))
+
+
+def unpack_bitmap(words: np.ndarray, n: int) -> np.ndarray:
+    return _words_to_bits(words, n).astype(bool)
+
+
+def pack_codes(codes: np.ndarray, nbits: int) -> np.ndarray:
+    codes = codes.astype(np.int64)
+    assert codes.size == 0 or (codes.min() >= 0 and codes.max() < (1 << nbits))
+    bits = ((codes[:, None] >> np.arange(nbits)[None, :]) & 1).astype(np.uint8)
+    return _bits_to_words(bits.reshape(-1))
+
+
+def unpack_codes(words: np.ndarray, n: int, nbits: int) -> np.ndarray:
+    bits = _words_to_bits(words, n * nbits).reshape(n, nbits).astype(np.int64)
+    return (bits << np.arange(nbits)[None, :]).sum(axis=1)
+
+
+def _pad16(nbytes: int) -> int:
+    return (nbytes + 15) // 16 * 16
+
+
+def blob_size(n: int, n_w: int, n_o: int, nbits: int) -> int:
+    """Closed-form size of one compressed tensor (bytes)."""
+    size = HEADER_BYTES + 3 * 4 * (1 << nbits)
+    size += _pad16(8 * ((n + 63) // 64))
+    size += _pad16(8 * ((n_w + 63) // 64))
+    size += _pad16(8 * ((n_w * nbits + 63) // 64))
+    size += 2 * _pad16(8 * ((n_o * nbits + 63) // 64))
+    return size
+
+
+def _section(words: np.ndarray) -> bytes:
+    raw = words.astype("<u8").tobytes()
+    return raw + b"\0" * (_pad16(len(raw)) - len(raw))
+
+
+def build_blob(*, n, nbits, flags, iters, alpha, beta, med, mean32, t_w, r_o,
+               Cw, Cm, Cv, Mw, Mo_over_survivors, codes_w, codes_m, codes_v) -> bytes:
+    n_w = int(Mw.sum())
+    n_o = int(Mo_over_survivors.sum())
+    total = blob_size(n, n_w, n_o, nbits)
+    head = struct.pack("<IIIIQQQffffffQII",
+                       MAGIC, VERSION, nbits, flags, n, n_w, n_o,
+                       float(f32(alpha)), float(f32(beta)), float(med), float(mean32),
+                       float(t_w), float(r_o), total, iters, 0)
+    assert len(head) == HEADER_BYTES
+    parts = [head]
+    for C in (Cw, Cm, Cv):
+        book = np.concatenate([np.zeros(1, dtype=f32), C.astype(f32)])
+        parts.append(book.astype("<f4").tobytes())
+    parts.append(_section(pack_bitmap(Mw)))
+    parts.append(_section(pack_bitmap(Mo_over_survivors)))
+    parts.append(_section(pack_codes(codes_w, nbits)))
+    parts.append(_section(pack_codes(codes_m, nbits)))
+    parts.append(_section(pack_codes(codes_v, nbits)))
+    blob = b"".join(parts)
+    assert len(blob) == total
+    return blob
+
+
+def parse_blob(blob: bytes, n_expected: int | None = None) -> dict:
+    if len(blob) < HEADER_BYTES:
+        raise BlobError("shorter than a header")
+    (magic, version, nbits, flags, n, n_w, n_o, alpha, beta, med, mean32, t_w, r_o,
+     total, iters, reserved) = struct.unpack("<IIIIQQQffffffQII", blob[:HEADER_BYTES])
+    if magic != MAGIC:
+        raise BlobError("bad magic")
+    if version != VERSION:
+        raise BlobError("bad version")
+    if not 2 <= nbits <= 8:
+        raise BlobError("nbits out of range")
+    if n_expected is not None and n != n_expected:
+        raise BlobError("element count mismatch")
+    if not (n_o <= n_w <= n):
+        raise BlobError("inconsistent counts")
+    if total != blob_size(n, n_w, n_o, nbits) or len(blob) < total:
+        raise BlobError("inconsistent size")
+    E = 1 << nbits
+    off = HEADER_BYTES
+    books = []
+    for _ in range(3):
+        books.append(np.frombuffer(blob, dtype="<f4", count=E, offset=off).astype(f32))
+        off += 4 * E
+
+    def take(nwords):
+        nonlocal off
+        arr = np.frombuffer(blob, dtype="<u8", count=nwords, offset=off).astype(np.uint64)
+        off += _pad16(8 * nwords)
+        return arr
+
+    bw = take((n + 63) // 64)
+    bo = take((n_w + 63) // 64)
+    cw = take((n_w * nbits + 63) // 64)
+    cm = take((n_o * nbits + 63) // 64)
+    cv = take((n_o * nbits + 63) // 64)
+    return dict(nbits=nbits, flags=flags, n=n, n_w=n_w, n_o=n_o, alpha=f32(alpha),
+                beta=f32(beta), median=f32(med), mean_abs_m=f32(mean32), t_w=f32(t_w),
+                r_o=f32(r_o), blob_bytes=total, iters=iters,
+                book_w=books[0], book_m=books[1], book_v=books[2],
+                bitmap_w=bw, bitmap_o=bo, codes_w=cw, codes_m=cm, codes_v=cv)
+
+
+@dataclass
+class CompressResult:
+    blob: bytes
+    W_recon: np.ndarray
+    m_recon: np.ndarray
+    v_recon: np.ndarray
+    n: int
+    n_w: int
+    n_o: int
+    median: np.float32
+    abs_sum_m: float
+    mean_abs_m: np.float32
+    t_w: np.float32
+    r_o: np.float32
+    Mw: np.ndarray
+    Mo: np.ndarray
+    C: dict = field(default_factory=dict)        # stream -> fp32[K] centres
+    assign: dict = field(default_factory=dict)   # stream -> int64 assignment (0-based)
+    obj: dict = field(default_factory=dict)      # stream -> final objective
+    x: dict = field(default_factory=dict)        # stream -> surviving values
+
+    @property
+    def ratio(self) -> float:
+        return 12.0 * self.n / len(self.blob)
+
+
+# --------------------------------------------------------------------------
+# Alg. 1 (without the final general-purpose archive stage) for one tensor.
+# --------------------------------------------------------------------------
+def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
+                  flags=0) -> CompressResult:
+    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
+    W = np.ascontiguousarray(W, dtype=f32).ravel()
+    m = np.ascontiguousarray(m, dtype=f32).ravel()
+    v = np.ascontiguousarray(v, dtype=f32).ravel()
+    n = W.size
+    assert W_prev.size == n and m.size == n and v.size == n
+    assert 2 <= nbits <= 8 and iters >= 0 and flags == 0
+    for arr in (W_prev, W, m, v):
+        if not np.all(np.isfinite(arr)):
+            raise NonFiniteError("NaN or Inf in an input")
+    K = (1 << nbits) - 1
+
+    if n == 0:
+        z = np.zeros(0, dtype=f32)
+        zb = np.zeros(0, dtype=bool)
+        zc = np.zeros(0, dtype=np.int64)
+        C0 = np.zeros(K, dtype=f32)
+        blob = build_blob(n=0, nbits=nbits, flags=flags, iters=iters, alpha=alpha, beta=beta,
+                          med=f32(0), mean32=f32(0), t_w=f32(0), r_o=f32(0),
+                          Cw=C0, Cm=C0, Cv=C0, Mw=zb, Mo_over_survivors=zb,
+                          codes_w=zc, codes_m=zc, codes_v=zc)
+        return CompressResult(blob, z, z, z, 0, 0, 0, f32(0), 0.0, f32(0), f32(0), f32(0),
+                              zb, zb, dict(w=C0, m=C0, v=C0), dict(w=zc, m=zc, v=zc),
+                              dict(w=0.0, m=0.0, v=0.0), dict(w=z, m=z, v=z))
+
+    with np.errstate(over="ignore"):
+        d = residual(W_prev, W)                               # Alg. 1 step 1
+    if not np.all(np.isfinite(d)):
+        raise NonFiniteError("the residual overflows fp32")
+    med = lower_median_abs(d)                                 # Eq. r_w
+    S, mean32 = exact_mean_abs(m)                             # Eq. r_o
+    Mw, t_w = weight_mask(d, v, alpha, med)                   # Eq. r_w
+    Mo, r_o = momentum_mask(m, Mw, beta, mean32)              # Eq. r_o
+    xw, xm, xv = d[Mw], m[Mo], v[Mo]                          # survivors, index order
+
+    C, A, O = {}, {}, {}
+    for name, x in (("w", xw), ("m", xm), ("v", xv)):         # Alg. 1 steps 3-4
+        C[name], A[name] = lloyd(x, K, iters)
+        O[name] = objective(x, C[name], A[name])
+
+    blob = build_blob(n=n, nbits=nbits, flags=flags, iters=iters, alpha=alpha, beta=beta,
+                      med=med, mean32=mean32, t_w=t_w, r_o=r_o,
+                      Cw=C["w"], Cm=C["m"], Cv=C["v"], Mw=Mw, Mo_over_survivors=Mo[Mw],
+                      codes_w=A["w"] + 1, codes_m=A["m"] + 1, codes_v=A["v"] + 1)
+
+    # Alg. 2 applied to what was just stored (the copy kept for the next step).
+    W_rec = W_prev.copy()
+    W_rec[Mw] = (W_prev[Mw] + C["w"][A["w"]]).astype(f32)
+    m_rec = np.zeros(n, dtype=f32)
+    v_rec = np.zeros(n, dtype=f32)
+    m_rec[Mo] = C["m"][A["m"]]
+    v_rec[Mo] = C["v"][A["v"]]
+    return CompressResult(blob, W_rec, m_rec, v_rec, n, int(Mw.sum()), int(Mo.sum()),
+                          med, S, mean32, t_w, r_o, Mw, Mo, C, A, O,
+                          dict(w=xw, m=xm, v=xv))
+
+
+# --------------------------------------------------------------------------
+# Alg. 2 for one tensor, from the stored bytes alone.
+# --------------------------------------------------------------------------
+def decompress_step(W_prev, blob: bytes):
+    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
+    p = parse_blob(blob, n_expected=W_prev.size)
+    n, n_w, n_o, nbits = p["n"], p["n_w"], p["n_o"], p["nbits"]
+    Mw = unpack_bitmap(p["bitmap_w"], n)
+    Mo_s = unpack_bitmap(p["bitmap_o"], n_w)
+    if int(Mw.sum()) != n_w or int(Mo_s.sum()) != n_o:
+        raise BlobError("bitmap population does not match the header")
+    cw = unpack_codes(p["codes_w"], n_w, nbits)
+    cm = unpack_codes(p["codes_m"], n_o, nbits)
+    cv = unpack_codes(p["codes_v"], n_o, nbits)
+    W_rec = W_prev.copy()
+    idx_w = np.flatnonzero(Mw)
+    W_rec[idx_w] = (W_prev[idx_w] + p["book_w"][cw]).astype(f32)   # Alg. 2 steps 2 and 4
+    idx_o = idx_w[Mo_s]
+    m_rec = np.zeros(n, dtype=f32)
+    v_rec = np.zeros(n, dtype=f32)
+    m_rec[idx_o] = p["book_m"][cm]                                  # Alg. 2 step 3
+    v_rec[idx_o] = p["book_v"][cv]
+    return W_rec, m_rec, v_rec
