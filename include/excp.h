@@ -1,0 +1,175 @@
+/*
+ * excp.h -- C ABI of the MI355X (gfx950) ExCP checkpoint-compression hot path.
+ *
+ * What is computed (per flat fp32 tensor; "ExCP", arxiv 2406.11257):
+ *   compress   = Alg. 1 without its last, general-purpose archive step:
+ *                residual against the previous *reconstructed* weights
+ *                (Sec. 3.1, Eq. "ckpt_res"), joint weight / momentum pruning
+ *                (Sec. 3.2, Eq. "r_w" and Eq. "r_o"), k-means codebook
+ *                quantisation of the survivors to 2^nbits - 1 centres with code
+ *                0 kept for "pruned" (Sec. 3.3, Sec. 4.2), bit packing
+ *                (Sec. 4.2) -- plus the reconstructed weights that Sec. 3.4
+ *                says are kept for the next step.
+ *   decompress = Alg. 2: codebook look-up and add to the previous weights.
+ *
+ * Naming.  The paper swaps the usual Adam symbols.  Here `m` is the FIRST
+ * moment (signed), `v` the SECOND moment (non-negative, under the square root
+ * of Eq. "r_w").
+ *
+ * Exact definition (all fp32 operations are IEEE binary32, round to nearest
+ * even, one rounding each, no fused multiply-add, denormals kept):
+ *   d_i    = W_t[i] - W_prev_recon[i]
+ *   med    = the ((n-1)/2)-th smallest of |d_i|  (0-based; lower median)
+ *   t_w    = alpha * med ;  r_i = t_w / sqrt(v_i) ;  M_w(i) = |d_i| > r_i
+ *   mean   = fp32( fp64(exact sum of |m_i|) / n ) ; r_o = beta * mean
+ *   M_o(i) = M_w(i) and |m_i| > r_o
+ *   streams: d at M_w (n_w values), m and v at M_o (n_o values each), in
+ *   index order; each stream is clustered on its own: K = 2^nbits - 1 centres
+ *   start at the order statistics of rank ((2k+1) len)/(2K), then exactly
+ *   `lloyd_iters` updates (nearest centre by squared fp64 distance, ties to the
+ *   lower index; centre = fp32(fp64 sum / count); empty clusters keep their
+ *   centre); code = 1 + index of the nearest final centre.
+ *   reconstruct: W_hat[i] = W_prev_recon[i] + C_w[code] at M_w, else
+ *   W_prev_recon[i]; m_hat, v_hat = C[code] at M_o, else +0.
+ *
+ * Compressed tensor ("blob"), little endian, every section padded to 16 B:
+ *   header (80 B): u32 magic "EXCP", u32 version=1, u32 nbits, u32 flags,
+ *                  u64 n, u64 n_w, u64 n_o, f32 alpha, beta, med, mean, t_w,
+ *                  r_o, u64 blob_bytes, u32 lloyd_iters, u32 0
+ *   3 codebooks  : 2^nbits fp32 each (weights, m, v); entry 0 = +0.0
+ *   bitmap_w     : ceil(n/64)   u64, bit (i & 63) of word (i >> 6) = M_w(i)
+ *   bitmap_o     : ceil(n_w/64) u64 over the M_w survivors in index order
+ *   codes_w/m/v  : nbits-wide codes, element j in bits [j*nbits, (j+1)*nbits)
+ *                  of a little-endian bit stream stored as u64 words
+ *
+ * Memory and ownership.  Every tensor pointer below is DEVICE memory on the
+ * context's GPU (4-byte aligned is enough); blobs are DEVICE memory, 16-byte
+ * aligned.  The caller owns all of them and the HIP stream.  The context owns
+ * only its workspace, allocated in excp_create; no entry point allocates
+ * afterwards.  stats / blob_bytes outputs are HOST memory.
+ *
+ * Execution.  Work is enqueued on the context's stream.  excp_compress_tensors
+ * and excp_decompress_tensors return after enqueueing; excp_collect waits for
+ * the stream and reports per-tensor results and data-dependent errors.  The
+ * single-tensor calls wait themselves.  A context is not thread-safe, and a
+ * new batch may be submitted only after the previous one was collected.
+ *
+ * Errors.  0 on success, a negative EXCP_E_* otherwise; nothing throws.
+ * Argument errors are returned at once and enqueue nothing.  Data-dependent
+ * errors (non-finite input, blob capacity, damaged blob) are returned by
+ * excp_collect; the outputs of a failed tensor are unspecified but no memory
+ * outside the caller's buffers is touched.
+ */
+#ifndef EXCP_H
+#define EXCP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EXCP_OK            0
+#define EXCP_E_ARG        -1   /* null pointer, nbits outside [2,8], negative / non-finite alpha or beta,
+                                  lloyd_iters < 0, unknown flags, tensor larger than the context allows */
+#define EXCP_E_CAP        -2   /* blob_cap smaller than the compressed tensor */
+#define EXCP_E_NONFINITE  -3   /* NaN or Inf in an input, or the residual overflows fp32 */
+#define EXCP_E_BLOB       -4   /* decompress: bad magic / version / sizes / bitmap population */
+#define EXCP_E_HIP        -5   /* a HIP call failed, or the device could not be used */
+#define EXCP_E_STATE      -6   /* call order violated (batch pending / nothing to collect) */
+#define EXCP_E_INTERNAL   -7   /* a device-side wait gave up (should not happen) */
+
+#define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
+
+typedef struct excp_ctx excp_ctx;
+
+/* One tensor of a compress batch (Alg. 1 inputs). */
+typedef struct {
+    const float *W_prev_recon;   /* device, n: reconstructed weights of the previous checkpoint */
+    const float *W_t;            /* device, n: current weights                                    */
+    const float *m_t;            /* device, n: Adam first moment                                  */
+    const float *v_t;            /* device, n: Adam second moment                                 */
+    uint64_t     n;              /* elements; 0 is allowed (header-only blob)                     */
+    void        *blob;           /* device, 16-B aligned: receives the compressed tensor          */
+    uint64_t     blob_cap;       /* bytes available at blob (excp_blob_bound never fails)         */
+    float       *W_recon_out;    /* device, n, nullable: reconstructed weights of THIS checkpoint;
+                                    may be the same pointer as W_prev_recon (in-place update)      */
+} excp_tensor;
+
+/* One tensor of a decompress batch (Alg. 2 inputs). */
+typedef struct {
+    const float *W_prev_recon;   /* device, n */
+    const void  *blob;           /* device, 16-B aligned */
+    uint64_t     blob_bytes;     /* bytes readable at blob */
+    uint64_t     n;              /* must equal the n stored in the blob */
+    float       *W_recon_out;    /* device, n, nullable; may equal W_prev_recon */
+    float       *m_out;          /* device, n, nullable */
+    float       *v_out;          /* device, n, nullable */
+} excp_blob;
+
+/* Per-tensor results (host). */
+typedef struct {
+    uint64_t n, n_w, n_o;        /* elements, kept residuals, kept moment pairs        */
+    uint64_t blob_bytes;         /* size of the compressed tensor                      */
+    uint64_t nonfinite;          /* count of non-finite inputs seen                    */
+    double   abs_sum_m;          /* exact sum of |m|, rounded once to fp64            */
+    double   obj_w, obj_m, obj_v;/* final k-means objective of each stream            */
+    float    median_abs_dw;      /* med                                                */
+    float    mean_abs_m;         /* mean                                               */
+    float    t_w, r_o;           /* alpha*med, beta*mean                               */
+    int32_t  status;             /* EXCP_OK or the EXCP_E_* of this tensor             */
+    int32_t  reserved;
+} excp_stats;
+
+/* Create a context on `hip_device`, working on `hip_stream` (a hipStream_t, borrowed; NULL = the
+ * default stream).  `max_tensor_elems` bounds one tensor (<= EXCP_MAX_TENSOR_ELEMS);
+ * `max_group_elems` (>= max_tensor_elems) is how many elements are processed together: the
+ * workspace is about 12.3 bytes per group element, and a larger batch is run as several groups. */
+int excp_create(excp_ctx **out, int hip_device, void *hip_stream,
+                uint64_t max_tensor_elems, uint64_t max_group_elems);
+void excp_destroy(excp_ctx *ctx);
+
+/* Worst-case compressed size of an n-element tensor (every element kept). */
+uint64_t excp_blob_bound(uint64_t n, int nbits);
+/* Exact compressed size for given counts (the closed form of the layout above). */
+uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits);
+
+/* Alg. 1 (minus the archive step) for `count` tensors; asynchronous.  flags must be 0. */
+int excp_compress_tensors(excp_ctx *ctx, int count, const excp_tensor *tensors,
+                          float alpha, float beta, int nbits, int lloyd_iters, uint32_t flags);
+
+/* Alg. 2 for `count` tensors; asynchronous. */
+int excp_decompress_tensors(excp_ctx *ctx, int count, const excp_blob *blobs);
+
+/* Wait for the pending batch; fill stats[0..count) (nullable); return EXCP_OK or the first
+ * per-tensor error.  After a decompress batch only n, n_w, n_o, blob_bytes and status are set. */
+int excp_collect(excp_ctx *ctx, excp_stats *stats);
+
+/* Single-tensor forms (Alg. 1 / Alg. 2 argument lists); they wait for completion.
+ * blob_bytes and stats are host pointers and may be NULL. */
+int excp_compress_step(excp_ctx *ctx,
+                       const float *W_prev_recon, const float *W_t, const float *m_t, const float *v_t,
+                       uint64_t n, float alpha, float beta, int nbits, int lloyd_iters, uint32_t flags,
+                       void *blob_out, uint64_t blob_cap, uint64_t *blob_bytes,
+                       float *W_recon_out, excp_stats *stats);
+int excp_decompress_step(excp_ctx *ctx, const float *W_prev_recon, const void *blob, uint64_t blob_bytes,
+                         uint64_t n, float *W_recon_out, float *m_out, float *v_out);
+
+/* Per-stage timing.  When enabled, HIP events bracket every kernel stage of the next batches;
+ * after excp_collect, excp_stage_ms returns the summed milliseconds and launches of stage `i`
+ * (0 <= i < excp_stage_count()); excp_stage_name names it. */
+int         excp_set_profiling(excp_ctx *ctx, int enabled);
+int         excp_stage_count(void);
+const char *excp_stage_name(int i);
+int         excp_stage_ms(excp_ctx *ctx, int i, double *ms, int *launches);
+
+/* Bytes of device workspace the context holds. */
+uint64_t excp_workspace_bytes(const excp_ctx *ctx);
+
+const char *excp_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EXCP_H */

@@ -1,0 +1,11 @@
+"""MI355X-native ExCP checkpoint compression: thin Python binding of libexcp.so.
+
+Every step of the method runs in the HIP library; this module only marshals
+arguments (torch tensors -> device pointers) for the C ABI of include/excp.h.
+There is no CPU fallback: loading fails loudly if the library is not built.
+"""
+from .binding import (  # noqa: F401
+    EXCP_OK, EXCP_E_ARG, EXCP_E_CAP, EXCP_E_NONFINITE, EXCP_E_BLOB, EXCP_E_HIP, EXCP_E_STATE,
+    EXCP_E_INTERNAL, ExcpError, ExcpStats, Context, lib, lib_path,
+    excp_blob_bound, excp_blob_size, excp_strerror,
+)

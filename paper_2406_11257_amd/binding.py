@@ -1,0 +1,238 @@
+"""ctypes binding of include/excp.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+EXCP_OK, EXCP_E_ARG, EXCP_E_CAP, EXCP_E_NONFINITE = 0, -1, -2, -3
+EXCP_E_BLOB, EXCP_E_HIP, EXCP_E_STATE, EXCP_E_INTERNAL = -4, -5, -6, -7
+
+
+class ExcpTensor(C.Structure):
+    _fields_ = [("W_prev_recon", C.c_void_p), ("W_t", C.c_void_p), ("m_t", C.c_void_p),
+                ("v_t", C.c_void_p), ("n", C.c_uint64), ("blob", C.c_void_p),
+                ("blob_cap", C.c_uint64), ("W_recon_out", C.c_void_p)]
+
+
+class ExcpBlob(C.Structure):
+    _fields_ = [("W_prev_recon", C.c_void_p), ("blob", C.c_void_p), ("blob_bytes", C.c_uint64),
+                ("n", C.c_uint64), ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p),
+                ("v_out", C.c_void_p)]
+
+
+class ExcpStats(C.Structure):
+    _fields_ = [("n", C.c_uint64), ("n_w", C.c_uint64), ("n_o", C.c_uint64),
+                ("blob_bytes", C.c_uint64), ("nonfinite", C.c_uint64),
+                ("abs_sum_m", C.c_double), ("obj_w", C.c_double), ("obj_m", C.c_double),
+                ("obj_v", C.c_double), ("median_abs_dw", C.c_float), ("mean_abs_m", C.c_float),
+                ("t_w", C.c_float), ("r_o", C.c_float), ("status", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ExcpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {excp_strerror(code)} ({code})")
+
+
+SYMBOLS = {
+    "excp_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_uint64, C.c_uint64]),
+    "excp_destroy": (None, [C.c_void_p]),
+    "excp_blob_bound": (C.c_uint64, [C.c_uint64, C.c_int]),
+    "excp_blob_size": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int]),
+    "excp_compress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpTensor), C.c_float, C.c_float,
+                                        C.c_int, C.c_int, C.c_uint32]),
+    "excp_decompress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpBlob)]),
+    "excp_collect": (C.c_int, [C.c_void_p, C.POINTER(ExcpStats)]),
+    "excp_compress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                     C.c_float, C.c_float, C.c_int, C.c_int, C.c_uint32, C.c_void_p,
+                                     C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p, C.POINTER(ExcpStats)]),
+    "excp_decompress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
+                                       C.c_void_p, C.c_void_p, C.c_void_p]),
+    "excp_set_profiling": (C.c_int, [C.c_void_p, C.c_int]),
+    "excp_stage_count": (C.c_int, []),
+    "excp_stage_name": (C.c_char_p, [C.c_int]),
+    "excp_stage_ms": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
+    "excp_workspace_bytes": (C.c_uint64, [C.c_void_p]),
+    "excp_strerror": (C.c_char_p, [C.c_int]),
+}
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libexcp.so")
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -m paper_2406_11257_amd.build` "
+                              "(or __graft_entry__.build()) first")
+        L = C.CDLL(path)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def excp_strerror(code: int) -> str:
+    return lib().excp_strerror(code).decode()
+
+
+def excp_blob_bound(n: int, nbits: int) -> int:
+    return int(lib().excp_blob_bound(n, nbits))
+
+
+def excp_blob_size(n: int, n_w: int, n_o: int, nbits: int) -> int:
+    return int(lib().excp_blob_size(n, n_w, n_o, nbits))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check_f32(t, name, device):
+    import torch
+    if t.dtype != torch.float32 or not t.is_contiguous() or t.device != device:
+        raise TypeError(f"{name} must be a contiguous float32 tensor on {device}")
+
+
+class Context:
+    """Owns one excp_ctx.  Tensors are torch CUDA tensors; blobs are uint8 CUDA tensors."""
+
+    def __init__(self, max_tensor_elems: int, max_group_elems: int | None = None, device=None, stream=None):
+        import torch
+        self.device = torch.device("cuda", torch.cuda.current_device()) if device is None else torch.device(device)
+        if self.device.index is None:
+            self.device = torch.device("cuda", torch.cuda.current_device())
+        self._stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        handle = C.c_void_p()
+        group = max_tensor_elems if max_group_elems is None else max_group_elems
+        rc = lib().excp_create(C.byref(handle), self.device.index, C.c_void_p(self._stream.cuda_stream),
+                               max_tensor_elems, group)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_create")
+        self._h = handle
+        self._keep = None
+        self._count = 0
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().excp_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @property
+    def workspace_bytes(self) -> int:
+        return int(lib().excp_workspace_bytes(self._h))
+
+    # -- batched -----------------------------------------------------------------
+    def excp_compress_tensors(self, tensors, alpha=5e-5, beta=2.0, nbits=4, lloyd_iters=10, flags=0):
+        """tensors: sequence of (W_prev_recon, W_t, m_t, v_t, blob, W_recon_out-or-None)."""
+        arr = (ExcpTensor * max(len(tensors), 1))()
+        for i, (Wp, W, m, v, blob, Wout) in enumerate(tensors):
+            for t, nm in ((Wp, "W_prev_recon"), (W, "W_t"), (m, "m_t"), (v, "v_t")):
+                _check_f32(t, nm, self.device)
+            n = W.numel()
+            if not (Wp.numel() == n == m.numel() == v.numel()):
+                raise ValueError("tensor lengths differ")
+            if Wout is not None:
+                _check_f32(Wout, "W_recon_out", self.device)
+                if Wout.numel() != n:
+                    raise ValueError("W_recon_out length differs")
+            arr[i] = ExcpTensor(Wp.data_ptr(), W.data_ptr(), m.data_ptr(), v.data_ptr(), n,
+                                blob.data_ptr(), blob.numel() * blob.element_size(),
+                                0 if Wout is None else Wout.data_ptr())
+        rc = lib().excp_compress_tensors(self._h, len(tensors), arr, alpha, beta, nbits, lloyd_iters, flags)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_compress_tensors")
+        self._keep = (tensors, arr)
+        self._count = len(tensors)
+
+    def excp_decompress_tensors(self, blobs):
+        """blobs: sequence of (W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out)."""
+        arr = (ExcpBlob * max(len(blobs), 1))()
+        for i, (Wp, blob, nbytes, n, Wout, mout, vout) in enumerate(blobs):
+            _check_f32(Wp, "W_prev_recon", self.device)
+            for t, nm in ((Wout, "W_recon_out"), (mout, "m_out"), (vout, "v_out")):
+                if t is not None:
+                    _check_f32(t, nm, self.device)
+                    if t.numel() != n:
+                        raise ValueError(nm + " length differs")
+            if Wp.numel() != n:
+                raise ValueError("W_prev_recon length differs")
+            if nbytes > blob.numel() * blob.element_size():
+                raise ValueError("blob_bytes exceeds the blob tensor")
+            arr[i] = ExcpBlob(Wp.data_ptr(), blob.data_ptr(), nbytes, n,
+                              0 if Wout is None else Wout.data_ptr(),
+                              0 if mout is None else mout.data_ptr(),
+                              0 if vout is None else vout.data_ptr())
+        rc = lib().excp_decompress_tensors(self._h, len(blobs), arr)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_decompress_tensors")
+        self._keep = (blobs, arr)
+        self._count = len(blobs)
+
+    def excp_collect(self, check=True):
+        stats = (ExcpStats * max(self._count, 1))()
+        rc = lib().excp_collect(self._h, stats)
+        self._keep = None
+        out = [stats[i] for i in range(self._count)]
+        if check and rc != EXCP_OK:
+            raise ExcpError(rc, "excp_collect")
+        return rc, out
+
+    # -- single tensor -------------------------------------------------------------
+    def excp_compress_step(self, Wp, W, m, v, blob, alpha=5e-5, beta=2.0, nbits=4, lloyd_iters=10,
+                           flags=0, W_recon_out=None, check=True):
+        for t, nm in ((Wp, "W_prev_recon"), (W, "W_t"), (m, "m_t"), (v, "v_t")):
+            _check_f32(t, nm, self.device)
+        n = W.numel()
+        if not (Wp.numel() == n == m.numel() == v.numel()):
+            raise ValueError("tensor lengths differ")
+        if W_recon_out is not None:
+            _check_f32(W_recon_out, "W_recon_out", self.device)
+        nbytes = C.c_uint64(0)
+        st = ExcpStats()
+        rc = lib().excp_compress_step(self._h, _ptr(Wp), _ptr(W), _ptr(m), _ptr(v), n, alpha, beta, nbits,
+                                      lloyd_iters, flags, _ptr(blob), blob.numel() * blob.element_size(),
+                                      C.byref(nbytes), _ptr(W_recon_out), C.byref(st))
+        if check and rc != EXCP_OK:
+            raise ExcpError(rc, "excp_compress_step")
+        return rc, int(nbytes.value), st
+
+    def excp_decompress_step(self, Wp, blob, blob_bytes, W_recon_out=None, m_out=None, v_out=None, check=True):
+        _check_f32(Wp, "W_prev_recon", self.device)
+        n = Wp.numel()
+        for t, nm in ((W_recon_out, "W_recon_out"), (m_out, "m_out"), (v_out, "v_out")):
+            if t is not None:
+                _check_f32(t, nm, self.device)
+                if t.numel() != n:
+                    raise ValueError(nm + " length differs")
+        rc = lib().excp_decompress_step(self._h, _ptr(Wp), _ptr(blob), blob_bytes, n, _ptr(W_recon_out),
+                                        _ptr(m_out), _ptr(v_out))
+        if check and rc != EXCP_OK:
+            raise ExcpError(rc, "excp_decompress_step")
+        return rc
+
+    # -- timing ----------------------------------------------------------------------
+    def excp_set_profiling(self, enabled: bool):
+        rc = lib().excp_set_profiling(self._h, int(enabled))
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_set_profiling")
+
+    def stage_times(self) -> dict:
+        out = {}
+        for i in range(lib().excp_stage_count()):
+            ms, launches = C.c_double(0), C.c_int(0)
+            lib().excp_stage_ms(self._h, i, C.byref(ms), C.byref(launches))
+            out[lib().excp_stage_name(i).decode()] = (ms.value, launches.value)
+        return out

@@ -1,0 +1,149 @@
+// Device-side tables shared by the ExCP kernels and their host orchestrator.
+// One "group" of tensors is processed by every kernel at once: kernels walk a
+// tile list (EXCP_TILE elements per tile, tiles of all tensors back to back)
+// or a chunk list (EXCP_CHUNK survivors per chunk) and find their tensor from
+// these tables, so no launch depends on a value that only the device knows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define EXCP_TILE        4096u     // elements per tile of the full-tensor passes (256 threads x 16)
+#define EXCP_CHUNK       8192u     // survivors per chunk of the survivor passes
+#define EXCP_THREADS     256
+#define EXCP_ABSM_BINS   40        // u64 accumulators, 8 binary exponents apart, for the exact sum of |m|
+#define EXCP_MAX_K       255
+#define EXCP_HEADER      80u
+#define EXCP_MAGIC       0x50435845u
+#define EXCP_VERSION     1u
+#define EXCP_SPIN_LIMIT  (1u << 26)  // polls before a look-back wait gives up and flags an error
+
+typedef unsigned long long u64;
+typedef unsigned int u32;
+
+// Host-filled description of one tensor of a compress group.
+struct TDesc {
+    const float *Wp, *W, *m, *v;
+    u64 n;
+    unsigned char *blob;
+    u64 blob_cap;
+    float *W_out;
+    u64 elem_off;      // start of this tensor's survivor slots in the group workspace
+    u32 tile_begin;    // first tile of this tensor in the group's tile list
+    u32 tile_count;
+};
+
+// Device-written per-tensor state of a compress group.
+struct TState {
+    u64 absm[EXCP_ABSM_BINS];   // sum_g absm[g] * 2^(8g - 149) == exact sum of |m|
+    u64 nonfinite;
+    u64 n_w, n_o;
+    u64 off_bo, off_cw, off_cm, off_cv, blob_bytes;
+    double abs_sum;
+    double obj[3];
+    u32 sel_prefix;             // median radix select: key prefix found so far
+    u32 sel_rank;               // rank still to find inside that prefix
+    u32 med_bits;
+    float mean32, t_w, r_o;
+    int status;
+    int pad;
+};
+
+// One survivor stream (3 per tensor: residual, m, v) during codebook construction.
+struct SegState {
+    u64 len;
+    u32 chunk_begin;            // first chunk of this stream in the group's chunk list
+    u32 nslots;                 // distinct key prefixes still alive in the multi-rank select
+    u32 prefix[EXCP_MAX_K];     // per rank k: key prefix found so far
+    u32 rank[EXCP_MAX_K];       // per rank k: rank still to find inside that prefix
+    u32 slot_of_rank[EXCP_MAX_K];
+    u32 slot_prefix[EXCP_MAX_K];// sorted distinct prefixes
+    float C[EXCP_MAX_K + 1];    // current centres (K used)
+};
+
+// Host-filled description of one tensor of a decompress group.
+struct DDesc {
+    const float *Wp;
+    const unsigned char *blob;
+    u64 blob_bytes;
+    u64 n;
+    float *W_out, *m_out, *v_out;
+    u32 tile_begin, tile_count;
+};
+
+struct DState {
+    u64 n_w, n_o, blob_bytes;
+    u64 off_bw, off_bo, off_cw, off_cm, off_cv;
+    u32 nbits;
+    int status;
+    u64 pop_w, pop_o;           // bitmap populations found while scanning
+};
+
+// Result record copied back to the host after a batch.
+struct HostRec {
+    u64 n, n_w, n_o, blob_bytes, nonfinite;
+    double abs_sum, obj[3];
+    float med, mean32, t_w, r_o;
+    int status;
+    int pad;
+};
+
+struct GroupParams {
+    float alpha, beta;
+    int nbits, K, iters;
+    u32 flags;
+    u32 ntensors, ntiles;
+};
+
+static __host__ __device__ inline u64 excp_pad16(u64 b) { return (b + 15ull) & ~15ull; }
+static __host__ __device__ inline u64 excp_words(u64 bits) { return (bits + 63ull) >> 6; }
+
+// ---- launchers (defined next to their kernels) --------------------------------------------
+struct Workspace {
+    // group tables
+    TDesc *desc; TState *st; SegState *seg; u32 *tile_begin;   // tile_begin has ntensors+1 entries
+    // survivors
+    float *xw, *xm, *xv;
+    // median select
+    u32 *med_hist;            // [tensor][2048]
+    // look-back status words, one per tile
+    u64 *tile_status;
+    // survivor passes
+    u32 *chunk_total;         // [1]
+    u32 *seg_chunk_begin;     // [segments + 1] first chunk of every survivor stream
+    u32 *hist1;               // [segment][4096]
+    u32 *bin2slot;            // [segment][4096] bytes packed as u8
+    u32 *hist2;               // [segment][slots][1024]  (slots = min(K,15) unless large-K storage exists)
+    u64 hist2_slots;          // slot capacity per segment of hist2
+    double *part_sum;         // [chunk][K]
+    u32 *part_cnt;            // [chunk][K]
+    double *part_obj;         // [chunk]
+    u32 max_chunks;
+    // decode
+    DDesc *ddesc; DState *dst;
+    u32 *dec_cnt_w, *dec_cnt_o;   // per tile counts -> exclusive bases
+    // flags
+    int *err_flag;
+    HostRec *rec_dev;
+    u32 rec_base;             // index of this group's first tensor in rec_dev
+    int grid_persistent;      // co-resident workgroups for the look-back kernel
+    int grid_stream;          // workgroups for the other persistent kernels
+};
+
+void launch_zero_u32(u32 *p, u64 count, hipStream_t s);
+void launch_stats_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
+void launch_median_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
+void launch_mask_compact(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_init_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
+void launch_init_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
+void launch_lloyd_accum(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_lloyd_update(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s);
+void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which, hipStream_t s);
+void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s);
+void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s);
+void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s);
+int  query_persistent_grid(int device);

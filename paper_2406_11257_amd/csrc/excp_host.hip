@@ -1,0 +1,496 @@
+// Host side of the ExCP library: argument checks, grouping of tensors, workspace, launch order
+// (Alg. 1 and Alg. 2), result collection.  No computation of the method happens here.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/excp.h"
+#include "excp_device.h"
+
+namespace {
+
+constexpr u32 kMaxGroupTensors = 1024;   // tensors processed together
+constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress call
+
+enum Stage {
+    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_LAYOUT, ST_INIT_HIST, ST_INIT_RESOLVE,
+    ST_LLOYD_ACCUM, ST_LLOYD_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE, ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC,
+    ST_COUNT
+};
+const char *kStageNames[ST_COUNT] = {
+    "stats_hist", "select_hist", "select_resolve", "mask_compact", "layout", "init_hist", "init_resolve",
+    "lloyd_accum", "lloyd_update", "assign_pack", "finalize", "decode_prep", "decode_main", "misc"};
+
+struct Span { int stage; hipEvent_t a, b; };
+
+}  // namespace
+
+struct excp_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    u64 max_tensor = 0, max_group = 0;
+    Workspace w{};
+    // per-batch arrays (device) and their pinned staging (host)
+    TDesc *desc_all = nullptr; TState *st_all = nullptr;
+    DDesc *ddesc_all = nullptr; DState *dst_all = nullptr;
+    u32 *tile_begin_all = nullptr;
+    TDesc *h_desc = nullptr; DDesc *h_ddesc = nullptr; u32 *h_tile_begin = nullptr; HostRec *h_rec = nullptr;
+    int *h_err = nullptr;
+    u64 hist2_bytes = 0, part_entries = 0, status_words = 0;
+    u64 ws_bytes = 0;
+    std::vector<void *> allocs;
+    // pending batch
+    int pending = 0;      // 0 none, 1 compress, 2 decompress
+    int pending_count = 0;
+    // profiling
+    bool profiling = false;
+    std::vector<Span> spans;
+    std::vector<hipEvent_t> free_events;
+    double stage_ms[ST_COUNT] = {0};
+    int stage_launches[ST_COUNT] = {0};
+};
+
+namespace {
+
+template <class T>
+bool dev_alloc(excp_ctx *c, T **p, u64 count) {
+    u64 bytes = count * sizeof(T);
+    if (bytes == 0) bytes = 16;
+    void *q = nullptr;
+    if (hipMalloc(&q, bytes) != hipSuccess) return false;
+    c->allocs.push_back(q);
+    c->ws_bytes += bytes;
+    *p = (T *)q;
+    return true;
+}
+
+struct StageTimer {
+    excp_ctx *c; int stage; hipEvent_t a = nullptr, b = nullptr;
+    StageTimer(excp_ctx *ctx, int st) : c(ctx), stage(st) {
+        if (!c->profiling) return;
+        auto get = [&]() {
+            hipEvent_t e = nullptr;
+            if (!c->free_events.empty()) { e = c->free_events.back(); c->free_events.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
+            return e;
+        };
+        a = get(); b = get();
+        if (a) (void)hipEventRecord(a, c->stream);
+    }
+    ~StageTimer() {
+        if (!c->profiling || !a || !b) return;
+        (void)hipEventRecord(b, c->stream);
+        c->spans.push_back({stage, a, b});
+    }
+};
+
+u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits) {
+    u64 s = EXCP_HEADER + 12ull * (1ull << nbits);
+    s += excp_pad16(8 * excp_words(n));
+    s += excp_pad16(8 * excp_words(nw));
+    s += excp_pad16(8 * excp_words(nw * (u64)nbits));
+    s += 2 * excp_pad16(8 * excp_words(no * (u64)nbits));
+    return s;
+}
+
+struct Group { u32 first, count, ntiles; };
+
+// Split [0, count) into groups: at most kMaxGroupTensors tensors, cap_elems elements, tcap tensors.
+template <class GetN>
+void make_groups(int count, u64 cap_elems, u32 tcap, GetN get_n, std::vector<Group> &out) {
+    u32 i = 0;
+    while (i < (u32)count) {
+        Group g{i, 0, 0};
+        u64 elems = 0;
+        while (i < (u32)count && g.count < tcap) {
+            u64 n = get_n(i);
+            if (g.count && elems + n > cap_elems) break;
+            elems += n;
+            g.ntiles += (u32)((n + EXCP_TILE - 1) / EXCP_TILE);
+            ++g.count; ++i;
+        }
+        out.push_back(g);
+    }
+}
+
+void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32 ntiles) {
+    {
+        StageTimer t(c, ST_DECODE_PREP);
+        launch_decode_count(w, ntensors, ntiles, 0, c->stream);
+        launch_decode_scan(w, ntensors, 0, c->stream);
+        launch_decode_count(w, ntensors, ntiles, 1, c->stream);
+        launch_decode_scan(w, ntensors, 1, c->stream);
+    }
+    {
+        StageTimer t(c, ST_DECODE_MAIN);
+        launch_decode_main(w, ntensors, ntiles, c->stream);
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *excp_strerror(int code) {
+    switch (code) {
+        case EXCP_OK: return "ok";
+        case EXCP_E_ARG: return "invalid argument";
+        case EXCP_E_CAP: return "blob capacity too small";
+        case EXCP_E_NONFINITE: return "non-finite input";
+        case EXCP_E_BLOB: return "malformed compressed tensor";
+        case EXCP_E_HIP: return "HIP error";
+        case EXCP_E_STATE: return "call order violated";
+        case EXCP_E_INTERNAL: return "device-side wait gave up";
+        default: return "unknown error";
+    }
+}
+
+uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits) {
+    if (nbits < 2 || nbits > 8 || n_w > n || n_o > n_w) return 0;
+    return blob_size_host(n, n_w, n_o, nbits);
+}
+
+uint64_t excp_blob_bound(uint64_t n, int nbits) {
+    if (nbits < 2 || nbits > 8) return 0;
+    return blob_size_host(n, n, n, nbits);
+}
+
+int excp_stage_count(void) { return ST_COUNT; }
+const char *excp_stage_name(int i) { return (i >= 0 && i < ST_COUNT) ? kStageNames[i] : ""; }
+
+int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_tensor_elems,
+                uint64_t max_group_elems) {
+    if (!out) return EXCP_E_ARG;
+    *out = nullptr;
+    if (max_tensor_elems == 0 || max_tensor_elems > EXCP_MAX_TENSOR_ELEMS) return EXCP_E_ARG;
+    if (max_group_elems < max_tensor_elems) return EXCP_E_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || hip_device < 0 || hip_device >= ndev) return EXCP_E_HIP;
+    if (hipSetDevice(hip_device) != hipSuccess) return EXCP_E_HIP;
+    excp_ctx *c = new (std::nothrow) excp_ctx();
+    if (!c) return EXCP_E_HIP;
+    c->device = hip_device;
+    c->stream = (hipStream_t)hip_stream;
+    c->max_tensor = max_tensor_elems;
+    c->max_group = max_group_elems;
+    Workspace &w = c->w;
+    const u64 G = max_group_elems;
+    const u64 max_tiles = G / EXCP_TILE + kMaxGroupTensors + 1;
+    const u64 chunks_group = 3 * (G / EXCP_CHUNK) + 3 * kMaxGroupTensors + 3;
+    const u64 chunks_tensor = 3 * (max_tensor_elems / EXCP_CHUNK) + 3 * kMaxGroupTensors + 6;
+    c->part_entries = chunks_group * 15 > chunks_tensor * 255 ? chunks_group * 15 : chunks_tensor * 255;
+    c->hist2_bytes = 3ull * kMaxGroupTensors * 15 * 1024 * 4;
+    c->status_words = max_tiles;
+    bool ok = true;
+    ok = ok && dev_alloc(c, &c->desc_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->st_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->ddesc_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->dst_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->tile_begin_all, (u64)kMaxBatchTensors * 2 + 16);
+    ok = ok && dev_alloc(c, &w.seg, 3ull * kMaxGroupTensors);
+    ok = ok && dev_alloc(c, &w.xw, G);
+    ok = ok && dev_alloc(c, &w.xm, G);
+    ok = ok && dev_alloc(c, &w.xv, G);
+    ok = ok && dev_alloc(c, &w.med_hist, (u64)kMaxGroupTensors * 2048);
+    ok = ok && dev_alloc(c, &w.tile_status, max_tiles);
+    ok = ok && dev_alloc(c, &w.chunk_total, 4);
+    ok = ok && dev_alloc(c, &w.seg_chunk_begin, 3ull * kMaxGroupTensors + 4);
+    ok = ok && dev_alloc(c, &w.hist1, 3ull * kMaxGroupTensors * 4096);
+    ok = ok && dev_alloc(c, &w.bin2slot, 3ull * kMaxGroupTensors * 1024);
+    ok = ok && dev_alloc(c, (unsigned char **)&w.hist2, c->hist2_bytes);
+    ok = ok && dev_alloc(c, &w.part_sum, c->part_entries);
+    ok = ok && dev_alloc(c, &w.part_cnt, c->part_entries);
+    ok = ok && dev_alloc(c, &w.part_obj, chunks_group);
+    ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles);
+    ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles);
+    ok = ok && dev_alloc(c, &w.err_flag, 4);
+    ok = ok && dev_alloc(c, &w.rec_dev, kMaxBatchTensors);
+    w.max_chunks = (u32)(chunks_group > 0xffffffffull ? 0xffffffffull : chunks_group);
+    if (ok) {
+        ok = hipHostMalloc((void **)&c->h_desc, sizeof(TDesc) * kMaxBatchTensors) == hipSuccess &&
+             hipHostMalloc((void **)&c->h_ddesc, sizeof(DDesc) * kMaxBatchTensors) == hipSuccess &&
+             hipHostMalloc((void **)&c->h_tile_begin, sizeof(u32) * (kMaxBatchTensors * 2 + 16)) == hipSuccess &&
+             hipHostMalloc((void **)&c->h_rec, sizeof(HostRec) * kMaxBatchTensors) == hipSuccess &&
+             hipHostMalloc((void **)&c->h_err, 16) == hipSuccess;
+    }
+    if (ok) {
+        int grid = query_persistent_grid(hip_device);
+        if (grid <= 0) ok = false;
+        w.grid_persistent = grid;
+        w.grid_stream = grid;
+    }
+    if (ok) {
+        launch_zero_u32(w.med_hist, (u64)kMaxGroupTensors * 2048, c->stream);
+        launch_zero_u32(w.hist1, 3ull * kMaxGroupTensors * 4096, c->stream);
+        launch_zero_u32(w.hist2, c->hist2_bytes / 4, c->stream);
+        launch_zero_u32((u32 *)w.err_flag, 4, c->stream);
+        ok = hipStreamSynchronize(c->stream) == hipSuccess;
+    }
+    if (!ok) { excp_destroy(c); return EXCP_E_HIP; }
+    *out = c;
+    return EXCP_OK;
+}
+
+void excp_destroy(excp_ctx *c) {
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    for (void *p : c->allocs) (void)hipFree(p);
+    if (c->h_desc) (void)hipHostFree(c->h_desc);
+    if (c->h_ddesc) (void)hipHostFree(c->h_ddesc);
+    if (c->h_tile_begin) (void)hipHostFree(c->h_tile_begin);
+    if (c->h_rec) (void)hipHostFree(c->h_rec);
+    if (c->h_err) (void)hipHostFree(c->h_err);
+    for (auto &s : c->spans) { (void)hipEventDestroy(s.a); (void)hipEventDestroy(s.b); }
+    for (auto e : c->free_events) (void)hipEventDestroy(e);
+    delete c;
+}
+
+uint64_t excp_workspace_bytes(const excp_ctx *c) { return c ? c->ws_bytes : 0; }
+
+int excp_set_profiling(excp_ctx *c, int enabled) {
+    if (!c) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    c->profiling = enabled != 0;
+    return EXCP_OK;
+}
+
+int excp_stage_ms(excp_ctx *c, int i, double *ms, int *launches) {
+    if (!c || i < 0 || i >= ST_COUNT) return EXCP_E_ARG;
+    if (ms) *ms = c->stage_ms[i];
+    if (launches) *launches = c->stage_launches[i];
+    return EXCP_OK;
+}
+
+int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, float alpha, float beta,
+                          int nbits, int lloyd_iters, uint32_t flags) {
+    if (!c || count < 0 || (count && !tensors)) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || flags != 0) return EXCP_E_ARG;
+    if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
+    const int K = (1 << nbits) - 1;
+    for (int i = 0; i < count; ++i) {
+        const excp_tensor &t = tensors[i];
+        if (t.n > c->max_tensor) return EXCP_E_ARG;
+        if (!t.blob || ((uintptr_t)t.blob & 15u)) return EXCP_E_ARG;
+        if (t.n && (!t.W_prev_recon || !t.W_t || !t.m_t || !t.v_t)) return EXCP_E_ARG;
+        // the part of the blob whose place does not depend on the data must fit
+        if (t.blob_cap < EXCP_HEADER + 12ull * (1ull << nbits) + excp_pad16(8 * excp_words(t.n))) return EXCP_E_CAP;
+    }
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+    // group limits that depend on K: slot histograms and per-chunk partials
+    u64 cap_elems = c->max_group;
+    u32 tcap = kMaxGroupTensors;
+    {
+        u64 t_by_hist = c->hist2_bytes / (3ull * (u64)K * 4096ull);
+        if (t_by_hist < tcap) tcap = (u32)t_by_hist;
+        u64 chunks_ok = c->part_entries / (u64)K;                 // chunks whose partials fit
+        u64 elems_ok = chunks_ok > 3ull * tcap + 3 ? (chunks_ok - 3ull * tcap - 3) / 3 * EXCP_CHUNK : 0;
+        if (elems_ok < cap_elems) cap_elems = elems_ok;
+        if (cap_elems < c->max_tensor) cap_elems = c->max_tensor;   // a single tensor always fits by construction
+    }
+    std::vector<Group> groups;
+    make_groups(count, cap_elems, tcap, [&](u32 i) { return (u64)tensors[i].n; }, groups);
+
+    u32 tb_off = 0;
+    std::vector<u32> tb_offsets;
+    for (const Group &g : groups) {
+        u64 elem_off = 0; u32 tile = 0;
+        tb_offsets.push_back(tb_off);
+        for (u32 q = 0; q < g.count; ++q) {
+            const excp_tensor &t = tensors[g.first + q];
+            TDesc &d = c->h_desc[g.first + q];
+            d.Wp = t.W_prev_recon; d.W = t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
+            d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = t.W_recon_out;
+            d.elem_off = elem_off; d.tile_begin = tile;
+            d.tile_count = (u32)((t.n + EXCP_TILE - 1) / EXCP_TILE);
+            c->h_tile_begin[tb_off + q] = tile;
+            elem_off += t.n; tile += d.tile_count;
+        }
+        c->h_tile_begin[tb_off + g.count] = tile;
+        tb_off += g.count + 1;
+    }
+    hipStream_t s = c->stream;
+    if (count) {
+        if (hipMemcpyAsync(c->desc_all, c->h_desc, sizeof(TDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
+            return EXCP_E_HIP;
+        launch_zero_u32((u32 *)c->st_all, (u64)count * sizeof(TState) / 4, s);
+    }
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        const Group &g = groups[gi];
+        Workspace w = c->w;
+        w.desc = c->desc_all + g.first;
+        w.st = c->st_all + g.first;
+        w.ddesc = c->ddesc_all + g.first;
+        w.dst = c->dst_all + g.first;
+        w.tile_begin = c->tile_begin_all + tb_offsets[gi];
+        w.rec_base = 0;
+        w.rec_dev = c->w.rec_dev + g.first;
+        w.hist2_slots = (u64)K;
+        GroupParams p{};
+        p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
+        p.ntensors = g.count; p.ntiles = g.ntiles;
+        { StageTimer t(c, ST_MISC); launch_zero_u32((u32 *)w.tile_status, 2ull * g.ntiles, s); }
+        { StageTimer t(c, ST_STATS); launch_stats_hist(w, p, 0, s); }
+        { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, 0, s); }
+        for (int pass = 1; pass <= 2; ++pass) {
+            { StageTimer t(c, ST_SELECT); launch_stats_hist(w, p, pass, s); }
+            { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, pass, s); }
+        }
+        { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, s); }
+        { StageTimer t(c, ST_LAYOUT); launch_layout(w, p, s); }
+        for (int pass = 1; pass <= 3; ++pass) {
+            { StageTimer t(c, ST_INIT_HIST); launch_init_hist(w, p, pass, s); }
+            { StageTimer t(c, ST_INIT_RESOLVE); launch_init_resolve(w, p, pass, s); }
+        }
+        for (int it = 0; it < lloyd_iters; ++it) {
+            { StageTimer t(c, ST_LLOYD_ACCUM); launch_lloyd_accum(w, p, s); }
+            { StageTimer t(c, ST_LLOYD_UPDATE); launch_lloyd_update(w, p, s); }
+        }
+        { StageTimer t(c, ST_ASSIGN_PACK); launch_assign_pack(w, p, s); }
+        { StageTimer t(c, ST_FINALIZE); launch_finalize(w, p, s); }
+        bool any_out = false;
+        for (u32 q = 0; q < g.count; ++q) any_out = any_out || tensors[g.first + q].W_recon_out != nullptr;
+        if (any_out) {
+            { StageTimer t(c, ST_MISC); launch_decode_from_compress(w, p, s); }
+            run_decode_prep_and_main(c, w, g.count, g.ntiles);
+        }
+    }
+    if (count) {
+        if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
+    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    c->pending = 1;
+    c->pending_count = count;
+    return EXCP_OK;
+}
+
+int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
+    if (!c || count < 0 || (count && !blobs)) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+    for (int i = 0; i < count; ++i) {
+        const excp_blob &b = blobs[i];
+        if (b.n > c->max_tensor) return EXCP_E_ARG;
+        if (!b.blob || ((uintptr_t)b.blob & 15u)) return EXCP_E_ARG;
+        if (b.n && !b.W_prev_recon) return EXCP_E_ARG;
+    }
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+    std::vector<Group> groups;
+    make_groups(count, c->max_group, kMaxGroupTensors, [&](u32 i) { return (u64)blobs[i].n; }, groups);
+    u32 tb_off = 0;
+    std::vector<u32> tb_offsets;
+    for (const Group &g : groups) {
+        u32 tile = 0;
+        tb_offsets.push_back(tb_off);
+        for (u32 q = 0; q < g.count; ++q) {
+            const excp_blob &b = blobs[g.first + q];
+            DDesc &d = c->h_ddesc[g.first + q];
+            d.Wp = b.W_prev_recon; d.blob = (const unsigned char *)b.blob; d.blob_bytes = b.blob_bytes; d.n = b.n;
+            d.W_out = b.W_recon_out; d.m_out = b.m_out; d.v_out = b.v_out;
+            d.tile_begin = tile; d.tile_count = (u32)((b.n + EXCP_TILE - 1) / EXCP_TILE);
+            c->h_tile_begin[tb_off + q] = tile;
+            tile += d.tile_count;
+        }
+        c->h_tile_begin[tb_off + g.count] = tile;
+        tb_off += g.count + 1;
+    }
+    hipStream_t s = c->stream;
+    if (count) {
+        if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        const Group &g = groups[gi];
+        Workspace w = c->w;
+        w.ddesc = c->ddesc_all + g.first;
+        w.dst = c->dst_all + g.first;
+        w.tile_begin = c->tile_begin_all + tb_offsets[gi];
+        w.rec_dev = c->w.rec_dev + g.first;
+        w.rec_base = 0;
+        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, s); }
+        run_decode_prep_and_main(c, w, g.count, g.ntiles);
+        { StageTimer t(c, ST_MISC); launch_decode_finish(w, g.count, s); }
+    }
+    if (count) {
+        if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
+    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    c->pending = 2;
+    c->pending_count = count;
+    return EXCP_OK;
+}
+
+int excp_collect(excp_ctx *c, excp_stats *stats) {
+    if (!c) return EXCP_E_ARG;
+    if (!c->pending) return EXCP_E_STATE;
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+    hipError_t e = hipStreamSynchronize(c->stream);
+    c->pending = 0;
+    for (int i = 0; i < ST_COUNT; ++i) { c->stage_ms[i] = 0; c->stage_launches[i] = 0; }
+    for (auto &sp : c->spans) {
+        float ms = 0.f;
+        if (e == hipSuccess && hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) {
+            c->stage_ms[sp.stage] += ms;
+            c->stage_launches[sp.stage] += 1;
+        }
+        c->free_events.push_back(sp.a);
+        c->free_events.push_back(sp.b);
+    }
+    c->spans.clear();
+    if (e != hipSuccess) return EXCP_E_HIP;
+    int first = EXCP_OK;
+    if (*c->h_err) {
+        first = EXCP_E_INTERNAL;
+        launch_zero_u32((u32 *)c->w.err_flag, 4, c->stream);
+        (void)hipStreamSynchronize(c->stream);
+    }
+    for (int i = 0; i < c->pending_count; ++i) {
+        const HostRec &r = c->h_rec[i];
+        if (stats) {
+            excp_stats &o = stats[i];
+            memset(&o, 0, sizeof(o));
+            o.n = r.n; o.n_w = r.n_w; o.n_o = r.n_o; o.blob_bytes = r.blob_bytes; o.nonfinite = r.nonfinite;
+            o.abs_sum_m = r.abs_sum; o.obj_w = r.obj[0]; o.obj_m = r.obj[1]; o.obj_v = r.obj[2];
+            o.median_abs_dw = r.med; o.mean_abs_m = r.mean32; o.t_w = r.t_w; o.r_o = r.r_o;
+            o.status = r.status;
+        }
+        if (first == EXCP_OK && r.status != 0) first = r.status;
+    }
+    return first;
+}
+
+int excp_compress_step(excp_ctx *c, const float *W_prev_recon, const float *W_t, const float *m_t,
+                       const float *v_t, uint64_t n, float alpha, float beta, int nbits, int lloyd_iters,
+                       uint32_t flags, void *blob_out, uint64_t blob_cap, uint64_t *blob_bytes,
+                       float *W_recon_out, excp_stats *stats) {
+    excp_tensor t{W_prev_recon, W_t, m_t, v_t, n, blob_out, blob_cap, W_recon_out};
+    int rc = excp_compress_tensors(c, 1, &t, alpha, beta, nbits, lloyd_iters, flags);
+    if (rc != EXCP_OK) return rc;
+    excp_stats st;
+    rc = excp_collect(c, &st);
+    if (blob_bytes) *blob_bytes = st.blob_bytes;
+    if (stats) *stats = st;
+    return rc;
+}
+
+int excp_decompress_step(excp_ctx *c, const float *W_prev_recon, const void *blob, uint64_t blob_bytes,
+                         uint64_t n, float *W_recon_out, float *m_out, float *v_out) {
+    excp_blob b{W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out};
+    int rc = excp_decompress_tensors(c, 1, &b);
+    if (rc != EXCP_OK) return rc;
+    return excp_collect(c, nullptr);
+}
+
+}  // extern "C"

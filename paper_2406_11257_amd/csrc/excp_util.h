@@ -1,0 +1,93 @@
+// Small device helpers shared by the ExCP kernels (wave64, gfx950).
+#pragma once
+#include "excp_device.h"
+
+#define WAVE 64
+
+__device__ __forceinline__ u32 f2u(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ float u2f(u32 x) { return __uint_as_float(x); }
+
+__device__ __forceinline__ u64 ballot64(bool p) { return __ballot(p); }
+__device__ __forceinline__ u32 lane_id() { return threadIdx.x & 63u; }
+__device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
+    u32 lo = (u32)v, hi = (u32)(v >> 32);
+    lo = __shfl_xor(lo, m, WAVE);
+    hi = __shfl_xor(hi, m, WAVE);
+    return ((u64)hi << 32) | lo;
+}
+__device__ __forceinline__ u64 wave_sum_u64(u64 v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += shfl_xor_u64(v, m);
+    return v;
+}
+__device__ __forceinline__ u32 wave_sum_u32(u32 v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, WAVE);
+    return v;
+}
+__device__ __forceinline__ u32 wave_max_u32(u32 v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = max(v, (u32)__shfl_xor(v, m, WAVE));
+    return v;
+}
+__device__ __forceinline__ double shfl_xor_f64(double v, int m) {
+    return __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(v), m));
+}
+
+// Largest t with begin[t] <= x (begin is non-decreasing, begin[0] == 0, count+1 entries,
+// begin[count] > x).  Entries may repeat (empty items); the item found is never empty.
+__device__ __forceinline__ u32 find_owner(const u32 *__restrict__ begin, u32 count, u32 x) {
+    u32 lo = 0, hi = count;          // invariant: begin[lo] <= x < begin[hi]
+    while (hi - lo > 1) {
+        u32 mid = (lo + hi) >> 1;
+        if (begin[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Order-preserving map of fp32 bit patterns to unsigned keys (and back).
+__device__ __forceinline__ u32 key_of(float x) {
+    u32 u = f2u(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float val_of(u32 k) {
+    return u2f((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// Device-scope loads / stores of the look-back status words.
+__device__ __forceinline__ u64 ld_status(const u64 *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_status(u64 *p, u64 v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Index of the nearest centre exactly as the definition states it: all distances are
+// (fp64(x) - fp64(C[k]))^2 with one rounding for the difference and one for the square, the
+// smallest wins and ties go to the lower index.  C must be non-decreasing; because rounding is
+// monotone, the minimum over all k is attained next to x, and an equal-distance plateau can only
+// extend to the left of the chosen index.
+__device__ __forceinline__ int nearest_centre(float x, const float *C, int K, double *dist_out) {
+    int lo = 0, hi = K;                    // count of centres <= x by bisection
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (C[mid] <= x) lo = mid + 1; else hi = mid;
+    }
+    int j = lo - 1;                        // largest index with C[j] <= x, or -1
+    int a = j < 0 ? 0 : j;
+    int b = (j + 1 < K) ? j + 1 : K - 1;
+    double xd = (double)x;
+    double da = xd - (double)C[a]; da = da * da;
+    double db = xd - (double)C[b]; db = db * db;
+    int pick = a; double dp = da;
+    if (db < da) { pick = b; dp = db; }
+    while (pick > 0) {
+        double dl = xd - (double)C[pick - 1]; dl = dl * dl;
+        if (dl != dp) break;
+        --pick;
+    }
+    if (dist_out) *dist_out = dp;
+    return pick;
+}
