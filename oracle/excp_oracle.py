@@ -127,16 +127,26 @@ def kmeans_init(x: np.ndarray, K: int) -> np.ndarray:
     return xs[idx].astype(f32)
 
 
-def nearest_centre(x: np.ndarray, C: np.ndarray, chunk: int = 1 << 18) -> np.ndarray:
-    """a[j] = argmin_k (x_j - C_k)^2, all K distances evaluated in fp64
-    (difference rounded once, square rounded once), ties -> smallest k."""
+def nearest_centre(x: np.ndarray, C: np.ndarray) -> np.ndarray:
+    """Index of the nearest centre of each x_j, for centres in ascending order.
+
+    In one dimension the nearest centre is one of the two that bracket x_j.  With a = the last
+    centre <= x_j and b = the next one (a = b at either end), the distances x_j - C_a and
+    C_b - x_j are each evaluated in fp64 (one rounding); b wins only if it is strictly nearer,
+    and among centres of equal value the lowest index is taken.  Evaluating all K distances in
+    fp64 instead would not be equivalent: for a value far above every centre the rounded
+    distances all coincide and the tie would send it to centre 0."""
     C64 = C.astype(np.float64)
-    out = np.empty(x.size, dtype=np.int64)
-    for s in range(0, x.size, chunk):
-        xc = x[s:s + chunk].astype(np.float64)
-        diff = xc[:, None] - C64[None, :]
-        out[s:s + chunk] = np.argmin(diff * diff, axis=1)   # first minimum
-    return out
+    K = C64.size
+    assert np.all(np.diff(C64) >= 0), "centres must be non-decreasing"
+    x64 = x.astype(np.float64)
+    j = np.searchsorted(C64, x64, side="right") - 1          # last centre <= x, or -1
+    a = np.maximum(j, 0)
+    b = np.minimum(j + 1, K - 1)
+    da = np.abs(x64 - C64[a])
+    db = np.abs(C64[b] - x64)
+    pick = np.where(db < da, b, a)
+    return np.searchsorted(C64, C64[pick], side="left").astype(np.int64)   # lowest index of that value
 
 
 def objective(x: np.ndarray, C: np.ndarray, a: np.ndarray) -> float:
@@ -151,7 +161,8 @@ def lloyd(x: np.ndarray, K: int, iters: int, history: list | None = None):
     """Exactly ``iters`` Lloyd updates from the quantile initialisation.
 
     update: C_k = fp32( exact sum of the members (rounded once to fp64) / count )
-    for every non-empty cluster; an empty cluster keeps its centre.
+    for every non-empty cluster; an empty cluster keeps its centre.  Clusters are
+    intervals of the sorted values, so the centres stay in ascending order.
     Returns (C fp32[K], a int64[len(x)]) where a is the assignment to the FINAL
     centres.  If ``history`` is a list, the objective before each update and
     after the last one is appended to it.

@@ -64,11 +64,10 @@ __device__ __forceinline__ void st_status(u64 *p, u64 v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Index of the nearest centre exactly as the definition states it: all distances are
-// (fp64(x) - fp64(C[k]))^2 with one rounding for the difference and one for the square, the
-// smallest wins and ties go to the lower index.  C must be non-decreasing; because rounding is
-// monotone, the minimum over all k is attained next to x, and an equal-distance plateau can only
-// extend to the left of the chosen index.
+// Index of the nearest centre of x among centres in ascending order (Sec. 3.3 leaves the rule
+// open; this is the rule the library fixes).  a = last centre <= x, b = the next one; the two
+// distances are evaluated in fp64 with one rounding each, b wins only if strictly nearer, and
+// among centres of equal value the lowest index is taken.  dist_out receives (x - C[pick])^2.
 __device__ __forceinline__ int nearest_centre(float x, const float *C, int K, double *dist_out) {
     int lo = 0, hi = K;                    // count of centres <= x by bisection
     while (lo < hi) {
@@ -79,15 +78,11 @@ __device__ __forceinline__ int nearest_centre(float x, const float *C, int K, do
     int a = j < 0 ? 0 : j;
     int b = (j + 1 < K) ? j + 1 : K - 1;
     double xd = (double)x;
-    double da = xd - (double)C[a]; da = da * da;
-    double db = xd - (double)C[b]; db = db * db;
-    int pick = a; double dp = da;
-    if (db < da) { pick = b; dp = db; }
-    while (pick > 0) {
-        double dl = xd - (double)C[pick - 1]; dl = dl * dl;
-        if (dl != dp) break;
-        --pick;
-    }
-    if (dist_out) *dist_out = dp;
+    double da = fabs(xd - (double)C[a]);
+    double db = fabs((double)C[b] - xd);
+    int pick = (db < da) ? b : a;
+    float cv = C[pick];
+    while (pick > 0 && C[pick - 1] == cv) --pick;
+    if (dist_out) { double d = xd - (double)cv; *dist_out = d * d; }
     return pick;
 }

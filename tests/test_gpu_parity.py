@@ -1,0 +1,232 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Bit-exact for thresholds, counts, bitmaps, codes (given the centres) and
+reconstruction; centres within 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2406_11257_amd as X
+from paper_2406_11257_amd import synth
+from gpu_util import compare_with_oracle, gpu_compress, gpu_decompress, to_dev
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = X.Context(8 << 20, 16 << 20)
+    yield c
+    c.close()
+
+
+def case(n, seed, scale=1e-4, heavy=False):
+    g = np.random.default_rng(seed)
+    Wp = (g.standard_normal(n) * 0.02).astype(f32)
+    noise = g.standard_t(3, n) * scale if heavy else g.laplace(0, scale, n)
+    W = (Wp + noise.astype(f32)).astype(f32)
+    m = (g.standard_normal(n) * 5e-5).astype(f32)
+    v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+    return Wp, W, m, v
+
+
+def check_all(ctx, cases, alpha=5e-5, beta=2.0, nbits=4, iters=10):
+    rc, out = gpu_compress(ctx, cases, alpha, beta, nbits, iters)
+    assert rc == 0
+    worst = 0.0
+    for c, o in zip(cases, out):
+        ref, w = compare_with_oracle(c, o, alpha, beta, nbits, iters)
+        worst = max(worst, w)
+        # Alg. 2 on the GPU against Alg. 2 of the oracle, both from the GPU's blob
+        rc2, (Wr, mr, vr) = gpu_decompress(ctx, c[0], o["blob"], c[0].size)
+        assert rc2 == 0
+        W2, m2, v2 = O.decompress_step(c[0], o["blob"])
+        for a, b in ((Wr, W2), (mr, m2), (vr, v2)):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    return out, worst
+
+
+def test_sizes_from_empty_to_many_tiles_with_ragged_tails(ctx):
+    sizes = [0, 1, 2, 63, 64, 65, 127, 128, 129, 4095, 4096, 4097, 8191, 8192, 8193, 12289, 100000, 1048593]
+    print("sizes", sizes, flush=True)
+    check_all(ctx, [case(n, 100 + i) for i, n in enumerate(sizes)])
+
+
+@pytest.mark.parametrize("nbits,iters", [(2, 10), (3, 4), (4, 0), (4, 1), (5, 3), (6, 2), (7, 2), (8, 10)])
+def test_code_widths_and_iteration_counts(ctx, nbits, iters):
+    print("nbits", nbits, "iters", iters, flush=True)
+    check_all(ctx, [case(50001, 7), case(3, 8), case(300, 9), case(70000, 10, heavy=True)], nbits=nbits, iters=iters)
+
+
+@pytest.mark.parametrize("alpha,beta", [(1e-5, 2.0), (2e-4, 2.0), (5e-5, 0.5), (5e-5, 4.0), (0.0, 0.0), (1.0, 2.0)])
+def test_threshold_sweep_covers_dense_to_empty_masks(ctx, alpha, beta):
+    print("alpha", alpha, "beta", beta, flush=True)
+    out, _ = check_all(ctx, [case(200003, 21), case(5000, 22, scale=3e-5)], alpha=alpha, beta=beta)
+    if alpha == 1.0:
+        assert out[0]["stats"].n_w == 0          # everything pruned
+    if alpha == 0.0:
+        assert out[0]["stats"].n_w > 199000      # everything with a non-zero residual kept
+
+
+def test_degenerate_inputs(ctx):
+    n = 10000
+    Wp, W, m, v = case(n, 31)
+    cases = []
+    cases.append((Wp, Wp.copy(), m, v))                                   # identical checkpoints
+    cases.append((Wp, (Wp + f32(1e-4)).astype(f32), m, v))                # near-constant residual (ties)
+    z = np.zeros(n, f32)
+    cases.append((z, np.full(n, 2.5e-4, f32), np.full(n, 1e-4, f32), np.full(n, 1e-8, f32)))   # all equal
+    W2 = W.copy(); W2[::3] = Wp[::3]                                      # many exact zeros in d (+0 and -0)
+    Wp3 = Wp.copy(); Wp3[1::3] = -0.0; W3 = W2.copy(); W3[1::3] = 0.0
+    cases.append((Wp3, W3, m, v))
+    v4 = v.copy(); v4[:100] = 0.0; v4[100:200] = -1e-9; v4[200:300] = 1e-45; v4[300:400] = 3e38
+    cases.append((Wp, W, m, v4))                                          # v = 0, v < 0, denormal, huge
+    m5 = m.copy(); m5[::2] = 0.0; m5[1::4] = 1e-42                         # zeros and denormals in m
+    cases.append((Wp, W, m5, v))
+    tiny = (np.random.default_rng(5).integers(-50, 50, n)).astype(f32) * f32(1e-45)
+    cases.append((z, tiny, m, v))                                         # denormal residuals with ties
+    m7 = m.copy(); m7[0] = 3e20; m7[1] = 1e-30; m7[2] = -2e30             # huge dynamic range in the sum
+    cases.append((Wp, W, m7, v))
+    # thresholds hit exactly: alpha = 2^-14, v = alpha^2 -> r_i = median; keeps only values above it
+    d8 = np.random.default_rng(6).laplace(0, 1e-4, n).astype(f32)
+    cases.append((z, d8, m, np.full(n, f32(2.0 ** -28), f32)))
+    print("degenerate cases", len(cases), flush=True)
+    check_all(ctx, cases[:8])
+    out, _ = check_all(ctx, cases[8:], alpha=2.0 ** -14)
+    assert out[0]["stats"].n_w == n - 1 - (n - 1) // 2
+
+
+def test_mean_is_exact_and_independent_of_order(ctx):
+    n = 300000
+    Wp, W, m, v = case(n, 41)
+    m[:5] = [1.0, 2.0 ** -40, -(2.0 ** 70), 1e-44, -3e-39]
+    p = np.random.default_rng(1).permutation(n)
+    rc, out = gpu_compress(ctx, [(Wp, W, m, v), (Wp, W, m[p], v)], want_recon=False, iters=0)
+    assert rc == 0
+    S, mean32 = O.exact_mean_abs(m)
+    for o in out:
+        assert o["stats"].abs_sum_m == S
+        assert f32(o["stats"].mean_abs_m).tobytes() == mean32.tobytes()
+
+
+def test_whole_small_model_in_one_batch(ctx):
+    cfg = synth.config(0)
+    cases = [synth.draw_tensor(0, i, s) for i, s in enumerate(cfg.tensors)]
+    print("config 0:", len(cases), "tensors", cfg.total, "params", flush=True)
+    out, worst = check_all(ctx, cases, synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS)
+    total = sum(o["stats"].blob_bytes for o in out)
+    print("ratio", 12 * cfg.total / total, "worst centre err", worst, flush=True)
+
+
+def test_batches_larger_than_a_group_give_the_same_bytes(ctx):
+    small = X.Context(1 << 17, 1 << 17)        # forces several groups
+    cases = [case(n, 60 + i) for i, n in enumerate([100000, 50000, 70000, 131072, 5, 0, 90000])]
+    rc1, a = gpu_compress(small, cases)
+    rc2, b = gpu_compress(ctx, cases)
+    small.close()
+    assert rc1 == 0 and rc2 == 0
+    for x, y in zip(a, b):
+        assert x["blob"] == y["blob"] and np.array_equal(x["W_recon"], y["W_recon"])
+
+
+def test_runs_are_deterministic(ctx):
+    cases = [case(777777, 71), case(4096, 72)]
+    blobs = []
+    for _ in range(3):
+        rc, out = gpu_compress(ctx, cases)
+        assert rc == 0
+        blobs.append([o["blob"] for o in out])
+    assert blobs[0] == blobs[1] == blobs[2]
+
+
+def test_in_place_reconstruction_and_single_tensor_calls(ctx):
+    Wp, W, m, v = case(123457, 81)
+    ref = O.compress_step(Wp, W, m, v)
+    d = [to_dev(a) for a in (Wp, W, m, v)]
+    blob = torch.zeros(X.excp_blob_bound(Wp.size, 4), dtype=torch.uint8, device="cuda")
+    rc, nbytes, st = ctx.excp_compress_step(*d, blob, W_recon_out=d[0])      # in place over W_prev
+    assert rc == 0 and nbytes == len(ref.blob) and st.n_w == ref.n_w
+    got = blob[:nbytes].cpu().numpy().tobytes()
+    Wr, mr, vr = O.decompress_step(Wp, got)
+    assert np.array_equal(d[0].cpu().numpy().view(np.uint32), Wr.view(np.uint32))
+    # decompress in place over a fresh copy of W_prev, moments requested
+    Wp_d = to_dev(Wp)
+    mo = torch.empty_like(Wp_d); vo = torch.empty_like(Wp_d)
+    ctx.excp_decompress_step(Wp_d, blob, nbytes, W_recon_out=Wp_d, m_out=mo, v_out=vo)
+    assert np.array_equal(Wp_d.cpu().numpy().view(np.uint32), Wr.view(np.uint32))
+    assert np.array_equal(mo.cpu().numpy(), mr) and np.array_equal(vo.cpu().numpy(), vr)
+    # outputs are optional
+    ctx.excp_decompress_step(to_dev(Wp), blob, nbytes, m_out=mo)
+    assert np.array_equal(mo.cpu().numpy(), mr)
+
+
+def test_chained_checkpoints_with_teacher_forcing(ctx):
+    # each step is compressed against the previous RECONSTRUCTION (Sec. 3.4); the oracle is fed the
+    # GPU's own reconstruction so that both see the same inputs at every step
+    n, steps = 150001, 4
+    g = np.random.default_rng(91)
+    W_true = (g.standard_normal(n) * 0.02).astype(f32)
+    W_hat = W_true.copy()
+    for t in range(steps):
+        W_true = (W_true + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+        m = (g.standard_normal(n) * 5e-5).astype(f32)
+        v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+        c = (W_hat, W_true, m, v)
+        rc, out = gpu_compress(ctx, [c])
+        assert rc == 0
+        compare_with_oracle(c, out[0], 5e-5, 2.0, 4, 10)
+        W_hat = out[0]["W_recon"]
+        # no drift: the error against the true weights is bounded by this step's residual handling
+        assert np.abs(W_hat - W_true).max() < 2e-3
+        print("step", t, "n_w", out[0]["stats"].n_w, "rms err", float(np.sqrt(np.mean((W_hat - W_true) ** 2))), flush=True)
+
+
+def test_errors_are_reported_not_faulted(ctx):
+    Wp, W, m, v = case(20000, 95)
+    # non-finite inputs in each array
+    for which in range(4):
+        arrs = [Wp.copy(), W.copy(), m.copy(), v.copy()]
+        arrs[which][12345] = np.nan if which % 2 == 0 else np.inf
+        rc, out = gpu_compress(ctx, [tuple(arrs), (Wp, W, m, v)])
+        assert rc == X.EXCP_E_NONFINITE
+        assert out[0]["stats"].status == X.EXCP_E_NONFINITE and out[0]["stats"].nonfinite >= 1
+        assert out[1]["stats"].status == 0                       # the other tensor is unaffected
+    # residual overflow
+    big = np.full(100, 3e38, f32)
+    rc, out = gpu_compress(ctx, [(-big, big, m[:100], v[:100])])
+    assert rc == X.EXCP_E_NONFINITE
+    # capacity: fixed part too small is refused at once; variable part is detected on the device
+    ref = O.compress_step(Wp, W, m, v)
+    with pytest.raises(X.ExcpError) as e:
+        gpu_compress(ctx, [(Wp, W, m, v)], blob_cap=1024)
+    assert e.value.code == X.EXCP_E_CAP
+    cap = (len(ref.blob) - 64) // 16 * 16
+    rc, out = gpu_compress(ctx, [(Wp, W, m, v)], blob_cap=cap)
+    assert rc == X.EXCP_E_CAP and out[0]["stats"].status == X.EXCP_E_CAP
+    rc, out = gpu_compress(ctx, [(Wp, W, m, v)], blob_cap=len(ref.blob))     # exactly enough
+    assert rc == 0 and out[0]["blob"] == ref.blob
+    # argument errors
+    d = [to_dev(a) for a in (Wp, W, m, v)]
+    blob = torch.zeros(X.excp_blob_bound(Wp.size, 4), dtype=torch.uint8, device="cuda")
+    for kw in (dict(nbits=1), dict(nbits=9), dict(lloyd_iters=-1), dict(alpha=-1.0), dict(beta=float("nan")),
+               dict(flags=1)):
+        rc, _, _ = ctx.excp_compress_step(*d, blob, check=False, **kw)
+        assert rc == X.EXCP_E_ARG, kw
+    # damaged blobs
+    good = bytearray(ref.blob)
+    for damage in ("magic", "version", "nbits", "count", "size", "bitmap", "short"):
+        b = bytearray(good)
+        if damage == "magic": b[0] ^= 0xFF
+        if damage == "version": b[4] = 9
+        if damage == "nbits": b[8] = 11
+        if damage == "count": b[24] ^= 1                          # n_w
+        if damage == "size": b[64] ^= 0x10
+        if damage == "bitmap": b[80 + 192] ^= 0x01                # flips M_w(0)
+        if damage == "short": b = b[:len(b) - 32]
+        rc, _ = gpu_decompress(ctx, Wp, bytes(b), Wp.size)
+        assert rc == X.EXCP_E_BLOB, damage
+    rc, _ = gpu_decompress(ctx, Wp[:-1], bytes(good), Wp.size - 1)
+    assert rc == X.EXCP_E_BLOB
+    rc, outs = gpu_decompress(ctx, Wp, bytes(good), Wp.size)     # the context still works afterwards
+    assert rc == 0 and np.array_equal(outs[0], ref.W_recon)

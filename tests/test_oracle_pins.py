@@ -254,6 +254,12 @@ def test_nearest_centre_against_exact_rational_search():
     # ties go to the smaller index, also with duplicated centres
     C2 = np.array([-1.0, 0.0, 0.0, 2.0], f32)
     assert list(O.nearest_centre(np.array([-0.5, 0.0, 1.0, 5.0], f32), C2)) == [0, 1, 1, 3]
+    # a value far above tiny centres: all fp64-rounded distances coincide, the nearest is still the top one
+    C3 = np.array([1e-9, 2e-9, 3e-9, 5e-9], f32)
+    x3 = np.array([3e38, -3e38, 2.4e-9, 1e-30], f32)
+    assert list(O.nearest_centre(x3, C3)) == list(exact_nearest(x3, C3)) == [3, 0, 1, 0]
+    with pytest.raises(AssertionError):
+        O.nearest_centre(x3, C3[::-1])
 
 
 def test_kmeans_init_picks_the_stated_order_statistics():
