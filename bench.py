@@ -1,0 +1,215 @@
+#!/usr/bin/env python3
+"""Throughput of the ExCP compress step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic checkpoint: residual, exact
+thresholds, joint masks + compaction, k-means codebooks (10 Lloyd iterations), code packing and the
+reconstructed weights kept for the next checkpoint -- for every tensor of the model, with W_prev,
+W, m and v already resident in HBM.  The workload is the LLaMA-7B-shaped checkpoint (291 tensors,
+6.74e9 parameters) when it fits on the device, otherwise the largest Pythia-shaped one that does.
+
+Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def stage_bytes_per_param(p_w, p_o, nbits, iters):
+    """Algorithmic HBM bytes per parameter of each kernel stage (what the method must move)."""
+    s = p_w + 2.0 * p_o
+    bitmaps = 0.125 * (1.0 + p_w)
+    return {
+        "stats_hist": 12.0 + 0.125,                       # read W_prev, W, m; clear the M_o bitmap region
+        "select_hist": 2 * 8.0,                            # two refinement passes over W_prev, W
+        "mask_compact": 16.0 + bitmaps + 4.0 * s,          # read all four arrays; write bitmaps + survivors
+        "init_hist": 3 * 4.0 * s,                          # three select passes over the survivors
+        "lloyd_accum": iters * 4.0 * s,                    # one read of the survivors per iteration
+        "assign_pack": 4.0 * s + s * nbits / 8.0,          # read survivors, write codes
+        "decode_main": 4.0 + bitmaps + s * nbits / 8.0 + 4.0,   # read W_prev, bitmaps, codes; write W_hat
+    }
+
+
+def survey_step_bytes_per_param(p_w, p_o):
+    """Step-level accounting used for the '% of HBM roofline' headline: 32.2 + 58.5 s (+ 8 for W_hat)."""
+    s = p_w + 2.0 * p_o
+    return 32.2 + 58.5 * s + 8.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=-1, help="workload config id (default: largest that fits)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2406_11257_amd as X
+    from paper_2406_11257_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda", 0)
+    free, total_mem = torch.cuda.mem_get_info()
+    alpha, beta, nbits, iters = synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS
+
+    def need_bytes(cfg, group):
+        N = cfg.total
+        return 20 * N + 1.8 * N + 12.4 * group + (2 << 30)   # inputs + W_hat, blobs, workspace, slack
+
+    cid = args.config
+    if cid < 0:
+        for cand in (3, 2, 1, 0):
+            cfg = synth.config(cand)
+            if need_bytes(cfg, max(cfg.total // 3, max(t.n for t in cfg.tensors))) < free:
+                cid = cand
+                break
+    cfg = synth.config(cid)
+    N = cfg.total
+    max_n = max(t.n for t in cfg.tensors)
+    group = max(N // 3 + 1, max_n) if N > (1 << 30) else N
+    print(f"[bench] workload config {cid} ({cfg.name}): {len(cfg.tensors)} tensors, {N} params; "
+          f"free HBM {free / 2**30:.1f} GiB", file=sys.stderr, flush=True)
+
+    # ---- inputs resident in HBM: four flat arrays, one view per tensor -------------------------
+    t0 = time.time()
+    flat = [torch.empty(N, dtype=torch.float32, device=dev) for _ in range(5)]   # Wp, W, m, v, W_hat
+    offs, o = [], 0
+    for i, spec in enumerate(cfg.tensors):
+        Wp, W, m, v = synth.torch_draw_tensor(cid, i, spec, dev)
+        for buf, src in zip(flat, (Wp, W, m, v)):
+            buf[o:o + spec.n].copy_(src)
+        del Wp, W, m, v
+        offs.append(o)
+        o += spec.n
+    torch.cuda.synchronize()
+    print(f"[bench] inputs drawn on the device in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    caps = [X.excp_blob_bound(t.n, nbits) for t in cfg.tensors]
+    boffs = np.concatenate([[0], np.cumsum(caps)]).astype(np.int64)
+    blob_flat = torch.empty(int(boffs[-1]), dtype=torch.uint8, device=dev)
+    ctx = X.Context(max_n, group, device=dev)
+    tensors = []
+    for i, spec in enumerate(cfg.tensors):
+        a, b = offs[i], offs[i] + spec.n
+        tensors.append((flat[0][a:b], flat[1][a:b], flat[2][a:b], flat[3][a:b],
+                        blob_flat[int(boffs[i]):int(boffs[i + 1])], flat[4][a:b]))
+
+    def step():
+        ctx.excp_compress_tensors(tensors, alpha, beta, nbits, iters, 0)
+        return ctx.excp_collect()[1]
+
+    for _ in range(args.warmup):
+        stats = step()
+    ctx.excp_set_profiling(True)
+    stage_tot = {}
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_host = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        stats = step()
+        for k, (ms, launches) in ctx.stage_times().items():
+            a = stage_tot.setdefault(k, [0.0, 0])
+            a[0] += ms
+            a[1] += launches
+    ev1.record()
+    torch.cuda.synchronize()
+    host_ms = (time.perf_counter() - t_host) * 1e3
+    dev_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(host_ms, dev_ms) / args.steps
+    ctx.excp_set_profiling(False)
+
+    n_w = sum(s.n_w for s in stats)
+    n_o = sum(s.n_o for s in stats)
+    blob_bytes = sum(s.blob_bytes for s in stats)
+    p_w, p_o = n_w / N, n_o / N
+    params_per_s = N / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel ----------------------------------------------------------
+    per_param = stage_bytes_per_param(p_w, p_o, nbits, iters)
+    stage_report = {}
+    for k, (ms, launches) in stage_tot.items():
+        if launches == 0:
+            continue
+        e = {"ms_per_step": ms / args.steps, "launches_per_step": launches / args.steps}
+        if k in per_param:
+            e["algorithmic_GB_per_step"] = per_param[k] * N / 1e9
+            e["achieved_GBs"] = per_param[k] * N / 1e9 / (ms / args.steps * 1e-3)
+        stage_report[k] = e
+    dominant = max((k for k in stage_report if k in per_param), key=lambda k: stage_report[k]["ms_per_step"])
+    d = stage_report[dominant]
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": d["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": d["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_ms": d["ms_per_step"] / d["launches_per_step"],
+                "algorithmic_bytes_per_param": per_param[dominant]}
+    step_bytes = survey_step_bytes_per_param(p_w, p_o) * N
+    step_frac = step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
+
+    # ---- decompress (Alg. 2) timing, reported beside the headline --------------------------------
+    dec = [(flat[0][offs[i]:offs[i] + spec.n], tensors[i][4], int(stats[i].blob_bytes), spec.n,
+            flat[4][offs[i]:offs[i] + spec.n], None, None)
+           for i, spec in enumerate(cfg.tensors)]
+    ctx.excp_decompress_tensors(dec); ctx.excp_collect()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(max(1, args.steps)):
+        ctx.excp_decompress_tensors(dec)
+        ctx.excp_collect()
+    torch.cuda.synchronize()
+    dec_ms = (time.perf_counter() - t1) * 1e3 / max(1, args.steps)
+
+    # ---- CPU oracle on a bounded sample of the same workload -----------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle as O
+        budget_elems = 6_000_000
+        pick = min(range(len(cfg.tensors)), key=lambda i: (abs(cfg.tensors[i].n - budget_elems), i))
+        a, b = offs[pick], offs[pick] + min(cfg.tensors[pick].n, 3 * budget_elems)
+        host = [f[a:b].cpu().numpy() for f in flat[:4]]
+        t2 = time.perf_counter()
+        ref = O.compress_step(*host, alpha, beta, nbits, iters)
+        cpu_s = time.perf_counter() - t2
+        cpu = {"value": (b - a) / cpu_s, "unit": "params/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {b - a} elements of tensor {pick} ({cfg.tensors[pick].name}) of the same "
+                         f"checkpoint, {cpu_s:.1f} s; numpy, single thread; host has {os.cpu_count()} cores",
+               "keep_fractions": [ref.n_w / (b - a), ref.n_o / (b - a)]}
+
+    out = {
+        "metric": "checkpoint params compressed/sec and % of HBM roofline, 7B-shaped step",
+        "value": params_per_s, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {cid}: {cfg.name}-shaped checkpoint, {len(cfg.tensors)} tensors, {N} fp32 "
+                               f"params x (W_prev, W, m, v) resident in HBM; alpha={alpha}, beta={beta}, nbits={nbits}, "
+                               f"{iters} Lloyd iterations; W_hat emitted",
+                   "params": N, "tensors": len(cfg.tensors), "group_elems": group},
+        "state_GBs": 16.0 * N / (ms_per_step * 1e-3) / 1e9,
+        "hbm_roofline_pct_step": 100.0 * step_frac,
+        "step_algorithmic_bytes_per_param": survey_step_bytes_per_param(p_w, p_o),
+        "keep_fractions": {"p_w": p_w, "p_o": p_o},
+        "compression_ratio": 12.0 * N / blob_bytes,
+        "decompress_ms": dec_ms, "decompress_params_per_s": N / (dec_ms * 1e-3),
+        "workspace_GB": ctx.workspace_bytes / 1e9,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "stages": stage_report,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -144,13 +144,13 @@ def torch_draw_tensor(cid: int, idx: int, spec: TensorSpec, device, step: int = 
     dist, scale = noise_recipe(cid, idx, spec)
     u = torch.empty(n, dtype=torch.float32, device=device).uniform_(-0.5, 0.5, generator=g)
     if dist == "laplace":
-        noise = -scale * torch.sign(u) * torch.log1p(-2.0 * u.abs())
+        noise = -scale * torch.sign(u) * torch.log1p(-2.0 * u.abs().clamp_(max=0.49999997))
     else:   # Student-t(3) = N / sqrt(chi2_3 / 3)
         z = torch.empty(n, dtype=torch.float32, device=device).normal_(generator=g)
         chi = torch.zeros(n, dtype=torch.float32, device=device)
         for _ in range(3):
             chi += torch.empty(n, dtype=torch.float32, device=device).normal_(generator=g) ** 2
-        noise = scale * z / torch.sqrt(chi / 3.0)
+        noise = scale * z / torch.sqrt(chi.clamp_(min=1e-12) / 3.0)
         del z, chi
     W = Wp + noise
     del noise, u
