@@ -52,11 +52,7 @@ struct TState {
 struct SegState {
     u64 len;
     u32 chunk_begin;            // first chunk of this stream in the group's chunk list
-    u32 nslots;                 // distinct key prefixes still alive in the multi-rank select
-    u32 prefix[EXCP_MAX_K];     // per rank k: key prefix found so far
-    u32 rank[EXCP_MAX_K];       // per rank k: rank still to find inside that prefix
-    u32 slot_of_rank[EXCP_MAX_K];
-    u32 slot_prefix[EXCP_MAX_K];// sorted distinct prefixes
+    u32 pad;
     float C[EXCP_MAX_K + 1];    // current centres (K used)
 };
 
@@ -110,12 +106,13 @@ struct Workspace {
     // survivor passes
     u32 *chunk_total;         // [1]
     u32 *seg_chunk_begin;     // [segments + 1] first chunk of every survivor stream
-    u32 *hist1;               // [segment][4096]
-    u32 *bin2slot;            // [segment][4096] bytes packed as u8
-    u32 *hist2;               // [segment][slots][1024]  (slots = min(K,15) unless large-K storage exists)
-    u64 hist2_slots;          // slot capacity per segment of hist2
-    double *part_sum;         // [chunk][K]
-    u32 *part_cnt;            // [chunk][K]
+    float *pw, *pm, *pv;      // survivors partitioned into value-ordered buckets (same offsets as xw/xm/xv)
+    u32 *km_split;            // [segment][256] bucket splitter keys (entry 255 = 0xffffffff)
+    u32 *km_cnt;              // [chunk][256] bucket counts, then positions, of every chunk
+    u32 *km_begin;            // [segment][257] first position of every bucket
+    u64 *km_bsum;             // [segment][256][EXCP_ABSM_BINS] exact signed sum of every bucket
+    u32 *km_min, *km_max;     // [segment][256] smallest / largest key of every bucket
+    u64 *km_acc;              // [segment][EXCP_MAX_K][EXCP_ABSM_BINS + 1] per-centre exact sum and count
     double *part_obj;         // [chunk]
     u32 max_chunks;
     // decode
@@ -134,10 +131,10 @@ void launch_stats_hist(const Workspace &w, const GroupParams &g, int pass, hipSt
 void launch_median_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
 void launch_mask_compact(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
-void launch_init_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
-void launch_init_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
-void launch_lloyd_accum(const Workspace &w, const GroupParams &g, hipStream_t s);
-void launch_lloyd_update(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
+void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s);

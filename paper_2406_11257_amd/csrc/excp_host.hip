@@ -17,13 +17,14 @@ constexpr u32 kMaxGroupTensors = 1024;   // tensors processed together
 constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress call
 
 enum Stage {
-    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_LAYOUT, ST_INIT_HIST, ST_INIT_RESOLVE,
-    ST_LLOYD_ACCUM, ST_LLOYD_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE, ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC,
-    ST_COUNT
+    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
+    ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
+    ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC, ST_COUNT
 };
 const char *kStageNames[ST_COUNT] = {
-    "stats_hist", "select_hist", "select_resolve", "mask_compact", "layout", "init_hist", "init_resolve",
-    "lloyd_accum", "lloyd_update", "assign_pack", "finalize", "decode_prep", "decode_main", "misc"};
+    "stats_hist", "select_hist", "select_resolve", "mask_compact", "layout", "km_sample", "km_count", "km_scan",
+    "km_scatter", "km_bucket_stats", "km_init", "km_iter", "km_update", "assign_pack", "finalize",
+    "decode_prep", "decode_main", "misc"};
 
 struct Span { int stage; hipEvent_t a, b; };
 
@@ -40,7 +41,7 @@ struct excp_ctx {
     u32 *tile_begin_all = nullptr;
     TDesc *h_desc = nullptr; DDesc *h_ddesc = nullptr; u32 *h_tile_begin = nullptr; HostRec *h_rec = nullptr;
     int *h_err = nullptr;
-    u64 hist2_bytes = 0, part_entries = 0, status_words = 0;
+    u64 status_words = 0;
     u64 ws_bytes = 0;
     std::vector<void *> allocs;
     // pending batch
@@ -181,9 +182,6 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     const u64 G = max_group_elems;
     const u64 max_tiles = G / EXCP_TILE + kMaxGroupTensors + 1;
     const u64 chunks_group = 3 * (G / EXCP_CHUNK) + 3 * kMaxGroupTensors + 3;
-    const u64 chunks_tensor = 3 * (max_tensor_elems / EXCP_CHUNK) + 3 * kMaxGroupTensors + 6;
-    c->part_entries = chunks_group * 15 > chunks_tensor * 255 ? chunks_group * 15 : chunks_tensor * 255;
-    c->hist2_bytes = 3ull * kMaxGroupTensors * 15 * 1024 * 4;
     c->status_words = max_tiles;
     bool ok = true;
     ok = ok && dev_alloc(c, &c->desc_all, kMaxBatchTensors);
@@ -199,11 +197,18 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.tile_status, max_tiles);
     ok = ok && dev_alloc(c, &w.chunk_total, 4);
     ok = ok && dev_alloc(c, &w.seg_chunk_begin, 3ull * kMaxGroupTensors + 4);
-    ok = ok && dev_alloc(c, &w.hist1, 3ull * kMaxGroupTensors * 4096);
-    ok = ok && dev_alloc(c, &w.bin2slot, 3ull * kMaxGroupTensors * 1024);
-    ok = ok && dev_alloc(c, (unsigned char **)&w.hist2, c->hist2_bytes);
-    ok = ok && dev_alloc(c, &w.part_sum, c->part_entries);
-    ok = ok && dev_alloc(c, &w.part_cnt, c->part_entries);
+    const u64 nseg_max = 3ull * kMaxGroupTensors;
+    const u64 acc_words = nseg_max * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
+    ok = ok && dev_alloc(c, &w.pw, G);
+    ok = ok && dev_alloc(c, &w.pm, G);
+    ok = ok && dev_alloc(c, &w.pv, G);
+    ok = ok && dev_alloc(c, &w.km_split, nseg_max * 256);
+    ok = ok && dev_alloc(c, &w.km_cnt, chunks_group * 256);
+    ok = ok && dev_alloc(c, &w.km_begin, nseg_max * 257);
+    ok = ok && dev_alloc(c, &w.km_bsum, nseg_max * 256 * EXCP_ABSM_BINS);
+    ok = ok && dev_alloc(c, &w.km_min, nseg_max * 256);
+    ok = ok && dev_alloc(c, &w.km_max, nseg_max * 256);
+    ok = ok && dev_alloc(c, &w.km_acc, acc_words);
     ok = ok && dev_alloc(c, &w.part_obj, chunks_group);
     ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles);
     ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles);
@@ -225,8 +230,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     }
     if (ok) {
         launch_zero_u32(w.med_hist, (u64)kMaxGroupTensors * 2048, c->stream);
-        launch_zero_u32(w.hist1, 3ull * kMaxGroupTensors * 4096, c->stream);
-        launch_zero_u32(w.hist2, c->hist2_bytes / 4, c->stream);
+        launch_zero_u32((u32 *)w.km_acc, 2 * acc_words, c->stream);
         launch_zero_u32((u32 *)w.err_flag, 4, c->stream);
         ok = hipStreamSynchronize(c->stream) == hipSuccess;
     }
@@ -283,17 +287,8 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         if (t.blob_cap < EXCP_HEADER + 12ull * (1ull << nbits) + excp_pad16(8 * excp_words(t.n))) return EXCP_E_CAP;
     }
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
-    // group limits that depend on K: slot histograms and per-chunk partials
-    u64 cap_elems = c->max_group;
-    u32 tcap = kMaxGroupTensors;
-    {
-        u64 t_by_hist = c->hist2_bytes / (3ull * (u64)K * 4096ull);
-        if (t_by_hist < tcap) tcap = (u32)t_by_hist;
-        u64 chunks_ok = c->part_entries / (u64)K;                 // chunks whose partials fit
-        u64 elems_ok = chunks_ok > 3ull * tcap + 3 ? (chunks_ok - 3ull * tcap - 3) / 3 * EXCP_CHUNK : 0;
-        if (elems_ok < cap_elems) cap_elems = elems_ok;
-        if (cap_elems < c->max_tensor) cap_elems = c->max_tensor;   // a single tensor always fits by construction
-    }
+    const u64 cap_elems = c->max_group;
+    const u32 tcap = kMaxGroupTensors;
     std::vector<Group> groups;
     make_groups(count, cap_elems, tcap, [&](u32 i) { return (u64)tensors[i].n; }, groups);
 
@@ -332,7 +327,6 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         w.tile_begin = c->tile_begin_all + tb_offsets[gi];
         w.rec_base = 0;
         w.rec_dev = c->w.rec_dev + g.first;
-        w.hist2_slots = (u64)K;
         GroupParams p{};
         p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
         p.ntensors = g.count; p.ntiles = g.ntiles;
@@ -345,13 +339,15 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         }
         { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, s); }
         { StageTimer t(c, ST_LAYOUT); launch_layout(w, p, s); }
-        for (int pass = 1; pass <= 3; ++pass) {
-            { StageTimer t(c, ST_INIT_HIST); launch_init_hist(w, p, pass, s); }
-            { StageTimer t(c, ST_INIT_RESOLVE); launch_init_resolve(w, p, pass, s); }
-        }
+        { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
+        { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }
+        { StageTimer t(c, ST_KM_SCAN); launch_km_partition(w, p, 2, s); }
+        { StageTimer t(c, ST_KM_SCATTER); launch_km_partition(w, p, 3, s); }
+        { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }
+        { StageTimer t(c, ST_KM_INIT); launch_km_init(w, p, s); }
         for (int it = 0; it < lloyd_iters; ++it) {
-            { StageTimer t(c, ST_LLOYD_ACCUM); launch_lloyd_accum(w, p, s); }
-            { StageTimer t(c, ST_LLOYD_UPDATE); launch_lloyd_update(w, p, s); }
+            { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, s); }
+            { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
         }
         { StageTimer t(c, ST_ASSIGN_PACK); launch_assign_pack(w, p, s); }
         { StageTimer t(c, ST_FINALIZE); launch_finalize(w, p, s); }

@@ -126,12 +126,11 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 n
     }
 }
 
-__device__ __forceinline__ u32 read_code(const u64 *__restrict__ codes, u64 j, u32 nbits) {
-    const u64 bit = j * nbits;
-    const u64 wi = bit >> 6;
-    const u32 sh = (u32)(bit & 63ull);
-    u64 v = codes[wi] >> sh;
-    if (sh + nbits > 64u) v |= codes[wi + 1] << (64u - sh);
+// Code j of an nbits-wide little-endian bit stream.  Both words are always loaded (the second one
+// clamped to the last word) so that no load sits behind a data-dependent branch.
+__device__ __forceinline__ u32 extract_code(u64 w0, u64 w1, u32 sh, u32 nbits) {
+    u64 v = w0 >> sh;
+    if (sh) v |= w1 << (64u - sh);
     return (u32)(v & ((1ull << nbits) - 1ull));
 }
 
@@ -156,12 +155,17 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 n
         const u64 n = D.n;
         const u32 ltile = tile - D.tile_begin;
         const u64 base = (u64)ltile * EXCP_TILE;
+        const float *__restrict__ Wp = D.Wp;
         const u64 *__restrict__ bmw = (const u64 *)(D.blob + S.off_bw);
         const u64 *__restrict__ bmo = (const u64 *)(D.blob + S.off_bo);
         const u64 *__restrict__ cw = (const u64 *)(D.blob + S.off_cw);
         const u64 *__restrict__ cm = (const u64 *)(D.blob + S.off_cm);
         const u64 *__restrict__ cv = (const u64 *)(D.blob + S.off_cv);
         const u64 nwords = excp_words(n);
+        const u64 n_w = S.n_w, n_o = S.n_o;
+        const bool pow2 = (64u % nbits) == 0u;
+        const bool moments = (D.m_out != nullptr) || (D.v_out != nullptr);
+        const bool inplace = D.W_out == D.Wp;
 
         // survivors before each of the tile's 64 bitmap words
         const u64 wword = (u64)ltile * 64 + lane;
@@ -178,58 +182,93 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 n
         }
         const u32 excl = incl - pc;
         const u64 q_tile = w.dec_cnt_w[tile];          // survivors before this tile
-        const u64 o_tile = w.dec_cnt_o[tile];          // moment survivors before this tile
-        // bitmap_o words that cover this tile's survivors: word (q_tile >> 6) + lane, 65th in lane 0
-        const u64 ow0 = q_tile >> 6;
-        const u64 nw_words = excp_words(S.n_w);
-        u64 oword = (ow0 + lane < nw_words) ? bmo[ow0 + lane] : 0ull;
-        u64 oword64 = (ow0 + 64 < nw_words) ? bmo[ow0 + 64] : 0ull;
-        u64 oword_m = oword;
-        if (lane == 0) oword_m &= ~((1ull << (q_tile & 63ull)) - 1ull);   // bits before the tile's first survivor
-        u32 opc = __popcll(oword_m), oincl = opc;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            u32 v = __shfl_up(oincl, off, WAVE);
-            if (lane >= (u32)off) oincl += v;
-        }
-        const u32 oexcl = oincl - opc;
-        const u32 ototal = __shfl(oincl, 63, WAVE);
+        const u64 cw_last = n_w ? excp_words(n_w * nbits) - 1 : 0;
 
-#pragma unroll 4
-        for (int j = 0; j < 16; ++j) {
-            const u32 wi = wave * 16 + j;
-            const u64 idx = base + (u64)(wi * 64 + lane);
-            const u32 lo = __shfl((u32)myword, wi, WAVE), hi = __shfl((u32)(myword >> 32), wi, WAVE);
-            const u64 mw = ((u64)hi << 32) | lo;
-            const u32 wexcl = __shfl(excl, wi, WAVE);
-            const bool ok = idx < n;
-            const bool kw = ok && ((mw >> lane) & 1ull);
-            // survivor position (meaningful only where kw); every cross-lane read below is done by
-            // the whole wave, outside divergent code
-            const u64 q = q_tile + wexcl + __popcll(mw & lt_mask);
-            const u32 rel = (u32)((q >> 6) - ow0);                 // 0..64 where kw
-            const u32 src = rel & 63u;
-            const u32 olo = __shfl((u32)oword, src, WAVE), ohi = __shfl((u32)(oword >> 32), src, WAVE);
-            u32 opre = __shfl(oexcl, src, WAVE);
-            u64 ow = ((u64)ohi << 32) | olo;
-            if (rel == 64u) { ow = oword64; opre = ototal; }
-            const float wp = ok ? D.Wp[idx] : 0.f;
-            float outw = wp, outm = 0.f, outv = 0.f;
-            if (kw) {
-                outw = wp + s_book[read_code(cw, q, nbits)];
-                const u32 bitpos = (u32)(q & 63ull);
-                if ((ow >> bitpos) & 1ull) {
-                    u64 below = ow & ((1ull << bitpos) - 1ull);
-                    if (rel == 0u) below &= ~((1ull << (q_tile & 63ull)) - 1ull);
-                    const u64 qo = o_tile + opre + __popcll(below);
-                    outm = s_book[256u + read_code(cm, qo, nbits)];
-                    outv = s_book[512u + read_code(cv, qo, nbits)];
+        // moments: prefix popcounts of the bitmap_o words that cover this tile's survivors
+        const u64 o_tile = w.dec_cnt_o[tile];          // moment survivors before this tile
+        const u64 ow0 = q_tile >> 6;
+        const u64 nw_words = excp_words(n_w);
+        u64 oword = 0, oword64 = 0; u32 oexcl = 0, ototal = 0;
+        if (moments) {
+            oword = (ow0 + lane < nw_words) ? bmo[ow0 + lane] : 0ull;
+            oword64 = (ow0 + 64 < nw_words) ? bmo[ow0 + 64] : 0ull;
+            u64 oword_m = oword;
+            if (lane == 0) oword_m &= ~((1ull << (q_tile & 63ull)) - 1ull);   // bits before the tile's first survivor
+            u32 opc = __popcll(oword_m), oincl = opc;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                u32 v = __shfl_up(oincl, off, WAVE);
+                if (lane >= (u32)off) oincl += v;
+            }
+            oexcl = oincl - opc;
+            ototal = __shfl(oincl, 63, WAVE);
+        }
+        const u64 cm_last = n_o ? excp_words(n_o * nbits) - 1 : 0;
+
+        for (int half = 0; half < 2; ++half) {
+            // ---- weights: all loads of eight batches first, then the arithmetic ----------------
+            float wp[8]; u64 c0[8], c1[8]; u64 qq[8]; bool kwv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u32 wi = wave * 16 + half * 8 + j;
+                const u64 idx = base + (u64)(wi * 64 + lane);
+                const u32 lo = __shfl((u32)myword, wi, WAVE), hi = __shfl((u32)(myword >> 32), wi, WAVE);
+                const u64 mw = ((u64)hi << 32) | lo;
+                const u32 wexcl = __shfl(excl, wi, WAVE);
+                const bool ok = idx < n;
+                kwv[j] = ok && ((mw >> lane) & 1ull);
+                u64 q = q_tile + wexcl + __popcll(mw & lt_mask);   // survivor position where kept
+                if (q >= n_w) q = n_w ? n_w - 1 : 0;               // keeps every address in range
+                qq[j] = q;
+                wp[j] = Wp[ok ? idx : n - 1];
+                const u64 wi0 = (q * nbits) >> 6;
+                c0[j] = n_w ? cw[wi0] : 0ull;
+                c1[j] = (!pow2 && n_w) ? cw[wi0 < cw_last ? wi0 + 1 : cw_last] : 0ull;
+            }
+            if (D.W_out) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const u64 idx = base + (u64)((wave * 16 + half * 8 + j) * 64 + lane);
+                    const u32 code = extract_code(c0[j], c1[j], (u32)((qq[j] * nbits) & 63ull), nbits);
+                    const float outw = kwv[j] ? wp[j] + s_book[code] : wp[j];
+                    if (idx < n && (!inplace || kwv[j])) D.W_out[idx] = outw;
                 }
             }
-            if (ok) {
-                if (D.W_out && (D.W_out != D.Wp || kw)) D.W_out[idx] = outw;
-                if (D.m_out) D.m_out[idx] = outm;
-                if (D.v_out) D.v_out[idx] = outv;
+            if (!moments) continue;
+            // ---- moments: M_o bit and rank of every survivor -----------------------------------
+            bool kov[8]; u64 m0[8], m1[8], v0[8], v1[8]; u32 shv[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u64 q = qq[j];
+                const u32 rel = (u32)((q >> 6) - ow0);             // 0..64 where kept
+                const u32 src = rel & 63u;
+                const u32 olo = __shfl((u32)oword, src, WAVE), ohi = __shfl((u32)(oword >> 32), src, WAVE);
+                u32 opre = __shfl(oexcl, src, WAVE);
+                u64 ow = ((u64)ohi << 32) | olo;
+                if (rel >= 64u) { ow = oword64; opre = ototal; }
+                const u32 bitpos = (u32)(q & 63ull);
+                kov[j] = kwv[j] && ((ow >> bitpos) & 1ull);
+                u64 below = ow & ((1ull << bitpos) - 1ull);
+                if (rel == 0u) below &= ~((1ull << (q_tile & 63ull)) - 1ull);
+                u64 qo = o_tile + opre + __popcll(below);
+                if (qo >= n_o) qo = n_o ? n_o - 1 : 0;
+                const u64 wi0 = (qo * nbits) >> 6;
+                const u64 wi1 = wi0 < cm_last ? wi0 + 1 : cm_last;
+                shv[j] = (u32)((qo * nbits) & 63ull);
+                m0[j] = n_o ? cm[wi0] : 0ull;
+                v0[j] = n_o ? cv[wi0] : 0ull;
+                m1[j] = (!pow2 && n_o) ? cm[wi1] : 0ull;
+                v1[j] = (!pow2 && n_o) ? cv[wi1] : 0ull;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const u64 idx = base + (u64)((wave * 16 + half * 8 + j) * 64 + lane);
+                if (idx < n) {
+                    const float outm = kov[j] ? s_book[256u + extract_code(m0[j], m1[j], shv[j], nbits)] : 0.f;
+                    const float outv = kov[j] ? s_book[512u + extract_code(v0[j], v1[j], shv[j], nbits)] : 0.f;
+                    if (D.m_out) D.m_out[idx] = outm;
+                    if (D.v_out) D.v_out[idx] = outv;
+                }
             }
         }
     }

@@ -1,311 +1,530 @@
 // Non-uniform quantisation of the surviving values (Sec. 3.3): per stream, K = 2^nbits - 1
 // centres by Lloyd's algorithm, then codes = 1 + nearest centre packed nbits each (Sec. 4.2).
 //
-//   init      : the K order statistics of rank ((2k+1) len)/(2K), found exactly by a three-pass
-//               multi-rank radix select over order-preserving 32-bit keys (12 + 10 + 10 bits);
-//   iteration : every workgroup keeps the centres in LDS, accumulates per-centre (fp64 sum, count)
-//               for its chunk in lane-private LDS bins, reduces them in a fixed order and writes one
-//               partial per chunk; a second kernel adds the partials in chunk order and moves the
-//               centres.  Nothing is accumulated with floating-point atomics when K <= 15, so the
-//               result does not depend on scheduling;
-//   final     : nearest final centre, objective, bit packing into the blob's code sections.
+// One-dimensional Lloyd has structure that makes re-reading every value in every iteration
+// unnecessary: clusters are intervals, and the assignment is monotone in the value.  So each stream
+// is first PARTITIONED into 256 value-ordered buckets of roughly equal population (splitters from a
+// sorted sample), and for every bucket the exact count, exact sum, minimum and maximum are stored.
+// In an iteration a bucket whose minimum and maximum go to the same centre contributes its stored
+// totals; only the (at most K-1) buckets that a cluster border cuts are read element by element.
+// The same buckets give the initial centres (order statistics of rank ((2k+1) len)/(2K)) with a
+// radix select inside one bucket per rank.
 //
-// All survivor passes walk one chunk list (8192 values per chunk) that spans every stream of every
-// tensor of the group; its length is only known on the device.
+// All sums are exact: a value is mant * 2^(pos-149); mantissas are added as integers in windows of
+// 40 binary orders and filed into signed 64-bit bins 8 binary orders apart (the representation of
+// the exact sum of |m| in the statistics pass, here with sign).  A centre is therefore
+// fp32(round-once-fp64(exact sum) / count), independent of the order in which values were met, so
+// integer atomics may be used freely and the partition need not be stable.
+//
+// The survivor passes walk one chunk list (8192 values per chunk) spanning every stream of every
+// tensor of the group; its length is known only on the device.
 #include "excp_util.h"
 
 namespace {
+
+constexpr u32 NBKT = 256;
+constexpr u32 SAMPLE = 4096;
+constexpr u32 PER_THREAD = EXCP_CHUNK / EXCP_THREADS;   // 32
 
 __device__ __forceinline__ const float *seg_data(const Workspace &w, u32 sidx) {
     const u32 t = sidx / 3u, which = sidx % 3u;
     const float *basep = which == 0 ? w.xw : (which == 1 ? w.xm : w.xv);
     return basep + w.desc[t].elem_off;
 }
+__device__ __forceinline__ float *seg_part(const Workspace &w, u32 sidx) {
+    const u32 t = sidx / 3u, which = sidx % 3u;
+    float *basep = which == 0 ? w.pw : (which == 1 ? w.pm : w.pv);
+    return basep + w.desc[t].elem_off;
+}
 
-// ------------------------------------------------------------------ multi-rank select, histograms
-// PASS 1: 4096-bin histogram of key >> 20 per stream (LDS, flushed when the stream changes).
-// PASS 2: for keys whose top 12 bits are a live prefix: 1024-bin histogram of bits 19..10 per slot.
-// PASS 3: for keys whose top 22 bits are a live prefix: 1024-bin histogram of bits 9..0 per slot.
-template <int PASS, bool LDS_SLOTS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_init_hist(Workspace w, GroupParams g) {
-    extern __shared__ u32 smem[];
-    // PASS 1: smem = hist[4096]
-    // PASS 2: smem = bin2slot bytes [4096] (as 1024 u32) followed by hist[slots][1024] when LDS_SLOTS
-    // PASS 3: smem = slot_prefix[256]
+// number of splitters (split[0..254]) that are <= key: the bucket of key, 0..255
+__device__ __forceinline__ u32 bucket_of(const u32 *split, u32 key) {
+    u32 lo = 0;
+#pragma unroll
+    for (u32 step = 128; step >= 1; step >>= 1) {
+        u32 probe = lo + step - 1;                 // <= 254
+        if (split[probe] <= key) lo += step;
+    }
+    return lo < 255u ? lo : 255u;
+}
+
+// ---------------------------------------------------------------- exact signed accumulation
+// Adds the values x[j] (j < N) with sel[j] set, for the whole wave, to a set of signed bins through
+// add(bin, delta): sum_g bins[g] * 2^(8g-149) grows by exactly the sum of the selected values.
+template <int N, class Add>
+__device__ __forceinline__ void wave_exact_add(const float (&x)[N], const bool (&sel)[N], Add add) {
+    const u32 lane = lane_id();
+    u32 pmax = 0, any = 0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        u32 mb = f2u(x[j]) & 0x7fffffffu;
+        u32 e = mb >> 23;
+        u32 pos = (e ? e : 1u) - 1u;
+        if (sel[j] && mb) { pmax = max(pmax, pos); any = 1; }
+    }
+    if (!__any(any)) return;
+    pmax = wave_max_u32(pmax);
+    const u32 B = pmax > 39u ? pmax - 39u : 0u;
+    u64 pL = 0, pH = 0, nL = 0, nH = 0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        u32 u = f2u(x[j]);
+        u32 mb = u & 0x7fffffffu;
+        u32 e = mb >> 23;
+        u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+        u32 pos = (e ? e : 1u) - 1u;
+        if (sel[j] && mant) {
+            const bool neg = u >> 31;
+            if (pos >= B) {
+                u64 term = (u64)mant << (pos - B);
+                if (neg) { nL += term & 0xffffffffull; nH += term >> 32; }
+                else { pL += term & 0xffffffffull; pH += term >> 32; }
+            } else {
+                u64 d = (u64)mant << (pos & 7u);
+                add(pos >> 3, neg ? (u64)0 - d : d);
+            }
+        }
+    }
+#pragma unroll
+    for (int sgn = 0; sgn < 2; ++sgn) {
+        u64 aL = sgn ? nL : pL, aH = sgn ? nH : pH;
+        if (!__any(aL != 0 || aH != 0)) continue;
+        aL = wave_sum_u64(aL);
+        aH = wave_sum_u64(aH);
+        if (lane == 0) {
+            u64 lo64 = aL + (aH << 32);
+            u64 hi64 = (aH >> 32) + (lo64 < aL ? 1ull : 0ull);
+            u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                u32 p = B + 32u * q;
+                if (piece[q]) { u64 d = piece[q] << (p & 7u); add(p >> 3, sgn ? (u64)0 - d : d); }
+            }
+        }
+    }
+}
+
+// Signed bins -> the exact sum rounded once (to nearest, ties to even) to fp64.
+__device__ double signed_bins_to_double(const u64 *bins) {
+    u32 limb[14];
+    for (int i = 0; i < 14; ++i) limb[i] = 0;
+    for (int g = 0; g < EXCP_ABSM_BINS; ++g) {
+        long long c = (long long)bins[g];
+        if (!c) continue;
+        // sign-extended 64-bit value shifted left by 8g, added into a 448-bit two's complement number
+        u32 bit = 8u * g, li = bit >> 5, sh = bit & 31u;
+        u32 ext = c < 0 ? 0xffffffffu : 0u;
+        u64 uc = (u64)c;
+        u64 carry = 0;
+        for (u32 q = 0; li + q < 14; ++q) {
+            // 32-bit slice q of (sign-extended c) << sh
+            u32 lo_part, hi_part;
+            auto word = [&](int idx) -> u32 { return idx < 0 ? 0u : (idx == 0 ? (u32)uc : (idx == 1 ? (u32)(uc >> 32) : ext)); };
+            lo_part = word((int)q);
+            hi_part = word((int)q - 1);
+            u32 slice = sh ? ((lo_part << sh) | (hi_part >> (32 - sh))) : lo_part;
+            u64 s = (u64)limb[li + q] + slice + carry;
+            limb[li + q] = (u32)s;
+            carry = s >> 32;
+        }
+    }
+    const bool neg = limb[13] >> 31;
+    if (neg) {                                  // magnitude = two's complement negation
+        u64 carry = 1;
+        for (int i = 0; i < 14; ++i) { u64 s = (u64)(~limb[i]) + carry; limb[i] = (u32)s; carry = s >> 32; }
+    }
+    int top = -1;
+    for (int i = 13; i >= 0; --i) if (limb[i]) { top = i; break; }
+    if (top < 0) return 0.0;
+    int msb = 32 * top + (31 - __clz((int)limb[top]));
+    auto bit_at = [&](int p) -> u32 { return p < 0 ? 0u : (limb[p >> 5] >> (p & 31)) & 1u; };
+    double mag;
+    if (msb <= 52) {
+        u64 x = (u64)limb[0] | ((u64)limb[1] << 32);
+        mag = ldexp((double)x, -149);
+    } else {
+        u64 mant = 0;
+        for (int p = msb; p >= msb - 52; --p) mant = (mant << 1) | bit_at(p);
+        u32 guard = bit_at(msb - 53), sticky = 0;
+        for (int p = msb - 54; p >= 0 && !sticky; --p) sticky |= bit_at(p);
+        if (guard && (sticky || (mant & 1ull))) mant += 1;
+        mag = ldexp((double)mant, msb - 52 - 149);
+    }
+    return neg ? -mag : mag;
+}
+
+// ---------------------------------------------------------------- P0: splitters from a sorted sample
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupParams g) {
+    __shared__ u32 key[SAMPLE];
+    const u32 sidx = blockIdx.x, tid = threadIdx.x;
+    const u64 len = w.seg[sidx].len;
+    if (len == 0) return;
+    const float *__restrict__ x = seg_data(w, sidx);
+    const u32 ns = len < SAMPLE ? (u32)len : SAMPLE;
+    for (u32 i = tid; i < SAMPLE; i += EXCP_THREADS)
+        key[i] = (i < ns) ? key_of(x[((u64)i * len) / ns]) : 0xffffffffu;
+    __syncthreads();
+    for (u32 k = 2; k <= SAMPLE; k <<= 1) {
+        for (u32 j = k >> 1; j > 0; j >>= 1) {
+            for (u32 t = tid; t < SAMPLE / 2; t += EXCP_THREADS) {
+                u32 i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                u32 p = i | j;
+                u32 a = key[i], b = key[p];
+                bool asc = (i & k) == 0;
+                if ((a > b) == asc) { key[i] = b; key[p] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    u32 *split = w.km_split + (u64)sidx * NBKT;
+    for (u32 b = tid; b < NBKT; b += EXCP_THREADS) {
+        u32 idx = (u32)(((u64)(b + 1) * ns) / NBKT);
+        if (idx >= ns) idx = ns - 1;
+        split[b] = (b == NBKT - 1) ? 0xffffffffu : key[idx];
+    }
+}
+
+// ---------------------------------------------------------------- P1: per-chunk bucket counts
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_count(Workspace w, GroupParams g) {
+    __shared__ u32 split[NBKT];
+    __shared__ u32 hist[NBKT];
     const u32 tid = threadIdx.x;
     const u32 total = *w.chunk_total;
     const u32 G = gridDim.x, b = blockIdx.x;
     const u32 lo = (u32)(((u64)b * total) / G), hi = (u32)(((u64)(b + 1) * total) / G);
     if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
-    const u32 K = (u32)g.K;
-    const u32 lds_slots = K < 15u ? K : 15u;
-
-    u32 sidx = find_owner(w.seg_chunk_begin, nseg, lo);
-    u32 s_end = w.seg_chunk_begin[sidx + 1];
-
-    auto enter = [&](u32 sg) {
-        if (PASS == 1) {
-            for (u32 i = tid; i < 4096u; i += EXCP_THREADS) smem[i] = 0;
-        } else if (PASS == 2) {
-            const u32 *src = w.bin2slot + (u64)sg * 1024u;
-            for (u32 i = tid; i < 1024u; i += EXCP_THREADS) smem[i] = src[i];
-            if (LDS_SLOTS) for (u32 i = tid; i < lds_slots * 1024u; i += EXCP_THREADS) smem[1024u + i] = 0;
-        } else {
-            const SegState &S = w.seg[sg];
-            for (u32 i = tid; i < 256u; i += EXCP_THREADS) smem[i] = (i < S.nslots) ? S.slot_prefix[i] : 0xffffffffu;
-        }
-        __syncthreads();
-    };
-    auto leave = [&](u32 sg) {
-        __syncthreads();
-        if (PASS == 1) {
-            u32 *dst = w.hist1 + (u64)sg * 4096u;
-            for (u32 i = tid; i < 4096u; i += EXCP_THREADS) { u32 c = smem[i]; if (c) atomicAdd(&dst[i], c); }
-        } else if (PASS == 2 && LDS_SLOTS) {
-            u32 *dst = w.hist2 + (u64)sg * w.hist2_slots * 1024u;
-            const u32 ns = w.seg[sg].nslots;
-            for (u32 i = tid; i < ns * 1024u; i += EXCP_THREADS) { u32 c = smem[1024u + i]; if (c) atomicAdd(&dst[i], c); }
-        }
-        __syncthreads();
-    };
-
-    enter(sidx);
-    for (u32 c = lo; c < hi; ++c) {
-        if (c >= s_end) {
-            leave(sidx);
-            sidx = find_owner(w.seg_chunk_begin, nseg, c);
-            s_end = w.seg_chunk_begin[sidx + 1];
-            enter(sidx);
-        }
-        const SegState &S = w.seg[sidx];
-        const float *__restrict__ x = seg_data(w, sidx);
-        const u64 len = S.len;
-        const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
-        const u32 nslots = S.nslots;
-        u32 *gh = w.hist2 + (u64)sidx * w.hist2_slots * 1024u;
-        const unsigned char *b2s = (const unsigned char *)smem;
-#pragma unroll 4
-        for (u32 it = 0; it < EXCP_CHUNK / EXCP_THREADS; ++it) {
-            u64 idx = base + (u64)it * EXCP_THREADS + tid;
-            if (idx < len) {
-                u32 k = key_of(x[idx]);
-                if (PASS == 1) {
-                    atomicAdd(&smem[k >> 20], 1u);
-                } else if (PASS == 2) {
-                    u32 slot = b2s[k >> 20];
-                    if (slot != 0xffu) {
-                        u32 bin = (k >> 10) & 1023u;
-                        if (LDS_SLOTS) atomicAdd(&smem[1024u + slot * 1024u + bin], 1u);
-                        else atomicAdd(&gh[(u64)slot * 1024u + bin], 1u);
-                    }
-                } else {
-                    u32 p = k >> 10;
-                    u32 l = 0, h = nslots;            // lower bound of p among the sorted live prefixes
-                    while (l < h) { u32 mid = (l + h) >> 1; if (smem[mid] < p) l = mid + 1; else h = mid; }
-                    if (l < nslots && smem[l] == p) atomicAdd(&gh[(u64)l * 1024u + (k & 1023u)], 1u);
-                }
-            }
-        }
-    }
-    leave(sidx);
-}
-
-// ------------------------------------------------------------------ multi-rank select, resolve
-// One workgroup per stream.  After pass 1 the wanted ranks are placed in the 4096-bin histogram;
-// after passes 2 and 3 each rank descends inside the 1024-bin histogram of its slot.  Live prefixes
-// are kept sorted and distinct ("slots").
-template <int PASS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_init_resolve(Workspace w, GroupParams g) {
-    __shared__ u32 s_sum[EXCP_THREADS];
-    __shared__ u32 s_prefix[EXCP_MAX_K + 1];
-    const u32 sidx = blockIdx.x, tid = threadIdx.x;
-    SegState &S = w.seg[sidx];
-    const u64 len = S.len;
-    const u32 K = (u32)g.K;
-    if (len == 0) {
-        if (PASS == 3) for (u32 k = tid; k < K; k += EXCP_THREADS) S.C[k] = 0.f;
-        if (PASS == 1 && tid == 0) S.nslots = 0;
-        return;
-    }
-    if (PASS == 1) {
-        u32 *H = w.hist1 + (u64)sidx * 4096u;
-        u32 c[16], local = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { c[i] = H[tid * 16 + i]; local += c[i]; H[tid * 16 + i] = 0; }
-        s_sum[tid] = local;
-        __syncthreads();
-        for (int off = 1; off < EXCP_THREADS; off <<= 1) {
-            u32 v = (tid >= (u32)off) ? s_sum[tid - off] : 0u;
-            __syncthreads();
-            s_sum[tid] += v;
-            __syncthreads();
-        }
-        // every rank k finds the thread whose bins contain it
-        for (u32 k = 0; k < K; ++k) {
-            u32 r = (u32)(((u64)(2 * k + 1) * len) / (2ull * K));
-            u32 before = s_sum[tid] - local;
-            if (r >= before && r < before + local) {
-                u32 rr = r - before;
-                int i = 0;
-                while (rr >= c[i]) { rr -= c[i]; ++i; }
-                S.prefix[k] = tid * 16 + i;
-                S.rank[k] = rr;
-                s_prefix[k] = tid * 16 + i;
-            }
-        }
-    } else {
-        const u32 *H = w.hist2 + (u64)sidx * w.hist2_slots * 1024u;
-        for (u32 k = tid; k < K; k += EXCP_THREADS) {
-            const u32 *h = H + (u64)S.slot_of_rank[k] * 1024u;
-            u32 r = S.rank[k], bin = 0;
-            while (bin < 1023u) { u32 cnt = h[bin]; if (r < cnt) break; r -= cnt; ++bin; }
-            u32 np = (S.prefix[k] << 10) | bin;
-            S.prefix[k] = np;
-            S.rank[k] = r;
-            s_prefix[k] = np;
-            if (PASS == 3) S.C[k] = val_of(np);
-        }
-    }
-    __syncthreads();
-    if (PASS != 3 && tid == 0) {
-        // ranks ascend, so prefixes are non-decreasing: distinct ones in order are the slots
-        u32 ns = 0;
-        for (u32 k = 0; k < K; ++k) {
-            if (k == 0 || s_prefix[k] != s_prefix[k - 1]) { S.slot_prefix[ns] = s_prefix[k]; ++ns; }
-            S.slot_of_rank[k] = ns - 1;
-        }
-        S.nslots = ns;
-    }
-    __syncthreads();
-    if (PASS == 1) {
-        // byte table: top-12-bit bin -> slot (0xff = not wanted)
-        u32 *tab = w.bin2slot + (u64)sidx * 1024u;
-        const u32 ns = S.nslots;
-        for (u32 i = tid; i < 1024u; i += EXCP_THREADS) {
-            u32 packed = 0;
-            for (u32 q = 0; q < 4; ++q) {
-                u32 bin = i * 4 + q, slot = 0xffu;
-                u32 l = 0, h = ns;
-                while (l < h) { u32 mid = (l + h) >> 1; if (S.slot_prefix[mid] < bin) l = mid + 1; else h = mid; }
-                if (l < ns && S.slot_prefix[l] == bin) slot = l;
-                packed |= slot << (8 * q);
-            }
-            tab[i] = packed;
-        }
-    }
-    if (PASS == 2 || PASS == 3) {
-        // clear the slot histograms this stream used (ready for the next pass / next batch)
-        u32 *H = w.hist2 + (u64)sidx * w.hist2_slots * 1024u;
-        const u32 used = (PASS == 2) ? w.seg[sidx].nslots : K;   // upper bound of slots written
-        u32 lim = used > w.hist2_slots ? (u32)w.hist2_slots : used;
-        for (u32 i = tid; i < lim * 1024u; i += EXCP_THREADS) H[i] = 0;
-    }
-}
-
-// ------------------------------------------------------------------ Lloyd accumulation
-// K <= 15: bins are private to a lane ([k][tid] layout, conflict free).  K > 15: bins are shared by
-// the workgroup and filled with LDS atomics.
-template <bool SMALLK>
-__global__ __launch_bounds__(EXCP_THREADS) void k_lloyd_accum(Workspace w, GroupParams g) {
-    extern __shared__ unsigned char smraw[];
-    __shared__ float s_C[EXCP_MAX_K + 1];
-    const u32 tid = threadIdx.x, lane = tid & 63u;
-    const u32 total = *w.chunk_total;
-    const u32 G = gridDim.x, b = blockIdx.x;
-    const u32 lo = (u32)(((u64)b * total) / G), hi = (u32)(((u64)(b + 1) * total) / G);
-    if (lo >= hi) return;
-    const u32 nseg = 3u * g.ntensors;
-    const int K = g.K;
-    double *bsum = (double *)smraw;                                   // SMALLK: [16][256]; else [256]
-    u32 *bcnt = (u32 *)(smraw + (SMALLK ? 16 * EXCP_THREADS * 8 : 256 * 8));
-
     u32 sidx = 0xffffffffu, s_end = 0;
     for (u32 c = lo; c < hi; ++c) {
         if (sidx == 0xffffffffu || c >= s_end) {
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
-            for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = w.seg[sidx].C[k];
-            __syncthreads();
+            split[tid] = w.km_split[(u64)sidx * NBKT + tid];
         }
+        hist[tid] = 0;
+        __syncthreads();
         const SegState &S = w.seg[sidx];
         const float *__restrict__ x = seg_data(w, sidx);
         const u64 len = S.len;
         const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
-        if (SMALLK) {
+#pragma unroll 8
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u64 idx = base + (u64)it * EXCP_THREADS + tid;
+            if (idx < len) atomicAdd(&hist[bucket_of(split, key_of(x[idx]))], 1u);
+        }
+        __syncthreads();
+        w.km_cnt[(u64)c * NBKT + tid] = hist[tid];
+        __syncthreads();
+    }
+}
+
+// ---------------------------------------------------------------- P2: offsets of every (chunk, bucket)
+// 1024 threads: thread (q, b) owns bucket b over one quarter of the stream's chunks.
+__global__ __launch_bounds__(1024) void k_km_scan(Workspace w, GroupParams g) {
+    __shared__ u32 tot[4][NBKT];
+    __shared__ u32 begin[NBKT + 1];
+    const u32 sidx = blockIdx.x, tid = threadIdx.x, q = tid >> 8, b = tid & 255u;
+    const u64 len = w.seg[sidx].len;
+    if (len == 0) return;
+    const u32 c0 = w.seg[sidx].chunk_begin, c1 = w.seg_chunk_begin[sidx + 1];
+    const u32 nq = (c1 - c0 + 3) / 4;
+    const u32 a0 = min(c0 + q * nq, c1), a1 = min(a0 + nq, c1);
+    u32 *cnt = w.km_cnt;
+    u32 s = 0;
+#pragma unroll 8
+    for (u32 c = a0; c < a1; ++c) s += cnt[(u64)c * NBKT + b];
+    tot[q][b] = s;
+    __syncthreads();
+    if (q == 0) begin[b + 1] = tot[0][b] + tot[1][b] + tot[2][b] + tot[3][b];
+    if (tid == 0) begin[0] = 0;
+    __syncthreads();
+    // inclusive scan of begin[1..256] by the first 256 threads
+    for (u32 off = 1; off < NBKT; off <<= 1) {
+        u32 v = 0;
+        if (q == 0 && b >= off) v = begin[b + 1 - off];
+        __syncthreads();
+        if (q == 0) begin[b + 1] += v;
+        __syncthreads();
+    }
+    if (q == 0) {
+        w.km_begin[(u64)sidx * (NBKT + 1) + b + 1] = begin[b + 1];
+        if (b == 0) w.km_begin[(u64)sidx * (NBKT + 1)] = 0;
+    }
+    u32 run = begin[b];
+    for (u32 qq = 0; qq < q; ++qq) run += tot[qq][b];
+#pragma unroll 4
+    for (u32 c = a0; c < a1; ++c) {
+        u32 v = cnt[(u64)c * NBKT + b];
+        cnt[(u64)c * NBKT + b] = run;
+        run += v;
+    }
+}
+
+// ---------------------------------------------------------------- P3: scatter into buckets
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupParams g) {
+    __shared__ u32 split[NBKT];
+    __shared__ u32 hist[NBKT], loff[NBKT], goff[NBKT], fill[NBKT];
+    __shared__ float sval[EXCP_CHUNK];
+    __shared__ unsigned char sbkt[EXCP_CHUNK];
+    const u32 tid = threadIdx.x;
+    const u32 total = *w.chunk_total;
+    const u32 G = gridDim.x, bid = blockIdx.x;
+    const u32 lo = (u32)(((u64)bid * total) / G), hi = (u32)(((u64)(bid + 1) * total) / G);
+    if (lo >= hi) return;
+    const u32 nseg = 3u * g.ntensors;
+    u32 sidx = 0xffffffffu, s_end = 0;
+    for (u32 c = lo; c < hi; ++c) {
+        if (sidx == 0xffffffffu || c >= s_end) {
+            __syncthreads();
+            sidx = find_owner(w.seg_chunk_begin, nseg, c);
+            s_end = w.seg_chunk_begin[sidx + 1];
+            split[tid] = w.km_split[(u64)sidx * NBKT + tid];
+        }
+        hist[tid] = 0; fill[tid] = 0;
+        goff[tid] = w.km_cnt[(u64)c * NBKT + tid];
+        __syncthreads();
+        const SegState &S = w.seg[sidx];
+        const float *__restrict__ x = seg_data(w, sidx);
+        float *__restrict__ part = seg_part(w, sidx);
+        const u64 len = S.len;
+        const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
+        float v[PER_THREAD];
+        unsigned char bk[PER_THREAD];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) { bsum[k * EXCP_THREADS + tid] = 0.0; bcnt[k * EXCP_THREADS + tid] = 0; }
-        } else {
-            if (tid < 256) { bsum[tid] = 0.0; bcnt[tid] = 0; }
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u32 e = it * EXCP_THREADS + tid;
+            v[it] = (e < clen) ? x[base + e] : 0.f;
+        }
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u32 e = it * EXCP_THREADS + tid;
+            u32 bb = bucket_of(split, key_of(v[it]));
+            bk[it] = (unsigned char)bb;
+            if (e < clen) atomicAdd(&hist[bb], 1u);
+        }
+        __syncthreads();
+        // exclusive scan of the 256 bucket counts
+        {
+            u32 mine = hist[tid];
+            loff[tid] = mine;
+            __syncthreads();
+            for (u32 off = 1; off < NBKT; off <<= 1) {
+                u32 a = (tid >= off) ? loff[tid - off] : 0u;
+                __syncthreads();
+                loff[tid] += a;
+                __syncthreads();
+            }
+            u32 incl = loff[tid];
+            __syncthreads();
+            loff[tid] = incl - mine;
             __syncthreads();
         }
-#pragma unroll 4
-        for (u32 it = 0; it < EXCP_CHUNK / EXCP_THREADS; ++it) {
-            u64 idx = base + (u64)it * EXCP_THREADS + tid;
-            if (idx < len) {
-                float xv = x[idx];
-                int a = nearest_centre(xv, s_C, K, nullptr);
-                if (SMALLK) {
-                    bsum[a * EXCP_THREADS + tid] += (double)xv;
-                    bcnt[a * EXCP_THREADS + tid] += 1u;
-                } else {
-                    atomicAdd(&bsum[a], (double)xv);
-                    atomicAdd(&bcnt[a], 1u);
-                }
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u32 e = it * EXCP_THREADS + tid;
+            if (e < clen) {
+                u32 bb = bk[it];
+                u32 pos = loff[bb] + atomicAdd(&fill[bb], 1u);
+                sval[pos] = v[it];
+                sbkt[pos] = (unsigned char)bb;
             }
         }
         __syncthreads();
-        double *ps = w.part_sum + (u64)c * (u32)K;
-        u32 *pc = w.part_cnt + (u64)c * (u32)K;
-        if (SMALLK) {
-            // thread (k = tid / 16, part = tid % 16) adds 16 lane bins in order, then a 16-lane tree
-            const u32 k = tid >> 4, part = tid & 15u;
-            double sacc = 0.0; u32 cacc = 0;
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                sacc += bsum[k * EXCP_THREADS + part * 16 + q];
-                cacc += bcnt[k * EXCP_THREADS + part * 16 + q];
-            }
-#pragma unroll
-            for (int mm = 8; mm >= 1; mm >>= 1) {
-                sacc += shfl_xor_f64(sacc, mm);
-                cacc += __shfl_xor(cacc, mm, WAVE);
-            }
-            if (part == 0 && k < (u32)K) { ps[k] = sacc; pc[k] = cacc; }
-            (void)lane;
-        } else {
-            for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) { ps[k] = bsum[k]; pc[k] = bcnt[k]; }
+        for (u32 p = tid; p < clen; p += EXCP_THREADS) {
+            u32 bb = sbkt[p];
+            part[(u64)goff[bb] + (p - loff[bb])] = sval[p];
         }
         __syncthreads();
     }
 }
 
-// One workgroup per stream: add the chunk partials in a fixed order and move the centres.
-__global__ __launch_bounds__(EXCP_THREADS) void k_lloyd_update(Workspace w, GroupParams g) {
-    const u32 sidx = blockIdx.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+// ---------------------------------------------------------------- P4: exact totals per bucket
+// One wave per (stream, bucket): exact signed sum, minimum and maximum key.
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_bucket_stats(Workspace w, GroupParams g) {
+    __shared__ u64 bins[4][EXCP_ABSM_BINS];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 nseg = 3u * g.ntensors;
+    const u64 gw = (u64)blockIdx.x * 4 + wave;
+    if (gw >= (u64)nseg * NBKT) return;
+    const u32 sidx = (u32)(gw / NBKT), b = (u32)(gw % NBKT);
+    if (w.seg[sidx].len == 0) return;
+    const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
+    const u32 p0 = begin[b], p1 = begin[b + 1];
+    u64 *out = w.km_bsum + ((u64)sidx * NBKT + b) * EXCP_ABSM_BINS;
+    if (lane < EXCP_ABSM_BINS) bins[wave][lane] = 0;
+    u32 kmin = 0xffffffffu, kmax = 0;
+    const float *__restrict__ part = seg_part(w, sidx);
+    u64 *mybins = bins[wave];
+    auto add = [&](u32 bin, u64 d) { atomicAdd(&mybins[bin], d); };
+    for (u32 p = p0; p < p1; p += 64 * 8) {
+        float x[8]; bool sel[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            u32 i = p + j * 64 + lane;
+            sel[j] = i < p1;
+            x[j] = sel[j] ? part[i] : 0.f;
+            if (sel[j]) { u32 k = key_of(x[j]); kmin = min(kmin, k); kmax = max(kmax, k); }
+        }
+        wave_exact_add<8>(x, sel, add);
+    }
+#pragma unroll
+    for (int mm = 32; mm >= 1; mm >>= 1) {
+        kmin = min(kmin, (u32)__shfl_xor(kmin, mm, WAVE));
+        kmax = max(kmax, (u32)__shfl_xor(kmax, mm, WAVE));
+    }
+    if (lane < EXCP_ABSM_BINS) out[lane] = bins[wave][lane];
+    if (lane == 0) { w.km_min[(u64)sidx * NBKT + b] = kmin; w.km_max[(u64)sidx * NBKT + b] = kmax; }
+}
+
+// ---------------------------------------------------------------- P6: initial centres
+// One workgroup per (stream, rank): radix select inside the bucket that holds the rank; the bits
+// that the bucket's minimum and maximum key share are known and skipped.
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupParams g) {
+    __shared__ u32 hist[256];
+    __shared__ u32 s_pick[2];
+    const u32 K = (u32)g.K;
+    const u32 sidx = blockIdx.x / K, k = blockIdx.x % K, tid = threadIdx.x;
+    SegState &S = w.seg[sidx];
+    const u64 len = S.len;
+    if (len == 0) { if (tid == 0) S.C[k] = 0.f; return; }
+    const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
+    const u32 r = (u32)(((u64)(2 * k + 1) * len) / (2ull * K));
+    u32 lo = 0, hi = NBKT;                  // begin[lo] <= r < begin[hi]
+    while (hi - lo > 1) { u32 mid = (lo + hi) >> 1; if (begin[mid] <= r) lo = mid; else hi = mid; }
+    const u32 b = lo, p0 = begin[b], p1 = begin[b + 1];
+    u32 rank = r - p0;
+    const u32 kmin = w.km_min[(u64)sidx * NBKT + b], kmax = w.km_max[(u64)sidx * NBKT + b];
+    const float *__restrict__ part = seg_part(w, sidx);
+    u32 diff = kmin ^ kmax;
+    if (diff == 0) { if (tid == 0) S.C[k] = val_of(kmin); return; }
+    int hb = 31 - __clz((int)diff);          // highest bit in which keys of this bucket differ
+    u32 prefix = kmin >> (hb + 1 > 31 ? 31 : hb + 1);
+    if (hb == 31) prefix = 0;
+    int top = hb;                            // bits [0, top] still unknown
+    while (top >= 0) {
+        const int width = top + 1 < 8 ? top + 1 : 8;
+        const int shift = top + 1 - width;
+        hist[tid] = 0;
+        __syncthreads();
+        for (u32 p = p0 + tid; p < p1; p += EXCP_THREADS) {
+            u32 key = key_of(part[p]);
+            bool match = (top == 31) ? true : ((key >> (top + 1)) == prefix);
+            if (match) atomicAdd(&hist[(key >> shift) & ((1u << width) - 1u)], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            u32 rr = rank, bin = 0;
+            const u32 nb = 1u << width;
+            while (bin + 1 < nb && rr >= hist[bin]) { rr -= hist[bin]; ++bin; }
+            s_pick[0] = bin; s_pick[1] = rr;
+        }
+        __syncthreads();
+        prefix = (top == 31 && width == 32) ? s_pick[0] : ((prefix << width) | s_pick[0]);
+        rank = s_pick[1];
+        top = shift - 1;
+        __syncthreads();
+    }
+    if (tid == 0) S.C[k] = val_of(prefix);
+}
+
+// ---------------------------------------------------------------- P5a: one Lloyd accumulation
+// R workgroups per stream.  Every workgroup classifies the 256 buckets against the current centres;
+// workgroup 0 files the stored totals of the uncut buckets, and the cut buckets are shared out.
+constexpr u32 ITER_R = 8;
+
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g) {
+    __shared__ float s_C[EXCP_MAX_K + 1];
+    __shared__ unsigned char s_alo[NBKT], s_ahi[NBKT];
+    __shared__ u32 s_list[NBKT];
+    __shared__ u32 s_wcnt[4];
+    __shared__ u32 s_n;
+    const u32 sidx = blockIdx.x / ITER_R, part_id = blockIdx.x % ITER_R;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const SegState &S = w.seg[sidx];
+    if (S.len == 0) return;
+    const int K = g.K;
+    for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = S.C[k];
+    __syncthreads();
+    const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
+    u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);     // [K][bins + count]
+    const u32 b = tid;
+    const u32 cntb = begin[b + 1] - begin[b];
+    u32 alo = 0, ahi = 0;
+    if (cntb) {
+        alo = (u32)nearest_centre(val_of(w.km_min[(u64)sidx * NBKT + b]), s_C, K, nullptr);
+        ahi = (u32)nearest_centre(val_of(w.km_max[(u64)sidx * NBKT + b]), s_C, K, nullptr);
+    }
+    s_alo[b] = (unsigned char)alo; s_ahi[b] = (unsigned char)ahi;
+    const bool cut = cntb && alo != ahi;
+    // ordered list of the cut buckets
+    const u64 bal = ballot64(cut);
+    if (lane == 0) s_wcnt[wave] = __popcll(bal);
+    __syncthreads();
+    u32 before = 0;
+    for (u32 q = 0; q < wave; ++q) before += s_wcnt[q];
+    if (cut) s_list[before + __popcll(bal & lanemask_lt())] = b;
+    if (tid == 0) s_n = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
+    if (part_id == 0 && cntb && !cut) {
+        u64 *dst = acc + (u64)alo * (EXCP_ABSM_BINS + 1);
+        const u64 *src = w.km_bsum + ((u64)sidx * NBKT + b) * EXCP_ABSM_BINS;
+        for (int q = 0; q < EXCP_ABSM_BINS; ++q) { u64 v = src[q]; if (v) atomicAdd(&dst[q], v); }
+        atomicAdd(&dst[EXCP_ABSM_BINS], (u64)cntb);
+    }
+    __syncthreads();
+    const u32 ncut = s_n;
+    const float *__restrict__ part = seg_part(w, sidx);
+    for (u32 bi = part_id; bi < ncut; bi += ITER_R) {
+        const u32 bb = s_list[bi];
+        const u32 p0 = begin[bb], p1 = begin[bb + 1];
+        const u32 c_lo = s_alo[bb], c_hi = s_ahi[bb];
+        for (u32 p = p0 + wave * 512; p < p1; p += 4 * 512) {
+            float x[8]; bool ok[8]; u32 a[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                u32 i = p + j * 64 + lane;
+                ok[j] = i < p1;
+                x[j] = ok[j] ? part[i] : 0.f;
+                a[j] = ok[j] ? (u32)nearest_centre(x[j], s_C, K, nullptr) : 0xffffffffu;
+            }
+            for (u32 cl = c_lo; cl <= c_hi; ++cl) {
+                bool sel[8]; u32 n = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { sel[j] = a[j] == cl; n += __popcll(ballot64(sel[j])); }
+                if (n == 0) continue;
+                u64 *dst = acc + (u64)cl * (EXCP_ABSM_BINS + 1);
+                auto add = [&](u32 bin, u64 d) { atomicAdd(&dst[bin], d); };
+                wave_exact_add<8>(x, sel, add);
+                if (lane == 0) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)n);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- P5b: move the centres
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupParams g) {
+    const u32 sidx = blockIdx.x, tid = threadIdx.x;
     SegState &S = w.seg[sidx];
     if (S.len == 0) return;
     const u32 K = (u32)g.K;
-    const u32 c0 = S.chunk_begin, c1 = w.seg_chunk_begin[sidx + 1];
-    for (u32 k = wave; k < K; k += 4) {
-        double sacc = 0.0; u64 cacc = 0;
-        for (u32 c = c0 + lane; c < c1; c += 64) {
-            sacc += w.part_sum[(u64)c * K + k];
-            cacc += w.part_cnt[(u64)c * K + k];
+    u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
+    for (u32 k = tid; k < K; k += EXCP_THREADS) {
+        u64 *a = acc + (u64)k * (EXCP_ABSM_BINS + 1);
+        const u64 cnt = a[EXCP_ABSM_BINS];
+        if (cnt) {
+            double sum = signed_bins_to_double(a);
+            S.C[k] = (float)(sum / (double)cnt);
         }
-#pragma unroll
-        for (int mm = 32; mm >= 1; mm >>= 1) {
-            sacc += shfl_xor_f64(sacc, mm);
-            cacc += shfl_xor_u64(cacc, mm);
-        }
-        if (lane == 0 && cacc) S.C[k] = (float)(sacc / (double)cacc);
+        for (int q = 0; q <= EXCP_ABSM_BINS; ++q) a[q] = 0;
     }
 }
 
-// ------------------------------------------------------------------ final assignment + packing
+// ---------------------------------------------------------------- final assignment + packing
+// A chunk's codes are staged as bytes in LDS, then each thread assembles whole 64-bit words.
 __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
+    __shared__ unsigned char s_code[EXCP_CHUNK + 64];
     __shared__ double s_red[EXCP_THREADS / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 total = *w.chunk_total;
@@ -332,23 +551,41 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
         const float *__restrict__ x = seg_data(w, sidx);
         const u64 len = S.len;
         const u64 ebase = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u32 clen = (len - ebase) < EXCP_CHUNK ? (u32)(len - ebase) : EXCP_CHUNK;
         const u64 nwords = excp_words(len * nbits);
         u64 *out = (u64 *)(w.desc[t].blob + (which == 0 ? T.off_cw : (which == 1 ? T.off_cm : T.off_cv)));
         const u64 wbase = (u64)(c - S.chunk_begin) * words_per_chunk;
         double obj = 0.0;
+        float v[PER_THREAD];
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u32 e = it * EXCP_THREADS + tid;
+            v[it] = (e < clen) ? x[ebase + e] : 0.f;
+        }
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            u32 e = it * EXCP_THREADS + tid;
+            u32 code = 0;
+            if (e < clen) {
+                double dist;
+                code = 1u + (u32)nearest_centre(v[it], s_C, K, &dist);
+                obj += dist;
+            }
+            s_code[e] = (unsigned char)code;
+        }
+        if (tid < 64) s_code[EXCP_CHUNK + tid] = 0;
+        __syncthreads();
         for (u32 wl = tid; wl < words_per_chunk; wl += EXCP_THREADS) {
             const u64 wg = wbase + wl;
             if (wg >= nwords) break;
-            const u64 bit0 = wg * 64ull;
-            u64 e = bit0 / nbits;
+            const u32 bit0 = wl * 64u;
+            u32 e = bit0 / nbits;
+            int sh = (int)(e * nbits) - (int)bit0;          // <= 0 for the first code of the word
             u64 word = 0;
-            while (e < len && e * nbits < bit0 + 64ull) {
-                double dist;
-                const u32 code = 1u + (u32)nearest_centre(x[e], s_C, K, &dist);
-                const long long sh = (long long)(e * nbits) - (long long)bit0;
-                if (sh >= 0) { word |= (u64)code << sh; obj += dist; }
-                else word |= (u64)code >> (-sh);
-                ++e;
+            while (sh < 64) {
+                u64 code = s_code[e];
+                word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
+                ++e; sh += (int)nbits;
             }
             out[wg] = word;
             if (wg == nwords - 1 && (nwords & 1ull)) out[nwords] = 0ull;     // 16-byte padding
@@ -358,18 +595,17 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
         if (lane == 0) s_red[wave] = obj;
         __syncthreads();
         if (tid == 0) w.part_obj[c] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-        (void)ebase;
         __syncthreads();
     }
 }
 
-// ------------------------------------------------------------------ header, codebooks, results
+// ---------------------------------------------------------------- header, codebooks, results
 __global__ __launch_bounds__(EXCP_THREADS) void k_finalize(Workspace w, GroupParams g, u32 rec_base) {
     __shared__ double s_obj[3];
     const u32 t = blockIdx.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const TDesc &D = w.desc[t];
     TState &T = w.st[t];
-    const u32 E = 1u << g.nbits, K = (u32)g.K;
+    const u32 E = 1u << g.nbits;
     if (wave < 3) {
         const u32 sidx = 3u * t + wave;
         double acc = 0.0;
@@ -401,51 +637,42 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_finalize(Workspace w, GroupPar
         hf[14] = T.t_w; hf[15] = T.r_o;
         h64[8] = T.blob_bytes;
         h[18] = (u32)g.iters; h[19] = 0u;
-        // padding word of bitmap_o (the bitmap region was cleared before the masks were written)
         HostRec &R = w.rec_dev[rec_base + t];
         R.n = D.n; R.n_w = T.n_w; R.n_o = T.n_o; R.blob_bytes = T.blob_bytes; R.nonfinite = T.nonfinite;
         R.abs_sum = T.abs_sum; R.obj[0] = s_obj[0]; R.obj[1] = s_obj[1]; R.obj[2] = s_obj[2];
         R.med = u2f(T.med_bits); R.mean32 = T.mean32; R.t_w = T.t_w; R.r_o = T.r_o;
         R.status = status; R.pad = 0;
     }
-    (void)K;
 }
 
 }  // namespace
 
-static size_t init_hist_smem(int pass, bool lds_slots, int K) {
-    if (pass == 1) return 4096 * 4;
-    if (pass == 2) return 1024 * 4 + (lds_slots ? (size_t)(K < 15 ? K : 15) * 1024 * 4 : 0);
-    return 256 * 4;
-}
-
-void launch_init_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s) {
-    dim3 grid(w.grid_stream), block(EXCP_THREADS);
-    const bool lds = g.K <= 15;
-    size_t sm = init_hist_smem(pass, lds, g.K);
-    if (pass == 1) hipLaunchKernelGGL((k_init_hist<1, true>), grid, block, sm, s, w, g);
-    else if (pass == 2 && lds) hipLaunchKernelGGL((k_init_hist<2, true>), grid, block, sm, s, w, g);
-    else if (pass == 2) hipLaunchKernelGGL((k_init_hist<2, false>), grid, block, sm, s, w, g);
-    else hipLaunchKernelGGL((k_init_hist<3, false>), grid, block, sm, s, w, g);
-}
-
-void launch_init_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s) {
+void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s) {
     if (!g.ntensors) return;
-    dim3 grid(3 * g.ntensors), block(EXCP_THREADS);
-    if (pass == 1) hipLaunchKernelGGL(k_init_resolve<1>, grid, block, 0, s, w, g);
-    else if (pass == 2) hipLaunchKernelGGL(k_init_resolve<2>, grid, block, 0, s, w, g);
-    else hipLaunchKernelGGL(k_init_resolve<3>, grid, block, 0, s, w, g);
+    const u32 nseg = 3 * g.ntensors;
+    switch (phase) {
+        case 0: hipLaunchKernelGGL(k_km_sample, dim3(nseg), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 1: hipLaunchKernelGGL(k_km_count, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 2: hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(1024), 0, s, w, g); break;
+        case 3: hipLaunchKernelGGL(k_km_scatter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 4: hipLaunchKernelGGL(k_km_bucket_stats, dim3(nseg * (NBKT / 4)), dim3(EXCP_THREADS), 0, s, w, g); break;
+        default: break;
+    }
 }
 
-void launch_lloyd_accum(const Workspace &w, const GroupParams &g, hipStream_t s) {
-    dim3 grid(w.grid_stream), block(EXCP_THREADS);
-    if (g.K <= 15) hipLaunchKernelGGL(k_lloyd_accum<true>, grid, block, 16 * EXCP_THREADS * 12, s, w, g);
-    else hipLaunchKernelGGL(k_lloyd_accum<false>, grid, block, 256 * 12, s, w, g);
-}
-
-void launch_lloyd_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
+void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_lloyd_update, dim3(3 * g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
+    hipLaunchKernelGGL(k_km_init, dim3(3 * g.ntensors * (u32)g.K), dim3(EXCP_THREADS), 0, s, w, g);
+}
+
+void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s) {
+    if (!g.ntensors) return;
+    hipLaunchKernelGGL(k_km_iter, dim3(3 * g.ntensors * ITER_R), dim3(EXCP_THREADS), 0, s, w, g);
+}
+
+void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
+    if (!g.ntensors) return;
+    hipLaunchKernelGGL(k_km_update, dim3(3 * g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s) {

@@ -15,7 +15,7 @@ __device__ __forceinline__ u64 pack_status(u32 flag, u32 cw, u32 co) {
     return ((u64)flag << 62) | ((u64)cw << 31) | (u64)co;
 }
 
-__global__ __launch_bounds__(EXCP_THREADS) void k_mask_compact(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_mask_compact(Workspace w, GroupParams g) {
     __shared__ u32 s_w[4], s_o[4], s_excl[2];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u64 lt_mask = lanemask_lt();
