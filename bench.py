@@ -29,8 +29,9 @@ def stage_bytes_per_param(p_w, p_o, nbits, iters):
         "stats_hist": 12.0 + 0.125,                       # read W_prev, W, m; clear the M_o bitmap region
         "select_hist": 2 * 8.0,                            # two refinement passes over W_prev, W
         "mask_compact": 16.0 + bitmaps + 4.0 * s,          # read all four arrays; write bitmaps + survivors
-        "init_hist": 3 * 4.0 * s,                          # three select passes over the survivors
-        "lloyd_accum": iters * 4.0 * s,                    # one read of the survivors per iteration
+        "km_count": 4.0 * s,                               # read the survivors, count per bucket
+        "km_scatter": 8.0 * s,                             # read the survivors, write them bucket by bucket
+        "km_bucket_stats": 4.0 * s,                        # read the partitioned survivors once
         "assign_pack": 4.0 * s + s * nbits / 8.0,          # read survivors, write codes
         "decode_main": 4.0 + bitmaps + s * nbits / 8.0 + 4.0,   # read W_prev, bitmaps, codes; write W_hat
     }
@@ -176,9 +177,10 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle as O
-        budget_elems = 6_000_000
-        pick = min(range(len(cfg.tensors)), key=lambda i: (abs(cfg.tensors[i].n - budget_elems), i))
-        a, b = offs[pick], offs[pick] + min(cfg.tensors[pick].n, 3 * budget_elems)
+        budget_elems = 16_000_000
+        big = [i for i in range(len(cfg.tensors)) if cfg.tensors[i].n >= 1_000_000] or list(range(len(cfg.tensors)))
+        pick = min(big, key=lambda i: (cfg.tensors[i].n, i))
+        a, b = offs[pick], offs[pick] + min(cfg.tensors[pick].n, budget_elems)
         host = [f[a:b].cpu().numpy() for f in flat[:4]]
         t2 = time.perf_counter()
         ref = O.compress_step(*host, alpha, beta, nbits, iters)

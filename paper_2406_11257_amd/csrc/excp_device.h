@@ -113,6 +113,9 @@ struct Workspace {
     u64 *km_bsum;             // [segment][256][EXCP_ABSM_BINS] exact signed sum of every bucket
     u32 *km_min, *km_max;     // [segment][256] smallest / largest key of every bucket
     u64 *km_acc;              // [segment][EXCP_MAX_K][EXCP_ABSM_BINS + 1] per-centre exact sum and count
+    void *km_items;           // work items of the Lloyd accumulation (cut buckets in pieces)
+    u32 *km_item_count;       // [1]
+    u32 km_item_cap;
     double *part_obj;         // [chunk]
     u32 max_chunks;
     // decode
@@ -133,6 +136,7 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, hipStream_t s
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_km_classify(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s);
@@ -141,6 +145,6 @@ void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipSt
 void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s);
 void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which, hipStream_t s);
 void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s);
-void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s);
+void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s);
 int  query_persistent_grid(int device);

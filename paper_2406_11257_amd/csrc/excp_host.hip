@@ -18,12 +18,12 @@ constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress ca
 
 enum Stage {
     ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
-    ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
+    ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_CLASSIFY, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
     ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC, ST_COUNT
 };
 const char *kStageNames[ST_COUNT] = {
     "stats_hist", "select_hist", "select_resolve", "mask_compact", "layout", "km_sample", "km_count", "km_scan",
-    "km_scatter", "km_bucket_stats", "km_init", "km_iter", "km_update", "assign_pack", "finalize",
+    "km_scatter", "km_bucket_stats", "km_init", "km_classify", "km_iter", "km_update", "assign_pack", "finalize",
     "decode_prep", "decode_main", "misc"};
 
 struct Span { int stage; hipEvent_t a, b; };
@@ -118,17 +118,19 @@ void make_groups(int count, u64 cap_elems, u32 tcap, GetN get_n, std::vector<Gro
     }
 }
 
-void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32 ntiles) {
+void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32 ntiles, bool moments) {
     {
         StageTimer t(c, ST_DECODE_PREP);
         launch_decode_count(w, ntensors, ntiles, 0, c->stream);
         launch_decode_scan(w, ntensors, 0, c->stream);
-        launch_decode_count(w, ntensors, ntiles, 1, c->stream);
-        launch_decode_scan(w, ntensors, 1, c->stream);
+        if (moments) {
+            launch_decode_count(w, ntensors, ntiles, 1, c->stream);
+            launch_decode_scan(w, ntensors, 1, c->stream);
+        }
     }
     {
         StageTimer t(c, ST_DECODE_MAIN);
-        launch_decode_main(w, ntensors, ntiles, c->stream);
+        launch_decode_main(w, ntensors, ntiles, moments, c->stream);
     }
 }
 
@@ -209,6 +211,10 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.km_min, nseg_max * 256);
     ok = ok && dev_alloc(c, &w.km_max, nseg_max * 256);
     ok = ok && dev_alloc(c, &w.km_acc, acc_words);
+    const u64 item_cap = chunks_group + nseg_max * 256;
+    ok = ok && dev_alloc(c, (unsigned char **)&w.km_items, item_cap * 16);
+    ok = ok && dev_alloc(c, &w.km_item_count, 4);
+    w.km_item_cap = (u32)(item_cap > 0xffffffffull ? 0xffffffffull : item_cap);
     ok = ok && dev_alloc(c, &w.part_obj, chunks_group);
     ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles);
     ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles);
@@ -231,6 +237,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     if (ok) {
         launch_zero_u32(w.med_hist, (u64)kMaxGroupTensors * 2048, c->stream);
         launch_zero_u32((u32 *)w.km_acc, 2 * acc_words, c->stream);
+        launch_zero_u32(w.km_item_count, 4, c->stream);
         launch_zero_u32((u32 *)w.err_flag, 4, c->stream);
         ok = hipStreamSynchronize(c->stream) == hipSuccess;
     }
@@ -346,6 +353,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }
         { StageTimer t(c, ST_KM_INIT); launch_km_init(w, p, s); }
         for (int it = 0; it < lloyd_iters; ++it) {
+            { StageTimer t(c, ST_KM_CLASSIFY); launch_km_classify(w, p, s); }
             { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, s); }
             { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
         }
@@ -355,7 +363,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         for (u32 q = 0; q < g.count; ++q) any_out = any_out || tensors[g.first + q].W_recon_out != nullptr;
         if (any_out) {
             { StageTimer t(c, ST_MISC); launch_decode_from_compress(w, p, s); }
-            run_decode_prep_and_main(c, w, g.count, g.ntiles);
+            run_decode_prep_and_main(c, w, g.count, g.ntiles, false);
         }
     }
     if (count) {
@@ -414,7 +422,10 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
         w.rec_dev = c->w.rec_dev + g.first;
         w.rec_base = 0;
         { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, s); }
-        run_decode_prep_and_main(c, w, g.count, g.ntiles);
+        bool moments = false;
+        for (u32 q = 0; q < g.count; ++q)
+            moments = moments || blobs[g.first + q].m_out != nullptr || blobs[g.first + q].v_out != nullptr;
+        run_decode_prep_and_main(c, w, g.count, g.ntiles, moments);
         { StageTimer t(c, ST_MISC); launch_decode_finish(w, g.count, s); }
     }
     if (count) {

@@ -134,6 +134,7 @@ __device__ __forceinline__ u32 extract_code(u64 w0, u64 w1, u32 sh, u32 nbits) {
     return (u32)(v & ((1ull << nbits) - 1ull));
 }
 
+template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
     __shared__ float s_book[3 * 256];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -164,7 +165,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 n
         const u64 nwords = excp_words(n);
         const u64 n_w = S.n_w, n_o = S.n_o;
         const bool pow2 = (64u % nbits) == 0u;
-        const bool moments = (D.m_out != nullptr) || (D.v_out != nullptr);
+        const bool moments = MOMENTS && ((D.m_out != nullptr) || (D.v_out != nullptr));
         const bool inplace = D.W_out == D.Wp;
 
         // survivors before each of the tile's 64 bitmap words
@@ -212,9 +213,11 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 n
             for (int j = 0; j < 8; ++j) {
                 const u32 wi = wave * 16 + half * 8 + j;
                 const u64 idx = base + (u64)(wi * 64 + lane);
-                const u32 lo = __shfl((u32)myword, wi, WAVE), hi = __shfl((u32)(myword >> 32), wi, WAVE);
+                // wi is the same for the whole wave: a scalar lane read, no cross-lane permute
+                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)myword, (int)wi);
+                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(myword >> 32), (int)wi);
                 const u64 mw = ((u64)hi << 32) | lo;
-                const u32 wexcl = __shfl(excl, wi, WAVE);
+                const u32 wexcl = (u32)__builtin_amdgcn_readlane((int)excl, (int)wi);
                 const bool ok = idx < n;
                 kwv[j] = ok && ((mw >> lane) & 1ull);
                 u64 q = q_tile + wexcl + __popcll(mw & lt_mask);   // survivor position where kept
@@ -234,7 +237,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 n
                     if (idx < n && (!inplace || kwv[j])) D.W_out[idx] = outw;
                 }
             }
-            if (!moments) continue;
+            if (!MOMENTS || !moments) continue;
             // ---- moments: M_o bit and rank of every survivor -----------------------------------
             bool kov[8]; u64 m0[8], m1[8], v0[8], v1[8]; u32 shv[8];
 #pragma unroll
@@ -325,10 +328,11 @@ void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t
     if (which == 0) hipLaunchKernelGGL(k_decode_scan<0>, dim3(ntensors), dim3(EXCP_THREADS), 0, s, w, ntensors);
     else hipLaunchKernelGGL(k_decode_scan<1>, dim3(ntensors), dim3(EXCP_THREADS), 0, s, w, ntensors);
 }
-void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s) {
+void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
     if (!ntiles) return;
     u32 blocks = ntiles < (u32)w.grid_stream * 4u ? ntiles : (u32)w.grid_stream * 4u;
-    hipLaunchKernelGGL(k_decode_main, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    if (moments) hipLaunchKernelGGL(k_decode_main<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    else hipLaunchKernelGGL(k_decode_main<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
 }
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s) {
     if (!ntensors) return;

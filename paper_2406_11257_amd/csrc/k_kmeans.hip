@@ -430,18 +430,16 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
 }
 
 // ---------------------------------------------------------------- P5a: one Lloyd accumulation
-// R workgroups per stream.  Every workgroup classifies the 256 buckets against the current centres;
-// workgroup 0 files the stored totals of the uncut buckets, and the cut buckets are shared out.
-constexpr u32 ITER_R = 8;
+// Classification (one workgroup per stream): every bucket is compared with the current centres.
+// A bucket whose smallest and largest value go to the same centre adds its stored totals to that
+// centre; a bucket that a cluster border cuts is split into work items of at most 8192 values.
+struct KmItem { u32 sidx, p0, p1, range; };      // range = alo | ahi << 8
 
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
-    __shared__ unsigned char s_alo[NBKT], s_ahi[NBKT];
-    __shared__ u32 s_list[NBKT];
-    __shared__ u32 s_wcnt[4];
-    __shared__ u32 s_n;
-    const u32 sidx = blockIdx.x / ITER_R, part_id = blockIdx.x % ITER_R;
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    __shared__ u32 s_scan[EXCP_THREADS];
+    __shared__ u32 s_base;
+    const u32 sidx = blockIdx.x, tid = threadIdx.x;
     const SegState &S = w.seg[sidx];
     if (S.len == 0) return;
     const int K = g.K;
@@ -450,53 +448,99 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupPara
     const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
     u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);     // [K][bins + count]
     const u32 b = tid;
-    const u32 cntb = begin[b + 1] - begin[b];
+    const u32 p0 = begin[b], p1 = begin[b + 1], cntb = p1 - p0;
     u32 alo = 0, ahi = 0;
     if (cntb) {
         alo = (u32)nearest_centre(val_of(w.km_min[(u64)sidx * NBKT + b]), s_C, K, nullptr);
         ahi = (u32)nearest_centre(val_of(w.km_max[(u64)sidx * NBKT + b]), s_C, K, nullptr);
     }
-    s_alo[b] = (unsigned char)alo; s_ahi[b] = (unsigned char)ahi;
     const bool cut = cntb && alo != ahi;
-    // ordered list of the cut buckets
-    const u64 bal = ballot64(cut);
-    if (lane == 0) s_wcnt[wave] = __popcll(bal);
-    __syncthreads();
-    u32 before = 0;
-    for (u32 q = 0; q < wave; ++q) before += s_wcnt[q];
-    if (cut) s_list[before + __popcll(bal & lanemask_lt())] = b;
-    if (tid == 0) s_n = s_wcnt[0] + s_wcnt[1] + s_wcnt[2] + s_wcnt[3];
-    if (part_id == 0 && cntb && !cut) {
+    if (cntb && !cut) {
         u64 *dst = acc + (u64)alo * (EXCP_ABSM_BINS + 1);
         const u64 *src = w.km_bsum + ((u64)sidx * NBKT + b) * EXCP_ABSM_BINS;
         for (int q = 0; q < EXCP_ABSM_BINS; ++q) { u64 v = src[q]; if (v) atomicAdd(&dst[q], v); }
         atomicAdd(&dst[EXCP_ABSM_BINS], (u64)cntb);
     }
+    const u32 nitems = cut ? (cntb + EXCP_CHUNK - 1) / EXCP_CHUNK : 0u;
+    s_scan[tid] = nitems;
     __syncthreads();
-    const u32 ncut = s_n;
-    const float *__restrict__ part = seg_part(w, sidx);
-    for (u32 bi = part_id; bi < ncut; bi += ITER_R) {
-        const u32 bb = s_list[bi];
-        const u32 p0 = begin[bb], p1 = begin[bb + 1];
-        const u32 c_lo = s_alo[bb], c_hi = s_ahi[bb];
-        for (u32 p = p0 + wave * 512; p < p1; p += 4 * 512) {
+    for (u32 off = 1; off < EXCP_THREADS; off <<= 1) {
+        u32 v = (tid >= off) ? s_scan[tid - off] : 0u;
+        __syncthreads();
+        s_scan[tid] += v;
+        __syncthreads();
+    }
+    if (tid == EXCP_THREADS - 1) s_base = s_scan[tid] ? atomicAdd(w.km_item_count, s_scan[tid]) : 0u;
+    __syncthreads();
+    u32 at = s_base + s_scan[tid] - nitems;
+    KmItem *items = (KmItem *)w.km_items;
+    for (u32 q = 0; q < nitems; ++q, ++at) {
+        if (at >= w.km_item_cap) { atomicExch(w.err_flag, 1); break; }
+        u32 a0 = p0 + q * EXCP_CHUNK, a1 = a0 + EXCP_CHUNK < p1 ? a0 + EXCP_CHUNK : p1;
+        items[at] = KmItem{sidx, a0, a1, alo | (ahi << 8)};
+    }
+}
+
+// Work items: the values of a cut bucket are assigned one by one and added, exactly, to their
+// centres.  Sums are gathered in LDS per item and flushed with a few integer atomics.
+constexpr u32 ITEM_R = 8;      // centres per item held in LDS; wider ranges go straight to global memory
+
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g) {
+    __shared__ float s_C[EXCP_MAX_K + 1];
+    __shared__ u64 s_bins[ITEM_R][EXCP_ABSM_BINS + 1];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const int K = g.K;
+    u32 nitems = *w.km_item_count;
+    if (nitems > w.km_item_cap) nitems = w.km_item_cap;
+    const KmItem *items = (const KmItem *)w.km_items;
+    u32 cur = 0xffffffffu;
+    for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
+        const KmItem I = items[it];
+        __syncthreads();
+        if (I.sidx != cur) {
+            for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = w.seg[I.sidx].C[k];
+            cur = I.sidx;
+        }
+        for (u32 i = tid; i < ITEM_R * (EXCP_ABSM_BINS + 1); i += EXCP_THREADS) (&s_bins[0][0])[i] = 0;
+        __syncthreads();
+        const u32 c_lo = I.range & 255u, c_hi = I.range >> 8;
+        const bool in_lds = (c_hi - c_lo) < ITEM_R;
+        u64 *acc = w.km_acc + (u64)I.sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
+        const float *__restrict__ part = seg_part(w, I.sidx);
+        for (u32 p = I.p0 + wave * 512; p < I.p1; p += 4 * 512) {
             float x[8]; bool ok[8]; u32 a[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 u32 i = p + j * 64 + lane;
-                ok[j] = i < p1;
+                ok[j] = i < I.p1;
                 x[j] = ok[j] ? part[i] : 0.f;
-                a[j] = ok[j] ? (u32)nearest_centre(x[j], s_C, K, nullptr) : 0xffffffffu;
             }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] = ok[j] ? (u32)nearest_centre(x[j], s_C, K, nullptr) : 0xffffffffu;
             for (u32 cl = c_lo; cl <= c_hi; ++cl) {
                 bool sel[8]; u32 n = 0;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) { sel[j] = a[j] == cl; n += __popcll(ballot64(sel[j])); }
                 if (n == 0) continue;
-                u64 *dst = acc + (u64)cl * (EXCP_ABSM_BINS + 1);
-                auto add = [&](u32 bin, u64 d) { atomicAdd(&dst[bin], d); };
-                wave_exact_add<8>(x, sel, add);
-                if (lane == 0) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)n);
+                if (in_lds) {
+                    u64 *dst = s_bins[cl - c_lo];
+                    auto add = [&](u32 bin, u64 d) { atomicAdd(&dst[bin], d); };
+                    wave_exact_add<8>(x, sel, add);
+                    if (lane == 0) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)n);
+                } else {
+                    u64 *dst = acc + (u64)cl * (EXCP_ABSM_BINS + 1);
+                    auto add = [&](u32 bin, u64 d) { atomicAdd(&dst[bin], d); };
+                    wave_exact_add<8>(x, sel, add);
+                    if (lane == 0) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)n);
+                }
+            }
+        }
+        __syncthreads();
+        if (in_lds) {
+            for (u32 i = tid; i < ITEM_R * (EXCP_ABSM_BINS + 1); i += EXCP_THREADS) {
+                u64 v = (&s_bins[0][0])[i];
+                u32 cl = c_lo + i / (EXCP_ABSM_BINS + 1);
+                if (v && cl <= c_hi) atomicAdd(&acc[(u64)cl * (EXCP_ABSM_BINS + 1) + i % (EXCP_ABSM_BINS + 1)], v);
             }
         }
     }
@@ -506,6 +550,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupPara
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupParams g) {
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
     SegState &S = w.seg[sidx];
+    if (sidx == 0 && tid == 0) *w.km_item_count = 0;       // the work list is rebuilt every iteration
     if (S.len == 0) return;
     const u32 K = (u32)g.K;
     u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
@@ -665,9 +710,14 @@ void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s) {
     hipLaunchKernelGGL(k_km_init, dim3(3 * g.ntensors * (u32)g.K), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
+void launch_km_classify(const Workspace &w, const GroupParams &g, hipStream_t s) {
+    if (!g.ntensors) return;
+    hipLaunchKernelGGL(k_km_classify, dim3(3 * g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
+}
+
 void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_iter, dim3(3 * g.ntensors * ITER_R), dim3(EXCP_THREADS), 0, s, w, g);
+    hipLaunchKernelGGL(k_km_iter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {

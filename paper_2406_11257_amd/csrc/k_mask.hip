@@ -84,27 +84,40 @@ __global__ __launch_bounds__(EXCP_THREADS) __attribute__((amdgpu_waves_per_eu(4,
                 const long long first = (long long)D.tile_begin;
                 u32 spins = 0;
                 bool giveup = false;
+                u64 total = 0;                                   // packed: survivors << 31 | moment survivors
                 while (true) {
-                    long long idx = pos - (long long)lane;
-                    u64 sv = (idx >= first) ? ld_status(&status[idx]) : pack_status(2, 0, 0);
-                    u32 flag = (u32)(sv >> 62);
-                    u64 m2 = ballot64(flag == 2u);
-                    u64 m0 = ballot64(flag == 0u);
-                    u64 want = ~0ull;
-                    if (m2) { int L = __ffsll((long long)m2) - 1; want = (L == 63) ? ~0ull : ((1ull << (L + 1)) - 1ull); }
-                    if (m0 & want) {
+                    // 256 predecessors per step: lane l reads tiles pos - l, pos - 64 - l, ...
+                    u64 sv[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        long long idx = pos - (long long)(q * 64 + lane);
+                        sv[q] = (idx >= first) ? ld_status(&status[idx]) : pack_status(2, 0, 0);
+                    }
+                    u64 part = 0;
+                    bool done = false, retry = false;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (done || retry) continue;
+                        const u32 flag = (u32)(sv[q] >> 62);
+                        const u64 m2 = ballot64(flag == 2u);
+                        const u64 m0 = ballot64(flag == 0u);
+                        u64 want = ~0ull;
+                        if (m2) { int L = __ffsll((long long)m2) - 1; want = (L == 63) ? ~0ull : ((1ull << (L + 1)) - 1ull); }
+                        if (m0 & want) { retry = true; continue; }
+                        if ((want >> lane) & 1ull) part += sv[q] & 0x3fffffffffffffffull;
+                        if (m2) done = true;
+                    }
+                    if (retry) {
                         if (++spins > EXCP_SPIN_LIMIT) { giveup = true; break; }
                         __builtin_amdgcn_s_sleep(1);
                         continue;
                     }
-                    bool mine = (want >> lane) & 1ull;
-                    u32 a = mine ? (u32)((sv >> 31) & 0x7fffffffu) : 0u;
-                    u32 c = mine ? (u32)(sv & 0x7fffffffu) : 0u;
-                    ew += wave_sum_u32(a);
-                    eo += wave_sum_u32(c);
-                    if (m2) break;
-                    pos -= 64;
+                    total += wave_sum_u64(part);
+                    if (done) break;
+                    pos -= 256;
                 }
+                ew = (u32)(total >> 31);
+                eo = (u32)(total & 0x7fffffffull);
                 if (giveup && lane == 0) atomicExch(w.err_flag, 1);
             }
             if (lane == 0) {
