@@ -102,7 +102,9 @@ struct Workspace {
     // median select
     u32 *med_hist;            // [tensor][2048]
     // look-back status words, one per tile
-    u64 *tile_status;
+    u64 *tile_status;         // per 2048-element sub-tile: survivors << 32 | moment survivors
+    u64 *mask_prefix;         // exclusive scan of tile_status within each tensor
+    u64 *mask_bo;             // [sub-tile][32] M_o bits of the sub-tile's survivors, local positions
     // survivor passes
     u32 *chunk_total;         // [1]
     u32 *seg_chunk_begin;     // [segments + 1] first chunk of every survivor stream
@@ -132,7 +134,7 @@ struct Workspace {
 void launch_zero_u32(u32 *p, u64 count, hipStream_t s);
 void launch_stats_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
 void launch_median_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
-void launch_mask_compact(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s);

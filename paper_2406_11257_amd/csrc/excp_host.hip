@@ -13,16 +13,16 @@
 
 namespace {
 
-constexpr u32 kMaxGroupTensors = 1024;   // tensors processed together
+constexpr u32 kMaxGroupTensors = 1024;   // tensors processed together (== EXCP_MAX_GROUP_TENSORS of the kernels)
 constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress call
 
 enum Stage {
-    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
+    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_MASK_SCAN, ST_MASK_GATHER, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
     ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_CLASSIFY, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
     ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC, ST_COUNT
 };
 const char *kStageNames[ST_COUNT] = {
-    "stats_hist", "select_hist", "select_resolve", "mask_compact", "layout", "km_sample", "km_count", "km_scan",
+    "stats_hist", "select_hist", "select_resolve", "mask_slots", "mask_scan", "mask_gather", "layout", "km_sample", "km_count", "km_scan",
     "km_scatter", "km_bucket_stats", "km_init", "km_classify", "km_iter", "km_update", "assign_pack", "finalize",
     "decode_prep", "decode_main", "misc"};
 
@@ -196,7 +196,9 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.xm, G);
     ok = ok && dev_alloc(c, &w.xv, G);
     ok = ok && dev_alloc(c, &w.med_hist, (u64)kMaxGroupTensors * 2048);
-    ok = ok && dev_alloc(c, &w.tile_status, max_tiles);
+    ok = ok && dev_alloc(c, &w.tile_status, 2 * max_tiles);      // one word per 2048-element sub-tile
+    ok = ok && dev_alloc(c, &w.mask_prefix, 2 * max_tiles);
+    ok = ok && dev_alloc(c, &w.mask_bo, 2 * max_tiles * 32);
     ok = ok && dev_alloc(c, &w.chunk_total, 4);
     ok = ok && dev_alloc(c, &w.seg_chunk_begin, 3ull * kMaxGroupTensors + 4);
     const u64 nseg_max = 3ull * kMaxGroupTensors;
@@ -282,7 +284,11 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (!c || count < 0 || (count && !tensors)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+#ifdef EXCP_TUNING
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xffu) != 0) return EXCP_E_ARG;   // tuning build only
+#else
     if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || flags != 0) return EXCP_E_ARG;
+#endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
     const int K = (1 << nbits) - 1;
     for (int i = 0; i < count; ++i) {
@@ -337,14 +343,15 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         GroupParams p{};
         p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
         p.ntensors = g.count; p.ntiles = g.ntiles;
-        { StageTimer t(c, ST_MISC); launch_zero_u32((u32 *)w.tile_status, 2ull * g.ntiles, s); }
         { StageTimer t(c, ST_STATS); launch_stats_hist(w, p, 0, s); }
         { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, 0, s); }
         for (int pass = 1; pass <= 2; ++pass) {
             { StageTimer t(c, ST_SELECT); launch_stats_hist(w, p, pass, s); }
             { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, pass, s); }
         }
-        { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, s); }
+        { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, 0, s); }
+        { StageTimer t(c, ST_MASK_SCAN); launch_mask_compact(w, p, 1, s); }
+        { StageTimer t(c, ST_MASK_GATHER); launch_mask_compact(w, p, 2, s); }
         { StageTimer t(c, ST_LAYOUT); launch_layout(w, p, s); }
         { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
         { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }

@@ -7,7 +7,7 @@
 __device__ __forceinline__ u32 f2u(float x) { return __float_as_uint(x); }
 __device__ __forceinline__ float u2f(u32 x) { return __uint_as_float(x); }
 
-__device__ __forceinline__ u64 ballot64(bool p) { return __ballot(p); }
+__device__ __forceinline__ u64 ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & 63u; }
 __device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
 
@@ -45,6 +45,21 @@ __device__ __forceinline__ u32 find_owner(const u32 *__restrict__ begin, u32 cou
         if (begin[mid] <= x) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+// Pointers read from descriptor tables are generic to the compiler; these casts state that they
+// point to global memory, which turns flat loads/stores into global ones with immediate offsets.
+#define EXCP_GLOBAL __attribute__((address_space(1)))
+template <class T>
+__device__ __forceinline__ const EXCP_GLOBAL T *gptr(const T *p) { return (const EXCP_GLOBAL T *)(uintptr_t)p; }
+template <class T>
+__device__ __forceinline__ EXCP_GLOBAL T *gptr(T *p) { return (EXCP_GLOBAL T *)(uintptr_t)p; }
+
+// Copy of a tile table in LDS (the per-tile owner search then costs no global round trips).
+#define EXCP_MAX_GROUP_TENSORS 1024
+__device__ __forceinline__ void load_tile_table(u32 *dst, const u32 *__restrict__ src, u32 count) {
+    for (u32 i = threadIdx.x; i <= count; i += blockDim.x) dst[i] = src[i];
+    __syncthreads();
 }
 
 // Order-preserving map of fp32 bit patterns to unsigned keys (and back).

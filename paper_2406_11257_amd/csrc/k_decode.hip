@@ -63,10 +63,12 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors) {
 // that belong to the tile's survivors (needs the scanned bitmap_w counts).  One wave per tile.
 template <int WHICH>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_count(Workspace w, u32 ntensors, u32 ntiles) {
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     const u32 lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const u32 wpb = EXCP_THREADS / 64;
+    load_tile_table(s_tiles, w.tile_begin, ntensors);
     for (u32 tile = blockIdx.x * wpb + wave; tile < ntiles; tile += gridDim.x * wpb) {
-        const u32 t = find_owner(w.tile_begin, ntensors, tile);
+        const u32 t = find_owner(s_tiles, ntensors, tile);
         const DDesc &D = w.ddesc[t];
         const DState &S = w.dst[t];
         u32 cnt = 0;
@@ -137,11 +139,13 @@ __device__ __forceinline__ u32 extract_code(u64 w0, u64 w1, u32 sh, u32 nbits) {
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
     __shared__ float s_book[3 * 256];
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u64 lt_mask = lanemask_lt();
     u32 cur_t = 0xffffffffu;
+    load_tile_table(s_tiles, w.tile_begin, ntensors);
     for (u32 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const u32 t = find_owner(w.tile_begin, ntensors, tile);
+        const u32 t = find_owner(s_tiles, ntensors, tile);
         const DDesc &D = w.ddesc[t];
         const DState &S = w.dst[t];
         if (S.status != 0) continue;

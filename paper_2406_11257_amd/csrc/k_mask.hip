@@ -1,59 +1,109 @@
-// Joint pruning masks (Sec. 3.2, Eq. "r_w" and Eq. "r_o") fused with an order-preserving stream
-// compaction of the survivors, in one pass over W_prev, W_t, m and v.
+// Joint pruning masks (Sec. 3.2, Eq. "r_w" and Eq. "r_o") and the order-preserving compaction of
+// the survivors.
 //
-// A tile is 4096 elements: 4 waves x 16 batches of 64, so that one wave ballot is one word of the
-// keep bitmap.  Survivor positions need the number of survivors in all earlier tiles of the same
-// tensor; tiles publish (aggregate, inclusive prefix) status words and look back over their
-// predecessors (single-pass chained scan).  Workgroups are persistent and take tiles b, b+G, ...
-// with every workgroup resident, so the tile a workgroup waits for is always owned by a running
-// workgroup; a bounded spin turns any violation of that into an error flag instead of a hang.
+// Pass A (k_mask_slots) reads W_prev, W_t, m and v once.  Work unit: a sub-tile of 2048 elements
+// (half a 4096-element tile): 4 waves x 8 batches of 64, so that one wave ballot is one word of the
+// keep bitmap.  It writes the keep bitmap, the sub-tile's survivor counts, and the survivors
+// themselves -- compacted in index order, together with their M_o bits -- into the sub-tile's own
+// slot of a scratch area.  No workgroup waits for another: where a survivor finally goes depends on
+// the counts of all earlier sub-tiles, and that is left to a scan (k_mask_scan, one workgroup per
+// tensor over its sub-tile counts) and to pass B (k_mask_gather), which copies every slot to its
+// place in the dense survivor arrays and merges the M_o bits into the blob.  The extra copy costs
+// 8 bytes per survivor; it replaces a chained scan whose waits cost more than that.
+#include <type_traits>
+
 #include "excp_util.h"
 
 namespace {
 
-__device__ __forceinline__ u64 pack_status(u32 flag, u32 cw, u32 co) {
-    return ((u64)flag << 62) | ((u64)cw << 31) | (u64)co;
-}
+#ifdef EXCP_TUNING
+#define TUNE(bit) ((g.flags >> (bit)) & 1u)
+#else
+#define TUNE(bit) 0u
+#endif
 
-__global__ __launch_bounds__(EXCP_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_mask_compact(Workspace w, GroupParams g) {
-    __shared__ u32 s_w[4], s_o[4], s_excl[2];
+constexpr u32 SUB = 2048;          // elements per sub-tile
+constexpr int NBATCH = 8;          // 64-element batches per wave and sub-tile
+constexpr u32 BO_WORDS = SUB / 64; // M_o words kept per sub-tile
+
+struct Regs {
+    float w[NBATCH], p[NBATCH], m[NBATCH], v[NBATCH];
+};
+
+// sub-tile s of the group -> (tensor, first element); slots live in the partition arrays, which are
+// free until the codebook stage
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_slots(Workspace w, GroupParams g) {
+    __shared__ float l_w[SUB], l_m[SUB], l_v[SUB];      // compacted survivors of one sub-tile
+    __shared__ u32 s_w[4], s_o[4];
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u64 lt_mask = lanemask_lt();
+    const u32 nsub = 2u * g.ntiles;
+    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
 
-    for (u32 tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
-        const u32 t = find_owner(w.tile_begin, g.ntensors, tile);
+    auto issue_loads = [&](u32 sub, Regs &R) {
+        if (sub >= nsub) return;
+        const u32 tile = sub >> 1;
+        const u32 t = find_owner(s_tiles, g.ntensors, tile);
         const TDesc &D = w.desc[t];
         const u64 n = D.n;
-        const u32 ltile = tile - D.tile_begin;
-        const u64 base = (u64)ltile * EXCP_TILE;
-        const float t_w = w.st[t].t_w, r_o = w.st[t].r_o;
-        const float *__restrict__ Wp = D.Wp, *__restrict__ W = D.W, *__restrict__ M = D.m, *__restrict__ V = D.v;
-
-        float dv[16], mv[16], vv[16];
-        u64 bw[16], bo[16];
-        u32 nf = 0, cw = 0, co = 0;
+        const u64 base = (u64)(tile - s_tiles[t]) * EXCP_TILE + (u64)(sub & 1u) * SUB;
+        if (base + SUB <= n) {
+            // full sub-tile: one address per array and lane, the batches are immediate offsets
+            const u64 first = base + (u64)(wave * (SUB / 4) + lane);
+            const EXCP_GLOBAL float *gW = gptr(D.W) + first, *gP = gptr(D.Wp) + first;
+            const EXCP_GLOBAL float *gM = gptr(D.m) + first, *gV = gptr(D.v) + first;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
-            bool ok = idx < n;
-            float a = ok ? W[idx] : 0.f;
-            float p = ok ? Wp[idx] : 0.f;
-            mv[j] = ok ? M[idx] : 0.f;
-            vv[j] = ok ? V[idx] : 1.f;
-            dv[j] = a - p;
+            for (int j = 0; j < NBATCH; ++j) {
+                R.w[j] = gW[j * 64]; R.p[j] = gP[j * 64]; R.m[j] = gM[j * 64]; R.v[j] = gV[j * 64];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NBATCH; ++j) {
+                const u64 idx = base + (u64)((wave * NBATCH + j) * 64 + lane);
+                const bool ok = idx < n;
+                R.w[j] = ok ? D.W[idx] : 0.f;
+                R.p[j] = ok ? D.Wp[idx] : 0.f;
+                R.m[j] = ok ? D.m[idx] : 0.f;
+                R.v[j] = ok ? D.v[idx] : 1.f;
+            }
         }
+    };
+
+    auto compute = [&](u32 sub, Regs &R, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        const u32 tile = sub >> 1;
+        const u32 t = find_owner(s_tiles, g.ntensors, tile);
+        const TDesc &D = w.desc[t];
+        const u64 n = D.n;
+        const u32 first_sub = 2u * s_tiles[t];
+        const u64 base = (u64)(sub - first_sub) * SUB;
+        const float t_w = w.st[t].t_w, r_o = w.st[t].r_o;
+        const u32 rem = FULL ? SUB : (u32)(n > base ? n - base : 0);      // valid elements here
+        u64 bw[NBATCH];
+        u32 nf = 0, cw = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
-            bool ok = idx < n;
-            float r = __fdiv_rn(t_w, __fsqrt_rn(vv[j]));
-            bool kw = ok && (fabsf(dv[j]) > r);
-            bool ko = kw && (fabsf(mv[j]) > r_o);
-            nf += ((f2u(vv[j]) & 0x7f800000u) == 0x7f800000u);
+        for (int j = 0; j < NBATCH; ++j) {
+            const u32 e = (wave * NBATCH + j) * 64 + lane;
+            const bool ok = FULL || e < rem;
+            R.w[j] = R.w[j] - R.p[j];                     // the residual
+            // |d| > t_w / sqrt(v) with correctly rounded sqrt and divide, decided by a cheap estimate
+            // when the estimate is not within 1e-5 of |d| (its own error is below 1e-6) and by the
+            // exact expression otherwise, so the result is always that of the exact expression.
+            // The estimate is trusted only for positive normal v and a positive normal estimate.
+            const float ad = fabsf(R.w[j]);
+            const float ra = t_w * __builtin_amdgcn_rsqf(R.v[j]);
+            const bool sure_keep = ad > ra * 1.00001f, sure_drop = ad < ra * 0.99999f;
+            const bool amb = !(sure_keep || sure_drop) || !__builtin_amdgcn_classf(R.v[j], 0x100) ||
+                             !__builtin_amdgcn_classf(ra, 0x100);
+            bool kw = sure_keep;
+            if (__any(amb)) {
+                if (amb) kw = ad > __fdiv_rn(t_w, __fsqrt_rn(R.v[j]));
+            }
+            kw = ok && kw;
+            nf += ((f2u(R.v[j]) & 0x7f800000u) == 0x7f800000u);
             bw[j] = ballot64(kw);
-            bo[j] = ballot64(ko);
             cw += __popcll(bw[j]);
-            co += __popcll(bo[j]);
         }
         // keep bitmap of the residual: one ballot per 64 elements
         {
@@ -61,118 +111,166 @@ __global__ __launch_bounds__(EXCP_THREADS) __attribute__((amdgpu_waves_per_eu(4,
             const u64 nwords = excp_words(n);
             u64 mine = 0;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) if (lane == (u32)j) mine = bw[j];
-            u64 word = (base >> 6) + wave * 16 + lane;
+            for (int j = 0; j < NBATCH; ++j) if (lane == (u32)j) mine = bw[j];
+            const u64 word = (base >> 6) + wave * NBATCH + lane;
             // words past the last element carry an all-zero ballot: that is the 16-byte padding
-            if (lane < 16 && word < nwords + (nwords & 1ull)) bm[word] = mine;
+            if (lane < NBATCH && word < nwords + (nwords & 1ull)) bm[word] = mine;
         }
         nf = wave_sum_u32(nf);
         if (lane == 0) {
-            s_w[wave] = cw; s_o[wave] = co;
+            s_w[wave] = cw;
             if (nf) atomicAdd(&w.st[t].nonfinite, (u64)nf);
         }
         __syncthreads();
         const u32 tw = s_w[0] + s_w[1] + s_w[2] + s_w[3];
-        const u32 to = s_o[0] + s_o[1] + s_o[2] + s_o[3];
-
-        if (wave == 0) {
-            u32 ew = 0, eo = 0;
-            u64 *status = w.tile_status;
-            if (ltile != 0) {
-                if (lane == 0) st_status(&status[tile], pack_status(1, tw, to));
-                long long pos = (long long)tile - 1;
-                const long long first = (long long)D.tile_begin;
-                u32 spins = 0;
-                bool giveup = false;
-                u64 total = 0;                                   // packed: survivors << 31 | moment survivors
-                while (true) {
-                    // 256 predecessors per step: lane l reads tiles pos - l, pos - 64 - l, ...
-                    u64 sv[4];
+        // compact the residual survivors (index order) in LDS, each with its M_o flag
+        u32 pw = 0;
+        for (u32 q = 0; q < wave; ++q) pw += s_w[q];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        long long idx = pos - (long long)(q * 64 + lane);
-                        sv[q] = (idx >= first) ? ld_status(&status[idx]) : pack_status(2, 0, 0);
-                    }
-                    u64 part = 0;
-                    bool done = false, retry = false;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (done || retry) continue;
-                        const u32 flag = (u32)(sv[q] >> 62);
-                        const u64 m2 = ballot64(flag == 2u);
-                        const u64 m0 = ballot64(flag == 0u);
-                        u64 want = ~0ull;
-                        if (m2) { int L = __ffsll((long long)m2) - 1; want = (L == 63) ? ~0ull : ((1ull << (L + 1)) - 1ull); }
-                        if (m0 & want) { retry = true; continue; }
-                        if ((want >> lane) & 1ull) part += sv[q] & 0x3fffffffffffffffull;
-                        if (m2) done = true;
-                    }
-                    if (retry) {
-                        if (++spins > EXCP_SPIN_LIMIT) { giveup = true; break; }
-                        __builtin_amdgcn_s_sleep(1);
-                        continue;
-                    }
-                    total += wave_sum_u64(part);
-                    if (done) break;
-                    pos -= 256;
-                }
-                ew = (u32)(total >> 31);
-                eo = (u32)(total & 0x7fffffffull);
-                if (giveup && lane == 0) atomicExch(w.err_flag, 1);
+        for (int j = 0; j < NBATCH; ++j) {
+            const u64 mw = bw[j];
+            const bool kw = (mw >> lane) & 1ull;
+            const u32 rk = pw + __popcll(mw & lt_mask);
+            if (kw) {
+                l_w[rk] = R.w[j]; l_m[rk] = R.m[j]; l_v[rk] = R.v[j];
             }
-            if (lane == 0) {
-                st_status(&status[tile], pack_status(2, ew + tw, eo + to));
-                s_excl[0] = ew; s_excl[1] = eo;
-                if (base + EXCP_TILE >= n) { w.st[t].n_w = (u64)ew + tw; w.st[t].n_o = (u64)eo + to; }
-            }
+            pw += __popcll(mw);
         }
         __syncthreads();
-        u32 pw = s_excl[0], po = s_excl[1];
-        for (u32 q = 0; q < wave; ++q) { pw += s_w[q]; po += s_o[q]; }
+        // second compaction, over the survivors: those whose moments are kept (M_o).  Survivor p
+        // is handled by thread p % 256; a ballot over 64 consecutive survivors is one M_o word.
+        const u64 slot = D.elem_off + base;
+        EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
+        float mm[NBATCH], vv2[NBATCH]; u64 bo[NBATCH]; u32 co = 0;
+#pragma unroll
+        for (int j = 0; j < NBATCH; ++j) {
+            const u32 p = (wave * NBATCH + j) * 64 + lane;       // survivor position in the sub-tile
+            const bool in = p < tw;
+            mm[j] = in ? l_m[p] : 0.f;
+            vv2[j] = in ? l_v[p] : 0.f;
+            if (in) sw[p] = l_w[p];
+            bo[j] = ballot64(in && fabsf(mm[j]) > r_o);
+            co += __popcll(bo[j]);
+        }
+        if (lane < NBATCH) {
+            u64 mine = 0;
+#pragma unroll
+            for (int j = 0; j < NBATCH; ++j) if (lane == (u32)j) mine = bo[j];
+            const u32 wordi = wave * NBATCH + lane;
+            if (wordi < ((tw + 63u) >> 6)) w.mask_bo[(u64)sub * BO_WORDS + wordi] = mine;
+        }
+        if (lane == 0) s_o[wave] = co;
+        __syncthreads();
+        const u32 to = s_o[0] + s_o[1] + s_o[2] + s_o[3];
+        if (tid == 0) w.tile_status[sub] = ((u64)tw << 32) | (u64)to;
+        u32 po = 0;
+        for (u32 q = 0; q < wave; ++q) po += s_o[q];
+#pragma unroll
+        for (int j = 0; j < NBATCH; ++j) {
+            const u64 mo = bo[j];
+            if ((mo >> lane) & 1ull) {
+                const u32 ro = po + __popcll(mo & lt_mask);
+                sm[ro] = mm[j]; sv[ro] = vv2[j];
+            }
+            po += __popcll(mo);
+        }
+        __syncthreads();
+    };
 
-        float *__restrict__ xw = w.xw + D.elem_off;
-        float *__restrict__ xm = w.xm + D.elem_off;
-        float *__restrict__ xv = w.xv + D.elem_off;
-        // M_o restricted to the survivors, as a bit stream that starts at survivor position pw
+    auto sub_is_full = [&](u32 sub) -> bool {
+        const u32 tile = sub >> 1;
+        const u32 t = find_owner(s_tiles, g.ntensors, tile);
+        const u64 base = (u64)(tile - s_tiles[t]) * EXCP_TILE + (u64)(sub & 1u) * SUB;
+        return base + SUB <= w.desc[t].n;
+    };
+    Regs A;
+    for (u32 sub = blockIdx.x; sub < nsub; sub += gridDim.x) {
+        issue_loads(sub, A);
+        if (sub_is_full(sub)) compute(sub, A, std::true_type{}); else compute(sub, A, std::false_type{});
+    }
+}
+
+// Exclusive scan of the sub-tile counts of one tensor (one workgroup per tensor); the totals are
+// the tensor's n_w and n_o.  Counts are packed (survivors << 32 | moment survivors).
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupParams g) {
+    __shared__ u64 s_sum[EXCP_THREADS];
+    const u32 t = blockIdx.x, tid = threadIdx.x;
+    const TDesc &D = w.desc[t];
+    const u32 nsub = 2u * D.tile_count;
+    u64 *cnt = w.tile_status + 2ull * D.tile_begin;
+    u64 carry = 0;
+    for (u32 base = 0; base < nsub; base += EXCP_THREADS * 4) {
+        // four consecutive sub-tiles per thread
+        u64 v[4], local = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 i = base + tid * 4 + q;
+            v[q] = (i < nsub) ? cnt[i] : 0ull;
+            local += v[q];
+        }
+        s_sum[tid] = local;
+        __syncthreads();
+        for (int off = 1; off < EXCP_THREADS; off <<= 1) {
+            u64 a = (tid >= (u32)off) ? s_sum[tid - off] : 0ull;
+            __syncthreads();
+            s_sum[tid] += a;
+            __syncthreads();
+        }
+        u64 run = carry + s_sum[tid] - local;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32 i = base + tid * 4 + q;
+            if (i < nsub) w.mask_prefix[2ull * D.tile_begin + i] = run;
+            run += v[q];
+        }
+        carry += s_sum[EXCP_THREADS - 1];
+        __syncthreads();
+    }
+    if (tid == 0) { w.st[t].n_w = carry >> 32; w.st[t].n_o = carry & 0xffffffffull; }
+}
+
+// Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays and
+// merges the sub-tile's M_o bits into the blob at the survivor position.
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, GroupParams g) {
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 nsub = 2u * g.ntiles;
+    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
+    for (u32 sub = blockIdx.x * 4 + wave; sub < nsub; sub += gridDim.x * 4) {
+        const u64 c = w.tile_status[sub];
+        const u32 tw = (u32)(c >> 32), to = (u32)c;
+        if (tw == 0) continue;
+        const u32 t = find_owner(s_tiles, g.ntensors, sub >> 1);
+        const TDesc &D = w.desc[t];
+        const u64 n = D.n;
+        const u64 pre = w.mask_prefix[sub];
+        const u32 pw = (u32)(pre >> 32), po = (u32)pre;
+        const u64 base = (u64)(sub - 2u * s_tiles[t]) * SUB;
+        const u64 slot = D.elem_off + base;
+        const EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
+        EXCP_GLOBAL float *xw = gptr(w.xw) + D.elem_off + pw;
+        EXCP_GLOBAL float *xm = gptr(w.xm) + D.elem_off + po;
+        EXCP_GLOBAL float *xv = gptr(w.xv) + D.elem_off + po;
+        for (u32 i = lane; i < tw; i += 64) xw[i] = sw[i];
+        for (u32 i = lane; i < to; i += 64) { xm[i] = sm[i]; xv[i] = sv[i]; }
+        // M_o bits: the sub-tile's local stream shifted to survivor position pw
         const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n));
         u64 *bmo = (u64 *)(D.blob + off_bo);
         const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
-        u64 acc = 0;
-        u32 fill = pw & 63u;
-        u64 wordidx = pw >> 6;
-        bool first = true;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const u64 mw = bw[j], mo = bo[j];
-            const bool kw = (mw >> lane) & 1ull, ko = (mo >> lane) & 1ull;
-            const u32 nb = __popcll(mw);
-            const u32 rk = __popcll(mw & lt_mask);
-            const u32 ro = __popcll(mo & lt_mask);
-            if (kw) xw[pw + rk] = dv[j];
-            if (ko) { xm[po + ro] = mv[j]; xv[po + ro] = vv[j]; }
-            // move each survivor's M_o bit to lane = its rank among the survivors of this batch
-            const u32 dest = kw ? rk : nb + (lane - rk);
-            const int got = __builtin_amdgcn_ds_permute((int)(dest << 2), ko ? 1 : 0);
-            const u64 cbits = ballot64(got != 0);
-            if (nb) {
-                acc |= cbits << fill;
-                if (fill + nb >= 64u) {
-                    if (lane == 0 && wordidx < cap_words) {
-                        if (first) atomicOr(&bmo[wordidx], acc); else bmo[wordidx] = acc;
-                    }
-                    first = false;
-                    acc = fill ? (cbits >> (64u - fill)) : 0ull;
-                    ++wordidx;
-                    fill = fill + nb - 64u;
-                } else {
-                    fill += nb;
-                }
+        const u32 sh = pw & 63u;
+        const u32 nloc = (tw + 63u) >> 6;                         // local words that hold bits
+        const u32 nout = (sh + tw + 63u) >> 6;                    // words touched, <= 33
+        const u64 *loc = w.mask_bo + (u64)sub * BO_WORDS;
+        if (lane < nout) {
+            const u64 cur = lane < nloc ? loc[lane] : 0ull;
+            const u64 below = (lane > 0 && lane - 1 < nloc) ? loc[lane - 1] : 0ull;
+            const u64 bits = sh ? ((cur << sh) | (below >> (64u - sh))) : cur;
+            const u64 wi = (u64)(pw >> 6) + lane;
+            if (wi < cap_words) {
+                if (lane == 0 || lane + 1 == nout) { if (bits) atomicOr(&bmo[wi], bits); }
+                else bmo[wi] = bits;
             }
-            pw += nb;
-            po += __popcll(mo);
         }
-        if (fill && lane == 0 && wordidx < cap_words && acc) atomicOr(&bmo[wordidx], acc);
-        __syncthreads();
     }
 }
 
@@ -247,14 +345,25 @@ int query_persistent_grid(int device) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, device) != hipSuccess) return -1;
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_mask_compact, EXCP_THREADS, 0) != hipSuccess || nb <= 0)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_mask_slots, EXCP_THREADS, 0) != hipSuccess || nb <= 0)
         return -1;
     return nb * prop.multiProcessorCount;
 }
 
-void launch_mask_compact(const Workspace &w, const GroupParams &g, hipStream_t s) {
+void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hipStream_t s) {
     if (!g.ntiles) return;
-    hipLaunchKernelGGL(k_mask_compact, dim3(w.grid_persistent), dim3(EXCP_THREADS), 0, s, w, g);
+    const u32 nsub = 2u * g.ntiles;
+    if (phase == 0) {
+        u32 grid = (u32)w.grid_stream * 2u;
+        if (grid > nsub) grid = nsub;
+        hipLaunchKernelGGL(k_mask_slots, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+    } else if (phase == 1) {
+        hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
+    } else {
+        u32 grid = (nsub + 3) / 4;
+        if (grid > (u32)w.grid_stream * 8u) grid = (u32)w.grid_stream * 8u;
+        hipLaunchKernelGGL(k_mask_gather, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+    }
 }
 
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s) {
