@@ -26,9 +26,9 @@ def stage_bytes_per_param(p_w, p_o, nbits, iters):
     s = p_w + 2.0 * p_o
     bitmaps = 0.125 * (1.0 + p_w)
     return {
-        "stats_hist": 12.0 + 0.125,                       # read W_prev, W, m; clear the M_o bitmap region
-        "select_hist": 2 * 8.0,                            # two refinement passes over W_prev, W
-        "mask_compact": 16.0 + bitmaps + 4.0 * s,          # read all four arrays; write bitmaps + survivors
+        "stats_stream": 12.0 + 0.125,                      # read W_prev, W, m; clear the M_o bitmap region
+        "mask_slots": 16.0 + 0.125 + 4.0 * s,              # read all four arrays; write keep bitmap + survivor slots
+        "mask_gather": 8.0 * s + 0.125 * p_w,              # slots -> dense survivor arrays; M_o bitmap
         "km_count": 4.0 * s,                               # read the survivors, count per bucket
         "km_scatter": 8.0 * s,                             # read the survivors, write them bucket by bucket
         "km_bucket_stats": 4.0 * s,                        # read the partitioned survivors once

@@ -28,6 +28,8 @@ struct TDesc {
     u64 blob_cap;
     float *W_out;
     u64 elem_off;      // start of this tensor's survivor slots in the group workspace
+    u64 cand_off;      // start and capacity of this tensor's median-candidate list
+    u64 cand_cap;
     u32 tile_begin;    // first tile of this tensor in the group's tile list
     u32 tile_count;
 };
@@ -40,8 +42,11 @@ struct TState {
     u64 off_bo, off_cw, off_cm, off_cv, blob_bytes;
     double abs_sum;
     double obj[3];
-    u32 sel_prefix;             // median radix select: key prefix found so far
-    u32 sel_rank;               // rank still to find inside that prefix
+    u32 br_lo, br_hi;           // median bracket (keys) from the sorted sample
+    u32 med_state;              // 0 select among candidates pending, 1 median known, 2 full-tensor fallback
+    u32 cand_count, cand_overflow, c_lt;   // keys inside / overflowing the list / below the bracket
+    u32 sel_base, sel_width;    // radix select: key bits decided so far, number of undecided low bits
+    u32 sel_rank;               // rank still to find among the undecided keys
     u32 med_bits;
     float mean32, t_w, r_o;
     int status;
@@ -101,6 +106,7 @@ struct Workspace {
     float *xw, *xm, *xv;
     // median select
     u32 *med_hist;            // [tensor][2048]
+    u32 *cand;                // median candidates (keys inside the sample bracket), per tensor
     // look-back status words, one per tile
     u64 *tile_status;         // per 2048-element sub-tile: survivors << 32 | moment survivors
     u64 *mask_prefix;         // exclusive scan of tile_status within each tensor
@@ -132,8 +138,7 @@ struct Workspace {
 };
 
 void launch_zero_u32(u32 *p, u64 count, hipStream_t s);
-void launch_stats_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
-void launch_median_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s);
+void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);

@@ -17,12 +17,12 @@ constexpr u32 kMaxGroupTensors = 1024;   // tensors processed together (== EXCP_
 constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress call
 
 enum Stage {
-    ST_STATS = 0, ST_SELECT, ST_SELECT_RESOLVE, ST_MASK_COMPACT, ST_MASK_SCAN, ST_MASK_GATHER, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
+    ST_SAMPLE = 0, ST_STATS, ST_SELECT, ST_SELECT_FALLBACK, ST_MASK_COMPACT, ST_MASK_SCAN, ST_MASK_GATHER, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
     ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_CLASSIFY, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
     ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC, ST_COUNT
 };
 const char *kStageNames[ST_COUNT] = {
-    "stats_hist", "select_hist", "select_resolve", "mask_slots", "mask_scan", "mask_gather", "layout", "km_sample", "km_count", "km_scan",
+    "median_sample", "stats_stream", "select_candidates", "select_fallback", "mask_slots", "mask_scan", "mask_gather", "layout", "km_sample", "km_count", "km_scan",
     "km_scatter", "km_bucket_stats", "km_init", "km_classify", "km_iter", "km_update", "assign_pack", "finalize",
     "decode_prep", "decode_main", "misc"};
 
@@ -196,6 +196,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.xm, G);
     ok = ok && dev_alloc(c, &w.xv, G);
     ok = ok && dev_alloc(c, &w.med_hist, (u64)kMaxGroupTensors * 2048);
+    ok = ok && dev_alloc(c, &w.cand, G / 12 + 4096ull * kMaxGroupTensors + 16);
     ok = ok && dev_alloc(c, &w.tile_status, 2 * max_tiles);      // one word per 2048-element sub-tile
     ok = ok && dev_alloc(c, &w.mask_prefix, 2 * max_tiles);
     ok = ok && dev_alloc(c, &w.mask_bo, 2 * max_tiles * 32);
@@ -308,7 +309,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     u32 tb_off = 0;
     std::vector<u32> tb_offsets;
     for (const Group &g : groups) {
-        u64 elem_off = 0; u32 tile = 0;
+        u64 elem_off = 0, cand_off = 0; u32 tile = 0;
         tb_offsets.push_back(tb_off);
         for (u32 q = 0; q < g.count; ++q) {
             const excp_tensor &t = tensors[g.first + q];
@@ -316,6 +317,8 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
             d.Wp = t.W_prev_recon; d.W = t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
             d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = t.W_recon_out;
             d.elem_off = elem_off; d.tile_begin = tile;
+            d.cand_off = cand_off; d.cand_cap = t.n / 12 + 4096;
+            cand_off += d.cand_cap;
             d.tile_count = (u32)((t.n + EXCP_TILE - 1) / EXCP_TILE);
             c->h_tile_begin[tb_off + q] = tile;
             elem_off += t.n; tile += d.tile_count;
@@ -343,11 +346,17 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         GroupParams p{};
         p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
         p.ntensors = g.count; p.ntiles = g.ntiles;
-        { StageTimer t(c, ST_STATS); launch_stats_hist(w, p, 0, s); }
-        { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, 0, s); }
-        for (int pass = 1; pass <= 2; ++pass) {
-            { StageTimer t(c, ST_SELECT); launch_stats_hist(w, p, pass, s); }
-            { StageTimer t(c, ST_SELECT_RESOLVE); launch_median_resolve(w, p, pass, s); }
+        { StageTimer t(c, ST_SAMPLE); launch_stats(w, p, 0, s); }
+        { StageTimer t(c, ST_STATS); launch_stats(w, p, 1, s); }
+        {
+            StageTimer t(c, ST_SELECT);
+            launch_stats(w, p, 2, s);
+            for (int pass = 0; pass < 3; ++pass) { launch_stats(w, p, 3, s); launch_stats(w, p, 4, s); }
+        }
+        {
+            StageTimer t(c, ST_SELECT_FALLBACK);     // does nothing unless a sample bracket missed its median
+            for (int pass = 0; pass < 3; ++pass) { launch_stats(w, p, 5 + pass, s); launch_stats(w, p, 8 + pass, s); }
+            launch_stats(w, p, 11, s);
         }
         { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, 0, s); }
         { StageTimer t(c, ST_MASK_SCAN); launch_mask_compact(w, p, 1, s); }

@@ -48,6 +48,24 @@ __device__ __forceinline__ u32 bucket_of(const u32 *split, u32 key) {
     return lo < 255u ? lo : 255u;
 }
 
+// The same search for N keys at once, step by step: the N LDS reads of a step are independent and
+// overlap, instead of N chains of eight dependent reads.
+template <int N>
+__device__ __forceinline__ void bucket_of_many(const u32 *split, const u32 (&key)[N], u32 (&out)[N]) {
+#pragma unroll
+    for (int e = 0; e < N; ++e) out[e] = 0;
+#pragma unroll
+    for (u32 step = 128; step >= 1; step >>= 1) {
+        u32 probe[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) probe[e] = split[out[e] + step - 1];
+#pragma unroll
+        for (int e = 0; e < N; ++e) if (probe[e] <= key[e]) out[e] += step;
+    }
+#pragma unroll
+    for (int e = 0; e < N; ++e) out[e] = out[e] < 255u ? out[e] : 255u;
+}
+
 // ---------------------------------------------------------------- exact signed accumulation
 // Adds the values x[j] (j < N) with sel[j] set, for the whole wave, to a set of signed bins through
 // add(bin, delta): sum_g bins[g] * 2^(8g-149) grows by exactly the sum of the selected values.
@@ -208,10 +226,22 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_count(Workspace w, GroupPar
         const float *__restrict__ x = seg_data(w, sidx);
         const u64 len = S.len;
         const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
-#pragma unroll 8
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            u64 idx = base + (u64)it * EXCP_THREADS + tid;
-            if (idx < len) atomicAdd(&hist[bucket_of(split, key_of(x[idx]))], 1u);
+        const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
+        const EXCP_GLOBAL float *gx = gptr(x) + base;
+#pragma unroll
+        for (u32 half = 0; half < 2; ++half) {
+            u32 key[PER_THREAD / 2], bk[PER_THREAD / 2];
+#pragma unroll
+            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
+                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
+                key[it] = key_of(gx[e < clen ? e : 0]);
+            }
+            bucket_of_many<PER_THREAD / 2>(split, key, bk);
+#pragma unroll
+            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
+                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
+                if (e < clen) atomicAdd(&hist[bk[it]], 1u);
+            }
         }
         __syncthreads();
         w.km_cnt[(u64)c * NBKT + tid] = hist[tid];
@@ -291,18 +321,25 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupP
         const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
         const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
         float v[PER_THREAD];
-        unsigned char bk[PER_THREAD];
+        u32 bk[PER_THREAD];
+        const EXCP_GLOBAL float *gx = gptr(x) + base;
 #pragma unroll
         for (u32 it = 0; it < PER_THREAD; ++it) {
             u32 e = it * EXCP_THREADS + tid;
-            v[it] = (e < clen) ? x[base + e] : 0.f;
+            v[it] = gx[e < clen ? e : 0];
         }
 #pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            u32 e = it * EXCP_THREADS + tid;
-            u32 bb = bucket_of(split, key_of(v[it]));
-            bk[it] = (unsigned char)bb;
-            if (e < clen) atomicAdd(&hist[bb], 1u);
+        for (u32 half = 0; half < 2; ++half) {
+            u32 key[PER_THREAD / 2], out[PER_THREAD / 2];
+#pragma unroll
+            for (u32 it = 0; it < PER_THREAD / 2; ++it) key[it] = key_of(v[half * (PER_THREAD / 2) + it]);
+            bucket_of_many<PER_THREAD / 2>(split, key, out);
+#pragma unroll
+            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
+                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
+                bk[half * (PER_THREAD / 2) + it] = out[it];
+                if (e < clen) atomicAdd(&hist[out[it]], 1u);
+            }
         }
         __syncthreads();
         // exclusive scan of the 256 bucket counts

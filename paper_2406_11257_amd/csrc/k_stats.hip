@@ -1,6 +1,11 @@
 // Full-tensor statistics for the pruning thresholds of Sec. 3.2:
-//   * the lower median of |W_t - W_prev| per tensor (Eq. "r_w") by a three-pass radix-histogram
-//     select over the 31-bit magnitude keys (11 + 11 + 9 bits), histograms held in LDS;
+//   * the lower median of |W_t - W_prev| per tensor (Eq. "r_w"), exactly, in ONE pass over the
+//     tensor: a sorted sample of 8192 residuals brackets the median between two keys lo <= hi; the
+//     streaming pass counts the keys below lo and collects the few per cent of keys inside the
+//     bracket; a radix-histogram select (LDS histograms, 11 bits per pass) over those candidates
+//     then finds the order statistic.  The bracket can miss (probability below 1e-6 per tensor, or
+//     adversarial data); the counts reveal that, and the tensor then takes the always-correct
+//     fallback: a three-pass radix-histogram select over the whole tensor (11 + 11 + 9 key bits);
 //   * the exact sum of |m| per tensor (Eq. "r_o") by integer accumulation: every |m_i| is
 //     mant * 2^(pos-149); a wave adds its mantissas in a 40-bit exponent window as integers and
 //     files the result into per-tensor u64 bins 8 binary orders apart, so the sum is exact and
@@ -10,116 +15,202 @@
 
 namespace {
 
-template <int PASS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_stats_hist(Workspace w, GroupParams g) {
-    constexpr int NB = (PASS == 2) ? 512 : 2048;
-    __shared__ u32 hist[NB];
-    __shared__ u64 bins[EXCP_ABSM_BINS];
-    __shared__ u32 s_nf;
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u32 G = gridDim.x, b = blockIdx.x;
-    const u32 lo = (u32)(((u64)b * g.ntiles) / G), hi = (u32)(((u64)(b + 1) * g.ntiles) / G);
-    if (lo >= hi) return;
+#ifdef EXCP_TUNING
+#define TUNE(bit) ((g.flags >> (bit)) & 1u)
+#else
+#define TUNE(bit) 0u
+#endif
 
-    for (u32 i = tid; i < NB; i += EXCP_THREADS) hist[i] = 0;
+constexpr u32 MED_SAMPLE = 8192;      // sample size (and the size up to which a tensor is simply sorted)
+constexpr u32 MED_HALF_WIDTH = 256;   // bracket = sample ranks 4096 -+ 256 (about 5.6 sigma)
+constexpr u32 CAND_PER_WAVE = 1024;
+
+enum { MED_PENDING = 0, MED_KNOWN = 1, MED_FALLBACK = 2 };
+
+__device__ __forceinline__ void sort_keys_lds(u32 *key, u32 count_pow2) {
+    const u32 tid = threadIdx.x;
+    for (u32 k = 2; k <= count_pow2; k <<= 1) {
+        for (u32 j = k >> 1; j > 0; j >>= 1) {
+            for (u32 t = tid; t < count_pow2 / 2; t += EXCP_THREADS) {
+                u32 i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                u32 p = i | j;
+                u32 a = key[i], b = key[p];
+                bool asc = (i & k) == 0;
+                if ((a > b) == asc) { key[i] = b; key[p] = a; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// One workgroup per tensor: sample (or all) residual magnitudes, sorted.
+__global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, GroupParams g) {
+    __shared__ u32 key[MED_SAMPLE];
+    const u32 t = blockIdx.x, tid = threadIdx.x;
+    const TDesc &D = w.desc[t];
+    TState &S = w.st[t];
+    const u64 n = D.n;
+    if (n == 0) { if (tid == 0) { S.med_bits = 0; S.med_state = MED_KNOWN; } return; }
+    const u32 ns = n < MED_SAMPLE ? (u32)n : MED_SAMPLE;
+    for (u32 i = tid; i < MED_SAMPLE; i += EXCP_THREADS) {
+        u32 k = 0xffffffffu;
+        if (i < ns) {
+            const u64 idx = n <= MED_SAMPLE ? (u64)i : ((u64)i * n) / MED_SAMPLE;
+            k = f2u(D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+        }
+        key[i] = k;
+    }
+    __syncthreads();
+    sort_keys_lds(key, MED_SAMPLE);
+    if (tid == 0) {
+        if (n <= MED_SAMPLE) {
+            S.med_bits = key[(n - 1) >> 1];
+            S.med_state = MED_KNOWN;
+        } else {
+            S.br_lo = key[MED_SAMPLE / 2 - MED_HALF_WIDTH];
+            S.br_hi = key[MED_SAMPLE / 2 + MED_HALF_WIDTH];
+            S.med_state = MED_PENDING;
+        }
+    }
+}
+
+// The streaming pass: exact sum of |m|, non-finite check, count of keys below the bracket and
+// collection of the keys inside it.  Persistent workgroups over contiguous tile ranges.
+__global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, GroupParams g) {
+    __shared__ u64 bins[EXCP_ABSM_BINS];
+    __shared__ u32 l_cand[4][CAND_PER_WAVE];
+    __shared__ u32 s_nf, s_lt;
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u64 lt_mask = lanemask_lt();
+    const u32 G = gridDim.x, b = blockIdx.x;
+    const u32 lo_tile = (u32)(((u64)b * g.ntiles) / G), hi_tile = (u32)(((u64)(b + 1) * g.ntiles) / G);
+    if (lo_tile >= hi_tile) return;
     if (tid < EXCP_ABSM_BINS) bins[tid] = 0;
-    if (tid == 0) s_nf = 0;
+    if (tid == 0) { s_nf = 0; s_lt = 0; }
     __syncthreads();
 
-    u32 t = find_owner(w.tile_begin, g.ntensors, lo);
+    u32 t = find_owner(w.tile_begin, g.ntensors, lo_tile);
     u32 t_end = w.tile_begin[t + 1];
-    u32 nf = 0;
+    u32 nf = 0, clt = 0;           // clt is the same in every lane of a wave
 
     auto flush = [&](u32 tt) {
+        if (lane == 0 && clt) atomicAdd(&s_lt, clt);
+        if (nf) atomicAdd(&s_nf, nf);
+        nf = 0; clt = 0;
         __syncthreads();
-        for (u32 i = tid; i < NB; i += EXCP_THREADS) {
-            u32 c = hist[i];
-            if (c) { atomicAdd(&w.med_hist[(u64)tt * 2048u + i], c); hist[i] = 0; }
+        if (tid < EXCP_ABSM_BINS) {
+            u64 c = bins[tid];
+            if (c) { atomicAdd(&w.st[tt].absm[tid], c); bins[tid] = 0; }
         }
-        if (PASS == 0) {
-            if (tid < EXCP_ABSM_BINS) {
-                u64 c = bins[tid];
-                if (c) { atomicAdd(&w.st[tt].absm[tid], c); bins[tid] = 0; }
-            }
-            if (nf) atomicAdd(&s_nf, nf);
-            nf = 0;
-            __syncthreads();
-            if (tid == 0 && s_nf) { atomicAdd(&w.st[tt].nonfinite, (u64)s_nf); s_nf = 0; }
+        if (tid == 0) {
+            if (s_nf) { atomicAdd(&w.st[tt].nonfinite, (u64)s_nf); s_nf = 0; }
+            if (s_lt) { atomicAdd(&w.st[tt].c_lt, s_lt); s_lt = 0; }
         }
         __syncthreads();
     };
 
-    for (u32 tile = lo; tile < hi; ++tile) {
+    for (u32 tile = lo_tile; tile < hi_tile; ++tile) {
         if (tile >= t_end) {
             flush(t);
             t = find_owner(w.tile_begin, g.ntensors, tile);
             t_end = w.tile_begin[t + 1];
         }
         const TDesc &D = w.desc[t];
+        TState &S = w.st[t];
         const u64 n = D.n;
         const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
-        const float *__restrict__ Wp = D.Wp, *__restrict__ W = D.W, *__restrict__ M = D.m;
-        u32 prefix = 0;
-        if (PASS > 0) prefix = w.st[t].sel_prefix;
+        const bool pending = S.med_state == MED_PENDING;
+        const u32 klo = S.br_lo, khi = S.br_hi;
 
-        u32 key[16];
-        u32 mb[16];
+        u32 key[16], mb[16];
+        u32 worst = 0;             // largest magnitude pattern seen: >= 0x7f800000 means Inf or NaN
+        if (base + EXCP_TILE <= n) {
+            const u64 first = base + (u64)(wave * 1024 + lane);
+            const EXCP_GLOBAL float *gW = gptr(D.W) + first, *gP = gptr(D.Wp) + first, *gM = gptr(D.m) + first;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
-            bool ok = idx < n;
-            float a = ok ? W[idx] : 0.f;
-            float p = ok ? Wp[idx] : 0.f;
-            float d = a - p;
-            u32 k = f2u(d) & 0x7fffffffu;
-            key[j] = ok ? k : 0xffffffffu;
-            if (PASS == 0) {
-                float mm = ok ? M[idx] : 0.f;
+            for (int j = 0; j < 16; ++j) {
+                const float a = gW[j * 64], p = gP[j * 64], mm = gM[j * 64];
+                key[j] = f2u(a - p) & 0x7fffffffu;
                 mb[j] = f2u(mm) & 0x7fffffffu;
-                u32 bad = ((f2u(a) & 0x7f800000u) == 0x7f800000u) || ((f2u(p) & 0x7f800000u) == 0x7f800000u) ||
-                          ((mb[j] & 0x7f800000u) == 0x7f800000u) || ((k & 0x7f800000u) == 0x7f800000u);
-                nf += bad;
-                if (bad) mb[j] = 0;
+                worst = max(max(worst, key[j]), max(mb[j], max(f2u(a) & 0x7fffffffu, f2u(p) & 0x7fffffffu)));
             }
-        }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            u32 k = key[j];
-            if (k != 0xffffffffu) {
-                if (PASS == 0) atomicAdd(&hist[k >> 20], 1u);
-                if (PASS == 1) { if ((k >> 20) == prefix) atomicAdd(&hist[(k >> 9) & 2047u], 1u); }
-                if (PASS == 2) { if ((k >> 9) == prefix) atomicAdd(&hist[k & 511u], 1u); }
-            }
-        }
-        if (PASS == 0) {
-            // exact sum of |m| for this wave's 1024 values
-            u32 pmax = 0;
+        } else {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                u32 e = mb[j] >> 23;
-                u32 pos = (e ? e : 1u) - 1u;
-                if (mb[j]) pmax = max(pmax, pos);
+                const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
+                const bool ok = idx < n;
+                const float a = ok ? D.W[idx] : 0.f, p = ok ? D.Wp[idx] : 0.f, mm = ok ? D.m[idx] : 0.f;
+                const u32 k = f2u(a - p) & 0x7fffffffu;
+                mb[j] = f2u(mm) & 0x7fffffffu;
+                worst = max(max(worst, k), max(mb[j], max(f2u(a) & 0x7fffffffu, f2u(p) & 0x7fffffffu)));
+                key[j] = ok ? k : 0xffffffffu;            // above every bracket, never a candidate
             }
-            pmax = wave_max_u32(pmax);
-            const u32 B = pmax > 39u ? pmax - 39u : 0u;
-            u64 accL = 0, accH = 0;
+        }
+        if (!TUNE(18) && __any(worst >= 0x7f800000u)) {
+            // rare: something is not finite; it is reported and keeps out of the sum
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                u32 e = mb[j] >> 23;
-                u32 mant = (mb[j] & 0x7fffffu) | (e ? 0x800000u : 0u);
-                u32 pos = (e ? e : 1u) - 1u;
-                if (mant) {
-                    if (pos >= B) {
-                        u64 term = (u64)mant << (pos - B);
-                        accL += term & 0xffffffffull;
-                        accH += term >> 32;
-                    } else {
-                        atomicAdd(&bins[pos >> 3], (u64)mant << (pos & 7u));
-                    }
+                if (key[j] != 0xffffffffu && (key[j] & 0x7f800000u) == 0x7f800000u) nf += 1;
+                if ((mb[j] & 0x7f800000u) == 0x7f800000u) { nf += 1; mb[j] = 0; }
+            }
+            if (nf == 0 && worst >= 0x7f800000u) nf = 1;
+        }
+        if (pending && !TUNE(16)) {
+            u32 wcount = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                clt += __popcll(ballot64(key[j] < klo));
+                const bool cand = key[j] >= klo && key[j] <= khi;
+                const u64 bal = ballot64(cand);
+                if (bal) {
+                    if (cand) l_cand[wave][wcount + __popcll(bal & lt_mask)] = key[j];
+                    wcount += __popcll(bal);
                 }
             }
-            accL = wave_sum_u64(accL);
-            accH = wave_sum_u64(accH);
+            if (wcount) {
+                // this wave's candidates go to the tensor's list (one atomic per wave and tile)
+                u32 at = 0;
+                if (lane == 0) at = atomicAdd(&S.cand_count, wcount);
+                at = __shfl(at, 0, WAVE);
+                if ((u64)at + wcount <= D.cand_cap) {
+                    u32 *dst = w.cand + D.cand_off + at;
+                    for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
+                } else if (lane == 0) {
+                    atomicOr(&S.cand_overflow, 1u);
+                }
+            }
+        }
+        if (!TUNE(17)) {
+            // exact sum of |m| for this wave's 1024 values.  Values within 2^24 of the wave's largest
+            // are multiples of one unit and below 2^48 units, so sixteen of them add exactly in
+            // fp64; the sum is then split into integers and filed into the bins.  Smaller values
+            // (rare) go to the bins one by one.
+            u32 big = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) big = max(big, mb[j]);
+            big = wave_max_u32(big);
+            const u32 emax = big >> 23;
+            const u32 pmax = (emax ? emax : 1u) - 1u;
+            const u32 B = pmax > 23u ? pmax - 23u : 0u;                 // window base position
+            const u32 thr = B ? ((B + 1u) << 23) : 0u;                  // patterns with pos >= B
+            double dsum = 0.0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const bool in = mb[j] >= thr;
+                dsum += in ? (double)u2f(mb[j]) : 0.0;
+                if (!in && mb[j]) {
+                    const u32 e = mb[j] >> 23;
+                    const u32 mant = (mb[j] & 0x7fffffu) | (e ? 0x800000u : 0u);
+                    const u32 pos = (e ? e : 1u) - 1u;
+                    atomicAdd(&bins[pos >> 3], (u64)mant << (pos & 7u));
+                }
+            }
+            // dsum = units * 2^(B-149), units an integer below 2^52
+            const double units = ldexp(dsum, 149 - (int)B);
+            const u32 hi32 = (u32)(units * 2.3283064365386963e-10);     // floor(units / 2^32)
+            const u32 lo32 = (u32)(units - (double)hi32 * 4294967296.0);
+            u64 accL = wave_sum_u64((u64)lo32);
+            u64 accH = wave_sum_u64((u64)hi32);
             if (lane == 0) {
                 u64 lo64 = accL + (accH << 32);
                 u64 hi64 = (accH >> 32) + (lo64 < accL ? 1ull : 0ull);
@@ -141,6 +232,172 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_hist(Workspace w, GroupP
         }
     }
     flush(t);
+}
+
+// After the streaming pass: does the bracket hold the median?  If so the select goes on inside
+// the candidates (base key, number of undecided low bits, rank); if not the tensor falls back.
+__global__ void k_cand_begin(Workspace w, GroupParams g) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= g.ntensors) return;
+    TState &S = w.st[t];
+    if (S.med_state != MED_PENDING) return;
+    const u64 n = w.desc[t].n;
+    const u64 r = (n - 1) >> 1;
+    const u64 below = S.c_lt, cnt = S.cand_count;
+    if (S.cand_overflow || cnt > w.desc[t].cand_cap || r < below || r >= below + cnt) {
+        S.med_state = MED_FALLBACK;
+        return;
+    }
+    const u32 span = S.br_hi - S.br_lo;
+    S.sel_base = S.br_lo;
+    S.sel_width = span ? 32u - (u32)__clz((int)span) : 0u;
+    S.sel_rank = (u32)(r - below);
+    if (span == 0) { S.med_bits = S.br_lo; S.med_state = MED_KNOWN; }
+}
+
+// One radix pass over the candidates: histogram of the top (up to 11) undecided bits.
+__global__ __launch_bounds__(EXCP_THREADS) void k_cand_hist(Workspace w, GroupParams g) {
+    __shared__ u32 hist[2048];
+    const u32 tid = threadIdx.x;
+    for (u32 i = tid; i < 2048; i += EXCP_THREADS) hist[i] = 0;
+    __syncthreads();
+    for (u32 t = 0; t < g.ntensors; ++t) {
+        const TState &S = w.st[t];
+        if (S.med_state != MED_PENDING || S.sel_width == 0) continue;
+        const u32 cnt = S.cand_count, base = S.sel_base, width = S.sel_width;
+        const u32 shift = width > 11u ? width - 11u : 0u;
+        const u64 limit = 1ull << width;
+        const u32 *c = w.cand + w.desc[t].cand_off;
+        bool any = false;
+        for (u32 i = blockIdx.x * EXCP_THREADS + tid; i < cnt; i += gridDim.x * EXCP_THREADS) {
+            const u32 rel = c[i] - base;                  // keys below base wrap around and drop out
+            if ((u64)rel < limit) atomicAdd(&hist[rel >> shift], 1u);
+            any = true;
+        }
+        if (__syncthreads_or(any)) {
+            for (u32 i = tid; i < 2048; i += EXCP_THREADS) {
+                u32 v = hist[i];
+                if (v) { atomicAdd(&w.med_hist[(u64)t * 2048u + i], v); hist[i] = 0; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ __launch_bounds__(EXCP_THREADS) void k_cand_resolve(Workspace w, GroupParams g) {
+    __shared__ u32 s_sum[EXCP_THREADS];
+    const u32 t = blockIdx.x, tid = threadIdx.x;
+    TState &S = w.st[t];
+    if (S.med_state != MED_PENDING || S.sel_width == 0) return;
+    u32 *H = w.med_hist + (u64)t * 2048u;
+    const u32 width = S.sel_width, shift = width > 11u ? width - 11u : 0u, rank = S.sel_rank, base = S.sel_base;
+    u32 c[8], local = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { c[i] = H[tid * 8 + i]; local += c[i]; H[tid * 8 + i] = 0; }
+    s_sum[tid] = local;
+    __syncthreads();
+    for (int off = 1; off < EXCP_THREADS; off <<= 1) {
+        u32 v = (tid >= (u32)off) ? s_sum[tid - off] : 0u;
+        __syncthreads();
+        s_sum[tid] += v;
+        __syncthreads();
+    }
+    const u32 before = s_sum[tid] - local;
+    if (rank >= before && rank < before + local) {           // exactly one thread
+        u32 r = rank - before;
+        int i = 0;
+        while (r >= c[i]) { r -= c[i]; ++i; }
+        const u32 nb = base + ((u32)(tid * 8 + i) << shift);
+        S.sel_base = nb;
+        S.sel_width = shift;
+        S.sel_rank = r;
+        if (shift == 0) { S.med_bits = nb; S.med_state = MED_KNOWN; }
+    }
+}
+
+// ---------------------------------------------------------------- fallback: select over the whole tensor
+template <int PASS>
+__global__ __launch_bounds__(EXCP_THREADS) void k_full_hist(Workspace w, GroupParams g) {
+    constexpr int NB = (PASS == 2) ? 512 : 2048;
+    __shared__ u32 hist[NB];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 G = gridDim.x, b = blockIdx.x;
+    const u32 lo = (u32)(((u64)b * g.ntiles) / G), hi = (u32)(((u64)(b + 1) * g.ntiles) / G);
+    if (lo >= hi) return;
+    for (u32 i = tid; i < NB; i += EXCP_THREADS) hist[i] = 0;
+    __syncthreads();
+    u32 t = find_owner(w.tile_begin, g.ntensors, lo);
+    u32 t_end = w.tile_begin[t + 1];
+    bool active = w.st[t].med_state == MED_FALLBACK;
+    auto flush = [&](u32 tt) {
+        __syncthreads();
+        if (active)
+            for (u32 i = tid; i < NB; i += EXCP_THREADS) {
+                u32 c = hist[i];
+                if (c) { atomicAdd(&w.med_hist[(u64)tt * 2048u + i], c); hist[i] = 0; }
+            }
+        __syncthreads();
+    };
+    for (u32 tile = lo; tile < hi; ++tile) {
+        if (tile >= t_end) {
+            flush(t);
+            t = find_owner(w.tile_begin, g.ntensors, tile);
+            t_end = w.tile_begin[t + 1];
+            active = w.st[t].med_state == MED_FALLBACK;
+        }
+        if (!active) { tile = t_end - 1; continue; }          // skip the rest of this tensor
+        const TDesc &D = w.desc[t];
+        const u64 n = D.n;
+        const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
+        const u32 prefix = PASS > 0 ? w.st[t].sel_base : 0u;
+#pragma unroll 4
+        for (int j = 0; j < 16; ++j) {
+            const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
+            if (idx < n) {
+                const u32 k = f2u(D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+                if (PASS == 0) atomicAdd(&hist[k >> 20], 1u);
+                if (PASS == 1) { if ((k >> 20) == prefix) atomicAdd(&hist[(k >> 9) & 2047u], 1u); }
+                if (PASS == 2) { if ((k >> 9) == prefix) atomicAdd(&hist[k & 511u], 1u); }
+            }
+        }
+    }
+    flush(t);
+}
+
+template <int PASS>
+__global__ __launch_bounds__(EXCP_THREADS) void k_full_resolve(Workspace w, GroupParams g) {
+    constexpr int NB = (PASS == 2) ? 512 : 2048;
+    constexpr int PER = NB / EXCP_THREADS;
+    __shared__ u32 s_sum[EXCP_THREADS];
+    const u32 t = blockIdx.x, tid = threadIdx.x;
+    const u64 n = w.desc[t].n;
+    TState &S = w.st[t];
+    if (S.med_state != MED_FALLBACK) return;
+    u32 *H = w.med_hist + (u64)t * 2048u;
+    const u32 rank = (PASS == 0) ? (u32)((n - 1) >> 1) : S.sel_rank;
+    const u32 prefix = (PASS == 0) ? 0u : S.sel_base;
+    u32 c[PER], local = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { c[i] = H[tid * PER + i]; local += c[i]; H[tid * PER + i] = 0; }
+    s_sum[tid] = local;
+    __syncthreads();
+    for (int off = 1; off < EXCP_THREADS; off <<= 1) {
+        u32 v = (tid >= (u32)off) ? s_sum[tid - off] : 0u;
+        __syncthreads();
+        s_sum[tid] += v;
+        __syncthreads();
+    }
+    const u32 before = s_sum[tid] - local;
+    if (rank >= before && rank < before + local) {           // exactly one thread
+        u32 r = rank - before;
+        int i = 0;
+        while (r >= c[i]) { r -= c[i]; ++i; }
+        const u32 bin = tid * PER + i;
+        const u32 np = (PASS == 2) ? ((prefix << 9) | bin) : ((prefix << 11) | bin);
+        S.sel_base = np;
+        S.sel_rank = r;
+        if (PASS == 2) { S.med_bits = np; S.med_state = MED_KNOWN; }
+    }
 }
 
 // Exact sum: bins[g] * 2^(8g-149) summed as one big integer, rounded once (to nearest, ties to
@@ -182,54 +439,21 @@ __device__ double absm_bins_to_double(const u64 *bins) {
     return ldexp((double)mant, msb - 52 - 149);
 }
 
-template <int PASS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_median_resolve(Workspace w, GroupParams g) {
-    constexpr int NB = (PASS == 2) ? 512 : 2048;
-    constexpr int PER = NB / EXCP_THREADS;
-    __shared__ u32 s_sum[EXCP_THREADS];
-    const u32 t = blockIdx.x, tid = threadIdx.x;
-    const u64 n = w.desc[t].n;
+// The two thresholds of every tensor: t_w = alpha * median, r_o = beta * fp32(exact sum / n).
+__global__ void k_thresholds(Workspace w, GroupParams g) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= g.ntensors) return;
     TState &S = w.st[t];
-    u32 *H = w.med_hist + (u64)t * 2048u;
-    if (n == 0) {
-        if (tid == 0 && PASS == 2) { S.med_bits = 0; S.mean32 = 0.f; S.t_w = 0.f; S.r_o = 0.f; S.abs_sum = 0.0; }
-        return;
-    }
-    u32 rank = (PASS == 0) ? (u32)((n - 1) >> 1) : S.sel_rank;
-    u32 prefix = (PASS == 0) ? 0u : S.sel_prefix;
-    u32 c[PER], local = 0;
-#pragma unroll
-    for (int i = 0; i < PER; ++i) { c[i] = H[tid * PER + i]; local += c[i]; H[tid * PER + i] = 0; }
-    s_sum[tid] = local;
-    __syncthreads();
-    // exclusive prefix of the per-thread sums (256 values; a plain doubling scan)
-    for (int off = 1; off < EXCP_THREADS; off <<= 1) {
-        u32 v = (tid >= (u32)off) ? s_sum[tid - off] : 0u;
-        __syncthreads();
-        s_sum[tid] += v;
-        __syncthreads();
-    }
-    u32 before = s_sum[tid] - local;
-    if (rank >= before && rank < before + local) {           // exactly one thread
-        u32 r = rank - before;
-        int i = 0;
-        while (r >= c[i]) { r -= c[i]; ++i; }
-        u32 bin = tid * PER + i;
-        u32 np = (PASS == 2) ? ((prefix << 9) | bin) : ((prefix << 11) | bin);
-        S.sel_prefix = np;
-        S.sel_rank = r;
-        if (PASS == 2) {
-            S.med_bits = np;
-            float med = u2f(np);
-            S.t_w = __fmul_rn(g.alpha, med);
-            double sum = absm_bins_to_double(S.absm);
-            double mean64 = sum / (double)n;
-            float mean32 = (float)mean64;
-            S.abs_sum = sum;
-            S.mean32 = mean32;
-            S.r_o = __fmul_rn(g.beta, mean32);
-        }
-    }
+    const u64 n = w.desc[t].n;
+    if (n == 0) { S.med_bits = 0; S.mean32 = 0.f; S.t_w = 0.f; S.r_o = 0.f; S.abs_sum = 0.0; return; }
+    const float med = u2f(S.med_bits);
+    S.t_w = __fmul_rn(g.alpha, med);
+    const double sum = absm_bins_to_double(S.absm);
+    const double mean64 = sum / (double)n;
+    const float mean32 = (float)mean64;
+    S.abs_sum = sum;
+    S.mean32 = mean32;
+    S.r_o = __fmul_rn(g.beta, mean32);
 }
 
 __global__ void k_zero_u32(u32 *p, u64 count) {
@@ -247,18 +471,25 @@ void launch_zero_u32(u32 *p, u64 count, hipStream_t s) {
     hipLaunchKernelGGL(k_zero_u32, dim3((u32)blocks), dim3(256), 0, s, p, count);
 }
 
-void launch_stats_hist(const Workspace &w, const GroupParams &g, int pass, hipStream_t s) {
-    if (!g.ntiles) return;
-    dim3 grid(w.grid_stream), block(EXCP_THREADS);
-    if (pass == 0) hipLaunchKernelGGL(k_stats_hist<0>, grid, block, 0, s, w, g);
-    else if (pass == 1) hipLaunchKernelGGL(k_stats_hist<1>, grid, block, 0, s, w, g);
-    else hipLaunchKernelGGL(k_stats_hist<2>, grid, block, 0, s, w, g);
-}
-
-void launch_median_resolve(const Workspace &w, const GroupParams &g, int pass, hipStream_t s) {
+// phase 0: sample, 1: streaming pass, 2: bracket check, 3: candidate histogram, 4: candidate resolve,
+// 5..7: fallback histograms, 8..10: fallback resolves, 11: thresholds
+void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream_t s) {
     if (!g.ntensors) return;
-    dim3 grid(g.ntensors), block(EXCP_THREADS);
-    if (pass == 0) hipLaunchKernelGGL(k_median_resolve<0>, grid, block, 0, s, w, g);
-    else if (pass == 1) hipLaunchKernelGGL(k_median_resolve<1>, grid, block, 0, s, w, g);
-    else hipLaunchKernelGGL(k_median_resolve<2>, grid, block, 0, s, w, g);
+    const dim3 block(EXCP_THREADS), per_tensor(g.ntensors), small((g.ntensors + 255) / 256);
+    const dim3 stream_grid(w.grid_stream);
+    switch (phase) {
+        case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, block, 0, s, w, g); break;
+        case 1: if (g.ntiles) hipLaunchKernelGGL(k_stats_stream, stream_grid, block, 0, s, w, g); break;
+        case 2: hipLaunchKernelGGL(k_cand_begin, small, dim3(256), 0, s, w, g); break;
+        case 3: hipLaunchKernelGGL(k_cand_hist, dim3(1024), block, 0, s, w, g); break;
+        case 4: hipLaunchKernelGGL(k_cand_resolve, per_tensor, block, 0, s, w, g); break;
+        case 5: if (g.ntiles) hipLaunchKernelGGL(k_full_hist<0>, stream_grid, block, 0, s, w, g); break;
+        case 6: if (g.ntiles) hipLaunchKernelGGL(k_full_hist<1>, stream_grid, block, 0, s, w, g); break;
+        case 7: if (g.ntiles) hipLaunchKernelGGL(k_full_hist<2>, stream_grid, block, 0, s, w, g); break;
+        case 8: hipLaunchKernelGGL(k_full_resolve<0>, per_tensor, block, 0, s, w, g); break;
+        case 9: hipLaunchKernelGGL(k_full_resolve<1>, per_tensor, block, 0, s, w, g); break;
+        case 10: hipLaunchKernelGGL(k_full_resolve<2>, per_tensor, block, 0, s, w, g); break;
+        case 11: hipLaunchKernelGGL(k_thresholds, small, dim3(256), 0, s, w, g); break;
+        default: break;
+    }
 }

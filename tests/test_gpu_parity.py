@@ -97,6 +97,27 @@ def test_degenerate_inputs(ctx):
     assert out[0]["stats"].n_w == n - 1 - (n - 1) // 2
 
 
+def test_median_fallback_when_the_sample_bracket_misses(ctx):
+    # the library brackets the median with a sorted sample of 8192 residuals taken at positions
+    # (i * n) // 8192; here exactly those positions are unrepresentative, so the bracket misses and the
+    # full-tensor select must take over -- the answer is still the exact order statistic
+    cases = []
+    for n, seed in ((100003, 1), (1 << 20, 2), (9000, 3)):
+        Wp, W, m, v = case(n, 200 + seed)
+        pos = (np.arange(8192, dtype=np.int64) * n) // 8192
+        W2 = W.copy()
+        W2[pos] = (Wp[pos] + f32(0.5)).astype(f32)        # every sampled residual is huge
+        cases.append((Wp, W2, m, v))
+        W3 = W.copy()
+        W3[pos] = Wp[pos]                                  # every sampled residual is zero
+        cases.append((Wp, W3, m, v))
+    # many equal values around the median (the bracket collapses to one key)
+    Wp, W, m, v = case(300000, 210)
+    W4 = W.copy(); W4[::2] = (Wp[::2] + f32(1e-4)).astype(f32)
+    cases.append((Wp, W4, m, v))
+    check_all(ctx, cases, iters=2)
+
+
 def test_mean_is_exact_and_independent_of_order(ctx):
     n = 300000
     Wp, W, m, v = case(n, 41)
