@@ -11,6 +11,7 @@ SOURCES = ["excp_host.hip", "k_stats.hip", "k_mask.hip", "k_kmeans.hip", "k_deco
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                       # every fp operation rounds once, as the method is defined
+    "-fhip-fp32-correctly-rounded-divide-sqrt",  # sqrtf and '/' are IEEE correctly rounded (thresholds are bit-exact)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]

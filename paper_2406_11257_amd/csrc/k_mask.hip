@@ -98,7 +98,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_slots(Workspace w, GroupP
                              !__builtin_amdgcn_classf(ra, 0x100);
             bool kw = sure_keep;
             if (__any(amb)) {
-                if (amb) kw = ad > __fdiv_rn(t_w, __fsqrt_rn(R.v[j]));
+                // sqrtf and '/' are the correctly rounded forms (the build passes
+                // -fhip-fp32-correctly-rounded-divide-sqrt); __fsqrt_rn is NOT on this target
+                if (amb) kw = ad > t_w / sqrtf(R.v[j]);
             }
             kw = ok && kw;
             nf += ((f2u(R.v[j]) & 0x7f800000u) == 0x7f800000u);

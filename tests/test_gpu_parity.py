@@ -161,6 +161,50 @@ def test_runs_are_deterministic(ctx):
     assert blobs[0] == blobs[1] == blobs[2]
 
 
+def test_reconstruction_is_stable_over_repeated_multi_tensor_batches(ctx):
+    # the reconstruction written by compress must equal Alg. 2 applied to the blob, every time,
+    # also when the same device buffers are reused by later batches
+    cases = [case(100000, 301), case(1048593, 302), case(77, 303)]
+    for rep in range(4):
+        rc, out = gpu_compress(ctx, cases)
+        assert rc == 0
+        for c, o in zip(cases, out):
+            Wr, _, _ = O.decompress_step(c[0], o["blob"])
+            assert np.array_equal(o["W_recon"].view(np.uint32), Wr.view(np.uint32)), rep
+
+
+def test_thresholds_decided_exactly_at_the_boundary(ctx):
+    # residuals placed within two units in the last place of their own threshold: the mask must
+    # follow the correctly rounded fp32 sqrt and divide, for normal, tiny and huge second moments
+    n_test = 1 << 21
+    g = np.random.default_rng(77)
+    cases, alphas = [], []
+    for lo_exp, hi_exp, t_w in ((-40, -10, 3e-9), (-126, 120, 1e-3), (-149, -120, 1e-30), (-20, 0, 7.3e-7)):
+        vb = np.exp2(g.uniform(lo_exp, hi_exp, n_test)).astype(f32)
+        with np.errstate(all="ignore"):
+            r = (f32(t_w) / np.sqrt(vb)).astype(f32)
+        k = g.integers(-2, 3, n_test)
+        d = r.copy()
+        for step in (1, 2):
+            up = k >= step
+            dn = k <= -step
+            d[up] = np.nextafter(d[up], f32(np.inf))
+            d[dn] = np.nextafter(d[dn], f32(0))
+        d = np.where(np.isfinite(d), d, f32(1e30)).astype(f32)
+        d *= g.choice(np.array([-1, 1], f32), n_test)
+        # n_test + 1 residuals equal to 1 make the median exactly 1, so t_w = alpha
+        W = np.concatenate([np.ones(n_test + 1, f32), d]).astype(f32)
+        v = np.concatenate([np.exp2(g.uniform(lo_exp, hi_exp, n_test + 1)).astype(f32), vb]).astype(f32)
+        m = (g.standard_normal(W.size) * 5e-5).astype(f32)
+        cases.append((np.zeros(W.size, f32), W, m, v))
+        alphas.append(t_w)
+    for c, a in zip(cases, alphas):
+        rc, out = gpu_compress(ctx, [c], alpha=a, iters=0, want_recon=False)
+        assert rc == 0
+        ref, _ = compare_with_oracle(c, out[0], a, 2.0, 4, 0)
+        assert ref.median == 1 and 0 < ref.n_w < c[0].size
+
+
 def test_in_place_reconstruction_and_single_tensor_calls(ctx):
     Wp, W, m, v = case(123457, 81)
     ref = O.compress_step(Wp, W, m, v)
