@@ -43,6 +43,26 @@ def survey_step_bytes_per_param(p_w, p_o):
     return 32.2 + 58.5 * s + 8.0
 
 
+STAGE_KERNEL = {"stats_stream": "k_stats_stream", "mask_slots": "k_mask_slots", "mask_gather": "k_mask_gather",
+                "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats",
+                "assign_pack": "k_assign_pack", "decode_main": "k_decode_main"}
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the committed counter summary (profiles/hbm_traffic.txt:
+    lines 'traffic <workload> <kernel> <fetch bytes> <write bytes>', already scaled by the copy-kernel
+    calibration), or None when that kernel / workload has not been measured."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as f:
+            for line in f:
+                p = line.split()
+                if len(p) == 5 and p[0] == "traffic" and p[1] == workload and p[2] == kernel:
+                    return float(p[3]) + float(p[4])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,9 +173,11 @@ def main():
         stage_report[k] = e
     dominant = max((k for k in stage_report if k in per_param), key=lambda k: stage_report[k]["ms_per_step"])
     d = stage_report[dominant]
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": d["achieved_GBs"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": d["achieved_GBs"] / HBM_PEAK_GBS, "traffic": None,
+    roofline = {"bound": "hbm", "kernel": STAGE_KERNEL[dominant], "achieved": d["achieved_GBs"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["achieved_GBs"] / HBM_PEAK_GBS,
+                "traffic": measured_traffic(STAGE_KERNEL[dominant], cfg.name),
                 "avg_launch_ms": d["ms_per_step"] / d["launches_per_step"],
+                "algorithmic_bytes_per_launch": per_param[dominant] * N / d["launches_per_step"],
                 "algorithmic_bytes_per_param": per_param[dominant]}
     step_bytes = survey_step_bytes_per_param(p_w, p_o) * N
     step_frac = step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
@@ -172,6 +194,11 @@ def main():
         ctx.excp_collect()
     torch.cuda.synchronize()
     dec_ms = (time.perf_counter() - t1) * 1e3 / max(1, args.steps)
+
+    # one plain copy of known size (1 GiB read + 1 GiB written): calibrates profiler byte counters
+    probe = min(N * 4, 1 << 30) & ~15
+    ctx.excp_copy_probe(flat[4], flat[0], probe)
+    torch.cuda.synchronize()
 
     # ---- CPU oracle on a bounded sample of the same workload -----------------------------------------
     cpu = None

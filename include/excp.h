@@ -125,7 +125,7 @@ typedef struct {
 /* Create a context on `hip_device`, working on `hip_stream` (a hipStream_t, borrowed; NULL = the
  * default stream).  `max_tensor_elems` bounds one tensor (<= EXCP_MAX_TENSOR_ELEMS);
  * `max_group_elems` (>= max_tensor_elems) is how many elements are processed together: the
- * workspace is about 12.3 bytes per group element, and a larger batch is run as several groups. */
+ * workspace is about 25 bytes per group element, and a larger batch is run as several groups. */
 int excp_create(excp_ctx **out, int hip_device, void *hip_stream,
                 uint64_t max_tensor_elems, uint64_t max_group_elems);
 void excp_destroy(excp_ctx *ctx);
@@ -163,6 +163,11 @@ int         excp_set_profiling(excp_ctx *ctx, int enabled);
 int         excp_stage_count(void);
 const char *excp_stage_name(int i);
 int         excp_stage_ms(excp_ctx *ctx, int i, double *ms, int *launches);
+
+/* Measurement aid: a plain device-to-device copy of nbytes (multiple of 16, both pointers 16-B
+ * aligned) on the context's stream, asynchronous.  Its HBM traffic is exactly nbytes read and
+ * nbytes written, which calibrates a profiler's byte counters. */
+int excp_copy_probe(excp_ctx *ctx, void *dst, const void *src, uint64_t nbytes);
 
 /* Bytes of device workspace the context holds. */
 uint64_t excp_workspace_bytes(const excp_ctx *ctx);

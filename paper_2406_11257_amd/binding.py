@@ -55,6 +55,7 @@ SYMBOLS = {
     "excp_stage_name": (C.c_char_p, [C.c_int]),
     "excp_stage_ms": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     "excp_workspace_bytes": (C.c_uint64, [C.c_void_p]),
+    "excp_copy_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64]),
     "excp_strerror": (C.c_char_p, [C.c_int]),
 }
 
@@ -222,6 +223,11 @@ class Context:
         if check and rc != EXCP_OK:
             raise ExcpError(rc, "excp_decompress_step")
         return rc
+
+    def excp_copy_probe(self, dst, src, nbytes: int):
+        rc = lib().excp_copy_probe(self._h, _ptr(dst), _ptr(src), nbytes)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_copy_probe")
 
     # -- timing ----------------------------------------------------------------------
     def excp_set_profiling(self, enabled: bool):

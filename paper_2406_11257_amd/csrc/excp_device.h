@@ -138,6 +138,7 @@ struct Workspace {
 };
 
 void launch_zero_u32(u32 *p, u64 count, hipStream_t s);
+void launch_copy_probe(const void *src, void *dst, u64 bytes, hipStream_t s);
 void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);

@@ -266,6 +266,13 @@ void excp_destroy(excp_ctx *c) {
 
 uint64_t excp_workspace_bytes(const excp_ctx *c) { return c ? c->ws_bytes : 0; }
 
+int excp_copy_probe(excp_ctx *c, void *dst, const void *src, uint64_t nbytes) {
+    if (!c || !dst || !src || (nbytes & 15u) || (((uintptr_t)dst | (uintptr_t)src) & 15u)) return EXCP_E_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+    launch_copy_probe(src, dst, nbytes, c->stream);
+    return hipGetLastError() == hipSuccess ? EXCP_OK : EXCP_E_HIP;
+}
+
 int excp_set_profiling(excp_ctx *c, int enabled) {
     if (!c) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;

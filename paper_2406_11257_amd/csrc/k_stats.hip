@@ -462,7 +462,21 @@ __global__ void k_zero_u32(u32 *p, u64 count) {
     for (; i < count; i += stride) p[i] = 0u;
 }
 
+// Plain streaming copy of 16-byte words: a kernel whose HBM traffic is known exactly (bytes read =
+// bytes written = the size), used to calibrate the profiler's byte counters.
+__global__ __launch_bounds__(256) void k_copy_probe(const uint4 *__restrict__ src, uint4 *__restrict__ dst, u64 count) {
+    u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) dst[i] = src[i];
+}
+
 }  // namespace
+
+void launch_copy_probe(const void *src, void *dst, u64 bytes, hipStream_t s) {
+    const u64 count = bytes / 16;
+    if (!count) return;
+    hipLaunchKernelGGL(k_copy_probe, dim3(8192), dim3(256), 0, s, (const uint4 *)src, (uint4 *)dst, count);
+}
 
 void launch_zero_u32(u32 *p, u64 count, hipStream_t s) {
     if (!count) return;
