@@ -128,153 +128,194 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 n
     }
 }
 
-// Code j of an nbits-wide little-endian bit stream.  Both words are always loaded (the second one
-// clamped to the last word) so that no load sits behind a data-dependent branch.
-__device__ __forceinline__ u32 extract_code(u64 w0, u64 w1, u32 sh, u32 nbits) {
-    u64 v = w0 >> sh;
-    if (sh) v |= w1 << (64u - sh);
-    return (u32)(v & ((1ull << nbits) - 1ull));
+// Four consecutive floats at an address that is only known to be 4-byte aligned.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
+#define DEC_CODE_WORDS 1032   // u32 words of one tile's codes: 4096 codes x 8 bits / 32 + slack
+#define DEC_OBIT_WORDS 136    // u32 words of bitmap_o covering one tile's survivors: 4096 / 32 + slack
+
+// Stage u32 words [first, first + count) of a blob section into LDS.
+__device__ __forceinline__ void stage_words(u32 *dst, const EXCP_GLOBAL u32 *src, u32 count) {
+    for (u32 i = threadIdx.x; i < count; i += EXCP_THREADS) dst[i] = src[i];
 }
 
+// 32 stream bits starting at bit p of a staged word array (p / 32 + 1 must be inside the array).
+__device__ __forceinline__ u32 window32(const u32 *s, u32 p) {
+    const u32 i = p >> 5;
+    return __builtin_amdgcn_alignbit(s[i + 1], s[i], p & 31u);
+}
+
+// One tile (4096 elements) per workgroup iteration.  Each wave scans the tile's 64 bitmap words,
+// the workgroup stages the tile's contiguous run of packed codes (and, for the moments, the run of
+// bitmap_o bits of its survivors with their prefix counts) in LDS, then every lane reconstructs four
+// consecutive elements: the codes of its survivors are consecutive fields of the staged stream, so
+// one 32-bit window read per lane holds all of them.
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
     __shared__ float s_book[3 * 256];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    __shared__ u32 s_cw[DEC_CODE_WORDS];
+    __shared__ u32 s_cm[MOMENTS ? DEC_CODE_WORDS : 1], s_cv[MOMENTS ? DEC_CODE_WORDS : 1];
+    __shared__ u32 s_ow[MOMENTS ? DEC_OBIT_WORDS : 1], s_oex[MOMENTS ? DEC_OBIT_WORDS : 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u64 lt_mask = lanemask_lt();
     u32 cur_t = 0xffffffffu;
     load_tile_table(s_tiles, w.tile_begin, ntensors);
     for (u32 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
         const u32 t = find_owner(s_tiles, ntensors, tile);
         const DDesc &D = w.ddesc[t];
         const DState &S = w.dst[t];
-        if (S.status != 0) continue;
-        const u32 nbits = S.nbits, E = 1u << nbits;
-        if (t != cur_t) {
-            __syncthreads();
-            const float *books = (const float *)(D.blob + EXCP_HEADER);
-            for (u32 i = tid; i < 3u * E; i += EXCP_THREADS) s_book[(i / E) * 256u + (i % E)] = books[i];
-            cur_t = t;
-            __syncthreads();
-        }
+        if (S.status != 0) continue;                       // same decision for the whole workgroup
+        const u32 nbits = S.nbits, E = 1u << nbits, cmask = E - 1u;
         const u64 n = D.n;
         const u32 ltile = tile - D.tile_begin;
         const u64 base = (u64)ltile * EXCP_TILE;
-        const float *__restrict__ Wp = D.Wp;
-        const u64 *__restrict__ bmw = (const u64 *)(D.blob + S.off_bw);
-        const u64 *__restrict__ bmo = (const u64 *)(D.blob + S.off_bo);
-        const u64 *__restrict__ cw = (const u64 *)(D.blob + S.off_cw);
-        const u64 *__restrict__ cm = (const u64 *)(D.blob + S.off_cm);
-        const u64 *__restrict__ cv = (const u64 *)(D.blob + S.off_cv);
-        const u64 nwords = excp_words(n);
-        const u64 n_w = S.n_w, n_o = S.n_o;
-        const bool pow2 = (64u % nbits) == 0u;
-        const bool moments = MOMENTS && ((D.m_out != nullptr) || (D.v_out != nullptr));
-        const bool inplace = D.W_out == D.Wp;
+        const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;   // elements of this tile
+        const unsigned char *blob = D.blob;
+        const bool has_w = D.W_out != nullptr;
+        const bool has_m = MOMENTS && D.m_out != nullptr, has_v = MOMENTS && D.v_out != nullptr;
+        const bool moments = has_m || has_v;
 
-        // survivors before each of the tile's 64 bitmap words
-        const u64 wword = (u64)ltile * 64 + lane;
-        u64 myword = (wword < nwords) ? bmw[wword] : 0ull;
-        {
-            u64 rem = (wword * 64 < n) ? n - wword * 64 : 0ull;
-            if (rem < 64) myword &= (1ull << rem) - 1ull;
+        // previous weights of the lane's 4 x 4 elements: issued first, consumed last
+        float wp[4][4];
+        if (has_w) {
+            const EXCP_GLOBAL float *Wp = gptr(D.Wp) + base;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+                if (off + 4u <= rem) {
+                    const f4u x = *(const EXCP_GLOBAL f4u *)(Wp + off);
+                    wp[k][0] = x.x; wp[k][1] = x.y; wp[k][2] = x.z; wp[k][3] = x.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) wp[k][j] = (off + (u32)j < rem) ? Wp[off + (u32)j] : 0.f;
+                }
+            }
         }
-        u32 pc = __popcll(myword), incl = pc;
+
+        // survivors before each of the tile's 64 bitmap words (every wave computes all 64)
+        u64 myword = 0;
+        {
+            const u64 wword = (u64)ltile * 64 + lane;
+            const u32 bits_here = (lane * 64u < rem) ? min(64u, rem - lane * 64u) : 0u;
+            if (bits_here) myword = gptr((const u64 *)(blob + S.off_bw))[wword];
+            if (bits_here < 64u) myword &= (1ull << bits_here) - 1ull;
+        }
+        const u32 pc = __popcll(myword);
+        u32 incl = pc;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            u32 v = __shfl_up(incl, off, WAVE);
+            const u32 v = __shfl_up(incl, off, WAVE);
             if (lane >= (u32)off) incl += v;
         }
         const u32 excl = incl - pc;
-        const u64 q_tile = w.dec_cnt_w[tile];          // survivors before this tile
-        const u64 cw_last = n_w ? excp_words(n_w * nbits) - 1 : 0;
-
-        // moments: prefix popcounts of the bitmap_o words that cover this tile's survivors
-        const u64 o_tile = w.dec_cnt_o[tile];          // moment survivors before this tile
-        const u64 ow0 = q_tile >> 6;
-        const u64 nw_words = excp_words(n_w);
-        u64 oword = 0, oword64 = 0; u32 oexcl = 0, ototal = 0;
-        if (moments) {
-            oword = (ow0 + lane < nw_words) ? bmo[ow0 + lane] : 0ull;
-            oword64 = (ow0 + 64 < nw_words) ? bmo[ow0 + 64] : 0ull;
-            u64 oword_m = oword;
-            if (lane == 0) oword_m &= ~((1ull << (q_tile & 63ull)) - 1ull);   // bits before the tile's first survivor
-            u32 opc = __popcll(oword_m), oincl = opc;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                u32 v = __shfl_up(oincl, off, WAVE);
-                if (lane >= (u32)off) oincl += v;
-            }
-            oexcl = oincl - opc;
-            ototal = __shfl(oincl, 63, WAVE);
+        const u32 cnt = __shfl(incl, 63, WAVE);            // survivors of this tile
+        const u32 q_tile = w.dec_cnt_w[tile];              // survivors before this tile
+        const u64 wbit0 = (u64)q_tile * nbits;
+        const u32 woff = (u32)(wbit0 & 31ull);
+        u32 o_tile = 0, ocnt = 0, moff = 0, ooff = 0;
+        if (MOMENTS && moments) {
+            o_tile = w.dec_cnt_o[tile];
+            const u32 o_next = (ltile + 1u < D.tile_count) ? w.dec_cnt_o[tile + 1] : (u32)S.pop_o;
+            ocnt = o_next - o_tile;
+            moff = (u32)(((u64)o_tile * nbits) & 31ull);
+            ooff = q_tile & 31u;
         }
-        const u64 cm_last = n_o ? excp_words(n_o * nbits) - 1 : 0;
 
-        for (int half = 0; half < 2; ++half) {
-            // ---- weights: all loads of eight batches first, then the arithmetic ----------------
-            float wp[8]; u64 c0[8], c1[8]; u64 qq[8]; bool kwv[8];
+        __syncthreads();                                   // the previous tile's LDS readers are done
+        if (t != cur_t) {
+            const EXCP_GLOBAL float *books = gptr((const float *)(blob + EXCP_HEADER));
+            for (u32 i = tid; i < 3u * E; i += EXCP_THREADS) s_book[(i / E) * 256u + (i % E)] = books[i];
+            cur_t = t;
+        }
+        stage_words(s_cw, gptr((const u32 *)(blob + S.off_cw)) + (wbit0 >> 5), (woff + cnt * nbits + 31u) >> 5);
+        if (MOMENTS && moments) {
+            const u64 mbit0 = (u64)o_tile * nbits;
+            const u32 mwords = (moff + ocnt * nbits + 31u) >> 5;
+            stage_words(s_cm, gptr((const u32 *)(blob + S.off_cm)) + (mbit0 >> 5), mwords);
+            stage_words(s_cv, gptr((const u32 *)(blob + S.off_cv)) + (mbit0 >> 5), mwords);
+            if (wave == 0) {
+                // bitmap_o bits [q_tile, q_tile + cnt) as u32 words, with the count of set bits before each word
+                const EXCP_GLOBAL u32 *bo = gptr((const u32 *)(blob + S.off_bo)) + (q_tile >> 5);
+                const u32 owords = (ooff + cnt + 31u) >> 5;        // <= 129
+                u32 carry = 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const u32 wi = wave * 16 + half * 8 + j;
-                const u64 idx = base + (u64)(wi * 64 + lane);
-                // wi is the same for the whole wave: a scalar lane read, no cross-lane permute
-                const u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)myword, (int)wi);
-                const u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(myword >> 32), (int)wi);
-                const u64 mw = ((u64)hi << 32) | lo;
-                const u32 wexcl = (u32)__builtin_amdgcn_readlane((int)excl, (int)wi);
-                const bool ok = idx < n;
-                kwv[j] = ok && ((mw >> lane) & 1ull);
-                u64 q = q_tile + wexcl + __popcll(mw & lt_mask);   // survivor position where kept
-                if (q >= n_w) q = n_w ? n_w - 1 : 0;               // keeps every address in range
-                qq[j] = q;
-                wp[j] = Wp[ok ? idx : n - 1];
-                const u64 wi0 = (q * nbits) >> 6;
-                c0[j] = n_w ? cw[wi0] : 0ull;
-                c1[j] = (!pow2 && n_w) ? cw[wi0 < cw_last ? wi0 + 1 : cw_last] : 0ull;
-            }
-            if (D.W_out) {
+                for (int c = 0; c < 3; ++c) {
+                    const u32 i = lane + 64u * (u32)c;
+                    u32 word = (i < owords) ? bo[i] : 0u;
+                    if (i == 0u) word &= ~((1u << ooff) - 1u);     // bits of earlier tiles' survivors
+                    const u32 opc = __popc(word);
+                    u32 oincl = opc;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const u64 idx = base + (u64)((wave * 16 + half * 8 + j) * 64 + lane);
-                    const u32 code = extract_code(c0[j], c1[j], (u32)((qq[j] * nbits) & 63ull), nbits);
-                    const float outw = kwv[j] ? wp[j] + s_book[code] : wp[j];
-                    if (idx < n && (!inplace || kwv[j])) D.W_out[idx] = outw;
+                    for (int off = 1; off < 64; off <<= 1) {
+                        const u32 v = __shfl_up(oincl, off, WAVE);
+                        if (lane >= (u32)off) oincl += v;
+                    }
+                    if (i < DEC_OBIT_WORDS) { s_ow[i] = word; s_oex[i] = carry + oincl - opc; }
+                    carry += __shfl(oincl, 63, WAVE);
                 }
             }
-            if (!MOMENTS || !moments) continue;
-            // ---- moments: M_o bit and rank of every survivor -----------------------------------
-            bool kov[8]; u64 m0[8], m1[8], v0[8], v1[8]; u32 shv[8];
+        }
+        __syncthreads();
+
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const u64 q = qq[j];
-                const u32 rel = (u32)((q >> 6) - ow0);             // 0..64 where kept
-                const u32 src = rel & 63u;
-                const u32 olo = __shfl((u32)oword, src, WAVE), ohi = __shfl((u32)(oword >> 32), src, WAVE);
-                u32 opre = __shfl(oexcl, src, WAVE);
-                u64 ow = ((u64)ohi << 32) | olo;
-                if (rel >= 64u) { ow = oword64; opre = ototal; }
-                const u32 bitpos = (u32)(q & 63ull);
-                kov[j] = kwv[j] && ((ow >> bitpos) & 1ull);
-                u64 below = ow & ((1ull << bitpos) - 1ull);
-                if (rel == 0u) below &= ~((1ull << (q_tile & 63ull)) - 1ull);
-                u64 qo = o_tile + opre + __popcll(below);
-                if (qo >= n_o) qo = n_o ? n_o - 1 : 0;
-                const u64 wi0 = (qo * nbits) >> 6;
-                const u64 wi1 = wi0 < cm_last ? wi0 + 1 : cm_last;
-                shv[j] = (u32)((qo * nbits) & 63ull);
-                m0[j] = n_o ? cm[wi0] : 0ull;
-                v0[j] = n_o ? cv[wi0] : 0ull;
-                m1[j] = (!pow2 && n_o) ? cm[wi1] : 0ull;
-                v1[j] = (!pow2 && n_o) ? cv[wi1] : 0ull;
+        for (int k = 0; k < 4; ++k) {
+            const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;   // first of the lane's 4 elements
+            const u32 wq = wave * 16u + (u32)k * 4u + (lane >> 4);       // their bitmap word
+            const u32 sub = (lane & 15u) * 4u;                           // their first bit in it
+            const u32 wlo = __shfl((u32)myword, wq, WAVE), whi = __shfl((u32)(myword >> 32), wq, WAVE);
+            const u32 wex = __shfl(excl, wq, WAVE);
+            const u64 word = ((u64)whi << 32) | wlo;
+            const u32 nib = (u32)(word >> sub) & 15u;
+            const u32 r = wex + __popcll(word & ((1ull << sub) - 1ull));   // tile rank of the lane's first survivor
+            u32 f = window32(s_cw, woff + r * nbits);
+            if (has_w) {
+                float out[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool kept = (nib >> j) & 1u;
+                    const float c = s_book[f & cmask];
+                    out[j] = kept ? wp[k][j] + c : wp[k][j];
+                    f = kept ? (f >> nbits) : f;
+                }
+                EXCP_GLOBAL float *Wo = gptr(D.W_out) + base;
+                if (off + 4u <= rem) {
+                    f4u y; y.x = out[0]; y.y = out[1]; y.z = out[2]; y.w = out[3];
+                    *(EXCP_GLOBAL f4u *)(Wo + off) = y;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) if (off + (u32)j < rem) Wo[off + (u32)j] = out[j];
+                }
             }
+            if (MOMENTS && moments) {
+                const u32 bpos = ooff + r;                                // the first survivor's bit in the staged bitmap_o
+                const u32 bi = bpos >> 5, bsh = bpos & 31u;
+                u32 obits = __builtin_amdgcn_alignbit(s_ow[bi + 1], s_ow[bi], bsh);
+                const u32 orank = s_oex[bi] + __popc(s_ow[bi] & ((1u << bsh) - 1u));
+                u32 fm = window32(s_cm, moff + orank * nbits);
+                u32 fv = window32(s_cv, moff + orank * nbits);
+                float om[4], ov[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const u64 idx = base + (u64)((wave * 16 + half * 8 + j) * 64 + lane);
-                if (idx < n) {
-                    const float outm = kov[j] ? s_book[256u + extract_code(m0[j], m1[j], shv[j], nbits)] : 0.f;
-                    const float outv = kov[j] ? s_book[512u + extract_code(v0[j], v1[j], shv[j], nbits)] : 0.f;
-                    if (D.m_out) D.m_out[idx] = outm;
-                    if (D.v_out) D.v_out[idx] = outv;
+                for (int j = 0; j < 4; ++j) {
+                    const bool kept = (nib >> j) & 1u;
+                    const bool ko = kept && (obits & 1u);
+                    om[j] = ko ? s_book[256u + (fm & cmask)] : 0.f;
+                    ov[j] = ko ? s_book[512u + (fv & cmask)] : 0.f;
+                    obits = kept ? (obits >> 1) : obits;
+                    fm = ko ? (fm >> nbits) : fm;
+                    fv = ko ? (fv >> nbits) : fv;
+                }
+                if (off + 4u <= rem) {
+                    f4u y;
+                    if (has_m) { y.x = om[0]; y.y = om[1]; y.z = om[2]; y.w = om[3]; *(EXCP_GLOBAL f4u *)(gptr(D.m_out) + base + off) = y; }
+                    if (has_v) { y.x = ov[0]; y.y = ov[1]; y.z = ov[2]; y.w = ov[3]; *(EXCP_GLOBAL f4u *)(gptr(D.v_out) + base + off) = y; }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (off + (u32)j < rem) {
+                            if (has_m) gptr(D.m_out)[base + off + (u32)j] = om[j];
+                            if (has_v) gptr(D.v_out)[base + off + (u32)j] = ov[j];
+                        }
+                    }
                 }
             }
         }
