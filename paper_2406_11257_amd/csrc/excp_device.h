@@ -50,7 +50,7 @@ struct TState {
     u32 med_bits;
     float mean32, t_w, r_o;
     int status;
-    int pad;
+    u32 absm_base;              // lowest bit position of the 24-position window used for the exact sum of |m|
 };
 
 // One survivor stream (3 per tensor: residual, m, v) during codebook construction.

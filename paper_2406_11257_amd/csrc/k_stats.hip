@@ -7,9 +7,12 @@
 //     adversarial data); the counts reveal that, and the tensor then takes the always-correct
 //     fallback: a three-pass radix-histogram select over the whole tensor (11 + 11 + 9 key bits);
 //   * the exact sum of |m| per tensor (Eq. "r_o") by integer accumulation: every |m_i| is
-//     mant * 2^(pos-149); a wave adds its mantissas in a 40-bit exponent window as integers and
-//     files the result into per-tensor u64 bins 8 binary orders apart, so the sum is exact and
-//     does not depend on the order of additions;
+//     mant * 2^(pos-149).  The sample fixes a window of 24 bit positions per tensor that holds
+//     practically every value; inside it a value is a multiple of one unit below 2^48 units, so a
+//     lane adds sixteen of them exactly in fp64, splits the sum into two 32-bit integers and keeps
+//     those in 64-bit counters; values outside the window (rare) are filed one by one.  Everything
+//     ends in per-tensor u64 bins 8 binary orders apart, so the sum is exact and does not depend on
+//     the order of additions;
 //   * non-finite detection on W_prev, W_t, m and the residual.
 #include "excp_util.h"
 
@@ -46,23 +49,35 @@ __device__ __forceinline__ void sort_keys_lds(u32 *key, u32 count_pow2) {
 // One workgroup per tensor: sample (or all) residual magnitudes, sorted.
 __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, GroupParams g) {
     __shared__ u32 key[MED_SAMPLE];
+    __shared__ u32 s_mmax;
     const u32 t = blockIdx.x, tid = threadIdx.x;
     const TDesc &D = w.desc[t];
     TState &S = w.st[t];
     const u64 n = D.n;
     if (n == 0) { if (tid == 0) { S.med_bits = 0; S.med_state = MED_KNOWN; } return; }
+    if (tid == 0) s_mmax = 0;
+    __syncthreads();
     const u32 ns = n < MED_SAMPLE ? (u32)n : MED_SAMPLE;
+    u32 mmax = 0;                                   // largest finite |m| pattern of the sample
     for (u32 i = tid; i < MED_SAMPLE; i += EXCP_THREADS) {
         u32 k = 0xffffffffu;
         if (i < ns) {
             const u64 idx = n <= MED_SAMPLE ? (u64)i : ((u64)i * n) / MED_SAMPLE;
             k = f2u(D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+            const u32 mb = f2u(D.m[idx]) & 0x7fffffffu;
+            if (mb < 0x7f800000u) mmax = max(mmax, mb);
         }
         key[i] = k;
     }
+    mmax = wave_max_u32(mmax);
+    if ((tid & 63u) == 0) atomicMax(&s_mmax, mmax);
     __syncthreads();
     sort_keys_lds(key, MED_SAMPLE);
     if (tid == 0) {
+        // window of the exact sum: its top sits 4 binary orders above the largest sampled |m|
+        const u32 e = s_mmax >> 23;
+        const u32 pos = (e ? e : 1u) - 1u;
+        S.absm_base = pos + 4u > 23u ? min(pos + 4u - 23u, 230u) : 0u;
         if (n <= MED_SAMPLE) {
             S.med_bits = key[(n - 1) >> 1];
             S.med_state = MED_KNOWN;
@@ -74,14 +89,17 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, Gro
     }
 }
 
+// Four consecutive floats at an address that is only known to be 4-byte aligned.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
 // The streaming pass: exact sum of |m|, non-finite check, count of keys below the bracket and
-// collection of the keys inside it.  Persistent workgroups over contiguous tile ranges.
+// collection of the keys inside it.  Persistent workgroups over contiguous tile ranges; a lane
+// takes four consecutive elements of each of four 256-element rows of its wave's quarter tile.
 __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, GroupParams g) {
     __shared__ u64 bins[EXCP_ABSM_BINS];
-    __shared__ u32 l_cand[4][CAND_PER_WAVE];
+    __shared__ u32 l_cand[4][2 * CAND_PER_WAVE + 1];   // per wave: staged candidates, plus a spare slot
     __shared__ u32 s_nf, s_lt;
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u64 lt_mask = lanemask_lt();
     const u32 G = gridDim.x, b = blockIdx.x;
     const u32 lo_tile = (u32)(((u64)b * g.ntiles) / G), hi_tile = (u32)(((u64)(b + 1) * g.ntiles) / G);
     if (lo_tile >= hi_tile) return;
@@ -92,9 +110,41 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
     u32 t = find_owner(w.tile_begin, g.ntensors, lo_tile);
     u32 t_end = w.tile_begin[t + 1];
     u32 nf = 0, clt = 0;           // clt is the same in every lane of a wave
+    u64 accL = 0, accH = 0;        // this lane's in-window units: sum of low / high 32-bit halves
+    u32 B = w.st[t].absm_base;     // window = bit positions [B, B + 24)
 
+    u32 wcount = 0;                // candidates this wave has staged in LDS (same in every lane)
+    auto flush_cand = [&](u32 tt) {
+        // the staged candidates go to the tensor's list: one reservation for many tiles
+        if (wcount) {
+            u32 at = 0;
+            if (lane == 0) at = atomicAdd(&w.st[tt].cand_count, wcount);
+            at = __shfl(at, 0, WAVE);
+            if ((u64)at + wcount <= w.desc[tt].cand_cap) {
+                EXCP_GLOBAL u32 *dst = gptr(w.cand) + w.desc[tt].cand_off + at;
+                for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
+            } else if (lane == 0) {
+                atomicOr(&w.st[tt].cand_overflow, 1u);
+            }
+            wcount = 0;
+        }
+    };
     auto flush = [&](u32 tt) {
-        if (lane == 0 && clt) atomicAdd(&s_lt, clt);
+        flush_cand(tt);
+        // the lanes' window sums, as three 32-bit pieces at positions B, B + 32, B + 64
+        const u64 sumL = wave_sum_u64(accL), sumH = wave_sum_u64(accH);
+        accL = 0; accH = 0;
+        if (lane == 0) {
+            const u64 lo64 = sumL + (sumH << 32);
+            const u64 hi64 = (sumH >> 32) + (lo64 < sumL ? 1ull : 0ull);
+            const u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                const u32 p = B + 32u * q;
+                if (piece[q]) atomicAdd(&bins[p >> 3], piece[q] << (p & 7u));
+            }
+            if (clt) atomicAdd(&s_lt, clt);
+        }
         if (nf) atomicAdd(&s_nf, nf);
         nf = 0; clt = 0;
         __syncthreads();
@@ -114,36 +164,51 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             flush(t);
             t = find_owner(w.tile_begin, g.ntensors, tile);
             t_end = w.tile_begin[t + 1];
+            B = w.st[t].absm_base;
         }
         const TDesc &D = w.desc[t];
         TState &S = w.st[t];
         const u64 n = D.n;
         const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
+        const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
         const bool pending = S.med_state == MED_PENDING;
-        const u32 klo = S.br_lo, khi = S.br_hi;
+        const u32 klo = S.br_lo, kspan = S.br_hi - klo;
 
         u32 key[16], mb[16];
         u32 worst = 0;             // largest magnitude pattern seen: >= 0x7f800000 means Inf or NaN
-        if (base + EXCP_TILE <= n) {
-            const u64 first = base + (u64)(wave * 1024 + lane);
-            const EXCP_GLOBAL float *gW = gptr(D.W) + first, *gP = gptr(D.Wp) + first, *gM = gptr(D.m) + first;
+        {
+            const EXCP_GLOBAL float *gW = gptr(D.W) + base, *gP = gptr(D.Wp) + base, *gM = gptr(D.m) + base;
+            if (rem == EXCP_TILE) {
+                f4u a[4], p[4], mm[4];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const float a = gW[j * 64], p = gP[j * 64], mm = gM[j * 64];
-                key[j] = f2u(a - p) & 0x7fffffffu;
-                mb[j] = f2u(mm) & 0x7fffffffu;
-                worst = max(max(worst, key[j]), max(mb[j], max(f2u(a) & 0x7fffffffu, f2u(p) & 0x7fffffffu)));
-            }
-        } else {
+                for (int k = 0; k < 4; ++k) {
+                    const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+                    a[k] = *(const EXCP_GLOBAL f4u *)(gW + off);
+                    p[k] = *(const EXCP_GLOBAL f4u *)(gP + off);
+                    mm[k] = *(const EXCP_GLOBAL f4u *)(gM + off);
+                }
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
-                const bool ok = idx < n;
-                const float a = ok ? D.W[idx] : 0.f, p = ok ? D.Wp[idx] : 0.f, mm = ok ? D.m[idx] : 0.f;
-                const u32 k = f2u(a - p) & 0x7fffffffu;
-                mb[j] = f2u(mm) & 0x7fffffffu;
-                worst = max(max(worst, k), max(mb[j], max(f2u(a) & 0x7fffffffu, f2u(p) & 0x7fffffffu)));
-                key[j] = ok ? k : 0xffffffffu;            // above every bracket, never a candidate
+                for (int k = 0; k < 4; ++k) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float av = a[k][j], pv = p[k][j];
+                        key[4 * k + j] = f2u(av - pv) & 0x7fffffffu;
+                        mb[4 * k + j] = f2u(mm[k][j]) & 0x7fffffffu;
+                        worst = max(max(worst, key[4 * k + j]),
+                                    max(mb[4 * k + j], max(f2u(av) & 0x7fffffffu, f2u(pv) & 0x7fffffffu)));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const u32 off = wave * 1024u + (u32)(j >> 2) * 256u + lane * 4u + (u32)(j & 3);
+                    const bool ok = off < rem;
+                    const float av = ok ? gW[off] : 0.f, pv = ok ? gP[off] : 0.f, mv = ok ? gM[off] : 0.f;
+                    const u32 k = f2u(av - pv) & 0x7fffffffu;
+                    mb[j] = f2u(mv) & 0x7fffffffu;
+                    worst = max(max(worst, k), max(mb[j], max(f2u(av) & 0x7fffffffu, f2u(pv) & 0x7fffffffu)));
+                    key[j] = ok ? k : 0xffffffffu;            // above every bracket, never a candidate
+                }
             }
         }
         if (!TUNE(18) && __any(worst >= 0x7f800000u)) {
@@ -156,47 +221,26 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             if (nf == 0 && worst >= 0x7f800000u) nf = 1;
         }
         if (pending && !TUNE(16)) {
-            u32 wcount = 0;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 clt += __popcll(ballot64(key[j] < klo));
-                const bool cand = key[j] >= klo && key[j] <= khi;
+                const bool cand = key[j] - klo <= kspan;      // klo <= key <= khi (a padded key wraps far above)
                 const u64 bal = ballot64(cand);
-                if (bal) {
-                    if (cand) l_cand[wave][wcount + __popcll(bal & lt_mask)] = key[j];
-                    wcount += __popcll(bal);
-                }
+                // branch-free: the others write to a spare slot past the end
+                const u32 below = __builtin_amdgcn_mbcnt_hi((u32)(bal >> 32), __builtin_amdgcn_mbcnt_lo((u32)bal, 0u));
+                l_cand[wave][cand ? wcount + below : 2 * CAND_PER_WAVE] = key[j];
+                wcount += __popcll(bal);
             }
-            if (wcount) {
-                // this wave's candidates go to the tensor's list (one atomic per wave and tile)
-                u32 at = 0;
-                if (lane == 0) at = atomicAdd(&S.cand_count, wcount);
-                at = __shfl(at, 0, WAVE);
-                if ((u64)at + wcount <= D.cand_cap) {
-                    u32 *dst = w.cand + D.cand_off + at;
-                    for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
-                } else if (lane == 0) {
-                    atomicOr(&S.cand_overflow, 1u);
-                }
-            }
+            if (wcount > CAND_PER_WAVE) flush_cand(t);        // room for another 1024 is kept
         }
         if (!TUNE(17)) {
-            // exact sum of |m| for this wave's 1024 values.  Values within 2^24 of the wave's largest
-            // are multiples of one unit and below 2^48 units, so sixteen of them add exactly in
-            // fp64; the sum is then split into integers and filed into the bins.  Smaller values
-            // (rare) go to the bins one by one.
-            u32 big = 0;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) big = max(big, mb[j]);
-            big = wave_max_u32(big);
-            const u32 emax = big >> 23;
-            const u32 pmax = (emax ? emax : 1u) - 1u;
-            const u32 B = pmax > 23u ? pmax - 23u : 0u;                 // window base position
-            const u32 thr = B ? ((B + 1u) << 23) : 0u;                  // patterns with pos >= B
+            // exact sum of |m|: in-window values are whole multiples of 2^(B-149) below 2^48 units,
+            // so this lane's sixteen add exactly in fp64.
+            const u32 thr_lo = B ? ((B + 1u) << 23) : 0u, span = ((B + 25u) << 23) - thr_lo;
             double dsum = 0.0;
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                const bool in = mb[j] >= thr;
+                const bool in = mb[j] - thr_lo < span;
                 dsum += in ? (double)u2f(mb[j]) : 0.0;
                 if (!in && mb[j]) {
                     const u32 e = mb[j] >> 23;
@@ -205,30 +249,19 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
                     atomicAdd(&bins[pos >> 3], (u64)mant << (pos & 7u));
                 }
             }
-            // dsum = units * 2^(B-149), units an integer below 2^52
-            const double units = ldexp(dsum, 149 - (int)B);
+            const double units = ldexp(dsum, 149 - (int)B);                // an integer below 2^52
             const u32 hi32 = (u32)(units * 2.3283064365386963e-10);     // floor(units / 2^32)
             const u32 lo32 = (u32)(units - (double)hi32 * 4294967296.0);
-            u64 accL = wave_sum_u64((u64)lo32);
-            u64 accH = wave_sum_u64((u64)hi32);
-            if (lane == 0) {
-                u64 lo64 = accL + (accH << 32);
-                u64 hi64 = (accH >> 32) + (lo64 < accL ? 1ull : 0ull);
-                u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
-#pragma unroll
-                for (int q = 0; q < 3; ++q) {
-                    u32 p = B + 32u * q;
-                    if (piece[q]) atomicAdd(&bins[p >> 3], piece[q] << (p & 7u));
-                }
-            }
-            // clear this tile's share of the bitmap_o region (filled later with atomic ORs)
-            if (tid < 66) {
-                u64 word = (base >> 6) + tid;
-                u64 nw = excp_words(n) + 2;
-                u64 off = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n)) + 8ull * word;
-                if (tid < 64 ? (word < nw) : (base + EXCP_TILE >= n && word < nw))
-                    if (off + 8 <= D.blob_cap) *(u64 *)(D.blob + off) = 0ull;
-            }
+            accL += lo32;
+            accH += hi32;
+        }
+        // clear this tile's share of the bitmap_o region (filled later with atomic ORs)
+        if (tid < 66) {
+            u64 word = (base >> 6) + tid;
+            u64 nw = excp_words(n) + 2;
+            u64 off = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n)) + 8ull * word;
+            if (tid < 64 ? (word < nw) : (base + EXCP_TILE >= n && word < nw))
+                if (off + 8 <= D.blob_cap) *(u64 *)(D.blob + off) = 0ull;
         }
     }
     flush(t);
