@@ -12,6 +12,8 @@
 #define EXCP_THREADS     256
 #define EXCP_ABSM_BINS   40        // u64 accumulators, 8 binary exponents apart, for the exact sum of |m|
 #define EXCP_MAX_K       255
+#define EXCP_KM_CELLS    4096u     // cells of the value -> bucket map (2048 per sign)
+#define EXCP_KM_MAP_WORDS (4u + EXCP_KM_CELLS / 4u)
 #define EXCP_HEADER      80u
 #define EXCP_MAGIC       0x50435845u
 #define EXCP_VERSION     1u
@@ -115,7 +117,7 @@ struct Workspace {
     u32 *chunk_total;         // [1]
     u32 *seg_chunk_begin;     // [segments + 1] first chunk of every survivor stream
     float *pw, *pm, *pv;      // survivors partitioned into value-ordered buckets (same offsets as xw/xm/xv)
-    u32 *km_split;            // [segment][256] bucket splitter keys (entry 255 = 0xffffffff)
+    u32 *km_split;            // [segment][EXCP_KM_MAP_WORDS] value -> bucket map: 4 parameters, then 4096 bucket bytes
     u32 *km_cnt;              // [chunk][256] bucket counts, then positions, of every chunk
     u32 *km_begin;            // [segment][257] first position of every bucket
     u64 *km_bsum;             // [segment][256][EXCP_ABSM_BINS] exact signed sum of every bucket

@@ -207,7 +207,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.pw, G);
     ok = ok && dev_alloc(c, &w.pm, G);
     ok = ok && dev_alloc(c, &w.pv, G);
-    ok = ok && dev_alloc(c, &w.km_split, nseg_max * 256);
+    ok = ok && dev_alloc(c, &w.km_split, nseg_max * EXCP_KM_MAP_WORDS);
     ok = ok && dev_alloc(c, &w.km_cnt, chunks_group * 256);
     ok = ok && dev_alloc(c, &w.km_begin, nseg_max * 257);
     ok = ok && dev_alloc(c, &w.km_bsum, nseg_max * 256 * EXCP_ABSM_BINS);

@@ -3,8 +3,11 @@
 //
 // One-dimensional Lloyd has structure that makes re-reading every value in every iteration
 // unnecessary: clusters are intervals, and the assignment is monotone in the value.  So each stream
-// is first PARTITIONED into 256 value-ordered buckets of roughly equal population (splitters from a
-// sorted sample), and for every bucket the exact count, exact sum, minimum and maximum are stored.
+// is first PARTITIONED into 256 value-ordered buckets of roughly equal population, and for every
+// bucket the exact count, exact sum, minimum and maximum are stored.  The bucket of a value comes
+// from arithmetic and one table look-up: the magnitude's bit pattern, offset and shifted, names one
+// of 2048 cells per sign (bit patterns of floats are ordered like the values, roughly
+// logarithmically), and a sample of the stream decides which run of cells forms which bucket.
 // In an iteration a bucket whose minimum and maximum go to the same centre contributes its stored
 // totals; only the (at most K-1) buckets that a cluster border cuts are read element by element.
 // The same buckets give the initial centres (order statistics of rank ((2k+1) len)/(2K)) with a
@@ -23,7 +26,7 @@
 namespace {
 
 constexpr u32 NBKT = 256;
-constexpr u32 SAMPLE = 4096;
+constexpr u32 SAMPLE = 8192;
 constexpr u32 PER_THREAD = EXCP_CHUNK / EXCP_THREADS;   // 32
 
 __device__ __forceinline__ const float *seg_data(const Workspace &w, u32 sidx) {
@@ -37,33 +40,23 @@ __device__ __forceinline__ float *seg_part(const Workspace &w, u32 sidx) {
     return basep + w.desc[t].elem_off;
 }
 
-// number of splitters (split[0..254]) that are <= key: the bucket of key, 0..255
-__device__ __forceinline__ u32 bucket_of(const u32 *split, u32 key) {
-    u32 lo = 0;
-#pragma unroll
-    for (u32 step = 128; step >= 1; step >>= 1) {
-        u32 probe = lo + step - 1;                 // <= 254
-        if (split[probe] <= key) lo += step;
-    }
-    return lo < 255u ? lo : 255u;
-}
+// Four consecutive floats at an address that is only known to be 4-byte aligned.
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
-// The same search for N keys at once, step by step: the N LDS reads of a step are independent and
-// overlap, instead of N chains of eight dependent reads.
-template <int N>
-__device__ __forceinline__ void bucket_of_many(const u32 *split, const u32 (&key)[N], u32 (&out)[N]) {
-#pragma unroll
-    for (int e = 0; e < N; ++e) out[e] = 0;
-#pragma unroll
-    for (u32 step = 128; step >= 1; step >>= 1) {
-        u32 probe[N];
-#pragma unroll
-        for (int e = 0; e < N; ++e) probe[e] = split[out[e] + step - 1];
-#pragma unroll
-        for (int e = 0; e < N; ++e) if (probe[e] <= key[e]) out[e] += step;
-    }
-#pragma unroll
-    for (int e = 0; e < N; ++e) out[e] = out[e] < 255u ? out[e] : 255u;
+constexpr u32 HALF_CELLS = EXCP_KM_CELLS / 2;
+
+// Value -> cell, monotone in the value: negative values fill cells 2047 down to 0 as their
+// magnitude grows, positive ones 2048 up to 4095.  map[0..3] = offset and shift of the negative
+// side, offset and shift of the positive side; magnitudes beyond the sampled range clamp.
+__device__ __forceinline__ u32 cell_of(float x, const u32 *map) {
+    const u32 bits = f2u(x), a = bits & 0x7fffffffu;
+    const bool neg = bits >> 31;
+    const u32 amin = neg ? map[0] : map[2], sh = neg ? map[1] : map[3];
+    const u32 c = min((max(a, amin) - amin) >> sh, HALF_CELLS - 1u);
+    return neg ? (c ^ (HALF_CELLS - 1u)) : (c | HALF_CELLS);
+}
+__device__ __forceinline__ u32 bucket_of(float x, const u32 *map) {
+    return ((const unsigned char *)(map + 4))[cell_of(x, map)];
 }
 
 // ---------------------------------------------------------------- exact signed accumulation
@@ -171,40 +164,108 @@ __device__ double signed_bins_to_double(const u64 *bins) {
     return neg ? -mag : mag;
 }
 
-// ---------------------------------------------------------------- P0: splitters from a sorted sample
+// ---------------------------------------------------------------- P0: value -> bucket map from a sample
+// One workgroup per stream.  The sample fixes the magnitude range of each sign (hence offset and
+// shift of the cells); the cells' sample counts, scanned, give every cell its bucket so that the
+// buckets hold about equal shares of the sample.
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupParams g) {
-    __shared__ u32 key[SAMPLE];
+    __shared__ float smp[SAMPLE];
+    __shared__ u32 cnt[EXCP_KM_CELLS];
+    __shared__ u32 s_map[4];
+    __shared__ u32 s_ext[4];                       // min / max magnitude of the negative, of the positive samples
+    __shared__ u32 s_part[EXCP_THREADS];
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
     const u64 len = w.seg[sidx].len;
     if (len == 0) return;
     const float *__restrict__ x = seg_data(w, sidx);
     const u32 ns = len < SAMPLE ? (u32)len : SAMPLE;
-    for (u32 i = tid; i < SAMPLE; i += EXCP_THREADS)
-        key[i] = (i < ns) ? key_of(x[((u64)i * len) / ns]) : 0xffffffffu;
+    if (tid < 4) s_ext[tid] = (tid & 1u) ? 0u : 0xffffffffu;
+    for (u32 c = tid; c < EXCP_KM_CELLS; c += EXCP_THREADS) cnt[c] = 0;
     __syncthreads();
-    for (u32 k = 2; k <= SAMPLE; k <<= 1) {
-        for (u32 j = k >> 1; j > 0; j >>= 1) {
-            for (u32 t = tid; t < SAMPLE / 2; t += EXCP_THREADS) {
-                u32 i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                u32 p = i | j;
-                u32 a = key[i], b = key[p];
-                bool asc = (i & k) == 0;
-                if ((a > b) == asc) { key[i] = b; key[p] = a; }
-            }
-            __syncthreads();
-        }
+    u32 mn[2] = {0xffffffffu, 0xffffffffu}, mx[2] = {0u, 0u};
+    for (u32 i = tid; i < ns; i += EXCP_THREADS) {
+        const float v = x[((u64)i * len) / ns];
+        smp[i] = v;
+        const u32 bits = f2u(v), a = bits & 0x7fffffffu, sg = bits >> 31;
+        if (sg) { mn[0] = min(mn[0], a); mx[0] = max(mx[0], a); } else { mn[1] = min(mn[1], a); mx[1] = max(mx[1], a); }
     }
-    u32 *split = w.km_split + (u64)sidx * NBKT;
-    for (u32 b = tid; b < NBKT; b += EXCP_THREADS) {
-        u32 idx = (u32)(((u64)(b + 1) * ns) / NBKT);
-        if (idx >= ns) idx = ns - 1;
-        split[b] = (b == NBKT - 1) ? 0xffffffffu : key[idx];
+#pragma unroll
+    for (int sg = 0; sg < 2; ++sg) {
+        u32 lo = mn[sg], hi = mx[sg];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            lo = min(lo, (u32)__shfl_xor(lo, m, WAVE));
+            hi = max(hi, (u32)__shfl_xor(hi, m, WAVE));
+        }
+        if ((tid & 63u) == 0) { atomicMin(&s_ext[2 * sg], lo); atomicMax(&s_ext[2 * sg + 1], hi); }
+    }
+    __syncthreads();
+    if (tid < 2) {
+        const u32 lo = s_ext[2 * tid], hi = s_ext[2 * tid + 1];
+        u32 amin = 0, sh = 20;                     // no sample of this sign: exponent and 3 mantissa bits
+        if (lo <= hi) {
+            const u32 width = hi - lo;             // (width >> sh) must stay below 2048
+            const u32 bits = width ? 32u - (u32)__clz((int)width) : 0u;
+            amin = lo;
+            sh = bits > 11u ? bits - 11u : 0u;
+        }
+        s_map[2 * tid] = amin; s_map[2 * tid + 1] = sh;
+    }
+    __syncthreads();
+    for (u32 i = tid; i < ns; i += EXCP_THREADS) atomicAdd(&cnt[cell_of(smp[i], s_map)], 1u);
+    __syncthreads();
+    // exclusive scan over the cells (16 consecutive cells per thread), then bucket = share of the sample below
+    constexpr u32 PER = EXCP_KM_CELLS / EXCP_THREADS;     // 16
+    u32 local[PER], sum = 0;
+#pragma unroll
+    for (u32 q = 0; q < PER; ++q) { local[q] = cnt[tid * PER + q]; sum += local[q]; }
+    s_part[tid] = sum;
+    __syncthreads();
+    for (u32 off = 1; off < EXCP_THREADS; off <<= 1) {
+        const u32 v = (tid >= off) ? s_part[tid - off] : 0u;
+        __syncthreads();
+        s_part[tid] += v;
+        __syncthreads();
+    }
+    u32 run = s_part[tid] - sum;
+    u32 *out = w.km_split + (u64)sidx * EXCP_KM_MAP_WORDS;
+    if (tid < 4) out[tid] = s_map[tid];
+#pragma unroll
+    for (u32 q4 = 0; q4 < PER / 4; ++q4) {
+        u32 word = 0;
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+            const u32 bkt = min((u32)(((u64)run * NBKT) / ns), NBKT - 1u);
+            word |= bkt << (8u * q);
+            run += local[q4 * 4 + q];
+        }
+        out[4 + tid * (PER / 4) + q4] = word;
     }
 }
 
+// Loads the 32 values a thread owns in a chunk: eight groups of four consecutive values (group it
+// starts at element (it * 256 + tid) * 4).  Values past the chunk's end are returned as NaN.
+__device__ __forceinline__ void load_chunk(const EXCP_GLOBAL float *gx, u32 clen, float (&v)[PER_THREAD]) {
+    const u32 tid = threadIdx.x;
+    if (clen == EXCP_CHUNK) {
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD / 4; ++it) {
+            const f4u q = *(const EXCP_GLOBAL f4u *)(gx + (it * EXCP_THREADS + tid) * 4u);
+            v[4 * it] = q.x; v[4 * it + 1] = q.y; v[4 * it + 2] = q.z; v[4 * it + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (u32 it = 0; it < PER_THREAD; ++it) {
+            const u32 e = ((it >> 2) * EXCP_THREADS + tid) * 4u + (it & 3u);
+            v[it] = e < clen ? gx[e] : __uint_as_float(0x7fc00000u);
+        }
+    }
+}
+__device__ __forceinline__ u32 chunk_elem(u32 it) { return ((it >> 2) * EXCP_THREADS + threadIdx.x) * 4u + (it & 3u); }
+
 // ---------------------------------------------------------------- P1: per-chunk bucket counts
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_count(Workspace w, GroupParams g) {
-    __shared__ u32 split[NBKT];
+    __shared__ u32 map[EXCP_KM_MAP_WORDS];
     __shared__ u32 hist[NBKT];
     const u32 tid = threadIdx.x;
     const u32 total = *w.chunk_total;
@@ -218,31 +279,19 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_count(Workspace w, GroupPar
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
-            split[tid] = w.km_split[(u64)sidx * NBKT + tid];
+            for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
         }
         hist[tid] = 0;
         __syncthreads();
         const SegState &S = w.seg[sidx];
-        const float *__restrict__ x = seg_data(w, sidx);
         const u64 len = S.len;
         const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
         const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
-        const EXCP_GLOBAL float *gx = gptr(x) + base;
+        float v[PER_THREAD];
+        load_chunk(gptr(seg_data(w, sidx)) + base, clen, v);
 #pragma unroll
-        for (u32 half = 0; half < 2; ++half) {
-            u32 key[PER_THREAD / 2], bk[PER_THREAD / 2];
-#pragma unroll
-            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
-                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
-                key[it] = key_of(gx[e < clen ? e : 0]);
-            }
-            bucket_of_many<PER_THREAD / 2>(split, key, bk);
-#pragma unroll
-            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
-                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
-                if (e < clen) atomicAdd(&hist[bk[it]], 1u);
-            }
-        }
+        for (u32 it = 0; it < PER_THREAD; ++it)
+            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) atomicAdd(&hist[bucket_of(v[it], map)], 1u);
         __syncthreads();
         w.km_cnt[(u64)c * NBKT + tid] = hist[tid];
         __syncthreads();
@@ -292,8 +341,8 @@ __global__ __launch_bounds__(1024) void k_km_scan(Workspace w, GroupParams g) {
 }
 
 // ---------------------------------------------------------------- P3: scatter into buckets
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupParams g) {
-    __shared__ u32 split[NBKT];
+__global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, GroupParams g) {
+    __shared__ u32 map[EXCP_KM_MAP_WORDS];
     __shared__ u32 hist[NBKT], loff[NBKT], goff[NBKT], fill[NBKT];
     __shared__ float sval[EXCP_CHUNK];
     __shared__ unsigned char sbkt[EXCP_CHUNK];
@@ -309,37 +358,24 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupP
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
-            split[tid] = w.km_split[(u64)sidx * NBKT + tid];
+            for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
         }
         hist[tid] = 0; fill[tid] = 0;
         goff[tid] = w.km_cnt[(u64)c * NBKT + tid];
         __syncthreads();
         const SegState &S = w.seg[sidx];
-        const float *__restrict__ x = seg_data(w, sidx);
         float *__restrict__ part = seg_part(w, sidx);
         const u64 len = S.len;
         const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
         const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
         float v[PER_THREAD];
-        u32 bk[PER_THREAD];
-        const EXCP_GLOBAL float *gx = gptr(x) + base;
+        u32 bk4[PER_THREAD / 4];                   // four bucket numbers per word
+        load_chunk(gptr(seg_data(w, sidx)) + base, clen, v);
 #pragma unroll
         for (u32 it = 0; it < PER_THREAD; ++it) {
-            u32 e = it * EXCP_THREADS + tid;
-            v[it] = gx[e < clen ? e : 0];
-        }
-#pragma unroll
-        for (u32 half = 0; half < 2; ++half) {
-            u32 key[PER_THREAD / 2], out[PER_THREAD / 2];
-#pragma unroll
-            for (u32 it = 0; it < PER_THREAD / 2; ++it) key[it] = key_of(v[half * (PER_THREAD / 2) + it]);
-            bucket_of_many<PER_THREAD / 2>(split, key, out);
-#pragma unroll
-            for (u32 it = 0; it < PER_THREAD / 2; ++it) {
-                const u32 e = (half * (PER_THREAD / 2) + it) * EXCP_THREADS + tid;
-                bk[half * (PER_THREAD / 2) + it] = out[it];
-                if (e < clen) atomicAdd(&hist[out[it]], 1u);
-            }
+            const u32 bb = bucket_of(v[it], map);
+            if ((it & 3u) == 0u) bk4[it >> 2] = bb; else bk4[it >> 2] |= bb << (8u * (it & 3u));
+            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) atomicAdd(&hist[bb], 1u);
         }
         __syncthreads();
         // exclusive scan of the 256 bucket counts
@@ -360,10 +396,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupP
         }
 #pragma unroll
         for (u32 it = 0; it < PER_THREAD; ++it) {
-            u32 e = it * EXCP_THREADS + tid;
-            if (e < clen) {
-                u32 bb = bk[it];
-                u32 pos = loff[bb] + atomicAdd(&fill[bb], 1u);
+            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) {
+                const u32 bb = (bk4[it >> 2] >> (8u * (it & 3u))) & 255u;
+                const u32 pos = loff[bb] + atomicAdd(&fill[bb], 1u);
                 sval[pos] = v[it];
                 sbkt[pos] = (unsigned char)bb;
             }
@@ -378,41 +413,100 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_scatter(Workspace w, GroupP
 }
 
 // ---------------------------------------------------------------- P4: exact totals per bucket
-// One wave per (stream, bucket): exact signed sum, minimum and maximum key.
+// One workgroup per four buckets of a stream; its four waves share every bucket (a quarter each),
+// so that one very large bucket does not leave a single wave working alone.  Values of a bucket
+// are neighbours in value, hence in exponent: a window of 40 bit positions placed from the first
+// values met holds practically all of them; inside it a lane adds shifted mantissas as integers
+// (low and high 32-bit halves in separate 64-bit counters, magnitudes of all values and of the
+// negative ones) with no cross-lane traffic; the rest (rare) is filed one by one.
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_bucket_stats(Workspace w, GroupParams g) {
     __shared__ u64 bins[4][EXCP_ABSM_BINS];
+    __shared__ u32 s_min[4], s_max[4];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 nseg = 3u * g.ntensors;
-    const u64 gw = (u64)blockIdx.x * 4 + wave;
-    if (gw >= (u64)nseg * NBKT) return;
-    const u32 sidx = (u32)(gw / NBKT), b = (u32)(gw % NBKT);
+    const u64 first = (u64)blockIdx.x * 4;                 // first of this workgroup's buckets
+    if (first >= (u64)nseg * NBKT) return;
+    const u32 sidx = (u32)(first / NBKT), b0 = (u32)(first % NBKT);
     if (w.seg[sidx].len == 0) return;
+    if (tid < 4 * EXCP_ABSM_BINS) (&bins[0][0])[tid] = 0;
+    if (tid < 4) { s_min[tid] = 0xffffffffu; s_max[tid] = 0; }
+    __syncthreads();
     const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
-    const u32 p0 = begin[b], p1 = begin[b + 1];
-    u64 *out = w.km_bsum + ((u64)sidx * NBKT + b) * EXCP_ABSM_BINS;
-    if (lane < EXCP_ABSM_BINS) bins[wave][lane] = 0;
-    u32 kmin = 0xffffffffu, kmax = 0;
-    const float *__restrict__ part = seg_part(w, sidx);
-    u64 *mybins = bins[wave];
-    auto add = [&](u32 bin, u64 d) { atomicAdd(&mybins[bin], d); };
-    for (u32 p = p0; p < p1; p += 64 * 8) {
-        float x[8]; bool sel[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            u32 i = p + j * 64 + lane;
-            sel[j] = i < p1;
-            x[j] = sel[j] ? part[i] : 0.f;
-            if (sel[j]) { u32 k = key_of(x[j]); kmin = min(kmin, k); kmax = max(kmax, k); }
+    const EXCP_GLOBAL float *part = gptr(seg_part(w, sidx));
+    for (u32 j = 0; j < 4; ++j) {
+        const u32 q0 = begin[b0 + j], q1 = begin[b0 + j + 1];
+        // this wave's quarter, cut at multiples of 256 values from the bucket's start
+        const u32 blocks = (q1 - q0 + 255u) >> 8, per = (blocks + 3u) >> 2;
+        const u32 p0 = min(q0 + wave * per * 256u, q1), p1 = min(p0 + per * 256u, q1);
+        if (p0 >= p1) continue;
+        u64 *mybins = bins[j];
+        // window base from the first (up to) 64 values: top 4 binary orders above their largest
+        u32 pm = 0;
+        {
+            const u32 i = p0 + lane;
+            const u32 mb = (i < p1) ? (f2u(part[i]) & 0x7fffffffu) : 0u;
+            const u32 e = mb >> 23;
+            pm = wave_max_u32((e ? e : 1u) - 1u);
         }
-        wave_exact_add<8>(x, sel, add);
-    }
+        const u32 B = pm + 4u > 39u ? pm + 4u - 39u : 0u;
+        u64 aL = 0, aH = 0, nL = 0, nH = 0;
+        u32 kmin = 0xffffffffu, kmax = 0;
+        auto take = [&](float xv) {
+            const u32 u = f2u(xv), mb = u & 0x7fffffffu, e = mb >> 23;
+            const u32 k = key_of(xv);
+            kmin = min(kmin, k); kmax = max(kmax, k);
+            const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+            const u32 pos = (e ? e : 1u) - 1u;
+            const bool neg = u >> 31;
+            if (pos - B < 40u) {
+                const u64 term = (u64)mant << (pos - B);
+                const u32 tl = (u32)term, th = (u32)(term >> 32);
+                aL += tl; aH += th;
+                nL += neg ? tl : 0u; nH += neg ? th : 0u;
+            } else if (mant) {
+                const u64 d = (u64)mant << (pos & 7u);
+                atomicAdd(&mybins[pos >> 3], neg ? (u64)0 - d : d);
+            }
+        };
+        for (u32 p = p0; p < p1; p += 256u) {
+            const u32 i = p + lane * 4u;
+            if (p + 256u <= p1) {
+                const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
+                take(q.x); take(q.y); take(q.z); take(q.w);
+            } else {
 #pragma unroll
-    for (int mm = 32; mm >= 1; mm >>= 1) {
-        kmin = min(kmin, (u32)__shfl_xor(kmin, mm, WAVE));
-        kmax = max(kmax, (u32)__shfl_xor(kmax, mm, WAVE));
+                for (u32 e = 0; e < 4; ++e) if (i + e < p1) take(part[i + e]);
+            }
+        }
+        // wave totals: magnitudes of all values (+) and twice those of the negative ones (-)
+        aL = wave_sum_u64(aL); aH = wave_sum_u64(aH);
+        nL = wave_sum_u64(nL); nH = wave_sum_u64(nH);
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            kmin = min(kmin, (u32)__shfl_xor(kmin, m, WAVE));
+            kmax = max(kmax, (u32)__shfl_xor(kmax, m, WAVE));
+        }
+        if (lane == 0) {
+            atomicMin(&s_min[j], kmin); atomicMax(&s_max[j], kmax);
+#pragma unroll
+            for (int sgn = 0; sgn < 2; ++sgn) {
+                const u64 L = sgn ? nL : aL, H = sgn ? nH : aH;
+                const u64 lo64 = L + (H << 32);
+                const u64 hi64 = (H >> 32) + (lo64 < L ? 1ull : 0ull);
+                const u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
+#pragma unroll
+                for (int q = 0; q < 3; ++q) {
+                    const u32 p = B + 32u * q;
+                    const u64 d = piece[q] << (p & 7u);
+                    if (piece[q]) atomicAdd(&mybins[p >> 3], sgn ? (u64)0 - 2ull * d : d);
+                }
+            }
+        }
     }
-    if (lane < EXCP_ABSM_BINS) out[lane] = bins[wave][lane];
-    if (lane == 0) { w.km_min[(u64)sidx * NBKT + b] = kmin; w.km_max[(u64)sidx * NBKT + b] = kmax; }
+    __syncthreads();
+    if (tid < 4 * EXCP_ABSM_BINS)
+        w.km_bsum[((u64)sidx * NBKT + b0) * EXCP_ABSM_BINS + tid] = (&bins[0][0])[tid];
+    if (tid < 4) { w.km_min[(u64)sidx * NBKT + b0 + tid] = s_min[tid]; w.km_max[(u64)sidx * NBKT + b0 + tid] = s_max[tid]; }
 }
 
 // ---------------------------------------------------------------- P6: initial centres
