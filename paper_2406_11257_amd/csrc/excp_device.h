@@ -61,6 +61,7 @@ struct SegState {
     u32 chunk_begin;            // first chunk of this stream in the group's chunk list
     u32 pad;
     float C[EXCP_MAX_K + 1];    // current centres (K used)
+    u32 cut[EXCP_MAX_K + 1];    // cut[k], 1 <= k < K: smallest key whose nearest centre has index >= k
 };
 
 // Host-filled description of one tensor of a decompress group.

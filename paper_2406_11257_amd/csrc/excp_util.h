@@ -101,3 +101,35 @@ __device__ __forceinline__ int nearest_centre(float x, const float *C, int K, do
     if (dist_out) { double d = xd - (double)cv; *dist_out = d * d; }
     return pick;
 }
+
+// The nearest-centre rule is monotone in the value, so it is fully described by K - 1 cut keys:
+// cut[k] = smallest key (order-preserving bit pattern) of a finite value whose nearest centre has
+// index >= k, or 0xffffffff when no finite value reaches k.  Found by bisection with the rule
+// itself, so "number of cut keys <= key(x)" IS nearest_centre(x), bit for bit.  Threads 1..K-1 of
+// the workgroup each find one; entries from K up to 255 are set to 0xffffffff.  C and cut are LDS
+// arrays of 256 entries; the caller synchronises before and after.
+__device__ __forceinline__ void compute_cut_keys(const float *C, int K, u32 *cut) {
+    const u32 k = threadIdx.x;
+    if (k == 0 || k > 255u) return;
+    u32 res = 0xffffffffu;
+    if ((int)k < K) {
+        u32 lo = 0x00800000u, hi = 0xff7fffffu;            // keys of -FLT_MAX and +FLT_MAX
+        if ((u32)nearest_centre(val_of(hi), C, K, nullptr) >= k) {
+            if ((u32)nearest_centre(val_of(lo), C, K, nullptr) >= k) hi = lo;
+            while (lo < hi) {                              // invariant: rule(hi) >= k
+                const u32 mid = lo + ((hi - lo) >> 1);
+                if ((u32)nearest_centre(val_of(mid), C, K, nullptr) >= k) hi = mid; else lo = mid + 1;
+            }
+            res = hi;
+        }
+    }
+    cut[k] = res;
+}
+
+// Number of cut keys <= key, i.e. the index of the nearest centre.  kp2 = smallest power of two >= K.
+__device__ __forceinline__ u32 centre_by_cuts(const u32 *cut, u32 kp2, u32 key) {
+    u32 lo = 0;
+    for (u32 step = kp2 >> 1; step >= 1; step >>= 1)
+        if (cut[lo + step] <= key) lo += step;
+    return lo;
+}

@@ -568,22 +568,27 @@ struct KmItem { u32 sidx, p0, p1, range; };      // range = alo | ahi << 8
 
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
+    __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u32 s_scan[EXCP_THREADS];
     __shared__ u32 s_base;
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
-    const SegState &S = w.seg[sidx];
+    SegState &S = w.seg[sidx];
     if (S.len == 0) return;
     const int K = g.K;
+    u32 kp2 = 1; while (kp2 < (u32)K) kp2 <<= 1;
     for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = S.C[k];
     __syncthreads();
+    compute_cut_keys(s_C, K, s_cut);
+    __syncthreads();
+    if (tid >= 1) S.cut[tid] = s_cut[tid];
     const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
     u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);     // [K][bins + count]
     const u32 b = tid;
     const u32 p0 = begin[b], p1 = begin[b + 1], cntb = p1 - p0;
     u32 alo = 0, ahi = 0;
     if (cntb) {
-        alo = (u32)nearest_centre(val_of(w.km_min[(u64)sidx * NBKT + b]), s_C, K, nullptr);
-        ahi = (u32)nearest_centre(val_of(w.km_max[(u64)sidx * NBKT + b]), s_C, K, nullptr);
+        alo = centre_by_cuts(s_cut, kp2, w.km_min[(u64)sidx * NBKT + b]);
+        ahi = centre_by_cuts(s_cut, kp2, w.km_max[(u64)sidx * NBKT + b]);
     }
     const bool cut = cntb && alo != ahi;
     if (cntb && !cut) {
@@ -616,27 +621,122 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
 // centres.  Sums are gathered in LDS per item and flushed with a few integer atomics.
 constexpr u32 ITEM_R = 8;      // centres per item held in LDS; wider ranges go straight to global memory
 
+// Files an integer total (low / high 32-bit halves summed separately in L and H, unit 2^(B-149))
+// into signed bins with global atomics, added or subtracted `times` times.
+__device__ __forceinline__ void file_total(u64 *bins, u64 L, u64 H, u32 B, bool subtract, u32 times) {
+    const u64 lo64 = L + (H << 32);
+    const u64 hi64 = (H >> 32) + (lo64 < L ? 1ull : 0ull);
+    const u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        const u32 p = B + 32u * q;
+        const u64 d = (piece[q] << (p & 7u)) * times;
+        if (piece[q]) atomicAdd(&bins[p >> 3], subtract ? (u64)0 - d : d);
+    }
+}
+
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
+    __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u64 s_bins[ITEM_R][EXCP_ABSM_BINS + 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int K = g.K;
+    u32 kp2 = 1; while (kp2 < (u32)K) kp2 <<= 1;
     u32 nitems = *w.km_item_count;
     if (nitems > w.km_item_cap) nitems = w.km_item_cap;
     const KmItem *items = (const KmItem *)w.km_items;
     u32 cur = 0xffffffffu;
     for (u32 it = blockIdx.x; it < nitems; it += gridDim.x) {
         const KmItem I = items[it];
+        const u32 c_lo = I.range & 255u, c_hi = I.range >> 8;
+        u64 *acc = w.km_acc + (u64)I.sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
+        if (c_hi - c_lo <= 2u) {
+            // ---- one or two borders inside the item (the usual case): per-lane integer totals of
+            // all values and of the values at or above each border; cluster totals are differences.
+            const u32 cut1 = w.seg[I.sidx].cut[c_lo + 1];
+            const u32 cut2 = (c_hi - c_lo == 2u) ? w.seg[I.sidx].cut[c_lo + 2] : 0xffffffffu;
+            const EXCP_GLOBAL float *part = gptr(seg_part(w, I.sidx));
+            const u32 blocks = (I.p1 - I.p0 + 255u) >> 8, per = (blocks + 3u) >> 2;
+            const u32 p0 = min(I.p0 + wave * per * 256u, I.p1), p1 = min(p0 + per * 256u, I.p1);
+            if (p0 >= p1) continue;                        // nothing for this wave (no barrier on this path)
+            u32 pm = 0;
+            {
+                const u32 i = p0 + lane;
+                const u32 mb = (i < p1) ? (f2u(part[i]) & 0x7fffffffu) : 0u;
+                const u32 e = mb >> 23;
+                pm = wave_max_u32((e ? e : 1u) - 1u);
+            }
+            const u32 B = pm + 4u > 39u ? pm + 4u - 39u : 0u;
+            // [0] all values, [1] values at or above border 1, [2] at or above border 2;
+            // a = magnitudes, n = magnitudes of the negative ones
+            u64 aL[3] = {0, 0, 0}, aH[3] = {0, 0, 0}, nL[3] = {0, 0, 0}, nH[3] = {0, 0, 0};
+            u32 cnt1 = 0, cnt2 = 0;
+            auto take = [&](float xv) {
+                const u32 u = f2u(xv), mb = u & 0x7fffffffu, e = mb >> 23;
+                const u32 key = key_of(xv);
+                const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+                const u32 pos = (e ? e : 1u) - 1u;
+                const bool neg = u >> 31;
+                const bool up1 = key >= cut1, up2 = key >= cut2;
+                cnt1 += up1; cnt2 += up2;
+                if (pos - B < 40u) {
+                    const u64 term = (u64)mant << (pos - B);
+                    const u32 tl = (u32)term, th = (u32)(term >> 32);
+                    const u32 ntl = neg ? tl : 0u, nth = neg ? th : 0u;
+                    aL[0] += tl; aH[0] += th; nL[0] += ntl; nH[0] += nth;
+                    aL[1] += up1 ? tl : 0u; aH[1] += up1 ? th : 0u; nL[1] += up1 ? ntl : 0u; nH[1] += up1 ? nth : 0u;
+                    aL[2] += up2 ? tl : 0u; aH[2] += up2 ? th : 0u; nL[2] += up2 ? ntl : 0u; nH[2] += up2 ? nth : 0u;
+                } else if (mant) {
+                    const u64 d = (u64)mant << (pos & 7u);
+                    const u32 cl = c_lo + (up1 ? 1u : 0u) + (up2 ? 1u : 0u);
+                    atomicAdd(&acc[(u64)cl * (EXCP_ABSM_BINS + 1) + (pos >> 3)], neg ? (u64)0 - d : d);
+                }
+            };
+            for (u32 p = p0; p < p1; p += 256u) {
+                const u32 i = p + lane * 4u;
+                if (p + 256u <= p1) {
+                    const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
+                    take(q.x); take(q.y); take(q.z); take(q.w);
+                } else {
+#pragma unroll
+                    for (u32 e = 0; e < 4; ++e) if (i + e < p1) take(part[i + e]);
+                }
+            }
+#pragma unroll
+            for (int s3 = 0; s3 < 3; ++s3) {
+                aL[s3] = wave_sum_u64(aL[s3]); aH[s3] = wave_sum_u64(aH[s3]);
+                nL[s3] = wave_sum_u64(nL[s3]); nH[s3] = wave_sum_u64(nH[s3]);
+            }
+            cnt1 = wave_sum_u32(cnt1); cnt2 = wave_sum_u32(cnt2);
+            if (lane == 0) {
+                // cluster c_lo + j receives set j minus set j + 1
+                const u32 cnt[4] = {p1 - p0, cnt1, cnt2, 0u};
+#pragma unroll
+                for (u32 j = 0; j < 3; ++j) {
+                    if (c_lo + j > c_hi) break;
+                    u64 *dst = acc + (u64)(c_lo + j) * (EXCP_ABSM_BINS + 1);
+                    file_total(dst, aL[j], aH[j], B, false, 1u);
+                    file_total(dst, nL[j], nH[j], B, true, 2u);
+                    if (j < 2 && c_lo + j < c_hi) {
+                        file_total(dst, aL[j + 1], aH[j + 1], B, true, 1u);
+                        file_total(dst, nL[j + 1], nH[j + 1], B, false, 2u);
+                    }
+                    const u32 nxt = (c_lo + j < c_hi) ? cnt[j + 1] : 0u;
+                    if (cnt[j] - nxt) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)(cnt[j] - nxt));
+                }
+            }
+            continue;
+        }
+        // ---- three or more borders inside one item (degenerate data): per-cluster accumulation
         __syncthreads();
         if (I.sidx != cur) {
             for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = w.seg[I.sidx].C[k];
+            for (u32 k = tid; k <= EXCP_MAX_K; k += EXCP_THREADS) s_cut[k] = w.seg[I.sidx].cut[k];
             cur = I.sidx;
         }
         for (u32 i = tid; i < ITEM_R * (EXCP_ABSM_BINS + 1); i += EXCP_THREADS) (&s_bins[0][0])[i] = 0;
         __syncthreads();
-        const u32 c_lo = I.range & 255u, c_hi = I.range >> 8;
         const bool in_lds = (c_hi - c_lo) < ITEM_R;
-        u64 *acc = w.km_acc + (u64)I.sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
         const float *__restrict__ part = seg_part(w, I.sidx);
         for (u32 p = I.p0 + wave * 512; p < I.p1; p += 4 * 512) {
             float x[8]; bool ok[8]; u32 a[8];
@@ -647,7 +747,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupPara
                 x[j] = ok[j] ? part[i] : 0.f;
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) a[j] = ok[j] ? (u32)nearest_centre(x[j], s_C, K, nullptr) : 0xffffffffu;
+            for (int j = 0; j < 8; ++j) a[j] = ok[j] ? centre_by_cuts(s_cut, kp2, key_of(x[j])) : 0xffffffffu;
             for (u32 cl = c_lo; cl <= c_hi; ++cl) {
                 bool sel[8]; u32 n = 0;
 #pragma unroll
@@ -700,7 +800,8 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupPa
 // A chunk's codes are staged as bytes in LDS, then each thread assembles whole 64-bit words.
 __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
-    __shared__ unsigned char s_code[EXCP_CHUNK + 64];
+    __shared__ u32 s_cut[EXCP_MAX_K + 1];
+    __shared__ __attribute__((aligned(8))) unsigned char s_code[EXCP_CHUNK + 64];
     __shared__ double s_red[EXCP_THREADS / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 total = *w.chunk_total;
@@ -709,6 +810,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
     if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
     const int K = g.K;
+    u32 kp2 = 1; while (kp2 < (u32)K) kp2 <<= 1;
     const u32 nbits = (u32)g.nbits;
     const u32 words_per_chunk = EXCP_CHUNK * nbits / 64u;
 
@@ -720,11 +822,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
             s_end = w.seg_chunk_begin[sidx + 1];
             for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = w.seg[sidx].C[k];
             __syncthreads();
+            compute_cut_keys(s_C, K, s_cut);       // the final centres' cut keys
+            __syncthreads();
         }
         const SegState &S = w.seg[sidx];
         const u32 t = sidx / 3u, which = sidx % 3u;
         const TState &T = w.st[t];
-        const float *__restrict__ x = seg_data(w, sidx);
         const u64 len = S.len;
         const u64 ebase = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
         const u32 clen = (len - ebase) < EXCP_CHUNK ? (u32)(len - ebase) : EXCP_CHUNK;
@@ -733,21 +836,21 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
         const u64 wbase = (u64)(c - S.chunk_begin) * words_per_chunk;
         double obj = 0.0;
         float v[PER_THREAD];
+        load_chunk(gptr(seg_data(w, sidx)) + ebase, clen, v);
 #pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            u32 e = it * EXCP_THREADS + tid;
-            v[it] = (e < clen) ? x[ebase + e] : 0.f;
-        }
+        for (u32 q = 0; q < PER_THREAD / 4; ++q) {
+            u32 four = 0;                          // the codes of four consecutive values, one per byte
 #pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            u32 e = it * EXCP_THREADS + tid;
-            u32 code = 0;
-            if (e < clen) {
-                double dist;
-                code = 1u + (u32)nearest_centre(v[it], s_C, K, &dist);
-                obj += dist;
+            for (u32 j = 0; j < 4; ++j) {
+                const u32 it = 4 * q + j;
+                if (clen == EXCP_CHUNK || chunk_elem(it) < clen) {
+                    const u32 pick = centre_by_cuts(s_cut, kp2, key_of(v[it]));
+                    const double d = (double)v[it] - (double)s_C[pick];
+                    obj += d * d;
+                    four |= (1u + pick) << (8u * j);
+                }
             }
-            s_code[e] = (unsigned char)code;
+            *(u32 *)(s_code + chunk_elem(4 * q)) = four;
         }
         if (tid < 64) s_code[EXCP_CHUNK + tid] = 0;
         __syncthreads();
