@@ -192,6 +192,25 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_slots(Workspace w, GroupP
     }
 }
 
+// One wave copies floats in batches of N x 64; every load of a batch is issued before its stores so
+// that a copy is not a chain of dependent round trips.
+template <int N>
+__device__ __forceinline__ void load_batch(float (&q)[N], const EXCP_GLOBAL float *src, u32 cnt, u32 b0, u32 lane) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const u32 i = b0 + (u32)k * 64u + lane;
+        q[k] = i < cnt ? src[i] : 0.f;
+    }
+}
+template <int N>
+__device__ __forceinline__ void store_batch(EXCP_GLOBAL float *dst, const float (&q)[N], u32 cnt, u32 b0, u32 lane) {
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const u32 i = b0 + (u32)k * 64u + lane;
+        if (i < cnt) dst[i] = q[k];
+    }
+}
+
 // Exclusive scan of the sub-tile counts of one tensor (one workgroup per tensor); the totals are
 // the tensor's n_w and n_o.  Counts are packed (survivors << 32 | moment survivors).
 __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupParams g) {
@@ -232,45 +251,77 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupPa
 }
 
 // Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays and
-// merges the sub-tile's M_o bits into the blob at the survivor position.
+// merges the sub-tile's M_o bits into the blob at the survivor position.  A workgroup takes 32
+// consecutive sub-tiles; their counts, prefixes and tensor data are fetched once, side by side,
+// into LDS, so that a wave's copies do not wait behind a chain of dependent look-ups.
+constexpr u32 GATHER_SUBS = 32;
+
 __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, GroupParams g) {
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    __shared__ u32 s_tw[GATHER_SUBS], s_to[GATHER_SUBS], s_pw[GATHER_SUBS], s_po[GATHER_SUBS], s_t[GATHER_SUBS];
+    __shared__ u64 s_slot[GATHER_SUBS], s_eoff[GATHER_SUBS];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 nsub = 2u * g.ntiles;
     load_tile_table(s_tiles, w.tile_begin, g.ntensors);
-    for (u32 sub = blockIdx.x * 4 + wave; sub < nsub; sub += gridDim.x * 4) {
-        const u64 c = w.tile_status[sub];
-        const u32 tw = (u32)(c >> 32), to = (u32)c;
-        if (tw == 0) continue;
-        const u32 t = find_owner(s_tiles, g.ntensors, sub >> 1);
-        const TDesc &D = w.desc[t];
-        const u64 n = D.n;
-        const u64 pre = w.mask_prefix[sub];
-        const u32 pw = (u32)(pre >> 32), po = (u32)pre;
-        const u64 base = (u64)(sub - 2u * s_tiles[t]) * SUB;
-        const u64 slot = D.elem_off + base;
-        const EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
-        EXCP_GLOBAL float *xw = gptr(w.xw) + D.elem_off + pw;
-        EXCP_GLOBAL float *xm = gptr(w.xm) + D.elem_off + po;
-        EXCP_GLOBAL float *xv = gptr(w.xv) + D.elem_off + po;
-        for (u32 i = lane; i < tw; i += 64) xw[i] = sw[i];
-        for (u32 i = lane; i < to; i += 64) { xm[i] = sm[i]; xv[i] = sv[i]; }
-        // M_o bits: the sub-tile's local stream shifted to survivor position pw
-        const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n));
-        u64 *bmo = (u64 *)(D.blob + off_bo);
-        const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
-        const u32 sh = pw & 63u;
-        const u32 nloc = (tw + 63u) >> 6;                         // local words that hold bits
-        const u32 nout = (sh + tw + 63u) >> 6;                    // words touched, <= 33
-        const u64 *loc = w.mask_bo + (u64)sub * BO_WORDS;
-        if (lane < nout) {
+    for (u32 sub0 = blockIdx.x * GATHER_SUBS; sub0 < nsub; sub0 += gridDim.x * GATHER_SUBS) {
+        __syncthreads();
+        if (tid < GATHER_SUBS) {
+            const u32 sub = sub0 + tid;
+            u32 tw = 0, to = 0;
+            if (sub < nsub) {
+                const u64 c = w.tile_status[sub], pre = w.mask_prefix[sub];
+                tw = (u32)(c >> 32); to = (u32)c;
+                const u32 t = find_owner(s_tiles, g.ntensors, sub >> 1);
+                const u64 eoff = w.desc[t].elem_off;
+                s_pw[tid] = (u32)(pre >> 32); s_po[tid] = (u32)pre; s_t[tid] = t;
+                s_eoff[tid] = eoff;
+                s_slot[tid] = eoff + (u64)(sub - 2u * s_tiles[t]) * SUB;
+            }
+            s_tw[tid] = tw; s_to[tid] = to;
+        }
+        __syncthreads();
+        for (u32 j = wave; j < GATHER_SUBS; j += 4) {
+            const u32 tw = s_tw[j], to = s_to[j];
+            if (tw == 0) continue;
+            const u32 sub = sub0 + j, t = s_t[j];
+            const u32 pw = s_pw[j], po = s_po[j];
+            const u64 slot = s_slot[j], eoff = s_eoff[j];
+            const EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
+            EXCP_GLOBAL float *xw = gptr(w.xw) + eoff + pw;
+            EXCP_GLOBAL float *xm = gptr(w.xm) + eoff + po;
+            EXCP_GLOBAL float *xv = gptr(w.xv) + eoff + po;
+            // M_o words of the sub-tile (needed below), fetched together with the values
+            const u32 nloc = (tw + 63u) >> 6;                     // local words that hold bits
+            const u64 *loc = w.mask_bo + (u64)sub * BO_WORDS;
             const u64 cur = lane < nloc ? loc[lane] : 0ull;
-            const u64 below = (lane > 0 && lane - 1 < nloc) ? loc[lane - 1] : 0ull;
-            const u64 bits = sh ? ((cur << sh) | (below >> (64u - sh))) : cur;
-            const u64 wi = (u64)(pw >> 6) + lane;
-            if (wi < cap_words) {
-                if (lane == 0 || lane + 1 == nout) { if (bits) atomicOr(&bmo[wi], bits); }
-                else bmo[wi] = bits;
+            {
+                // the first batch of all three runs in flight together (usually there is no second)
+                float qw[12], qm[4], qv[4];
+                load_batch<12>(qw, sw, tw, 0, lane); load_batch<4>(qm, sm, to, 0, lane); load_batch<4>(qv, sv, to, 0, lane);
+                store_batch<12>(xw, qw, tw, 0, lane); store_batch<4>(xm, qm, to, 0, lane); store_batch<4>(xv, qv, to, 0, lane);
+                for (u32 b0 = 768u; b0 < tw; b0 += 768u) { load_batch<12>(qw, sw, tw, b0, lane); store_batch<12>(xw, qw, tw, b0, lane); }
+                for (u32 b0 = 256u; b0 < to; b0 += 256u) {
+                    load_batch<4>(qm, sm, to, b0, lane); load_batch<4>(qv, sv, to, b0, lane);
+                    store_batch<4>(xm, qm, to, b0, lane); store_batch<4>(xv, qv, to, b0, lane);
+                }
+            }
+            // M_o bits: the sub-tile's local stream shifted to survivor position pw
+            const TDesc &D = w.desc[t];
+            const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(D.n));
+            u64 *bmo = (u64 *)(D.blob + off_bo);
+            const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
+            const u32 sh = pw & 63u;
+            const u32 nout = (sh + tw + 63u) >> 6;                    // words touched, <= 33
+            // the word of the lane below (lane 0 has none)
+            const u32 blo = __shfl_up((u32)cur, 1, WAVE), bhi = __shfl_up((u32)(cur >> 32), 1, WAVE);
+            const u64 below = lane > 0 ? (((u64)bhi << 32) | blo) : 0ull;
+            if (lane < nout) {
+                const u64 bits = sh ? ((cur << sh) | (below >> (64u - sh))) : cur;
+                const u64 wi = (u64)(pw >> 6) + lane;
+                if (wi < cap_words) {
+                    if (lane == 0 || lane + 1 == nout) { if (bits) atomicOr(&bmo[wi], bits); }
+                    else bmo[wi] = bits;
+                }
             }
         }
     }
@@ -362,7 +413,7 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
     } else if (phase == 1) {
         hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
     } else {
-        u32 grid = (nsub + 3) / 4;
+        u32 grid = (nsub + 31) / 32;
         if (grid > (u32)w.grid_stream * 8u) grid = (u32)w.grid_stream * 8u;
         hipLaunchKernelGGL(k_mask_gather, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     }
