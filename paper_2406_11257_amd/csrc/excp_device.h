@@ -125,7 +125,7 @@ struct Workspace {
     u32 *km_min, *km_max;     // [segment][256] smallest / largest key of every bucket
     u64 *km_acc;              // [segment][EXCP_MAX_K][EXCP_ABSM_BINS + 1] per-centre exact sum and count
     void *km_items;           // work items of the Lloyd accumulation (cut buckets in pieces)
-    u32 *km_item_count;       // [1]
+    u32 *km_item_count;       // [2] lengths of the two work lists used by alternate iterations
     u32 km_item_cap;
     double *part_obj;         // [chunk]
     u32 max_chunks;
@@ -147,8 +147,8 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
 void launch_layout(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hipStream_t s);
 void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s);
-void launch_km_classify(const Workspace &w, const GroupParams &g, hipStream_t s);
-void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s);
+void launch_km_classify(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s);
+void launch_km_iter(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s);
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);

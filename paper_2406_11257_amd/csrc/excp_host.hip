@@ -376,10 +376,11 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }
         { StageTimer t(c, ST_KM_INIT); launch_km_init(w, p, s); }
         for (int it = 0; it < lloyd_iters; ++it) {
-            { StageTimer t(c, ST_KM_CLASSIFY); launch_km_classify(w, p, s); }
-            { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, s); }
-            { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
+            // classification also moves the centres by the previous iteration's totals
+            { StageTimer t(c, ST_KM_CLASSIFY); launch_km_classify(w, p, it, s); }
+            { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, it, s); }
         }
+        if (lloyd_iters > 0) { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
         { StageTimer t(c, ST_ASSIGN_PACK); launch_assign_pack(w, p, s); }
         { StageTimer t(c, ST_FINALIZE); launch_finalize(w, p, s); }
         bool any_out = false;

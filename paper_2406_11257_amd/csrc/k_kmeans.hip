@@ -527,7 +527,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
     const u32 b = lo, p0 = begin[b], p1 = begin[b + 1];
     u32 rank = r - p0;
     const u32 kmin = w.km_min[(u64)sidx * NBKT + b], kmax = w.km_max[(u64)sidx * NBKT + b];
-    const float *__restrict__ part = seg_part(w, sidx);
+    const EXCP_GLOBAL float *gpart = gptr(seg_part(w, sidx));
     u32 diff = kmin ^ kmax;
     if (diff == 0) { if (tid == 0) S.C[k] = val_of(kmin); return; }
     int hb = 31 - __clz((int)diff);          // highest bit in which keys of this bucket differ
@@ -539,10 +539,22 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
         const int shift = top + 1 - width;
         hist[tid] = 0;
         __syncthreads();
-        for (u32 p = p0 + tid; p < p1; p += EXCP_THREADS) {
-            u32 key = key_of(part[p]);
-            bool match = (top == 31) ? true : ((key >> (top + 1)) == prefix);
+        auto tally = [&](float xv) {
+            const u32 key = key_of(xv);
+            const bool match = (top == 31) ? true : ((key >> (top + 1)) == prefix);
             if (match) atomicAdd(&hist[(key >> shift) & ((1u << width) - 1u)], 1u);
+        };
+        // 4096 values per round, sixteen per thread, every load of a round issued before its use
+        for (u32 q0 = p0; q0 < p1; q0 += 16u * EXCP_THREADS) {
+            if (q0 + 16u * EXCP_THREADS <= p1) {
+                f4u q[4];
+#pragma unroll
+                for (u32 j = 0; j < 4; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(gpart + q0 + (j * EXCP_THREADS + tid) * 4u);
+#pragma unroll
+                for (u32 j = 0; j < 4; ++j) { tally(q[j].x); tally(q[j].y); tally(q[j].z); tally(q[j].w); }
+            } else {
+                for (u32 p = q0 + tid; p < p1; p += EXCP_THREADS) tally(gpart[p]);
+            }
         }
         __syncthreads();
         if (tid == 0) {
@@ -560,23 +572,59 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
     if (tid == 0) S.C[k] = val_of(prefix);
 }
 
+// New centres of one stream from the iteration's totals: centre = fp32(exact sum / count), a
+// cluster without members keeps its centre; the totals are cleared for the next iteration.
+// Called by the whole workgroup (it holds barriers); the totals of sixteen centres at a time are
+// fetched into LDS side by side, so that no thread walks a chain of dependent global reads.
+// lds_C (optional) receives the centres as well.
+__device__ __forceinline__ void move_centres(const Workspace &w, const GroupParams &g, u32 sidx, float *lds_C) {
+    constexpr u32 STRIDE = EXCP_ABSM_BINS + 1, BATCH = 16;
+    __shared__ u64 s_acc[BATCH * STRIDE];
+    SegState &S = w.seg[sidx];
+    const u32 K = (u32)g.K, tid = threadIdx.x;
+    u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * STRIDE;
+    for (u32 k0 = 0; k0 < K; k0 += BATCH) {
+        const u32 nk = min(BATCH, K - k0);
+        __syncthreads();
+        for (u32 i = tid; i < nk * STRIDE; i += EXCP_THREADS) {
+            s_acc[i] = acc[(u64)k0 * STRIDE + i];
+            acc[(u64)k0 * STRIDE + i] = 0;
+        }
+        __syncthreads();
+        if (tid < nk) {
+            const u64 *a = s_acc + tid * STRIDE;
+            const u64 cnt = a[EXCP_ABSM_BINS];
+            float c = S.C[k0 + tid];
+            if (cnt) {
+                const double sum = signed_bins_to_double(a);
+                c = (float)(sum / (double)cnt);
+                S.C[k0 + tid] = c;
+            }
+            if (lds_C) lds_C[k0 + tid] = c;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- P5a: one Lloyd accumulation
 // Classification (one workgroup per stream): every bucket is compared with the current centres.
 // A bucket whose smallest and largest value go to the same centre adds its stored totals to that
 // centre; a bucket that a cluster border cuts is split into work items of at most 8192 values.
 struct KmItem { u32 sidx, p0, p1, range; };      // range = alo | ahi << 8
 
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, GroupParams g, u32 parity, u32 do_update) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u32 s_scan[EXCP_THREADS];
     __shared__ u32 s_base;
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
     SegState &S = w.seg[sidx];
+    // the work list of the next iteration (the other of two) starts empty; nobody reads it now
+    if (sidx == 0 && tid == 0) w.km_item_count[parity ^ 1u] = 0;
     if (S.len == 0) return;
     const int K = g.K;
     u32 kp2 = 1; while (kp2 < (u32)K) kp2 <<= 1;
-    for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = S.C[k];
+    if (do_update) move_centres(w, g, sidx, s_C);          // the previous iteration's totals
+    else for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = S.C[k];
     __syncthreads();
     compute_cut_keys(s_C, K, s_cut);
     __syncthreads();
@@ -594,7 +642,11 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
     if (cntb && !cut) {
         u64 *dst = acc + (u64)alo * (EXCP_ABSM_BINS + 1);
         const u64 *src = w.km_bsum + ((u64)sidx * NBKT + b) * EXCP_ABSM_BINS;
-        for (int q = 0; q < EXCP_ABSM_BINS; ++q) { u64 v = src[q]; if (v) atomicAdd(&dst[q], v); }
+        u64 tot[EXCP_ABSM_BINS];                   // all reads first: they must not queue behind the atomics
+#pragma unroll
+        for (int q = 0; q < EXCP_ABSM_BINS; ++q) tot[q] = src[q];
+#pragma unroll
+        for (int q = 0; q < EXCP_ABSM_BINS; ++q) if (tot[q]) atomicAdd(&dst[q], tot[q]);
         atomicAdd(&dst[EXCP_ABSM_BINS], (u64)cntb);
     }
     const u32 nitems = cut ? (cntb + EXCP_CHUNK - 1) / EXCP_CHUNK : 0u;
@@ -606,7 +658,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
         s_scan[tid] += v;
         __syncthreads();
     }
-    if (tid == EXCP_THREADS - 1) s_base = s_scan[tid] ? atomicAdd(w.km_item_count, s_scan[tid]) : 0u;
+    if (tid == EXCP_THREADS - 1) s_base = s_scan[tid] ? atomicAdd(&w.km_item_count[parity], s_scan[tid]) : 0u;
     __syncthreads();
     u32 at = s_base + s_scan[tid] - nitems;
     KmItem *items = (KmItem *)w.km_items;
@@ -635,14 +687,14 @@ __device__ __forceinline__ void file_total(u64 *bins, u64 L, u64 H, u32 B, bool 
     }
 }
 
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u64 s_bins[ITEM_R][EXCP_ABSM_BINS + 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int K = g.K;
     u32 kp2 = 1; while (kp2 < (u32)K) kp2 <<= 1;
-    u32 nitems = *w.km_item_count;
+    u32 nitems = w.km_item_count[parity];
     if (nitems > w.km_item_cap) nitems = w.km_item_cap;
     const KmItem *items = (const KmItem *)w.km_items;
     u32 cur = 0xffffffffu;
@@ -778,22 +830,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupPara
 }
 
 // ---------------------------------------------------------------- P5b: move the centres
+// After the last iteration (earlier ones are moved by the next classification kernel).
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupParams g) {
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
-    SegState &S = w.seg[sidx];
-    if (sidx == 0 && tid == 0) *w.km_item_count = 0;       // the work list is rebuilt every iteration
-    if (S.len == 0) return;
-    const u32 K = (u32)g.K;
-    u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
-    for (u32 k = tid; k < K; k += EXCP_THREADS) {
-        u64 *a = acc + (u64)k * (EXCP_ABSM_BINS + 1);
-        const u64 cnt = a[EXCP_ABSM_BINS];
-        if (cnt) {
-            double sum = signed_bins_to_double(a);
-            S.C[k] = (float)(sum / (double)cnt);
-        }
-        for (int q = 0; q <= EXCP_ABSM_BINS; ++q) a[q] = 0;
-    }
+    if (sidx == 0 && tid < 2) w.km_item_count[tid] = 0;    // both work lists start empty next time
+    if (w.seg[sidx].len == 0) return;
+    move_centres(w, g, sidx, nullptr);
 }
 
 // ---------------------------------------------------------------- final assignment + packing
@@ -944,14 +986,15 @@ void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s) {
     hipLaunchKernelGGL(k_km_init, dim3(3 * g.ntensors * (u32)g.K), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
-void launch_km_classify(const Workspace &w, const GroupParams &g, hipStream_t s) {
+void launch_km_classify(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_classify, dim3(3 * g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
+    hipLaunchKernelGGL(k_km_classify, dim3(3 * g.ntensors), dim3(EXCP_THREADS), 0, s, w, g,
+                       (u32)(iteration & 1), (u32)(iteration > 0));
 }
 
-void launch_km_iter(const Workspace &w, const GroupParams &g, hipStream_t s) {
+void launch_km_iter(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_iter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g);
+    hipLaunchKernelGGL(k_km_iter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g, (u32)(iteration & 1));
 }
 
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {

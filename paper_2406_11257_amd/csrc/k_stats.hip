@@ -3,7 +3,7 @@
 //     tensor: a sorted sample of 8192 residuals brackets the median between two keys lo <= hi; the
 //     streaming pass counts the keys below lo and collects the few per cent of keys inside the
 //     bracket; a radix-histogram select (LDS histograms, 11 bits per pass) over those candidates
-//     then finds the order statistic.  The bracket can miss (probability below 1e-6 per tensor, or
+//     then finds the order statistic.  The bracket can miss (probability about 2e-5 per tensor, or
 //     adversarial data); the counts reveal that, and the tensor then takes the always-correct
 //     fallback: a three-pass radix-histogram select over the whole tensor (11 + 11 + 9 key bits);
 //   * the exact sum of |m| per tensor (Eq. "r_o") by integer accumulation: every |m_i| is
@@ -25,7 +25,7 @@ namespace {
 #endif
 
 constexpr u32 MED_SAMPLE = 8192;      // sample size (and the size up to which a tensor is simply sorted)
-constexpr u32 MED_HALF_WIDTH = 256;   // bracket = sample ranks 4096 -+ 256 (about 5.6 sigma)
+constexpr u32 MED_HALF_WIDTH = 192;   // bracket = sample ranks 4096 -+ 192 (about 4.2 sigma of the sample rank)
 constexpr u32 CAND_PER_WAVE = 1024;
 
 enum { MED_PENDING = 0, MED_KNOWN = 1, MED_FALLBACK = 2 };
