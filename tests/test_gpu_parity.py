@@ -205,6 +205,52 @@ def test_thresholds_decided_exactly_at_the_boundary(ctx):
         assert ref.median == 1 and 0 < ref.n_w < c[0].size
 
 
+def test_tensors_at_addresses_that_are_only_four_byte_aligned(ctx):
+    # every array starts 1, 2 or 3 floats past a 256-byte boundary (the kernels use 16-byte accesses)
+    import torch
+    n = 300007
+    c = case(n, 411)
+    ref = O.compress_step(*c, 5e-5, 2.0, 4, 10)
+    for shift in (1, 2, 3):
+        views = []
+        for a in c:
+            buf = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+            buf[shift:shift + n] = torch.from_numpy(a).cuda()
+            views.append(buf[shift:shift + n])
+        cap = X.excp_blob_bound(n, 4)
+        blob = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+        wout = torch.full((n + 8,), 7.0, dtype=torch.float32, device="cuda")
+        ctx.excp_compress_tensors([(views[0], views[1], views[2], views[3], blob, wout[shift:shift + n])],
+                                  5e-5, 2.0, 4, 10, 0)
+        rc, stats = ctx.excp_collect(check=False)
+        assert rc == 0 and stats[0].status == 0
+        got = blob.cpu().numpy()[:int(stats[0].blob_bytes)].tobytes()
+        assert got == ref.blob, shift
+        full = wout.cpu().numpy()
+        assert np.array_equal(full[shift:shift + n].view(np.uint32), ref.W_recon.view(np.uint32))
+        assert np.all(full[:shift] == 7.0) and np.all(full[shift + n:] == 7.0)      # nothing outside the view
+        # Alg. 2 with misaligned inputs and outputs
+        outs = [torch.full((n + 8,), 9.0, dtype=torch.float32, device="cuda") for _ in range(3)]
+        rc = ctx.excp_decompress_step(views[0], blob, int(stats[0].blob_bytes), outs[0][shift:shift + n],
+                                      outs[1][shift:shift + n], outs[2][shift:shift + n], check=False)
+        assert rc == 0
+        for o, r in zip(outs, (ref.W_recon, ref.m_recon, ref.v_recon)):
+            h = o.cpu().numpy()
+            assert np.array_equal(h[shift:shift + n].view(np.uint32), r.view(np.uint32))
+            assert np.all(h[:shift] == 9.0) and np.all(h[shift + n:] == 9.0)
+
+
+def test_heavy_tails_and_one_sided_streams(ctx):
+    # Student-t residuals with huge outliers, and moments of a single sign: the bucket map must stay
+    # correct when one sign has no samples or the range is very wide
+    g = np.random.default_rng(512)
+    n = 400000
+    Wp, W, m, v = case(n, 511, heavy=True)
+    W = W.copy(); W[::50000] += f32(3.0)                        # a few enormous residuals
+    m2 = np.abs(m)                                              # first moment all positive
+    check_all(ctx, [(Wp, W, m, v), (Wp, W, m2, v), (Wp, W, -m2, v)])
+
+
 def test_in_place_reconstruction_and_single_tensor_calls(ctx):
     Wp, W, m, v = case(123457, 81)
     ref = O.compress_step(Wp, W, m, v)
