@@ -251,6 +251,18 @@ def test_heavy_tails_and_one_sided_streams(ctx):
     check_all(ctx, [(Wp, W, m, v), (Wp, W, m2, v), (Wp, W, -m2, v)])
 
 
+def test_tensors_of_the_other_benchmark_configurations(ctx):
+    # the first transformer layer of the Pythia-410M-shaped and Pythia-1.4B-shaped checkpoints (weaker
+    # updates on norm tensors in one, Student-t updates on every fifth tensor in the other), with the
+    # bigger matrices cut to their first 2 M elements so that the oracle stays quick
+    for cid in (1, 2):
+        cfg = synth.config(cid)
+        cases = [synth.draw_tensor(cid, i, cfg.tensors[i], n=min(cfg.tensors[i].n, 1 << 21)) for i in range(1, 13)]
+        out, worst = check_all(ctx, cases, synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS)
+        kept = sum(o["stats"].n_w for o in out) / sum(o["stats"].n for o in out)
+        print("config", cid, "first layer: kept fraction", round(kept, 4), "worst centre err", worst, flush=True)
+
+
 def test_in_place_reconstruction_and_single_tensor_calls(ctx):
     Wp, W, m, v = case(123457, 81)
     ref = O.compress_step(Wp, W, m, v)
