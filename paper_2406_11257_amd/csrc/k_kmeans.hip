@@ -839,11 +839,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupPa
 }
 
 // ---------------------------------------------------------------- final assignment + packing
-// A chunk's codes are staged as bytes in LDS, then each thread assembles whole 64-bit words.
+// A chunk's codes are ORed, four at a time, into the chunk's bit stream in LDS and leave as whole
+// 64-bit words.
 __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
-    __shared__ __attribute__((aligned(8))) unsigned char s_code[EXCP_CHUNK + 64];
+    __shared__ u32 s_pack[EXCP_CHUNK * 8 / 32 + 2];      // the chunk's packed codes (up to 8 bits each)
     __shared__ double s_red[EXCP_THREADS / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 total = *w.chunk_total;
@@ -879,9 +880,11 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
         double obj = 0.0;
         float v[PER_THREAD];
         load_chunk(gptr(seg_data(w, sidx)) + ebase, clen, v);
+        for (u32 i = tid; i < 2u * words_per_chunk + 2u; i += EXCP_THREADS) s_pack[i] = 0;
+        __syncthreads();
 #pragma unroll
         for (u32 q = 0; q < PER_THREAD / 4; ++q) {
-            u32 four = 0;                          // the codes of four consecutive values, one per byte
+            u32 field = 0;                         // the codes of four consecutive values, nbits each
 #pragma unroll
             for (u32 j = 0; j < 4; ++j) {
                 const u32 it = 4 * q + j;
@@ -889,26 +892,21 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, Group
                     const u32 pick = centre_by_cuts(s_cut, kp2, key_of(v[it]));
                     const double d = (double)v[it] - (double)s_C[pick];
                     obj += d * d;
-                    four |= (1u + pick) << (8u * j);
+                    field |= (1u + pick) << (nbits * j);
                 }
             }
-            *(u32 *)(s_code + chunk_elem(4 * q)) = four;
+            // into the chunk's bit stream at bit (first element) * nbits: at most two 32-bit words
+            const u32 bitpos = chunk_elem(4 * q) * nbits, wi = bitpos >> 5, sh = bitpos & 31u;
+            if (field) {
+                atomicOr(&s_pack[wi], field << sh);
+                if (sh && (field >> (32u - sh))) atomicOr(&s_pack[wi + 1], field >> (32u - sh));
+            }
         }
-        if (tid < 64) s_code[EXCP_CHUNK + tid] = 0;
         __syncthreads();
         for (u32 wl = tid; wl < words_per_chunk; wl += EXCP_THREADS) {
             const u64 wg = wbase + wl;
             if (wg >= nwords) break;
-            const u32 bit0 = wl * 64u;
-            u32 e = bit0 / nbits;
-            int sh = (int)(e * nbits) - (int)bit0;          // <= 0 for the first code of the word
-            u64 word = 0;
-            while (sh < 64) {
-                u64 code = s_code[e];
-                word |= (sh >= 0) ? (code << sh) : (code >> (-sh));
-                ++e; sh += (int)nbits;
-            }
-            out[wg] = word;
+            out[wg] = (u64)s_pack[2 * wl] | ((u64)s_pack[2 * wl + 1] << 32);
             if (wg == nwords - 1 && (nwords & 1ull)) out[nwords] = 0ull;     // 16-byte padding
         }
 #pragma unroll

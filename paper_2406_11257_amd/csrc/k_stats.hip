@@ -288,32 +288,54 @@ __global__ void k_cand_begin(Workspace w, GroupParams g) {
     if (span == 0) { S.med_bits = S.br_lo; S.med_state = MED_KNOWN; }
 }
 
-// One radix pass over the candidates: histogram of the top (up to 11) undecided bits.
+// One radix pass over the candidates: histogram of the top (up to 11) undecided bits.  A workgroup
+// takes the candidates that belong to 256 consecutive tiles of the group's tile list -- for each
+// tensor it meets, the matching share of that tensor's candidate list -- so that its LDS histogram
+// is flushed once per tensor it meets and not once per tensor of the group.
+constexpr u32 CAND_TILES = 256;
+
 __global__ __launch_bounds__(EXCP_THREADS) void k_cand_hist(Workspace w, GroupParams g) {
     __shared__ u32 hist[2048];
     const u32 tid = threadIdx.x;
+    const u32 lo = blockIdx.x * CAND_TILES, hi = min(lo + CAND_TILES, g.ntiles);
+    if (lo >= hi) return;
     for (u32 i = tid; i < 2048; i += EXCP_THREADS) hist[i] = 0;
     __syncthreads();
-    for (u32 t = 0; t < g.ntensors; ++t) {
+    u32 t = find_owner(w.tile_begin, g.ntensors, lo);
+    for (u32 a0 = lo; a0 < hi; ++t) {
+        const u32 tb = w.tile_begin[t], te = w.tile_begin[t + 1];
+        const u32 a1 = min(te, hi);                       // this workgroup's tiles of tensor t: [a0, a1)
         const TState &S = w.st[t];
-        if (S.med_state != MED_PENDING || S.sel_width == 0) continue;
-        const u32 cnt = S.cand_count, base = S.sel_base, width = S.sel_width;
-        const u32 shift = width > 11u ? width - 11u : 0u;
-        const u64 limit = 1ull << width;
-        const u32 *c = w.cand + w.desc[t].cand_off;
-        bool any = false;
-        for (u32 i = blockIdx.x * EXCP_THREADS + tid; i < cnt; i += gridDim.x * EXCP_THREADS) {
-            const u32 rel = c[i] - base;                  // keys below base wrap around and drop out
-            if ((u64)rel < limit) atomicAdd(&hist[rel >> shift], 1u);
-            any = true;
-        }
-        if (__syncthreads_or(any)) {
+        if (a1 > a0 && S.med_state == MED_PENDING && S.sel_width != 0) {
+            const u32 cnt = S.cand_count, base = S.sel_base, width = S.sel_width;
+            const u32 shift = width > 11u ? width - 11u : 0u;
+            const u64 limit = 1ull << width;
+            const u32 tc = te - tb;
+            const u32 i0 = (u32)(((u64)cnt * (a0 - tb)) / tc), i1 = (u32)(((u64)cnt * (a1 - tb)) / tc);
+            const EXCP_GLOBAL u32 *c = gptr(w.cand) + w.desc[t].cand_off;
+            auto tally = [&](u32 key) {
+                const u32 rel = key - base;               // keys below base wrap around and drop out
+                if ((u64)rel < limit) atomicAdd(&hist[rel >> shift], 1u);
+            };
+            for (u32 q0 = i0; q0 < i1; q0 += 4u * EXCP_THREADS) {
+                if (q0 + 4u * EXCP_THREADS <= i1) {
+                    u32 k[4];
+#pragma unroll
+                    for (u32 j = 0; j < 4; ++j) k[j] = c[q0 + j * EXCP_THREADS + tid];
+#pragma unroll
+                    for (u32 j = 0; j < 4; ++j) tally(k[j]);
+                } else {
+                    for (u32 i = q0 + tid; i < i1; i += EXCP_THREADS) tally(c[i]);
+                }
+            }
+            __syncthreads();
             for (u32 i = tid; i < 2048; i += EXCP_THREADS) {
-                u32 v = hist[i];
+                const u32 v = hist[i];
                 if (v) { atomicAdd(&w.med_hist[(u64)t * 2048u + i], v); hist[i] = 0; }
             }
             __syncthreads();
         }
+        a0 = a1;
     }
 }
 
@@ -528,7 +550,7 @@ void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream
         case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, block, 0, s, w, g); break;
         case 1: if (g.ntiles) hipLaunchKernelGGL(k_stats_stream, stream_grid, block, 0, s, w, g); break;
         case 2: hipLaunchKernelGGL(k_cand_begin, small, dim3(256), 0, s, w, g); break;
-        case 3: hipLaunchKernelGGL(k_cand_hist, dim3(1024), block, 0, s, w, g); break;
+        case 3: if (g.ntiles) hipLaunchKernelGGL(k_cand_hist, dim3((g.ntiles + CAND_TILES - 1) / CAND_TILES), block, 0, s, w, g); break;
         case 4: hipLaunchKernelGGL(k_cand_resolve, per_tensor, block, 0, s, w, g); break;
         case 5: if (g.ntiles) hipLaunchKernelGGL(k_full_hist<0>, stream_grid, block, 0, s, w, g); break;
         case 6: if (g.ntiles) hipLaunchKernelGGL(k_full_hist<1>, stream_grid, block, 0, s, w, g); break;
