@@ -386,8 +386,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         bool any_out = false;
         for (u32 q = 0; q < g.count; ++q) any_out = any_out || tensors[g.first + q].W_recon_out != nullptr;
         if (any_out) {
+            // (the per-tile survivor counts come from the mask pass: no bitmap counting here)
             { StageTimer t(c, ST_MISC); launch_decode_from_compress(w, p, s); }
-            run_decode_prep_and_main(c, w, g.count, g.ntiles, false);
+            { StageTimer t(c, ST_DECODE_MAIN); launch_decode_main(w, g.count, g.ntiles, false, s); }
         }
     }
     if (count) {

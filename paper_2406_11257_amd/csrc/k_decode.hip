@@ -351,6 +351,13 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     S.pop_w = 0; S.pop_o = 0;
 }
 
+// The compress path already knows how many survivors precede every tile: the exclusive scan of its
+// mask pass, taken at the tile's first sub-tile.
+__global__ void k_decode_counts_from_mask(Workspace w, u32 ntiles) {
+    const u32 tile = blockIdx.x * blockDim.x + threadIdx.x;
+    if (tile < ntiles) w.dec_cnt_w[tile] = (u32)(w.mask_prefix[2ull * tile] >> 32);
+}
+
 }  // namespace
 
 void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s) {
@@ -360,6 +367,7 @@ void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s) {
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
     hipLaunchKernelGGL(k_decode_from_compress, dim3((g.ntensors + 255) / 256), dim3(256), 0, s, w, g);
+    if (g.ntiles) hipLaunchKernelGGL(k_decode_counts_from_mask, dim3((g.ntiles + 255) / 256), dim3(256), 0, s, w, g.ntiles);
 }
 void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which, hipStream_t s) {
     if (!ntiles) return;
