@@ -232,10 +232,10 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
              hipHostMalloc((void **)&c->h_err, 16) == hipSuccess;
     }
     if (ok) {
-        int grid = query_persistent_grid(hip_device);
-        if (grid <= 0) ok = false;
-        w.grid_persistent = grid;
-        w.grid_stream = grid;
+        hipDeviceProp_t prop;
+        ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0;
+        w.cus = ok ? prop.multiProcessorCount : 0;
+        w.tune_wgs = 0;
     }
     if (ok) {
         launch_zero_u32(w.med_hist, (u64)kMaxGroupTensors * 2048, c->stream);
@@ -353,6 +353,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         GroupParams p{};
         p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
         p.ntensors = g.count; p.ntiles = g.ntiles;
+#ifdef EXCP_TUNING
+        w.tune_wgs = (flags >> 24) & 0xffu;
+#endif
         { StageTimer t(c, ST_SAMPLE); launch_stats(w, p, 0, s); }
         { StageTimer t(c, ST_STATS); launch_stats(w, p, 1, s); }
         {

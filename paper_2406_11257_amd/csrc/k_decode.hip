@@ -383,7 +383,8 @@ void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t
 }
 void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
     if (!ntiles) return;
-    u32 blocks = ntiles < (u32)w.grid_stream * 4u ? ntiles : (u32)w.grid_stream * 4u;
+    u32 blocks = excp_grid(w, 64);
+    if (blocks > ntiles) blocks = ntiles;
     if (moments) hipLaunchKernelGGL(k_decode_main<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
     else hipLaunchKernelGGL(k_decode_main<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
 }

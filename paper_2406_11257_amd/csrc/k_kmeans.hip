@@ -264,7 +264,7 @@ __device__ __forceinline__ void load_chunk(const EXCP_GLOBAL float *gx, u32 clen
 __device__ __forceinline__ u32 chunk_elem(u32 it) { return ((it >> 2) * EXCP_THREADS + threadIdx.x) * 4u + (it & 3u); }
 
 // ---------------------------------------------------------------- P1: per-chunk bucket counts
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_count(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_count(Workspace w, GroupParams g) {
     __shared__ u32 map[EXCP_KM_MAP_WORDS];
     __shared__ u32 hist[NBKT];
     const u32 tid = threadIdx.x;
@@ -687,7 +687,7 @@ __device__ __forceinline__ void file_total(u64 *bins, u64 L, u64 H, u32 B, bool 
     }
 }
 
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
+__global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u64 s_bins[ITEM_R][EXCP_ABSM_BINS + 1];
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupPa
 // ---------------------------------------------------------------- final assignment + packing
 // A chunk's codes are ORed, four at a time, into the chunk's bit stream in LDS and leave as whole
 // 64-bit words.
-__global__ __launch_bounds__(EXCP_THREADS) void k_assign_pack(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS, 5) void k_assign_pack(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u32 s_pack[EXCP_CHUNK * 8 / 32 + 2];      // the chunk's packed codes (up to 8 bits each)
@@ -971,9 +971,9 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
     const u32 nseg = 3 * g.ntensors;
     switch (phase) {
         case 0: hipLaunchKernelGGL(k_km_sample, dim3(nseg), dim3(EXCP_THREADS), 0, s, w, g); break;
-        case 1: hipLaunchKernelGGL(k_km_count, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 1: hipLaunchKernelGGL(k_km_count, dim3(excp_grid(w, 30)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 2: hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(1024), 0, s, w, g); break;
-        case 3: hipLaunchKernelGGL(k_km_scatter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 96)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 4: hipLaunchKernelGGL(k_km_bucket_stats, dim3(nseg * (NBKT / 4)), dim3(EXCP_THREADS), 0, s, w, g); break;
         default: break;
     }
@@ -992,7 +992,7 @@ void launch_km_classify(const Workspace &w, const GroupParams &g, int iteration,
 
 void launch_km_iter(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_iter, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g, (u32)(iteration & 1));
+    hipLaunchKernelGGL(k_km_iter, dim3(excp_grid(w, 10)), dim3(EXCP_THREADS), 0, s, w, g, (u32)(iteration & 1));
 }
 
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
@@ -1001,7 +1001,7 @@ void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
 }
 
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s) {
-    hipLaunchKernelGGL(k_assign_pack, dim3(w.grid_stream), dim3(EXCP_THREADS), 0, s, w, g);
+    hipLaunchKernelGGL(k_assign_pack, dim3(excp_grid(w, 5)), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s) {

@@ -32,7 +32,7 @@ struct Regs {
 
 // sub-tile s of the group -> (tensor, first element); slots live in the partition arrays, which are
 // free until the codebook stage
-__global__ __launch_bounds__(EXCP_THREADS) void k_mask_slots(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, GroupParams g) {
     __shared__ float l_w[SUB], l_m[SUB], l_v[SUB];      // compacted survivors of one sub-tile
     __shared__ u32 s_w[4], s_o[4];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
@@ -394,27 +394,18 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParam
 
 }  // namespace
 
-int query_persistent_grid(int device) {
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, device) != hipSuccess) return -1;
-    int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_mask_slots, EXCP_THREADS, 0) != hipSuccess || nb <= 0)
-        return -1;
-    return nb * prop.multiProcessorCount;
-}
-
 void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hipStream_t s) {
     if (!g.ntiles) return;
     const u32 nsub = 2u * g.ntiles;
     if (phase == 0) {
-        u32 grid = (u32)w.grid_stream * 2u;
+        u32 grid = excp_grid(w, 20);
         if (grid > nsub) grid = nsub;
         hipLaunchKernelGGL(k_mask_slots, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     } else if (phase == 1) {
         hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
     } else {
         u32 grid = (nsub + 31) / 32;
-        if (grid > (u32)w.grid_stream * 8u) grid = (u32)w.grid_stream * 8u;
+        if (grid > excp_grid(w, 48)) grid = excp_grid(w, 48);
         hipLaunchKernelGGL(k_mask_gather, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     }
 }

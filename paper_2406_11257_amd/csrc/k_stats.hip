@@ -545,7 +545,7 @@ void launch_zero_u32(u32 *p, u64 count, hipStream_t s) {
 void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream_t s) {
     if (!g.ntensors) return;
     const dim3 block(EXCP_THREADS), per_tensor(g.ntensors), small((g.ntensors + 255) / 256);
-    const dim3 stream_grid(w.grid_stream);
+    const dim3 stream_grid(excp_grid(w, 8));
     switch (phase) {
         case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, block, 0, s, w, g); break;
         case 1: if (g.ntiles) hipLaunchKernelGGL(k_stats_stream, stream_grid, block, 0, s, w, g); break;
