@@ -26,9 +26,9 @@ def stage_bytes_per_param(p_w, p_o, nbits, iters):
     s = p_w + 2.0 * p_o
     bitmaps = 0.125 * (1.0 + p_w)
     return {
-        "stats_stream": 12.0 + 0.125,                      # read W_prev, W, m; clear the M_o bitmap region
+        "stats_stream": 12.0,                              # read W_prev, W, m
         "mask_slots": 16.0 + 0.125 + 4.0 * s,              # read all four arrays; write keep bitmap + survivor slots
-        "mask_gather": 8.0 * s + 0.125 * p_w,              # slots -> dense survivor arrays; M_o bitmap
+        "mask_gather": 8.0 * s + 0.25 * p_w,               # slots -> dense survivor arrays; local M_o bits -> bitmap_o
         "km_count": 4.0 * s,                               # read the survivors, count per bucket
         "km_scatter": 8.0 * s,                             # read the survivors, write them bucket by bucket
         "km_bucket_stats": 4.0 * s,                        # read the partitioned survivors once

@@ -151,7 +151,7 @@ __device__ __forceinline__ u32 window32(const u32 *s, u32 p) {
 // consecutive elements: the codes of its survivors are consecutive fields of the staged stream, so
 // one 32-bit window read per lane holds all of them.
 template <bool MOMENTS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
+__global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
     __shared__ float s_book[3 * 256];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     __shared__ u32 s_cw[DEC_CODE_WORDS];

@@ -8,8 +8,9 @@
 // slot of a scratch area.  No workgroup waits for another: where a survivor finally goes depends on
 // the counts of all earlier sub-tiles, and that is left to a scan (k_mask_scan, one workgroup per
 // tensor over its sub-tile counts) and to pass B (k_mask_gather), which copies every slot to its
-// place in the dense survivor arrays and merges the M_o bits into the blob.  The extra copy costs
-// 8 bytes per survivor; it replaces a chained scan whose waits cost more than that.
+// place in the dense survivor arrays; k_mask_bitmap_o then assembles bitmap_o from the sub-tiles'
+// local bit streams.  The extra copy costs 8 bytes per survivor; it replaces a chained scan whose
+// waits cost more than that.
 #include <type_traits>
 
 #include "excp_util.h"
@@ -250,8 +251,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupPa
     if (tid == 0) { w.st[t].n_w = carry >> 32; w.st[t].n_o = carry & 0xffffffffull; }
 }
 
-// Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays and
-// merges the sub-tile's M_o bits into the blob at the survivor position.  A workgroup takes 32
+// Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays.  A workgroup takes 32
 // consecutive sub-tiles; their counts, prefixes and tensor data are fetched once, side by side,
 // into LDS, so that a wave's copies do not wait behind a chain of dependent look-ups.
 constexpr u32 GATHER_SUBS = 32;
@@ -290,10 +290,6 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
             EXCP_GLOBAL float *xw = gptr(w.xw) + eoff + pw;
             EXCP_GLOBAL float *xm = gptr(w.xm) + eoff + po;
             EXCP_GLOBAL float *xv = gptr(w.xv) + eoff + po;
-            // M_o words of the sub-tile (needed below), fetched together with the values
-            const u32 nloc = (tw + 63u) >> 6;                     // local words that hold bits
-            const u64 *loc = w.mask_bo + (u64)sub * BO_WORDS;
-            const u64 cur = lane < nloc ? loc[lane] : 0ull;
             {
                 // the first batch of all three runs in flight together (usually there is no second)
                 float qw[12], qm[4], qv[4];
@@ -305,25 +301,80 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
                     store_batch<4>(xm, qm, to, b0, lane); store_batch<4>(xv, qv, to, b0, lane);
                 }
             }
-            // M_o bits: the sub-tile's local stream shifted to survivor position pw
-            const TDesc &D = w.desc[t];
-            const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(D.n));
-            u64 *bmo = (u64 *)(D.blob + off_bo);
-            const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
-            const u32 sh = pw & 63u;
-            const u32 nout = (sh + tw + 63u) >> 6;                    // words touched, <= 33
-            // the word of the lane below (lane 0 has none)
-            const u32 blo = __shfl_up((u32)cur, 1, WAVE), bhi = __shfl_up((u32)(cur >> 32), 1, WAVE);
-            const u64 below = lane > 0 ? (((u64)bhi << 32) | blo) : 0ull;
-            if (lane < nout) {
-                const u64 bits = sh ? ((cur << sh) | (below >> (64u - sh))) : cur;
-                const u64 wi = (u64)(pw >> 6) + lane;
-                if (wi < cap_words) {
-                    if (lane == 0 || lane + 1 == nout) { if (bits) atomicOr(&bmo[wi], bits); }
-                    else bmo[wi] = bits;
-                }
+        }
+    }
+}
+
+// bitmap_o (the M_o bits of the survivors, in survivor order) from the sub-tiles' local bit
+// streams.  Output-centric: one lane builds one 64-bit word from the one to three sub-tiles whose
+// survivors it covers, so the words are written whole, once, with no atomics; a wave takes 64
+// consecutive words (4096 survivor positions) of one tensor.  The sub-tile that holds the wave's
+// first position is found by a 64-way search over the tensor's scanned survivor counts.
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_bitmap_o(Workspace w, GroupParams g) {
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    __shared__ u32 s_P[4][65], s_c[4][64];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
+    for (u32 blk = blockIdx.x * 4 + wave; blk < g.ntiles; blk += gridDim.x * 4) {
+        const u32 t = find_owner(s_tiles, g.ntensors, blk);
+        const u32 b = blk - s_tiles[t];                     // the tensor's b-th run of 64 words
+        const u32 n_w = (u32)w.st[t].n_w;
+        const u32 nwo = (u32)excp_words(n_w), padded = nwo + (nwo & 1u);   // section length, zero-padded to 16 bytes
+        if (64u * b >= padded) continue;
+        const TDesc &D = w.desc[t];
+        const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(D.n));
+        const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
+        const u32 sb = 2u * s_tiles[t], se = 2u * s_tiles[t + 1];
+        const u32 Q0 = 4096u * b;
+        // last sub-tile whose first survivor position is <= Q0 (positions are non-decreasing)
+        u32 lo = sb, hi = se;
+        while (hi - lo > 1u) {
+            const u32 span = hi - lo - 1u;                  // open choices lo + 1 .. hi - 1
+            const bool act = span > 64u || lane < span;
+            const u32 idx = span > 64u ? lo + 1u + (u32)(((u64)span * lane) >> 6) : lo + 1u + lane;
+            const u32 P = act ? (u32)(w.mask_prefix[idx] >> 32) : 0xffffffffu;
+            const u64 le = ballot64(act && P <= Q0);        // a run of ones from lane 0 up
+            const u32 cnt = __popcll(le), nact = span > 64u ? 64u : span;
+            const u32 up = __shfl(idx, cnt ? cnt - 1u : 0u, WAVE), dn = __shfl(idx, cnt < 64u ? cnt : 63u, WAVE);
+            if (cnt < nact) hi = dn;
+            if (cnt) lo = up;
+        }
+        const u32 s0 = lo;
+        // the next 64 sub-tiles: first survivor position and survivor count, side by side in LDS
+        {
+            const u32 si = s0 + lane;
+            const bool in = si < se;
+            s_P[wave][lane] = in ? (u32)(w.mask_prefix[si] >> 32) : 0xffffffffu;
+            s_c[wave][lane] = in ? (u32)(w.tile_status[si] >> 32) : 0u;
+            if (lane == 0) s_P[wave][64] = 0xffffffffu;
+        }
+        const u32 widx = 64u * b + lane;
+        if (widx >= padded) continue;
+        u64 word = 0;
+        if (widx < nwo) {
+            const u32 Q = widx * 64u;                        // this word covers survivor positions [Q, Q + 64)
+            u32 i = 0;                                       // last entry of the window with position <= Q
+#pragma unroll
+            for (u32 step = 32; step >= 1; step >>= 1) if (s_P[wave][i + step] <= Q) i += step;
+            for (;; ++i) {
+                const u32 cur = s0 + i;
+                if (cur >= se) break;
+                const u32 P = i < 64u ? s_P[wave][i] : (u32)(w.mask_prefix[cur] >> 32);
+                if (P >= Q + 64u) break;
+                const u32 c = i < 64u ? s_c[wave][i] : (u32)(w.tile_status[cur] >> 32);
+                if (P + c <= Q) continue;                    // ends before this word (or is empty)
+                const u32 a = max(Q, P), e = min(Q + 64u, P + c);      // overlap, in survivor positions
+                const u32 la = a - P, len = e - a;           // first local bit, number of bits
+                const u64 *loc = w.mask_bo + (u64)cur * BO_WORDS;
+                const u32 k = la >> 6, sh = la & 63u;
+                const u64 w0 = loc[k];
+                const u64 w1 = ((k + 1u) * 64u < c) ? loc[k + 1u] : 0ull;
+                u64 bits = sh ? ((w0 >> sh) | (w1 << (64u - sh))) : w0;
+                if (len < 64u) bits &= (1ull << len) - 1ull;
+                word |= bits << (a - Q);
             }
         }
+        if (widx < cap_words) ((u64 *)(D.blob + off_bo))[widx] = word;
     }
 }
 
@@ -407,6 +458,9 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
         u32 grid = (nsub + 31) / 32;
         if (grid > excp_grid(w, 48)) grid = excp_grid(w, 48);
         hipLaunchKernelGGL(k_mask_gather, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        u32 grid_o = (g.ntiles + 3) / 4;
+        if (grid_o > excp_grid(w, 16)) grid_o = excp_grid(w, 16);
+        hipLaunchKernelGGL(k_mask_bitmap_o, dim3(grid_o), dim3(EXCP_THREADS), 0, s, w, g);
     }
 }
 

@@ -255,14 +255,6 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             accL += lo32;
             accH += hi32;
         }
-        // clear this tile's share of the bitmap_o region (filled later with atomic ORs)
-        if (tid < 66) {
-            u64 word = (base >> 6) + tid;
-            u64 nw = excp_words(n) + 2;
-            u64 off = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n)) + 8ull * word;
-            if (tid < 64 ? (word < nw) : (base + EXCP_TILE >= n && word < nw))
-                if (off + 8 <= D.blob_cap) *(u64 *)(D.blob + off) = 0ull;
-        }
     }
     flush(t);
 }
