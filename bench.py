@@ -200,6 +200,19 @@ def main():
     ctx.excp_copy_probe(flat[4], flat[0], probe)
     torch.cuda.synchronize()
 
+    # ---- Alg. 3: a chain of 8 checkpoints in one pass (the same blob eight times: a valid chain) ------
+    chain_len = 8
+    chains = [(flat[0][offs[i]:offs[i] + spec.n], [tensors[i][4]] * chain_len, [int(stats[i].blob_bytes)] * chain_len,
+               flat[4][offs[i]:offs[i] + spec.n], None, None) for i, spec in enumerate(cfg.tensors)]
+    ctx.excp_reconstruct_chain(chains); ctx.excp_collect()
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for _ in range(max(1, args.steps)):
+        ctx.excp_reconstruct_chain(chains)
+        ctx.excp_collect()
+    torch.cuda.synchronize()
+    chain_ms = (time.perf_counter() - t4) * 1e3 / max(1, args.steps)
+
     # ---- CPU oracle on a bounded sample of the same workload -----------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -246,6 +259,7 @@ def main():
         "compression_ratio": 12.0 * N / blob_bytes,
         "decompress_ms": dec_ms, "decompress_params_per_s": N / (dec_ms * 1e-3),
         "decompress_with_moments_ms": dec3_ms,
+        "reconstruct_chain_ms": {"checkpoints": chain_len, "ms": chain_ms, "one_by_one_ms": chain_len * dec_ms},
         "workspace_GB": ctx.workspace_bytes / 1e9,
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -108,6 +108,22 @@ typedef struct {
     float       *v_out;          /* device, n, nullable */
 } excp_blob;
 
+/* One tensor of a chain reconstruction (Alg. 3): the weights the chain starts from and `steps`
+ * compressed checkpoints, oldest first; each was compressed against the reconstruction of the one
+ * before it.  `blobs` and `blob_bytes` are HOST arrays of `steps` entries; the blobs themselves are
+ * device memory, 16-B aligned. */
+#define EXCP_MAX_CHAIN 16
+typedef struct {
+    const float       *W0;          /* device, n: seed-initialised (or fully stored) weights      */
+    uint64_t           n;
+    int                steps;       /* 1 .. EXCP_MAX_CHAIN; longer chains: call again from W_out  */
+    const void *const *blobs;       /* host array of device pointers                              */
+    const uint64_t    *blob_bytes;  /* host array: bytes readable at each blob                    */
+    float             *W_out;       /* device, n, nullable; may equal W0                          */
+    float             *m_out;       /* device, n, nullable: moments stored in the LAST checkpoint */
+    float             *v_out;
+} excp_chain;
+
 /* Per-tensor results (host). */
 typedef struct {
     uint64_t n, n_w, n_o;        /* elements, kept residuals, kept moment pairs        */
@@ -141,6 +157,15 @@ int excp_compress_tensors(excp_ctx *ctx, int count, const excp_tensor *tensors,
 
 /* Alg. 2 for `count` tensors; asynchronous. */
 int excp_decompress_tensors(excp_ctx *ctx, int count, const excp_blob *blobs);
+
+/* Alg. 3 for `count` tensors; asynchronous.  The weights are read once and written once however
+ * long the chain is; every checkpoint adds its centres with one fp32 addition per kept element, so
+ * the result equals `steps` applications of Alg. 2 bit for bit.  EXCP_E_ARG if a chain is longer than
+ * EXCP_MAX_CHAIN, if all chains together hold more than 4096 checkpoints, or if one tensor's chain
+ * does not fit the context's tables (steps * ceil(n / 4096) tiles against max_group_elems / 4096).
+ * After excp_collect a tensor's status is that of its first damaged checkpoint; n_w, n_o and
+ * blob_bytes are those of its last one. */
+int excp_reconstruct_chain(excp_ctx *ctx, int count, const excp_chain *chains);
 
 /* Wait for the pending batch; fill stats[0..count) (nullable); return EXCP_OK or the first
  * per-tensor error.  After a decompress batch only n, n_w, n_o, blob_bytes and status are set. */

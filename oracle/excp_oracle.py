@@ -41,7 +41,7 @@ __all__ = [
     "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
     "pack_bitmap", "pack_codes", "unpack_bitmap", "unpack_codes",
     "blob_size", "build_blob", "parse_blob", "compress_step",
-    "decompress_step", "CompressResult", "BlobError", "NonFiniteError",
+    "decompress_step", "reconstruct_chain", "CompressResult", "BlobError", "NonFiniteError",
 ]
 
 MAGIC = 0x50435845          # bytes "EXCP" read as a little-endian u32
@@ -429,3 +429,14 @@ def decompress_step(W_prev, blob: bytes):
     m_rec[idx_o] = p["book_m"][cm]                                  # Alg. 2 step 3
     v_rec[idx_o] = p["book_v"][cv]
     return W_rec, m_rec, v_rec
+
+
+def reconstruct_chain(W0, blobs):
+    """Alg. 3: from the weights the chain starts with, apply the compressed checkpoints one after the
+    other (each is Alg. 2 against the reconstruction before it).  Returns the last reconstruction and
+    the moments stored in the last checkpoint."""
+    W = np.ascontiguousarray(W0, dtype=f32).ravel()
+    m = v = None
+    for blob in blobs:
+        W, m, v = decompress_step(W, blob)
+    return W, m, v

@@ -16,6 +16,12 @@ class ExcpTensor(C.Structure):
                 ("blob_cap", C.c_uint64), ("W_recon_out", C.c_void_p)]
 
 
+class ExcpChain(C.Structure):
+    _fields_ = [("W0", C.c_void_p), ("n", C.c_uint64), ("steps", C.c_int),
+                ("blobs", C.POINTER(C.c_void_p)), ("blob_bytes", C.POINTER(C.c_uint64)),
+                ("W_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p)]
+
+
 class ExcpBlob(C.Structure):
     _fields_ = [("W_prev_recon", C.c_void_p), ("blob", C.c_void_p), ("blob_bytes", C.c_uint64),
                 ("n", C.c_uint64), ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p),
@@ -39,6 +45,7 @@ class ExcpError(RuntimeError):
 SYMBOLS = {
     "excp_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_void_p, C.c_uint64, C.c_uint64]),
     "excp_destroy": (None, [C.c_void_p]),
+    "excp_reconstruct_chain": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "excp_blob_bound": (C.c_uint64, [C.c_uint64, C.c_int]),
     "excp_blob_size": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int]),
     "excp_compress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpTensor), C.c_float, C.c_float,
@@ -181,6 +188,37 @@ class Context:
             raise ExcpError(rc, "excp_decompress_tensors")
         self._keep = (blobs, arr)
         self._count = len(blobs)
+
+    def excp_reconstruct_chain(self, chains):
+        """chains: sequence of (W0, [blob tensors, oldest first], [blob_bytes], W_out, m_out, v_out)."""
+        arr = (ExcpChain * max(len(chains), 1))()
+        keep = []
+        for i, (W0, blobs, sizes, Wout, mout, vout) in enumerate(chains):
+            _check_f32(W0, "W0", self.device)
+            n = W0.numel()
+            for t, nm in ((Wout, "W_out"), (mout, "m_out"), (vout, "v_out")):
+                if t is not None:
+                    _check_f32(t, nm, self.device)
+                    if t.numel() != n:
+                        raise ValueError(nm + " length differs")
+            if len(blobs) != len(sizes):
+                raise ValueError("blobs and blob_bytes differ in length")
+            for b, nb in zip(blobs, sizes):
+                if nb > b.numel() * b.element_size():
+                    raise ValueError("blob_bytes exceeds the blob tensor")
+            ptrs = (C.c_void_p * max(len(blobs), 1))(*[b.data_ptr() for b in blobs])
+            nbs = (C.c_uint64 * max(len(blobs), 1))(*[int(x) for x in sizes])
+            keep.append((ptrs, nbs))
+            arr[i] = ExcpChain(W0.data_ptr(), n, len(blobs), C.cast(ptrs, C.POINTER(C.c_void_p)),
+                               C.cast(nbs, C.POINTER(C.c_uint64)),
+                               0 if Wout is None else Wout.data_ptr(),
+                               0 if mout is None else mout.data_ptr(),
+                               0 if vout is None else vout.data_ptr())
+        rc = lib().excp_reconstruct_chain(self._h, len(chains), arr)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_reconstruct_chain")
+        self._keep = (chains, arr, keep)
+        self._count = len(chains)
 
     def excp_collect(self, check=True):
         stats = (ExcpStats * max(self._count, 1))()

@@ -82,6 +82,16 @@ struct DState {
     u64 pop_w, pop_o;           // bitmap populations found while scanning
 };
 
+// Host-filled description of one tensor of a chain reconstruction: its decode descriptors (one per
+// compressed checkpoint, oldest first) are ddesc[first_desc .. first_desc + steps).
+struct CDesc {
+    const float *W0;
+    float *W_out;
+    u64 n;
+    u32 first_desc, steps;
+    u32 tile_begin, tile_count;     // in the group's list of tensor tiles
+};
+
 // Result record copied back to the host after a batch.
 struct HostRec {
     u64 n, n_w, n_o, blob_bytes, nonfinite;
@@ -131,6 +141,7 @@ struct Workspace {
     u32 max_chunks;
     // decode
     DDesc *ddesc; DState *dst;
+    CDesc *cdesc; u32 *chain_tile_begin;   // chain reconstruction: tensors and their tile table
     u32 *dec_cnt_w, *dec_cnt_o;   // per tile counts -> exclusive bases
     // flags
     int *err_flag;
@@ -162,3 +173,5 @@ void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which
 void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s);
 void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s);
+void launch_decode_chain(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s);
+void launch_chain_finish(const Workspace &w, u32 ntensors, hipStream_t s);

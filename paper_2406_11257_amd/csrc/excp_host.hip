@@ -33,11 +33,12 @@ struct Span { int stage; hipEvent_t a, b; };
 struct excp_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
-    u64 max_tensor = 0, max_group = 0;
+    u64 max_tensor = 0, max_group = 0, max_tiles = 0;
     Workspace w{};
     // per-batch arrays (device) and their pinned staging (host)
     TDesc *desc_all = nullptr; TState *st_all = nullptr;
     DDesc *ddesc_all = nullptr; DState *dst_all = nullptr;
+    CDesc *cdesc_all = nullptr; CDesc *h_cdesc = nullptr;
     u32 *tile_begin_all = nullptr;
     TDesc *h_desc = nullptr; DDesc *h_ddesc = nullptr; u32 *h_tile_begin = nullptr; HostRec *h_rec = nullptr;
     int *h_err = nullptr;
@@ -185,11 +186,13 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     const u64 max_tiles = G / EXCP_TILE + kMaxGroupTensors + 1;
     const u64 chunks_group = 3 * (G / EXCP_CHUNK) + 3 * kMaxGroupTensors + 3;
     c->status_words = max_tiles;
+    c->max_tiles = max_tiles;
     bool ok = true;
     ok = ok && dev_alloc(c, &c->desc_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->st_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->ddesc_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->dst_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->cdesc_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->tile_begin_all, (u64)kMaxBatchTensors * 2 + 16);
     ok = ok && dev_alloc(c, &w.seg, 3ull * kMaxGroupTensors);
     ok = ok && dev_alloc(c, &w.xw, G);
@@ -227,6 +230,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     if (ok) {
         ok = hipHostMalloc((void **)&c->h_desc, sizeof(TDesc) * kMaxBatchTensors) == hipSuccess &&
              hipHostMalloc((void **)&c->h_ddesc, sizeof(DDesc) * kMaxBatchTensors) == hipSuccess &&
+             hipHostMalloc((void **)&c->h_cdesc, sizeof(CDesc) * kMaxBatchTensors) == hipSuccess &&
              hipHostMalloc((void **)&c->h_tile_begin, sizeof(u32) * (kMaxBatchTensors * 2 + 16)) == hipSuccess &&
              hipHostMalloc((void **)&c->h_rec, sizeof(HostRec) * kMaxBatchTensors) == hipSuccess &&
              hipHostMalloc((void **)&c->h_err, 16) == hipSuccess;
@@ -256,6 +260,7 @@ void excp_destroy(excp_ctx *c) {
     for (void *p : c->allocs) (void)hipFree(p);
     if (c->h_desc) (void)hipHostFree(c->h_desc);
     if (c->h_ddesc) (void)hipHostFree(c->h_ddesc);
+    if (c->h_cdesc) (void)hipHostFree(c->h_cdesc);
     if (c->h_tile_begin) (void)hipHostFree(c->h_tile_begin);
     if (c->h_rec) (void)hipHostFree(c->h_rec);
     if (c->h_err) (void)hipHostFree(c->h_err);
@@ -455,6 +460,108 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
             moments = moments || blobs[g.first + q].m_out != nullptr || blobs[g.first + q].v_out != nullptr;
         run_decode_prep_and_main(c, w, g.count, g.ntiles, moments);
         { StageTimer t(c, ST_MISC); launch_decode_finish(w, g.count, s); }
+    }
+    if (count) {
+        if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
+    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    c->pending = 2;
+    c->pending_count = count;
+    return EXCP_OK;
+}
+
+int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
+    if (!c || count < 0 || (count && !chains)) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+    u64 total_descs = 0;
+    for (int i = 0; i < count; ++i) {
+        const excp_chain &ch = chains[i];
+        if (ch.n > c->max_tensor || ch.steps < 1 || ch.steps > EXCP_MAX_CHAIN) return EXCP_E_ARG;
+        if (!ch.blobs || !ch.blob_bytes) return EXCP_E_ARG;
+        if (ch.n && !ch.W0) return EXCP_E_ARG;
+        for (int j = 0; j < ch.steps; ++j)
+            if (!ch.blobs[j] || ((uintptr_t)ch.blobs[j] & 15u)) return EXCP_E_ARG;
+        // one tensor's checkpoints must fit the per-tile tables of one group
+        if ((u64)ch.steps * ((ch.n + EXCP_TILE - 1) / EXCP_TILE) > c->max_tiles) return EXCP_E_ARG;
+        total_descs += (u64)ch.steps;
+    }
+    if (total_descs > kMaxBatchTensors) return EXCP_E_ARG;
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+
+    // Groups: at most kMaxGroupTensors descriptors (one per tensor and checkpoint) and as many
+    // descriptor tiles as the per-tile count tables hold.
+    struct CGroup { u32 first, count, first_desc, ndescs, ntiles, tb_desc, tb_chain; };
+    std::vector<CGroup> groups;
+    u32 tb_off = 0, desc_off = 0;
+    for (u32 i = 0; i < (u32)count;) {
+        CGroup g{i, 0, desc_off, 0, 0, 0, 0};
+        u64 dtiles = 0;
+        while (i < (u32)count) {
+            const excp_chain &ch = chains[i];
+            const u64 tiles = (ch.n + EXCP_TILE - 1) / EXCP_TILE;
+            if (g.count && (g.ndescs + (u32)ch.steps > kMaxGroupTensors || dtiles + tiles * ch.steps > c->max_tiles)) break;
+            dtiles += tiles * ch.steps; g.ndescs += (u32)ch.steps; g.ntiles += (u32)tiles; ++g.count; ++i;
+        }
+        if (tb_off + g.ndescs + g.count + 2 > kMaxBatchTensors * 2 + 16) return EXCP_E_ARG;
+        g.tb_desc = tb_off; g.tb_chain = tb_off + g.ndescs + 1;
+        u32 dtile = 0, ctile = 0, d = 0;
+        for (u32 q = 0; q < g.count; ++q) {
+            const excp_chain &ch = chains[g.first + q];
+            const u32 tiles = (u32)((ch.n + EXCP_TILE - 1) / EXCP_TILE);
+            CDesc &cd = c->h_cdesc[g.first + q];
+            cd.W0 = ch.W0; cd.W_out = ch.W_out; cd.n = ch.n; cd.first_desc = d; cd.steps = (u32)ch.steps;
+            cd.tile_begin = ctile; cd.tile_count = tiles;
+            c->h_tile_begin[g.tb_chain + q] = ctile;
+            ctile += tiles;
+            for (int j = 0; j < ch.steps; ++j, ++d) {
+                DDesc &dd = c->h_ddesc[desc_off + d];
+                const bool last = j + 1 == ch.steps;
+                dd.Wp = nullptr; dd.blob = (const unsigned char *)ch.blobs[j]; dd.blob_bytes = ch.blob_bytes[j]; dd.n = ch.n;
+                dd.W_out = nullptr; dd.m_out = last ? ch.m_out : nullptr; dd.v_out = last ? ch.v_out : nullptr;
+                dd.tile_begin = dtile; dd.tile_count = tiles;
+                c->h_tile_begin[g.tb_desc + d] = dtile;
+                dtile += tiles;
+            }
+        }
+        c->h_tile_begin[g.tb_desc + g.ndescs] = dtile;
+        c->h_tile_begin[g.tb_chain + g.count] = ctile;
+        tb_off += g.ndescs + g.count + 2;
+        desc_off += g.ndescs;
+        groups.push_back(g);
+    }
+    hipStream_t s = c->stream;
+    if (count) {
+        if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * desc_off, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(c->cdesc_all, c->h_cdesc, sizeof(CDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    for (const CGroup &g : groups) {
+        Workspace w = c->w;
+        w.ddesc = c->ddesc_all + g.first_desc;
+        w.dst = c->dst_all + g.first_desc;
+        w.tile_begin = c->tile_begin_all + g.tb_desc;
+        w.cdesc = c->cdesc_all + g.first;
+        w.chain_tile_begin = c->tile_begin_all + g.tb_chain;
+        w.rec_dev = c->w.rec_dev + g.first;
+        w.rec_base = 0;
+        const u32 dtiles = c->h_tile_begin[g.tb_desc + g.ndescs];
+        bool moments = false;
+        for (u32 q = 0; q < g.count; ++q)
+            moments = moments || chains[g.first + q].m_out != nullptr || chains[g.first + q].v_out != nullptr;
+        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.ndescs, s); }
+        {
+            StageTimer t(c, ST_DECODE_PREP);
+            launch_decode_count(w, g.ndescs, dtiles, 0, s);
+            launch_decode_scan(w, g.ndescs, 0, s);
+            if (moments) { launch_decode_count(w, g.ndescs, dtiles, 1, s); launch_decode_scan(w, g.ndescs, 1, s); }
+        }
+        { StageTimer t(c, ST_DECODE_MAIN); launch_decode_chain(w, g.count, g.ntiles, s); }
+        if (moments) { StageTimer t(c, ST_DECODE_MAIN); launch_decode_main(w, g.ndescs, dtiles, true, s); }   // the last checkpoints' moments
+        { StageTimer t(c, ST_MISC); launch_chain_finish(w, g.count, s); }
     }
     if (count) {
         if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_count(Workspace w, u32 
                     if (rem < 64) v &= (1ull << rem) - 1ull;
                     cnt = __popcll(v);
                 }
-            } else {
+            } else if (D.m_out != nullptr || D.v_out != nullptr) {      // only where moments are wanted
                 const u64 *bm = (const u64 *)(D.blob + S.off_bo);
                 u64 p0 = w.dec_cnt_w[tile];
                 u64 p1 = (tile + 1 < D.tile_begin + D.tile_count) ? (u64)w.dec_cnt_w[tile + 1] : S.pop_w;
@@ -106,6 +106,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 n
     const DDesc &D = w.ddesc[t];
     DState &S = w.dst[t];
     u32 *cnt = (WHICH == 0 ? w.dec_cnt_w : w.dec_cnt_o) + D.tile_begin;
+    if (WHICH == 1 && D.m_out == nullptr && D.v_out == nullptr) return;    // bitmap_o is not used for this one
     u64 carry = 0;
     for (u32 base = 0; base < D.tile_count; base += EXCP_THREADS) {
         u32 i = base + tid;
@@ -174,6 +175,7 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
         const bool has_w = D.W_out != nullptr;
         const bool has_m = MOMENTS && D.m_out != nullptr, has_v = MOMENTS && D.v_out != nullptr;
         const bool moments = has_m || has_v;
+        if (!has_w && !moments) continue;                  // nothing to write for this one
 
         // previous weights of the lane's 4 x 4 elements: issued first, consumed last
         float wp[4][4];
@@ -322,6 +324,122 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
     }
 }
 
+// Alg. 3: W_0 plus a chain of compressed checkpoints, oldest first, in ONE pass over the weights.
+// A lane keeps its sixteen weights in registers and adds, checkpoint after checkpoint, the centre
+// of every kept element (one fp32 addition per checkpoint, exactly what applying Alg. 2 again and
+// again computes); W_0 is read once and the result written once, whatever the length of the chain.
+__global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u32 ntensors, u32 ntiles) {
+    __shared__ float s_book[256];
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    __shared__ u32 s_cw[DEC_CODE_WORDS];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    load_tile_table(s_tiles, w.chain_tile_begin, ntensors);
+    for (u32 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const u32 t = find_owner(s_tiles, ntensors, tile);
+        const CDesc &C = w.cdesc[t];
+        if (C.W_out == nullptr) continue;
+        bool good = true;                                  // every checkpoint of the chain parsed and counted fine
+        for (u32 j = 0; j < C.steps; ++j) good = good && w.dst[C.first_desc + j].status == 0;
+        if (!good) continue;                               // same decision for the whole workgroup
+        const u64 n = C.n;
+        const u32 ltile = tile - C.tile_begin;
+        const u64 base = (u64)ltile * EXCP_TILE;
+        const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
+        float wp[4][4];
+        {
+            const EXCP_GLOBAL float *W0 = gptr(C.W0) + base;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+                if (off + 4u <= rem) {
+                    const f4u x = *(const EXCP_GLOBAL f4u *)(W0 + off);
+                    wp[k][0] = x.x; wp[k][1] = x.y; wp[k][2] = x.z; wp[k][3] = x.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) wp[k][j] = (off + (u32)j < rem) ? W0[off + (u32)j] : 0.f;
+                }
+            }
+        }
+        for (u32 step = 0; step < C.steps; ++step) {
+            const DDesc &D = w.ddesc[C.first_desc + step];
+            const DState &S = w.dst[C.first_desc + step];
+            const u32 nbits = S.nbits, E = 1u << nbits, cmask = E - 1u;
+            const unsigned char *blob = D.blob;
+            u64 myword = 0;
+            {
+                const u64 wword = (u64)ltile * 64 + lane;
+                const u32 bits_here = (lane * 64u < rem) ? min(64u, rem - lane * 64u) : 0u;
+                if (bits_here) myword = gptr((const u64 *)(blob + S.off_bw))[wword];
+                if (bits_here < 64u) myword &= (1ull << bits_here) - 1ull;
+            }
+            const u32 pc = __popcll(myword);
+            u32 incl = pc;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const u32 v = __shfl_up(incl, off, WAVE);
+                if (lane >= (u32)off) incl += v;
+            }
+            const u32 excl = incl - pc;
+            const u32 cnt = __shfl(incl, 63, WAVE);
+            const u32 q_tile = w.dec_cnt_w[D.tile_begin + ltile];
+            const u64 wbit0 = (u64)q_tile * nbits;
+            const u32 woff = (u32)(wbit0 & 31ull);
+            __syncthreads();                               // the previous checkpoint's LDS readers are done
+            {
+                const EXCP_GLOBAL float *book = gptr((const float *)(blob + EXCP_HEADER));
+                for (u32 i = tid; i < E; i += EXCP_THREADS) s_book[i] = book[i];
+            }
+            stage_words(s_cw, gptr((const u32 *)(blob + S.off_cw)) + (wbit0 >> 5), (woff + cnt * nbits + 31u) >> 5);
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 wq = wave * 16u + (u32)k * 4u + (lane >> 4);
+                const u32 sub = (lane & 15u) * 4u;
+                const u32 wlo = __shfl((u32)myword, wq, WAVE), whi = __shfl((u32)(myword >> 32), wq, WAVE);
+                const u32 wex = __shfl(excl, wq, WAVE);
+                const u64 word = ((u64)whi << 32) | wlo;
+                const u32 nib = (u32)(word >> sub) & 15u;
+                const u32 r = wex + __popcll(word & ((1ull << sub) - 1ull));
+                u32 f = window32(s_cw, woff + r * nbits);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool kept = (nib >> j) & 1u;
+                    const float c = s_book[f & cmask];
+                    wp[k][j] = kept ? wp[k][j] + c : wp[k][j];
+                    f = kept ? (f >> nbits) : f;
+                }
+            }
+        }
+        EXCP_GLOBAL float *Wo = gptr(C.W_out) + base;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+            if (off + 4u <= rem) {
+                f4u y; y.x = wp[k][0]; y.y = wp[k][1]; y.z = wp[k][2]; y.w = wp[k][3];
+                *(EXCP_GLOBAL f4u *)(Wo + off) = y;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) if (off + (u32)j < rem) Wo[off + (u32)j] = wp[k][j];
+            }
+        }
+    }
+}
+
+// Per tensor of a chain: status = the first checkpoint that failed, counts and size of the last one.
+__global__ void k_chain_finish(Workspace w, u32 ntensors, u32 rec_base) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntensors) return;
+    const CDesc &C = w.cdesc[t];
+    int status = 0;
+    for (u32 j = 0; j < C.steps && status == 0; ++j) status = w.dst[C.first_desc + j].status;
+    const DState &S = w.dst[C.first_desc + C.steps - 1u];
+    HostRec &R = w.rec_dev[rec_base + t];
+    R.n = C.n; R.n_w = S.n_w; R.n_o = S.n_o; R.blob_bytes = S.blob_bytes; R.nonfinite = 0;
+    R.abs_sum = 0.0; R.obj[0] = R.obj[1] = R.obj[2] = 0.0;
+    R.med = R.mean32 = R.t_w = R.r_o = 0.f;
+    R.status = status; R.pad = 0;
+}
+
 __global__ void k_decode_finish(Workspace w, u32 ntensors, u32 rec_base) {
     const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= ntensors) return;
@@ -391,4 +509,14 @@ void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool momen
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s) {
     if (!ntensors) return;
     hipLaunchKernelGGL(k_decode_finish, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors, w.rec_base);
+}
+void launch_decode_chain(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s) {
+    if (!ntiles) return;
+    u32 blocks = excp_grid(w, 64);
+    if (blocks > ntiles) blocks = ntiles;
+    hipLaunchKernelGGL(k_decode_chain, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+}
+void launch_chain_finish(const Workspace &w, u32 ntensors, hipStream_t s) {
+    if (!ntensors) return;
+    hipLaunchKernelGGL(k_chain_finish, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors, w.rec_base);
 }

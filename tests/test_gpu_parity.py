@@ -263,6 +263,58 @@ def test_tensors_of_the_other_benchmark_configurations(ctx):
         print("config", cid, "first layer: kept fraction", round(kept, 4), "worst centre err", worst, flush=True)
 
 
+def test_chain_reconstruction_in_one_pass(ctx):
+    # Alg. 3: chains of 1..6 checkpoints (code widths differ along the chain), several tensors of
+    # different chain lengths in one call, in place and out of place, against the oracle's loop
+    g = np.random.default_rng(91)
+    sizes = [70001, 4096, 300000, 5]
+    widths = [4, 3, 8, 2, 5, 4]
+    chains = []
+    for ti, n in enumerate(sizes):
+        W0 = (g.standard_normal(n) * 0.02).astype(f32)
+        W_true, W_hat, blobs = W0.copy(), W0.copy(), []
+        for step in range(6 - ti):
+            W_true = (W_true + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+            m = (g.standard_normal(n) * 5e-5).astype(f32)
+            v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+            r = O.compress_step(W_hat, W_true, m, v, nbits=widths[step], iters=3)
+            blobs.append(r.blob)
+            W_hat = r.W_recon
+        chains.append((W0, blobs))
+    dev_chains, outs = [], []
+    for ci, (W0, blobs) in enumerate(chains):
+        db = []
+        for b in blobs:
+            t = torch.from_numpy(np.frombuffer(b, dtype=np.uint8).copy()).cuda()
+            db.append(t)
+        w0 = to_dev(W0)
+        n = W0.size
+        wo = w0 if ci % 2 else torch.full((n,), 3.0, dtype=torch.float32, device="cuda")     # odd ones in place
+        mo = torch.full((n,), 3.0, dtype=torch.float32, device="cuda")
+        vo = torch.full((n,), 3.0, dtype=torch.float32, device="cuda") if ci != 2 else None
+        dev_chains.append((w0, db, [len(b) for b in blobs], wo, mo, vo))
+        outs.append((wo, mo, vo))
+    ctx.excp_reconstruct_chain(dev_chains)
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    for (W0, blobs), (wo, mo, vo), st in zip(chains, outs, stats):
+        Wr, mr, vr = O.reconstruct_chain(W0, blobs)
+        assert st.status == 0 and st.blob_bytes == len(blobs[-1])
+        assert np.array_equal(wo.cpu().numpy().view(np.uint32), Wr.view(np.uint32))
+        assert np.array_equal(mo.cpu().numpy().view(np.uint32), mr.view(np.uint32))
+        if vo is not None:
+            assert np.array_equal(vo.cpu().numpy().view(np.uint32), vr.view(np.uint32))
+    # a damaged checkpoint in the middle of a chain is reported for that tensor only
+    bad = bytearray(chains[0][1][2]); bad[0] ^= 0xFF
+    dev_chains[0][1][2] = torch.from_numpy(np.frombuffer(bytes(bad), dtype=np.uint8).copy()).cuda()
+    ctx.excp_reconstruct_chain(dev_chains[:2])
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == X.EXCP_E_BLOB and stats[0].status == X.EXCP_E_BLOB and stats[1].status == 0
+    # argument errors
+    with pytest.raises(X.ExcpError):
+        ctx.excp_reconstruct_chain([(dev_chains[1][0], dev_chains[1][1] * 9, dev_chains[1][2] * 9, None, None, None)])
+
+
 def test_in_place_reconstruction_and_single_tensor_calls(ctx):
     Wp, W, m, v = case(123457, 81)
     ref = O.compress_step(Wp, W, m, v)

@@ -475,3 +475,34 @@ def test_blob_parser_rejects_damage():
     bad[80 + 192] ^= 1                                  # flip one keep bit
     with pytest.raises(O.BlobError):
         O.decompress_step(Wp, bytes(bad))
+
+
+def test_chain_reconstruction_tracks_the_true_weights():
+    # Alg. 3 on a free-running chain: every step is compressed against the previous reconstruction
+    # (Sec. 3.4), so the error does not accumulate -- at a pruned position it is at most that
+    # step's own threshold, at a kept one at most the distance to the nearest centre.
+    g = np.random.default_rng(77)
+    n = 20000
+    W0 = (g.standard_normal(n) * 0.02).astype(f32)
+    W_true, W_hat, blobs, rms = W0.copy(), W0.copy(), [], []
+    for step in range(5):
+        W_true = (W_true + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+        m = (g.standard_normal(n) * 5e-5).astype(f32)
+        v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+        r = O.compress_step(W_hat, W_true, m, v)
+        blobs.append(r.blob)
+        err = np.abs(W_true.astype(np.float64) - r.W_recon.astype(np.float64))
+        thr = float(r.t_w) / np.sqrt(v.astype(np.float64)) * (1 + 1e-6)
+        assert np.all(err[~r.Mw] <= thr[~r.Mw])
+        rms.append(float(np.sqrt(np.mean(err ** 2))))
+        W_hat = r.W_recon
+    assert max(rms) <= 1.5 * rms[0]                         # no drift along the chain
+    for k in range(1, 6):                                   # any prefix of the chain is a checkpoint
+        Wk, mk, vk = O.reconstruct_chain(W0, blobs[:k])
+        Wstep = W0
+        for b in blobs[:k]:
+            Wstep = O.decompress_step(Wstep, b)[0]
+        assert np.array_equal(Wk.view(np.uint32), Wstep.view(np.uint32))
+    assert np.array_equal(O.reconstruct_chain(W0, blobs)[0].view(np.uint32), W_hat.view(np.uint32))
+    # dropping a checkpoint from the middle gives different weights: the order and completeness matter
+    assert not np.array_equal(O.reconstruct_chain(W0, blobs[:2] + blobs[3:])[0], W_hat)
