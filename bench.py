@@ -154,6 +154,10 @@ def main():
     ms_per_step = max(host_ms, dev_ms) / args.steps
     ctx.excp_set_profiling(False)
 
+    # sanity of the last step (not timed): every tensor fine, sizes equal the closed form of the layout
+    for spec, st_ in zip(cfg.tensors, stats):
+        assert st_.status == 0 and st_.n == spec.n and st_.n_o <= st_.n_w <= st_.n
+        assert st_.blob_bytes == X.excp_blob_size(spec.n, st_.n_w, st_.n_o, nbits)
     n_w = sum(s.n_w for s in stats)
     n_o = sum(s.n_o for s in stats)
     blob_bytes = sum(s.blob_bytes for s in stats)

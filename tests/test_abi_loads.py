@@ -48,3 +48,4 @@ def test_argument_errors_need_no_gpu():
     assert L.excp_collect(None, None) == X.EXCP_E_ARG
     assert L.excp_compress_tensors(None, 0, None, 5e-5, 2.0, 4, 10, 0) == X.EXCP_E_ARG
     assert L.excp_create(None, 0, None, 1, 1) == X.EXCP_E_ARG
+    assert L.excp_reconstruct_chain(None, 0, None) == X.EXCP_E_ARG
