@@ -78,7 +78,7 @@ extern "C" {
 #define EXCP_E_BLOB       -4   /* decompress: bad magic / version / sizes / bitmap population */
 #define EXCP_E_HIP        -5   /* a HIP call failed, or the device could not be used */
 #define EXCP_E_STATE      -6   /* call order violated (batch pending / nothing to collect) */
-#define EXCP_E_INTERNAL   -7   /* a device-side wait gave up (should not happen) */
+#define EXCP_E_INTERNAL   -7   /* an internal work list overflowed (should not happen) */
 
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 

@@ -17,7 +17,6 @@
 #define EXCP_HEADER      80u
 #define EXCP_MAGIC       0x50435845u
 #define EXCP_VERSION     1u
-#define EXCP_SPIN_LIMIT  (1u << 26)  // polls before a look-back wait gives up and flags an error
 
 typedef unsigned long long u64;
 typedef unsigned int u32;
@@ -120,7 +119,7 @@ struct Workspace {
     // median select
     u32 *med_hist;            // [tensor][2048]
     u32 *cand;                // median candidates (keys inside the sample bracket), per tensor
-    // look-back status words, one per tile
+    // mask pass
     u64 *tile_status;         // per 2048-element sub-tile: survivors << 32 | moment survivors
     u64 *mask_prefix;         // exclusive scan of tile_status within each tensor
     u64 *mask_bo;             // [sub-tile][32] M_o bits of the sub-tile's survivors, local positions

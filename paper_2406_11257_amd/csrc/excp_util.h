@@ -71,14 +71,6 @@ __device__ __forceinline__ float val_of(u32 k) {
     return u2f((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// Device-scope loads / stores of the look-back status words.
-__device__ __forceinline__ u64 ld_status(const u64 *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_status(u64 *p, u64 v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // Index of the nearest centre of x among centres in ascending order (Sec. 3.3 leaves the rule
 // open; this is the rule the library fixes).  a = last centre <= x, b = the next one; the two
 // distances are evaluated in fp64 with one rounding each, b wins only if strictly nearer, and
