@@ -148,7 +148,7 @@ const char *excp_strerror(int code) {
         case EXCP_E_BLOB: return "malformed compressed tensor";
         case EXCP_E_HIP: return "HIP error";
         case EXCP_E_STATE: return "call order violated";
-        case EXCP_E_INTERNAL: return "device-side wait gave up";
+        case EXCP_E_INTERNAL: return "internal work list overflowed";
         default: return "unknown error";
     }
 }
