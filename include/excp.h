@@ -28,7 +28,8 @@
  *   start at the order statistics of rank ((2k+1) len)/(2K), then exactly
  *   `lloyd_iters` updates (nearest centre by squared fp64 distance, ties to the
  *   lower index; centre = fp32(fp64 sum / count); empty clusters keep their
- *   centre); code = 1 + index of the nearest final centre.
+ *   centre; the centres are re-sorted ascending after every update, which only
+ *   matters for heavily tied data); code = 1 + index of the nearest final centre.
  *   reconstruct: W_hat[i] = W_prev_recon[i] + C_w[code] at M_w, else
  *   W_prev_recon[i]; m_hat, v_hat = C[code] at M_o, else +0.
  *

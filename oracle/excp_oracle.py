@@ -162,7 +162,11 @@ def lloyd(x: np.ndarray, K: int, iters: int, history: list | None = None):
 
     update: C_k = fp32( exact sum of the members (rounded once to fp64) / count )
     for every non-empty cluster; an empty cluster keeps its centre.  Clusters are
-    intervals of the sorted values, so the centres stay in ascending order.
+    intervals of the sorted values, so the centres normally stay in ascending order;
+    the one exception is a run of EQUAL centres (heavily tied data): the lowest of them
+    takes all their members and may move past the ones that stay behind.  The centres
+    are therefore put back in ascending order after every update (a stable sort, a
+    no-op in the normal case); a codebook is a set of values, the order carries nothing.
     Returns (C fp32[K], a int64[len(x)]) where a is the assignment to the FINAL
     centres.  If ``history`` is a list, the objective before each update and
     after the last one is appended to it.
@@ -187,7 +191,7 @@ def lloyd(x: np.ndarray, K: int, iters: int, history: list | None = None):
                 S = math.fsum(xsorted[pos:pos + c].tolist())
                 newC[k] = f32(S / float(c))
             pos += c
-        C = newC
+        C = np.sort(newC, kind="stable")
     a = nearest_centre(x, C)
     if history is not None:
         history.append(objective(x, C, a))

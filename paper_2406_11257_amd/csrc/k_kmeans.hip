@@ -573,13 +573,15 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
 }
 
 // New centres of one stream from the iteration's totals: centre = fp32(exact sum / count), a
-// cluster without members keeps its centre; the totals are cleared for the next iteration.
+// cluster without members keeps its centre; then the centres are put back in ascending order; the
+// totals are cleared for the next iteration.
 // Called by the whole workgroup (it holds barriers); the totals of sixteen centres at a time are
 // fetched into LDS side by side, so that no thread walks a chain of dependent global reads.
 // lds_C (optional) receives the centres as well.
 __device__ __forceinline__ void move_centres(const Workspace &w, const GroupParams &g, u32 sidx, float *lds_C) {
     constexpr u32 STRIDE = EXCP_ABSM_BINS + 1, BATCH = 16;
     __shared__ u64 s_acc[BATCH * STRIDE];
+    __shared__ float s_new[EXCP_MAX_K + 1];
     SegState &S = w.seg[sidx];
     const u32 K = (u32)g.K, tid = threadIdx.x;
     u64 *acc = w.km_acc + (u64)sidx * EXCP_MAX_K * STRIDE;
@@ -598,10 +600,25 @@ __device__ __forceinline__ void move_centres(const Workspace &w, const GroupPara
             if (cnt) {
                 const double sum = signed_bins_to_double(a);
                 c = (float)(sum / (double)cnt);
-                S.C[k0 + tid] = c;
             }
-            if (lds_C) lds_C[k0 + tid] = c;
+            s_new[k0 + tid] = c;
         }
+    }
+    __syncthreads();
+    // Back into ascending order (stable; nothing moves unless a run of equal centres was torn apart:
+    // the lowest of them takes all their members and may pass the ones left behind).
+    float c = 0.f; u32 rank = 0;
+    if (tid < K) {
+        c = s_new[tid];
+        for (u32 j = 0; j < K; ++j) {
+            const float cj = s_new[j];
+            rank += (cj < c || (cj == c && j < tid)) ? 1u : 0u;
+        }
+    }
+    __syncthreads();
+    if (tid < K) {
+        S.C[rank] = c;
+        if (lds_C) lds_C[rank] = c;
     }
 }
 

@@ -315,6 +315,37 @@ def test_chain_reconstruction_in_one_pass(ctx):
         ctx.excp_reconstruct_chain([(dev_chains[1][0], dev_chains[1][1] * 9, dev_chains[1][2] * 9, None, None, None)])
 
 
+def test_random_small_cases(ctx):
+    # many small tensors with random sizes, parameters and value structure (ties, constant runs,
+    # few distinct values, wide dynamic range), all in a few batches
+    g = np.random.default_rng(2024)
+    for batch in range(4):
+        nbits = int(g.integers(2, 9)); iters = int(g.integers(0, 6))
+        alpha = float(10 ** g.uniform(-6, -3)); beta = float(g.uniform(0.0, 3.0))
+        cases = []
+        for _ in range(12):
+            n = int(g.integers(1, 30000))
+            kind = int(g.integers(0, 5))
+            Wp = (g.standard_normal(n) * 0.02).astype(f32)
+            if kind == 0:                                   # plain
+                d = g.laplace(0, 1e-4, n)
+            elif kind == 1:                                 # few distinct residual values
+                d = g.choice(np.array([-3e-4, -1e-4, 0.0, 1e-4, 2e-4, 5e-4]), n)
+            elif kind == 2:                                 # wide dynamic range
+                d = g.standard_normal(n) * 10.0 ** g.uniform(-9, -1, n)
+            elif kind == 3:                                 # mostly unchanged weights
+                d = np.where(g.random(n) < 0.2, g.laplace(0, 1e-4, n), 0.0)
+            else:                                           # one sign only
+                d = np.abs(g.laplace(0, 1e-4, n))
+            W = (Wp + d.astype(f32)).astype(f32)
+            m = (g.standard_normal(n) * 5e-5).astype(f32)
+            if kind == 1:
+                m = np.round(m * 2e5).astype(f32) / f32(2e5)          # ties among the moments too
+            v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+            cases.append((Wp, W, m, v))
+        check_all(ctx, cases, alpha, beta, nbits, iters)
+
+
 def test_in_place_reconstruction_and_single_tensor_calls(ctx):
     Wp, W, m, v = case(123457, 81)
     ref = O.compress_step(Wp, W, m, v)

@@ -506,3 +506,21 @@ def test_chain_reconstruction_tracks_the_true_weights():
     assert np.array_equal(O.reconstruct_chain(W0, blobs)[0].view(np.uint32), W_hat.view(np.uint32))
     # dropping a checkpoint from the middle gives different weights: the order and completeness matter
     assert not np.array_equal(O.reconstruct_chain(W0, blobs[:2] + blobs[3:])[0], W_hat)
+
+
+def test_tied_data_keeps_the_centres_in_order():
+    # heavily tied data: several initial centres coincide; the lowest of a run of equal centres takes
+    # all their members and can move past the ones left behind, so the update re-sorts.  Pins: the
+    # centres stay sorted, every centre is a plain mean of the values assigned to it or an untouched
+    # initial value, the objective never rises, and the assignment equals exhaustive search.
+    g = np.random.default_rng(5)
+    base = np.array([-3e-4, -1e-4, 1e-4, 1.0001e-4, 1.0002e-4, 5e-4], dtype=f32)
+    x = g.choice(base, 5000, p=[0.05, 0.05, 0.3, 0.3, 0.25, 0.05]).astype(f32)
+    K = 15
+    hist = []
+    C, a = O.lloyd(x, K, 6, history=hist)
+    assert np.all(np.diff(C) >= 0)
+    assert all(h1 <= h0 * (1 + 1e-12) + 1e-30 for h0, h1 in zip(hist, hist[1:]))
+    d = np.abs(x.astype(np.float64)[:, None] - C.astype(np.float64)[None, :])
+    assert np.array_equal(d[np.arange(x.size), a], d.min(axis=1))          # a nearest centre each
+    assert len(np.unique(x)) <= K and hist[-1] < 1e-16                      # few values: (nearly) lossless
