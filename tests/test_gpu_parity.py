@@ -388,6 +388,49 @@ def test_chained_checkpoints_with_teacher_forcing(ctx):
         print("step", t, "n_w", out[0]["stats"].n_w, "rms err", float(np.sqrt(np.mean((W_hat - W_true) ** 2))), flush=True)
 
 
+@pytest.mark.parametrize("nbits", [2, 4, 8])
+@pytest.mark.parametrize("alpha,keep", [(1e-5, 0.71), (5e-5, 0.345), (2e-4, 0.075)])
+def test_chained_run_of_eight_checkpoints(ctx, nbits, alpha, keep):
+    # the chained configuration of the benchmark set: 8 checkpoints, W_{t+1} = W_t + Laplace(0, 1e-4),
+    # fresh moments, each compressed against the previous reconstruction; code widths 2 / 4 / 8 and
+    # three thresholds (keep fractions from about 0.7 down to under 0.1).  Shapes: one attention
+    # matrix cut to 256 K elements and one norm vector of the 410M-shaped model.
+    cfg = synth.config(4)
+    picks = [(7, 1 << 18), (1, None)]
+    state = []
+    for idx, cut in picks:
+        spec = cfg.tensors[idx]
+        n = spec.n if cut is None else min(spec.n, cut)
+        W0 = synth.draw_tensor(4, idx, spec, step=0, n=n)[0]
+        state.append(dict(idx=idx, spec=spec, n=n, W_true=W0.copy(), W_hat=W0.copy(), W0=W0, blobs=[]))
+    for step in range(1, 9):
+        cases = []
+        for stt in state:
+            _, Wn, m, v = synth.draw_tensor(4, stt["idx"], stt["spec"], step=step, n=stt["n"])
+            noise = synth.draw_noise(4, step, stt["idx"], stt["spec"], stt["n"])
+            stt["W_true"] = (stt["W_true"] + noise).astype(f32)
+            cases.append((stt["W_hat"], stt["W_true"], m, v))
+        rc, out = gpu_compress(ctx, cases, alpha, 2.0, nbits, 10)
+        assert rc == 0
+        for stt, c, o in zip(state, cases, out):
+            compare_with_oracle(c, o, alpha, 2.0, nbits, 10)
+            stt["W_hat"] = o["W_recon"]
+            stt["blobs"].append(o["blob"])
+        big = out[0]["stats"]
+        assert abs(big.n_w / big.n - keep) < 0.03, (big.n_w / big.n, keep)
+    # Alg. 3 over the eight checkpoints gives the last reconstruction again
+    chains = []
+    for stt in state:
+        db = [torch.from_numpy(np.frombuffer(b, dtype=np.uint8).copy()).cuda() for b in stt["blobs"]]
+        chains.append((to_dev(stt["W0"]), db, [len(b) for b in stt["blobs"]],
+                       torch.empty(stt["n"], dtype=torch.float32, device="cuda"), None, None))
+    ctx.excp_reconstruct_chain(chains)
+    rc, _ = ctx.excp_collect(check=False)
+    assert rc == 0
+    for stt, ch in zip(state, chains):
+        assert np.array_equal(ch[3].cpu().numpy().view(np.uint32), stt["W_hat"].view(np.uint32))
+
+
 def test_errors_are_reported_not_faulted(ctx):
     Wp, W, m, v = case(20000, 95)
     # non-finite inputs in each array
