@@ -162,8 +162,7 @@ int excp_decompress_tensors(excp_ctx *ctx, int count, const excp_blob *blobs);
 /* Alg. 3 for `count` tensors; asynchronous.  The weights are read once and written once however
  * long the chain is; every checkpoint adds its centres with one fp32 addition per kept element, so
  * the result equals `steps` applications of Alg. 2 bit for bit.  EXCP_E_ARG if a chain is longer than
- * EXCP_MAX_CHAIN, if all chains together hold more than 4096 checkpoints, or if one tensor's chain
- * does not fit the context's tables (steps * ceil(n / 4096) tiles against max_group_elems / 4096).
+ * EXCP_MAX_CHAIN or if all chains together hold more than 4096 checkpoints.
  * After excp_collect a tensor's status is that of its first damaged checkpoint; n_w, n_o and
  * blob_bytes are those of its last one. */
 int excp_reconstruct_chain(excp_ctx *ctx, int count, const excp_chain *chains);

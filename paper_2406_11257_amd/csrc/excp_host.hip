@@ -222,8 +222,9 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.km_item_count, 4);
     w.km_item_cap = (u32)(item_cap > 0xffffffffull ? 0xffffffffull : item_cap);
     ok = ok && dev_alloc(c, &w.part_obj, chunks_group);
-    ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles);
-    ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles);
+    // per-tile survivor counts of decode; a chain reconstruction keeps those of all its checkpoints
+    ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles * EXCP_MAX_CHAIN);
+    ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles * EXCP_MAX_CHAIN);
     ok = ok && dev_alloc(c, &w.err_flag, 4);
     ok = ok && dev_alloc(c, &w.rec_dev, kMaxBatchTensors);
     w.max_chunks = (u32)(chunks_group > 0xffffffffull ? 0xffffffffull : chunks_group);
@@ -484,15 +485,14 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
         if (ch.n && !ch.W0) return EXCP_E_ARG;
         for (int j = 0; j < ch.steps; ++j)
             if (!ch.blobs[j] || ((uintptr_t)ch.blobs[j] & 15u)) return EXCP_E_ARG;
-        // one tensor's checkpoints must fit the per-tile tables of one group
-        if ((u64)ch.steps * ((ch.n + EXCP_TILE - 1) / EXCP_TILE) > c->max_tiles) return EXCP_E_ARG;
         total_descs += (u64)ch.steps;
     }
     if (total_descs > kMaxBatchTensors) return EXCP_E_ARG;
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
 
     // Groups: at most kMaxGroupTensors descriptors (one per tensor and checkpoint) and as many
-    // descriptor tiles as the per-tile count tables hold.
+    // descriptor tiles as the per-tile count tables hold (EXCP_MAX_CHAIN times a group's tiles, so
+    // any tensor the context accepts fits with its whole chain).
     struct CGroup { u32 first, count, first_desc, ndescs, ntiles, tb_desc, tb_chain; };
     std::vector<CGroup> groups;
     u32 tb_off = 0, desc_off = 0;
@@ -502,7 +502,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
         while (i < (u32)count) {
             const excp_chain &ch = chains[i];
             const u64 tiles = (ch.n + EXCP_TILE - 1) / EXCP_TILE;
-            if (g.count && (g.ndescs + (u32)ch.steps > kMaxGroupTensors || dtiles + tiles * ch.steps > c->max_tiles)) break;
+            if (g.count && (g.ndescs + (u32)ch.steps > kMaxGroupTensors || dtiles + tiles * ch.steps > c->max_tiles * EXCP_MAX_CHAIN)) break;
             dtiles += tiles * ch.steps; g.ndescs += (u32)ch.steps; g.ntiles += (u32)tiles; ++g.count; ++i;
         }
         if (tb_off + g.ndescs + g.count + 2 > kMaxBatchTensors * 2 + 16) return EXCP_E_ARG;
