@@ -431,6 +431,23 @@ def test_chained_run_of_eight_checkpoints(ctx, nbits, alpha, keep):
         assert np.array_equal(ch[3].cpu().numpy().view(np.uint32), stt["W_hat"].view(np.uint32))
 
 
+def test_more_tensors_than_one_group_holds(ctx):
+    # 1300 small tensors: more than the 1024 a group takes, so the batch runs as two groups by count
+    g = np.random.default_rng(33)
+    cases = [case(int(g.integers(1, 700)), 5000 + i) for i in range(1300)]
+    rc, out = gpu_compress(ctx, cases, iters=2)
+    assert rc == 0
+    for i in list(range(0, 1300, 97)) + [1023, 1024, 1025, 1299]:
+        compare_with_oracle(cases[i], out[i], 5e-5, 2.0, 4, 2)
+    for c, o in zip(cases, out):                       # all of them: sizes and the reconstruction's shape
+        st = o["stats"]
+        assert st.status == 0 and st.n == c[0].size and st.blob_bytes == X.excp_blob_size(st.n, st.n_w, st.n_o, 4)
+    # more tensors than a call accepts
+    tiny = [tuple(to_dev(a) for a in case(4, 1)) + (torch.zeros(256, dtype=torch.uint8, device="cuda"), None)]
+    with pytest.raises(X.ExcpError):
+        ctx.excp_compress_tensors(tiny * 4097, 5e-5, 2.0, 4, 1, 0)
+
+
 def test_errors_are_reported_not_faulted(ctx):
     Wp, W, m, v = case(20000, 95)
     # non-finite inputs in each array
