@@ -81,6 +81,10 @@ extern "C" {
 #define EXCP_E_STATE      -6   /* call order violated (batch pending / nothing to collect) */
 #define EXCP_E_INTERNAL   -7   /* an internal work list overflowed (should not happen) */
 
+/* flags of the compress calls (stored in the blob header; decompress does not need them) */
+#define EXCP_FLAG_MEDIAN_OF_WEIGHTS 1u  /* med = lower median of |W_t| instead of |d| (the other reading of Eq. "r_w") */
+#define EXCP_FLAG_NO_M2W            2u  /* ablation of Table "vit": r_i = alpha * med for every i (no 1/sqrt(v_i))   */
+
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 
 typedef struct excp_ctx excp_ctx;
@@ -152,7 +156,7 @@ uint64_t excp_blob_bound(uint64_t n, int nbits);
 /* Exact compressed size for given counts (the closed form of the layout above). */
 uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits);
 
-/* Alg. 1 (minus the archive step) for `count` tensors; asynchronous.  flags must be 0. */
+/* Alg. 1 (minus the archive step) for `count` tensors; asynchronous.  flags: 0 or EXCP_FLAG_* ORed. */
 int excp_compress_tensors(excp_ctx *ctx, int count, const excp_tensor *tensors,
                           float alpha, float beta, int nbits, int lloyd_iters, uint32_t flags);
 

@@ -36,7 +36,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 __all__ = [
-    "MAGIC", "VERSION", "HEADER_BYTES",
+    "MAGIC", "VERSION", "HEADER_BYTES", "FLAG_MEDIAN_OF_WEIGHTS", "FLAG_NO_M2W",
     "residual", "lower_median_abs", "exact_mean_abs", "weight_mask",
     "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
     "pack_bitmap", "pack_codes", "unpack_bitmap", "unpack_codes",
@@ -44,6 +44,8 @@ __all__ = [
     "decompress_step", "reconstruct_chain", "CompressResult", "BlobError", "NonFiniteError",
 ]
 
+FLAG_MEDIAN_OF_WEIGHTS = 1
+FLAG_NO_M2W = 2
 MAGIC = 0x50435845          # bytes "EXCP" read as a little-endian u32
 VERSION = 1
 HEADER_BYTES = 80
@@ -95,8 +97,12 @@ def exact_mean_abs(m: np.ndarray) -> tuple[float, np.float32]:
 # Evaluation order fixed as (alpha*med) / sqrt(v_i), three fp32 roundings.
 # v_i == 0 -> r = +inf -> pruned.  v_i < 0 -> sqrt = NaN -> comparison false.
 # --------------------------------------------------------------------------
-def weight_mask(d: np.ndarray, v: np.ndarray, alpha, med) -> tuple[np.ndarray, np.float32]:
+def weight_mask(d: np.ndarray, v: np.ndarray, alpha, med, use_moment: bool = True) -> tuple[np.ndarray, np.float32]:
+    """``use_moment=False`` is the ablation of Table "vit" without the momentum-to-weights check:
+    the threshold is the scalar alpha * med for every element."""
     t_w = f32(f32(alpha) * f32(med))
+    if not use_moment:
+        return np.abs(d.astype(f32, copy=False)) > t_w, t_w
     with np.errstate(divide="ignore", invalid="ignore", over="ignore", under="ignore"):
         root = np.sqrt(v.astype(f32, copy=False)).astype(f32)
         r = (t_w / root).astype(f32)
@@ -291,6 +297,8 @@ def parse_blob(blob: bytes, n_expected: int | None = None) -> dict:
         raise BlobError("bad version")
     if not 2 <= nbits <= 8:
         raise BlobError("nbits out of range")
+    if flags > 3:
+        raise BlobError("unknown flags")
     if n_expected is not None and n != n_expected:
         raise BlobError("element count mismatch")
     if not (n_o <= n_w <= n):
@@ -359,7 +367,7 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
     v = np.ascontiguousarray(v, dtype=f32).ravel()
     n = W.size
     assert W_prev.size == n and m.size == n and v.size == n
-    assert 2 <= nbits <= 8 and iters >= 0 and flags == 0
+    assert 2 <= nbits <= 8 and iters >= 0 and 0 <= flags <= 3
     for arr in (W_prev, W, m, v):
         if not np.all(np.isfinite(arr)):
             raise NonFiniteError("NaN or Inf in an input")
@@ -382,9 +390,11 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
         d = residual(W_prev, W)                               # Alg. 1 step 1
     if not np.all(np.isfinite(d)):
         raise NonFiniteError("the residual overflows fp32")
-    med = lower_median_abs(d)                                 # Eq. r_w
+    # flags: bit 0 = the median of Eq. r_w is taken over |W_t| instead of the residual (the other
+    # reading of "median(W)"); bit 1 = no momentum-to-weights check (Table "vit"): scalar threshold
+    med = lower_median_abs(W if flags & FLAG_MEDIAN_OF_WEIGHTS else d)      # Eq. r_w
     S, mean32 = exact_mean_abs(m)                             # Eq. r_o
-    Mw, t_w = weight_mask(d, v, alpha, med)                   # Eq. r_w
+    Mw, t_w = weight_mask(d, v, alpha, med, use_moment=not (flags & FLAG_NO_M2W))   # Eq. r_w
     Mo, r_o = momentum_mask(m, Mw, beta, mean32)              # Eq. r_o
     xw, xm, xv = d[Mw], m[Mo], v[Mo]                          # survivors, index order
 

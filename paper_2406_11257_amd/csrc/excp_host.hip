@@ -299,9 +299,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (c->pending) return EXCP_E_STATE;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
 #ifdef EXCP_TUNING
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xffu) != 0) return EXCP_E_ARG;   // tuning build only
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xfcu) != 0) return EXCP_E_ARG;   // tuning build only
 #else
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || flags != 0) return EXCP_E_ARG;
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~3u) != 0) return EXCP_E_ARG;
 #endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
     const int K = (1 << nbits) - 1;

@@ -43,7 +43,7 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors) {
     const u64 *h64 = (const u64 *)D.blob;
     const u32 nbits = h[2];
     const u64 n = h64[2], nw = h64[3], no = h64[4], total = h64[8];
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] == 0u;
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 4u;
     ok = ok && n == D.n && no <= nw && nw <= n;
     u64 off = EXCP_HEADER;
     if (ok) {

@@ -98,7 +98,9 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
             const bool amb = !(sure_keep || sure_drop) || !__builtin_amdgcn_classf(R.v[j], 0x100) ||
                              !__builtin_amdgcn_classf(ra, 0x100);
             bool kw = sure_keep;
-            if (__any(amb)) {
+            if (g.flags & 2u) {
+                kw = ad > t_w;                            // ablation: the same scalar threshold for every element
+            } else if (__any(amb)) {
                 // sqrtf and '/' are the correctly rounded forms (the build passes
                 // -fhip-fp32-correctly-rounded-divide-sqrt); __fsqrt_rn is NOT on this target
                 if (amb) kw = ad > t_w / sqrtf(R.v[j]);

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, Gro
         u32 k = 0xffffffffu;
         if (i < ns) {
             const u64 idx = n <= MED_SAMPLE ? (u64)i : ((u64)i * n) / MED_SAMPLE;
-            k = f2u(D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+            k = f2u((g.flags & 1u) ? D.W[idx] : D.W[idx] - D.Wp[idx]) & 0x7fffffffu;   // flag: median of |W_t|
             const u32 mb = f2u(D.m[idx]) & 0x7fffffffu;
             if (mb < 0x7f800000u) mmax = max(mmax, mb);
         }
@@ -176,6 +176,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
 
         u32 key[16], mb[16];
         u32 worst = 0;             // largest magnitude pattern seen: >= 0x7f800000 means Inf or NaN
+        const bool of_weights = (g.flags & 1u) != 0;       // the median is that of |W_t|, not of the residual
         {
             const EXCP_GLOBAL float *gW = gptr(D.W) + base, *gP = gptr(D.Wp) + base, *gM = gptr(D.m) + base;
             if (rem == EXCP_TILE) {
@@ -192,10 +193,10 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float av = a[k][j], pv = p[k][j];
-                        key[4 * k + j] = f2u(av - pv) & 0x7fffffffu;
+                        const u32 dk = f2u(av - pv) & 0x7fffffffu, wk = f2u(av) & 0x7fffffffu;
+                        key[4 * k + j] = of_weights ? wk : dk;
                         mb[4 * k + j] = f2u(mm[k][j]) & 0x7fffffffu;
-                        worst = max(max(worst, key[4 * k + j]),
-                                    max(mb[4 * k + j], max(f2u(av) & 0x7fffffffu, f2u(pv) & 0x7fffffffu)));
+                        worst = max(max(worst, dk), max(mb[4 * k + j], max(wk, f2u(pv) & 0x7fffffffu)));
                     }
                 }
             } else {
@@ -204,10 +205,10 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
                     const u32 off = wave * 1024u + (u32)(j >> 2) * 256u + lane * 4u + (u32)(j & 3);
                     const bool ok = off < rem;
                     const float av = ok ? gW[off] : 0.f, pv = ok ? gP[off] : 0.f, mv = ok ? gM[off] : 0.f;
-                    const u32 k = f2u(av - pv) & 0x7fffffffu;
+                    const u32 dk = f2u(av - pv) & 0x7fffffffu, wk = f2u(av) & 0x7fffffffu;
                     mb[j] = f2u(mv) & 0x7fffffffu;
-                    worst = max(max(worst, k), max(mb[j], max(f2u(av) & 0x7fffffffu, f2u(pv) & 0x7fffffffu)));
-                    key[j] = ok ? k : 0xffffffffu;            // above every bracket, never a candidate
+                    worst = max(max(worst, dk), max(mb[j], max(wk, f2u(pv) & 0x7fffffffu)));
+                    key[j] = ok ? (of_weights ? wk : dk) : 0xffffffffu;      // above every bracket, never a candidate
                 }
             }
         }
@@ -401,7 +402,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_full_hist(Workspace w, GroupPa
         for (int j = 0; j < 16; ++j) {
             const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
             if (idx < n) {
-                const u32 k = f2u(D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+                const u32 k = f2u((g.flags & 1u) ? D.W[idx] : D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
                 if (PASS == 0) atomicAdd(&hist[k >> 20], 1u);
                 if (PASS == 1) { if ((k >> 20) == prefix) atomicAdd(&hist[(k >> 9) & 2047u], 1u); }
                 if (PASS == 2) { if ((k >> 9) == prefix) atomicAdd(&hist[k & 511u], 1u); }

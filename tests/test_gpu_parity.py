@@ -448,6 +448,26 @@ def test_more_tensors_than_one_group_holds(ctx):
         ctx.excp_compress_tensors(tiny * 4097, 5e-5, 2.0, 4, 1, 0)
 
 
+@pytest.mark.parametrize("flags,alpha", [(1, 5e-5), (2, 0.7), (3, 0.01)])
+def test_ablation_switches(ctx, flags, alpha):
+    # median of |W_t| instead of the residual; scalar weight threshold (no momentum-to-weights check)
+    cases = [case(n, 700 + i) for i, n in enumerate([5, 4097, 150000, 1048593])]
+    dev = []
+    for (Wp, W, m, v) in cases:
+        blob = torch.zeros(X.excp_blob_bound(W.size, 4), dtype=torch.uint8, device="cuda")
+        dev.append((to_dev(Wp), to_dev(W), to_dev(m), to_dev(v), blob, torch.empty(W.size, dtype=torch.float32, device="cuda")))
+    ctx.excp_compress_tensors(dev, alpha, 2.0, 4, 5, flags)
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    for c, t, st in zip(cases, dev, stats):
+        ref = O.compress_step(*c, alpha, 2.0, 4, 5, flags=flags)
+        assert (st.n_w, st.n_o) == (ref.n_w, ref.n_o)
+        assert t[4][:int(st.blob_bytes)].cpu().numpy().tobytes() == ref.blob
+        assert np.array_equal(t[5].cpu().numpy().view(np.uint32), ref.W_recon.view(np.uint32))
+    with pytest.raises(X.ExcpError):
+        ctx.excp_compress_tensors(dev[:1], alpha, 2.0, 4, 5, 4)
+
+
 def test_errors_are_reported_not_faulted(ctx):
     Wp, W, m, v = case(20000, 95)
     # non-finite inputs in each array
@@ -476,7 +496,7 @@ def test_errors_are_reported_not_faulted(ctx):
     d = [to_dev(a) for a in (Wp, W, m, v)]
     blob = torch.zeros(X.excp_blob_bound(Wp.size, 4), dtype=torch.uint8, device="cuda")
     for kw in (dict(nbits=1), dict(nbits=9), dict(lloyd_iters=-1), dict(alpha=-1.0), dict(beta=float("nan")),
-               dict(flags=1)):
+               dict(flags=4)):
         rc, _, _ = ctx.excp_compress_step(*d, blob, check=False, **kw)
         assert rc == X.EXCP_E_ARG, kw
     # damaged blobs

@@ -524,3 +524,34 @@ def test_tied_data_keeps_the_centres_in_order():
     d = np.abs(x.astype(np.float64)[:, None] - C.astype(np.float64)[None, :])
     assert np.array_equal(d[np.arange(x.size), a], d.min(axis=1))          # a nearest centre each
     assert len(np.unique(x)) <= K and hist[-1] < 1e-16                      # few values: (nearly) lossless
+
+
+def test_ablation_switches():
+    # bit 1: without the momentum-to-weights check the mask is a plain comparison with alpha * med
+    # (brute force in exact arithmetic); bit 0: the median is that of |W_t|.  The moment mask and the
+    # rest of the pipeline are unchanged, and the flags travel in the header.
+    g = np.random.default_rng(8)
+    n = 3001
+    Wp = (g.standard_normal(n) * 0.02).astype(f32)
+    W = (Wp + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+    m = (g.standard_normal(n) * 5e-5).astype(f32)
+    v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+    d = (W - Wp).astype(f32)
+    r = O.compress_step(Wp, W, m, v, alpha=0.7, flags=O.FLAG_NO_M2W)
+    med = np.sort(np.abs(d))[(n - 1) // 2]
+    assert r.median == med and r.t_w == f32(f32(0.7) * med)
+    brute = np.array([Fraction(float(abs(x))) > Fraction(float(r.t_w)) for x in d])
+    assert np.array_equal(r.Mw, brute) and 0.3 < r.Mw.mean() < 0.7
+    assert np.array_equal(r.Mo, r.Mw & (np.abs(m) > r.r_o))
+    assert O.parse_blob(r.blob)["flags"] == O.FLAG_NO_M2W
+    r2 = O.compress_step(Wp, W, m, v, alpha=5e-5, flags=O.FLAG_MEDIAN_OF_WEIGHTS)
+    assert r2.median == np.sort(np.abs(W))[(n - 1) // 2]
+    base = O.compress_step(Wp, W, m, v, alpha=5e-5)
+    assert r2.median > base.median and r2.n_w < base.n_w          # |W| is far larger than |d|: fewer survive
+    r3 = O.compress_step(Wp, W, m, v, alpha=0.7, flags=3)
+    assert r3.t_w == f32(f32(0.7) * r2.median) and np.array_equal(r3.Mw, np.abs(d) > r3.t_w)
+    W3, m3, v3 = O.decompress_step(Wp, r3.blob)
+    assert np.array_equal(W3, r3.W_recon)
+    with pytest.raises(O.BlobError):
+        bad = bytearray(r.blob); bad[12] = 9
+        O.parse_blob(bytes(bad))
