@@ -184,9 +184,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
-                    a[k] = *(const EXCP_GLOBAL f4u *)(gW + off);
-                    p[k] = *(const EXCP_GLOBAL f4u *)(gP + off);
-                    mm[k] = *(const EXCP_GLOBAL f4u *)(gM + off);
+                    a[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gW + off));
+                    p[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gP + off));
+                    mm[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gM + off));
                 }
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
