@@ -45,7 +45,7 @@ def survey_step_bytes_per_param(p_w, p_o):
 
 STAGE_KERNEL = {"stats_stream": "k_stats_stream", "mask_slots": "k_mask_slots", "mask_gather": "k_mask_gather",
                 "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats",
-                "assign_pack": "k_assign_pack", "decode_main": "k_decode_main"}
+                "assign_pack": "k_assign_pack", "decode_main": "k_decode_main<false>"}
 
 
 def measured_traffic(kernel, workload):
@@ -66,9 +66,10 @@ def measured_traffic(kernel, workload):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=-1, help="workload config id (default: largest that fits)")
+    ap.add_argument("--groups", type=int, default=2, help="tensor groups a large checkpoint is processed in")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -89,19 +90,21 @@ def main():
 
     def need_bytes(cfg, group):
         N = cfg.total
-        return 20 * N + 1.8 * N + 12.4 * group + (2 << 30)   # inputs + W_hat, blobs, workspace, slack
+        return 20 * N + 1.8 * N + 26.0 * group + (2 << 30)   # inputs + W_hat, blobs, workspace, slack
 
     cid = args.config
     if cid < 0:
         for cand in (3, 2, 1, 0):
             cfg = synth.config(cand)
-            if need_bytes(cfg, max(cfg.total // 3, max(t.n for t in cfg.tensors))) < free:
+            if need_bytes(cfg, cfg.total // args.groups + max(t.n for t in cfg.tensors)) < free:
                 cid = cand
                 break
     cfg = synth.config(cid)
     N = cfg.total
     max_n = max(t.n for t in cfg.tensors)
-    group = max(N // 3 + 1, max_n) if N > (1 << 30) else N
+    # tensors are processed in groups that share one workspace; fewer groups mean fewer launches, more
+    # groups a smaller workspace.  N / ngroups + the largest tensor guarantees at most ngroups groups.
+    group = min(N, N // args.groups + max_n) if N > (1 << 30) else N
     print(f"[bench] workload config {cid} ({cfg.name}): {len(cfg.tensors)} tensors, {N} params; "
           f"free HBM {free / 2**30:.1f} GiB", file=sys.stderr, flush=True)
 
