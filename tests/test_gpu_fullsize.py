@@ -14,22 +14,37 @@ pytestmark = pytest.mark.gpu
 f32 = np.float32
 
 
-def run(ctx, spec_idx, spec, nbits=4, iters=10):
-    dev = torch.device("cuda", 0)
-    Wp, W, m, v = synth.torch_draw_tensor(3, spec_idx, spec, dev)
-    blob = torch.zeros(X.excp_blob_bound(spec.n, nbits), dtype=torch.uint8, device=dev)
-    Wout = torch.empty(spec.n, dtype=torch.float32, device=dev)
-    rc, nbytes, st = ctx.excp_compress_step(Wp, W, m, v, blob, synth.ALPHA, synth.BETA, nbits, iters,
-                                            W_recon_out=Wout)
-    assert rc == 0
-    return (Wp, W, m, v), blob, nbytes, st, Wout
-
-
-def test_one_attention_matrix_against_the_whole_oracle():
+@pytest.fixture(scope="module")
+def batch():
+    """One call in the benchmark's launch configuration: a context with the benchmark's limits (largest
+    tensor 131 072 000 elements, groups of N / 2 + that many elements) and a batch that mixes the four
+    tensor sizes of the LLaMA-7B-shaped checkpoint (embedding, attention, MLP, norm)."""
     cfg = synth.config(3)
+    dev = torch.device("cuda", 0)
+    max_n = max(t.n for t in cfg.tensors)
+    ctx = X.Context(max_n, cfg.total // 2 + max_n)
+    picks = [0, 1, 5, 8]          # embed_tokens 131 M, q_proj 16.8 M, gate_proj 45 M, input_layernorm 4096
+    items = {}
+    tensors = []
+    for idx in picks:
+        spec = cfg.tensors[idx]
+        Wp, W, m, v = synth.torch_draw_tensor(3, idx, spec, dev)
+        blob = torch.zeros(X.excp_blob_bound(spec.n, 4), dtype=torch.uint8, device=dev)
+        Wout = torch.empty(spec.n, dtype=torch.float32, device=dev)
+        tensors.append((Wp, W, m, v, blob, Wout))
+    ctx.excp_compress_tensors(tensors, synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS, 0)
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    for idx, t, st in zip(picks, tensors, stats):
+        items[idx] = (t[:4], t[4], int(st.blob_bytes), st, t[5])
+    yield ctx, cfg, items
+    ctx.close()
+
+
+def test_one_attention_matrix_against_the_whole_oracle(batch):
+    ctx, cfg, items = batch
     idx, spec = 1, cfg.tensors[1]                      # layers.0.self_attn.q_proj.weight, 16 777 216
-    ctx = X.Context(spec.n, spec.n)
-    dev_in, blob, nbytes, st, Wout = run(ctx, idx, spec)
+    dev_in, blob, nbytes, st, Wout = items[idx]
     case = tuple(t.cpu().numpy() for t in dev_in)
     got = dict(blob=blob[:nbytes].cpu().numpy().tobytes(), stats=st, W_recon=Wout.cpu().numpy())
     ref, worst = compare_with_oracle(case, got, synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS)
@@ -40,15 +55,22 @@ def test_one_attention_matrix_against_the_whole_oracle():
     ctx.excp_decompress_step(dev_in[0], blob, nbytes, *outs)
     for a, b in zip(outs, (ref.W_recon, ref.m_recon, ref.v_recon)):
         assert np.array_equal(a.cpu().numpy().view(np.uint32), b.view(np.uint32))
-    ctx.close()
 
 
-def test_largest_tensor_properties_and_sampled_elements():
-    cfg = synth.config(3)
+def test_norm_vector_in_the_same_batch(batch):
+    ctx, cfg, items = batch
+    dev_in, blob, nbytes, st, Wout = items[8]          # 4096 elements riding along with the big ones
+    case = tuple(t.cpu().numpy() for t in dev_in)
+    got = dict(blob=blob[:nbytes].cpu().numpy().tobytes(), stats=st, W_recon=Wout.cpu().numpy())
+    ref, _ = compare_with_oracle(case, got, synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS)
+    assert got["blob"] == ref.blob
+
+
+def test_largest_tensor_properties_and_sampled_elements(batch):
+    ctx, cfg, items = batch
     idx, spec = 0, cfg.tensors[0]                      # embed_tokens.weight, 131 072 000 elements
     n = spec.n
-    ctx = X.Context(n, n)
-    (Wp, W, m, v), blob, nbytes, st, Wout = run(ctx, idx, spec)
+    (Wp, W, m, v), blob, nbytes, st, Wout = items[idx]
     print("131M-element tensor: n_w", st.n_w, "n_o", st.n_o, "bytes", nbytes, flush=True)
     # --- thresholds against independent device-side library routines --------------------------
     d = W - Wp
@@ -107,4 +129,3 @@ def test_largest_tensor_properties_and_sampled_elements():
     # exactly is that every centre lies inside its stream's range and the objective is consistent
     assert st.obj_w > 0 and st.obj_m > 0 and st.obj_v > 0
     assert abs(12.0 * n / nbytes - 28.8) < 0.5                   # same ratio as every other tensor of this recipe
-    ctx.close()
