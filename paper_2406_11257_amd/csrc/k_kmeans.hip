@@ -625,7 +625,8 @@ __device__ __forceinline__ void move_centres(const Workspace &w, const GroupPara
 // ---------------------------------------------------------------- P5a: one Lloyd accumulation
 // Classification (one workgroup per stream): every bucket is compared with the current centres.
 // A bucket whose smallest and largest value go to the same centre adds its stored totals to that
-// centre; a bucket that a cluster border cuts is split into work items of at most 8192 values.
+// centre; a bucket that a cluster border cuts is split into work items of at most 16384 values.
+constexpr u32 KM_ITEM = 16384;                   // values per work item
 struct KmItem { u32 sidx, p0, p1, range; };      // range = alo | ahi << 8
 
 __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, GroupParams g, u32 parity, u32 do_update) {
@@ -666,7 +667,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
         for (int q = 0; q < EXCP_ABSM_BINS; ++q) if (tot[q]) atomicAdd(&dst[q], tot[q]);
         atomicAdd(&dst[EXCP_ABSM_BINS], (u64)cntb);
     }
-    const u32 nitems = cut ? (cntb + EXCP_CHUNK - 1) / EXCP_CHUNK : 0u;
+    const u32 nitems = cut ? (cntb + KM_ITEM - 1) / KM_ITEM : 0u;
     s_scan[tid] = nitems;
     __syncthreads();
     for (u32 off = 1; off < EXCP_THREADS; off <<= 1) {
@@ -681,7 +682,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
     KmItem *items = (KmItem *)w.km_items;
     for (u32 q = 0; q < nitems; ++q, ++at) {
         if (at >= w.km_item_cap) { atomicExch(w.err_flag, 1); break; }
-        u32 a0 = p0 + q * EXCP_CHUNK, a1 = a0 + EXCP_CHUNK < p1 ? a0 + EXCP_CHUNK : p1;
+        u32 a0 = p0 + q * KM_ITEM, a1 = a0 + KM_ITEM < p1 ? a0 + KM_ITEM : p1;
         items[at] = KmItem{sidx, a0, a1, alo | (ahi << 8)};
     }
 }
