@@ -41,7 +41,8 @@ __all__ = [
     "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
     "pack_bitmap", "pack_codes", "unpack_bitmap", "unpack_codes",
     "blob_size", "build_blob", "parse_blob", "compress_step",
-    "decompress_step", "reconstruct_chain", "CompressResult", "BlobError", "NonFiniteError",
+    "decompress_step", "reconstruct_chain", "dense_bytes", "head_bytes", "dense_pack", "dense_unpack",
+    "export_dense", "decompress_dense", "CompressResult", "BlobError", "NonFiniteError",
 ]
 
 FLAG_MEDIAN_OF_WEIGHTS = 1
@@ -454,3 +455,91 @@ def reconstruct_chain(W0, blobs):
     for blob in blobs:
         W, m, v = decompress_step(W, blob)
     return W, m, v
+
+
+# --------------------------------------------------------------------------
+# The stored layout of Sec. 4.2: one code per ELEMENT (0 = pruned, 1..K = centre index + 1), the
+# codes of 4 bits or fewer two to a byte, handed to a general-purpose archiver (Alg. 1, last step).
+# The paper does not say which element takes which half of the byte: here the even element takes
+# the low four bits.  Codes wider than four bits take one byte each.
+# --------------------------------------------------------------------------
+def dense_bytes(n: int, nbits: int) -> int:
+    return (n + 1) // 2 if nbits <= 4 else n
+
+
+def head_bytes(nbits: int) -> int:
+    """Header and the three codebooks: the leading bytes of a blob, kept verbatim beside the codes."""
+    return HEADER_BYTES + 12 * (1 << nbits)
+
+
+def dense_pack(codes: np.ndarray, nbits: int) -> np.ndarray:
+    codes = np.asarray(codes, dtype=np.int64)
+    assert codes.size == 0 or (codes.min() >= 0 and codes.max() < (1 << nbits))
+    if nbits > 4:
+        return codes.astype(np.uint8)
+    padded = np.zeros(2 * dense_bytes(codes.size, nbits), dtype=np.int64)     # an odd tail pairs with code 0
+    padded[:codes.size] = codes
+    return (padded[0::2] + 16 * padded[1::2]).astype(np.uint8)
+
+
+def dense_unpack(packed: np.ndarray, n: int, nbits: int) -> np.ndarray:
+    packed = np.asarray(packed, dtype=np.uint8)
+    if packed.size != dense_bytes(n, nbits):
+        raise BlobError("wrong length of a code tensor")
+    if nbits > 4:
+        return packed.astype(np.int64)
+    both = np.empty(2 * packed.size, dtype=np.int64)
+    both[0::2] = packed & 15
+    both[1::2] = packed >> 4
+    if n % 2 == 1 and both[n] != 0:
+        raise BlobError("the unused half of the last byte is not zero")
+    return both[:n]
+
+
+def export_dense(blob: bytes):
+    """Blob -> (head, codes_w, codes_m, codes_v): the per-element code tensors of Sec. 4.2."""
+    p = parse_blob(blob)
+    n, n_w, n_o, nbits = p["n"], p["n_w"], p["n_o"], p["nbits"]
+    Mw = unpack_bitmap(p["bitmap_w"], n)
+    Mo_s = unpack_bitmap(p["bitmap_o"], n_w)
+    if int(Mw.sum()) != n_w or int(Mo_s.sum()) != n_o:
+        raise BlobError("bitmap population does not match the header")
+    idx_w = np.flatnonzero(Mw)
+    idx_o = idx_w[Mo_s]
+    per_element = []
+    for idx, words, count in ((idx_w, p["codes_w"], n_w), (idx_o, p["codes_m"], n_o), (idx_o, p["codes_v"], n_o)):
+        e = np.zeros(n, dtype=np.int64)                      # pruned elements keep code 0
+        e[idx] = unpack_codes(words, count, nbits)
+        per_element.append(dense_pack(e, nbits))
+    return bytes(blob[:head_bytes(nbits)]), per_element[0], per_element[1], per_element[2]
+
+
+def decompress_dense(W_prev, head: bytes, codes_w, codes_m, codes_v):
+    """Alg. 2 from the stored layout of Sec. 4.2: look every element's code up in its codebook; code 0
+    leaves the previous weight untouched and gives a zero moment."""
+    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
+    n = W_prev.size
+    if len(head) < HEADER_BYTES:
+        raise BlobError("shorter than a header")
+    magic, version, nbits, flags, n_stored = struct.unpack("<IIIIQ", head[:24])
+    if magic != MAGIC or version != VERSION or not 2 <= nbits <= 8 or flags > 3 or n_stored != n:
+        raise BlobError("bad header")
+    if len(head) < head_bytes(nbits):
+        raise BlobError("codebooks missing")
+    E = 1 << nbits
+    books = [np.frombuffer(head, dtype="<f4", count=E, offset=HEADER_BYTES + 4 * E * k).astype(f32) for k in range(3)]
+    out = []
+    for k, packed in enumerate((codes_w, codes_m, codes_v)):
+        c = dense_unpack(packed, n, nbits)
+        if c.size and c.max() > E - 1:
+            raise BlobError("code beyond the codebook")
+        kept = c != 0
+        if k == 0:
+            r = W_prev.copy()
+            r[kept] = (W_prev[kept] + books[0][c[kept]]).astype(f32)
+        else:
+            r = np.zeros(n, dtype=f32)
+            r[kept] = books[k][c[kept]]
+        out.append(r)
+    return out[0], out[1], out[2]
+

@@ -555,3 +555,75 @@ def test_ablation_switches():
     with pytest.raises(O.BlobError):
         bad = bytearray(r.blob); bad[12] = 9
         O.parse_blob(bytes(bad))
+
+
+# ---------------------------------------------------------------- Sec. 4.2 stored layout (dense codes)
+def test_dense_layout_of_the_hand_built_example():
+    # the same five elements as above: codes per element (0 = pruned), two to a byte, even element low
+    Wp = np.zeros(5, f32)
+    W = np.array([1.0, 0.0, -2.0, 4.0, 8.0], f32)
+    m = np.array([1.0, 1.0, 9.0, 1.0, 8.0], f32)
+    v = np.full(5, 1e30, f32)
+    r = O.compress_step(Wp, W, m, v, alpha=1.0, beta=2.0, nbits=2, iters=3)
+    head, cw, cm, cv = O.export_dense(r.blob)
+    assert head == r.blob[:80 + 48]
+    # element codes: w = [1, 0, 1, 2, 3], m = v = [0, 0, 1, 0, 0]
+    assert cw.tobytes() == bytes([0x01, 0x21, 0x03])
+    assert cm.tobytes() == bytes([0x00, 0x01, 0x00]) and cv.tobytes() == cm.tobytes()
+    Wr, mr, vr = O.decompress_dense(Wp, head, cw, cm, cv)
+    assert list(Wr) == [-0.5, 0.0, -0.5, 4.0, 8.0]
+    assert list(mr) == [0, 0, 9.0, 0, 0] and list(vr) == [0, 0, f32(1e30), 0, 0]
+
+
+@pytest.mark.parametrize("nbits", [2, 3, 4, 5, 8])
+@pytest.mark.parametrize("n", [1, 2, 63, 1000, 1001])
+def test_dense_layout_against_an_elementwise_build(nbits, n):
+    Wp, W, m, v = small_case(n, seed=n + nbits)
+    r = O.compress_step(Wp, W, m, v, alpha=3e-5, beta=1.0, nbits=nbits, iters=4)
+    head, cw, cm, cv = O.export_dense(r.blob)
+    assert len(head) == 80 + 12 * 2 ** nbits == O.head_bytes(nbits)
+    # build the three code tensors element by element from the masks and assignments
+    want = {k: [0] * n for k in "wmv"}
+    jw = jo = 0
+    for i in range(n):
+        if r.Mw[i]:
+            want["w"][i] = int(r.assign["w"][jw]) + 1; jw += 1
+        if r.Mo[i]:
+            want["m"][i] = int(r.assign["m"][jo]) + 1
+            want["v"][i] = int(r.assign["v"][jo]) + 1; jo += 1
+    for got, key in ((cw, "w"), (cm, "m"), (cv, "v")):
+        e = want[key]
+        if nbits <= 4:
+            e = e + [0] * (len(e) % 2)
+            ref = bytes(e[2 * j] | (e[2 * j + 1] << 4) for j in range(len(e) // 2))      # "two int4 into one int8"
+        else:
+            ref = bytes(e)
+        assert got.tobytes() == ref and got.size == O.dense_bytes(n, nbits)
+        assert list(O.dense_unpack(got, n, nbits)) == want[key]
+    # the stored layout reconstructs exactly what the blob does
+    a = O.decompress_step(Wp, r.blob)
+    b = O.decompress_dense(Wp, head, cw, cm, cv)
+    for x, y in zip(a, b):
+        assert x.tobytes() == y.tobytes()
+    assert a[0].tobytes() == r.W_recon.tobytes()
+
+
+def test_dense_layout_rejects_damage_and_keeps_minus_zero():
+    Wp, W, m, v = small_case(101, seed=5)
+    Wp[:10] = -0.0; W[:10] = -0.0                       # pruned elements: -0.0 must stay -0.0 (no "+ 0.0")
+    r = O.compress_step(Wp, W, m, v, nbits=3, iters=2)
+    head, cw, cm, cv = O.export_dense(r.blob)
+    Wr, _, _ = O.decompress_dense(Wp, head, cw, cm, cv)
+    assert np.all(np.signbit(Wr[:10]))
+    bad = cw.copy(); bad[3] = 0x0F                      # code 15 > K = 7 of a 3-bit codebook... 8..15 do not exist
+    with pytest.raises(O.BlobError):
+        O.decompress_dense(Wp, head, bad, cm, cv)
+    with pytest.raises(O.BlobError):
+        O.decompress_dense(Wp, head, cw[:-1], cm, cv)
+    with pytest.raises(O.BlobError):
+        O.decompress_dense(Wp[:-1], head, cw, cm, cv)
+    odd = cw.copy(); odd[-1] |= 0x10                    # n is odd: the upper half of the last byte is unused
+    with pytest.raises(O.BlobError):
+        O.decompress_dense(Wp, head, odd, cm, cv)
+    with pytest.raises(O.BlobError):
+        O.decompress_dense(Wp, b"XXXX" + head[4:], cw, cm, cv)
