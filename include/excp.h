@@ -171,6 +171,50 @@ int excp_decompress_tensors(excp_ctx *ctx, int count, const excp_blob *blobs);
  * blob_bytes are those of its last one. */
 int excp_reconstruct_chain(excp_ctx *ctx, int count, const excp_chain *chains);
 
+/* The stored layout of Sec. 4.2 ("dense"): one code per ELEMENT, 0 = pruned, 1..2^nbits-1 = centre
+ * index + 1 -- the tensors Alg. 1 hands to its general-purpose archiver.  Codes of nbits <= 4 sit two
+ * to a byte, the even element in the low four bits (the paper does not say which half; an odd
+ * tensor leaves the last high half zero); wider codes take one byte each.  The header and the
+ * three codebooks travel beside them as the first excp_head_bytes(nbits) bytes of the blob. */
+uint64_t excp_dense_bytes(uint64_t n, int nbits);   /* bytes of one code tensor */
+uint64_t excp_head_bytes(int nbits);                /* 80 + 12 * 2^nbits; 0 for nbits outside [2,8] */
+
+/* One tensor of an export batch: blob -> per-element code tensors. */
+typedef struct {
+    const void *blob;            /* device, 16-B aligned */
+    uint64_t    blob_bytes;      /* bytes readable at blob */
+    uint64_t    n;               /* must equal the n stored in the blob */
+    void       *head;            /* device, 16-B aligned, nullable: receives excp_head_bytes(nbits) bytes */
+    uint8_t    *codes_w;         /* device, 16-B aligned, nullable: excp_dense_bytes(n, nbits) bytes each; */
+    uint8_t    *codes_m;         /*   every byte is written (pruned elements as code 0)                    */
+    uint8_t    *codes_v;
+} excp_dense_export;
+
+/* One tensor of a reconstruction from that layout (Alg. 2 on per-element codes). */
+typedef struct {
+    const float   *W_prev_recon; /* device, n; needed when W_recon_out is given */
+    const void    *head;         /* device, 16-B aligned: header and codebooks */
+    uint64_t       head_bytes;   /* bytes readable at head */
+    uint64_t       n;            /* must equal the n stored in the header */
+    const uint8_t *codes_w;      /* device, 16-B aligned; each needed when its output is given */
+    const uint8_t *codes_m;
+    const uint8_t *codes_v;
+    float         *W_recon_out;  /* device, n, nullable; may equal W_prev_recon */
+    float         *m_out;        /* device, n, nullable */
+    float         *v_out;        /* device, n, nullable */
+} excp_dense_blob;
+
+/* Blob -> the layout of Sec. 4.2, for `count` tensors; asynchronous, results by excp_collect (n,
+ * n_w, n_o, blob_bytes, status as after a decompress batch; EXCP_E_BLOB for a damaged blob). */
+int excp_export_dense(excp_ctx *ctx, int count, const excp_dense_export *items);
+
+/* Alg. 2 from the layout of Sec. 4.2, for `count` tensors; asynchronous.  W_hat[i] = W_prev_recon[i]
+ * + C_w[code] where the code is non-zero, else W_prev_recon[i] unchanged; moments C[code] or +0.
+ * Bit-identical to excp_decompress_tensors on the blob the codes were exported from.  EXCP_E_BLOB
+ * (by excp_collect) for a bad header, a code beyond the codebook or a set unused half-byte; the
+ * counts n_w, n_o reported are those stored in the header and are not re-counted. */
+int excp_decompress_dense(excp_ctx *ctx, int count, const excp_dense_blob *items);
+
 /* Wait for the pending batch; fill stats[0..count) (nullable); return EXCP_OK or the first
  * per-tensor error.  After a decompress batch only n, n_w, n_o, blob_bytes and status are set. */
 int excp_collect(excp_ctx *ctx, excp_stats *stats);

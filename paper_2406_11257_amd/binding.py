@@ -28,6 +28,17 @@ class ExcpBlob(C.Structure):
                 ("v_out", C.c_void_p)]
 
 
+class ExcpDenseExport(C.Structure):
+    _fields_ = [("blob", C.c_void_p), ("blob_bytes", C.c_uint64), ("n", C.c_uint64), ("head", C.c_void_p),
+                ("codes_w", C.c_void_p), ("codes_m", C.c_void_p), ("codes_v", C.c_void_p)]
+
+
+class ExcpDenseBlob(C.Structure):
+    _fields_ = [("W_prev_recon", C.c_void_p), ("head", C.c_void_p), ("head_bytes", C.c_uint64),
+                ("n", C.c_uint64), ("codes_w", C.c_void_p), ("codes_m", C.c_void_p), ("codes_v", C.c_void_p),
+                ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p)]
+
+
 class ExcpStats(C.Structure):
     _fields_ = [("n", C.c_uint64), ("n_w", C.c_uint64), ("n_o", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("nonfinite", C.c_uint64),
@@ -51,6 +62,10 @@ SYMBOLS = {
     "excp_compress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpTensor), C.c_float, C.c_float,
                                         C.c_int, C.c_int, C.c_uint32]),
     "excp_decompress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpBlob)]),
+    "excp_dense_bytes": (C.c_uint64, [C.c_uint64, C.c_int]),
+    "excp_head_bytes": (C.c_uint64, [C.c_int]),
+    "excp_export_dense": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpDenseExport)]),
+    "excp_decompress_dense": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpDenseBlob)]),
     "excp_collect": (C.c_int, [C.c_void_p, C.POINTER(ExcpStats)]),
     "excp_compress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                                      C.c_float, C.c_float, C.c_int, C.c_int, C.c_uint32, C.c_void_p,
@@ -100,6 +115,14 @@ def excp_blob_bound(n: int, nbits: int) -> int:
 
 def excp_blob_size(n: int, n_w: int, n_o: int, nbits: int) -> int:
     return int(lib().excp_blob_size(n, n_w, n_o, nbits))
+
+
+def excp_dense_bytes(n: int, nbits: int) -> int:
+    return int(lib().excp_dense_bytes(n, nbits))
+
+
+def excp_head_bytes(nbits: int) -> int:
+    return int(lib().excp_head_bytes(nbits))
 
 
 def _ptr(t):
@@ -188,6 +211,45 @@ class Context:
             raise ExcpError(rc, "excp_decompress_tensors")
         self._keep = (blobs, arr)
         self._count = len(blobs)
+
+    def excp_export_dense(self, items):
+        """items: sequence of (blob, blob_bytes, n, head, codes_w, codes_m, codes_v); the last four are
+        uint8 device tensors or None."""
+        arr = (ExcpDenseExport * max(len(items), 1))()
+        for i, (blob, nbytes, n, head, cw, cm, cv) in enumerate(items):
+            if nbytes > blob.numel() * blob.element_size():
+                raise ValueError("blob_bytes exceeds the blob tensor")
+            arr[i] = ExcpDenseExport(blob.data_ptr(), nbytes, n, *[0 if t is None else t.data_ptr()
+                                                                     for t in (head, cw, cm, cv)])
+        rc = lib().excp_export_dense(self._h, len(items), arr)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_export_dense")
+        self._keep = (items, arr)
+        self._count = len(items)
+
+    def excp_decompress_dense(self, items):
+        """items: sequence of (W_prev_recon, head, head_bytes, n, codes_w, codes_m, codes_v,
+        W_recon_out, m_out, v_out)."""
+        arr = (ExcpDenseBlob * max(len(items), 1))()
+        for i, (Wp, head, hbytes, n, cw, cm, cv, Wout, mout, vout) in enumerate(items):
+            if Wp is not None:
+                _check_f32(Wp, "W_prev_recon", self.device)
+                if Wp.numel() != n:
+                    raise ValueError("W_prev_recon length differs")
+            for t, nm in ((Wout, "W_recon_out"), (mout, "m_out"), (vout, "v_out")):
+                if t is not None:
+                    _check_f32(t, nm, self.device)
+                    if t.numel() != n:
+                        raise ValueError(nm + " length differs")
+            if hbytes > head.numel() * head.element_size():
+                raise ValueError("head_bytes exceeds the head tensor")
+            arr[i] = ExcpDenseBlob(0 if Wp is None else Wp.data_ptr(), head.data_ptr(), hbytes, n,
+                                   *[0 if t is None else t.data_ptr() for t in (cw, cm, cv, Wout, mout, vout)])
+        rc = lib().excp_decompress_dense(self._h, len(items), arr)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_decompress_dense")
+        self._keep = (items, arr)
+        self._count = len(items)
 
     def excp_reconstruct_chain(self, chains):
         """chains: sequence of (W0, [blob tensors, oldest first], [blob_bytes], W_out, m_out, v_out)."""

@@ -70,6 +70,11 @@ struct DDesc {
     u64 blob_bytes;
     u64 n;
     float *W_out, *m_out, *v_out;
+    // per-element code tensors (two codes of 4 bits or fewer per byte, else one per byte): written by
+    // the export of a blob, read by the reconstruction from that layout (then `blob` is the header
+    // with the codebooks and `head` is unused)
+    unsigned char *cw, *cm, *cv;
+    unsigned char *head;        // export: receives header and codebooks (nullable)
     u32 tile_begin, tile_count;
 };
 
@@ -172,5 +177,8 @@ void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which
 void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s);
 void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s);
+void launch_export_dense(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
+void launch_dense_parse(const Workspace &w, u32 ntensors, hipStream_t s);
+void launch_decode_dense(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s);
 void launch_decode_chain(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s);
 void launch_chain_finish(const Workspace &w, u32 ntensors, hipStream_t s);

@@ -19,12 +19,12 @@ constexpr u32 kMaxBatchTensors = 4096;   // tensors per compress / decompress ca
 enum Stage {
     ST_SAMPLE = 0, ST_STATS, ST_SELECT, ST_SELECT_FALLBACK, ST_MASK_COMPACT, ST_MASK_SCAN, ST_MASK_GATHER, ST_LAYOUT, ST_KM_SAMPLE, ST_KM_COUNT, ST_KM_SCAN,
     ST_KM_SCATTER, ST_KM_BUCKET_STATS, ST_KM_INIT, ST_KM_CLASSIFY, ST_KM_ITER, ST_KM_UPDATE, ST_ASSIGN_PACK, ST_FINALIZE,
-    ST_DECODE_PREP, ST_DECODE_MAIN, ST_MISC, ST_COUNT
+    ST_DECODE_PREP, ST_DECODE_MAIN, ST_EXPORT_DENSE, ST_DECODE_DENSE, ST_MISC, ST_COUNT
 };
 const char *kStageNames[ST_COUNT] = {
     "median_sample", "stats_stream", "select_candidates", "select_fallback", "mask_slots", "mask_scan", "mask_gather", "layout", "km_sample", "km_count", "km_scan",
     "km_scatter", "km_bucket_stats", "km_init", "km_classify", "km_iter", "km_update", "assign_pack", "finalize",
-    "decode_prep", "decode_main", "misc"};
+    "decode_prep", "decode_main", "export_dense", "decode_dense", "misc"};
 
 struct Span { int stage; hipEvent_t a, b; };
 
@@ -133,6 +133,74 @@ void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32
         StageTimer t(c, ST_DECODE_MAIN);
         launch_decode_main(w, ntensors, ntiles, moments, c->stream);
     }
+}
+
+// Shared by the two calls that work on the per-element code tensors of Sec. 4.2.  `fill` writes the
+// descriptor of tensor i (everything but the tile fields).
+template <class Fill>
+int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
+    if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+    std::vector<Group> groups;
+    make_groups(count, c->max_group, kMaxGroupTensors, [&](u32 i) { DDesc d; fill(i, d); return (u64)d.n; }, groups);
+    u32 tb_off = 0;
+    std::vector<u32> tb_offsets;
+    for (const Group &g : groups) {
+        u32 tile = 0;
+        tb_offsets.push_back(tb_off);
+        for (u32 q = 0; q < g.count; ++q) {
+            DDesc &d = c->h_ddesc[g.first + q];
+            fill(g.first + q, d);
+            d.tile_begin = tile; d.tile_count = (u32)((d.n + EXCP_TILE - 1) / EXCP_TILE);
+            c->h_tile_begin[tb_off + q] = tile;
+            tile += d.tile_count;
+        }
+        c->h_tile_begin[tb_off + g.count] = tile;
+        tb_off += g.count + 1;
+    }
+    hipStream_t s = c->stream;
+    if (count) {
+        if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
+            hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    for (size_t gi = 0; gi < groups.size(); ++gi) {
+        const Group &g = groups[gi];
+        Workspace w = c->w;
+        w.ddesc = c->ddesc_all + g.first;
+        w.dst = c->dst_all + g.first;
+        w.tile_begin = c->tile_begin_all + tb_offsets[gi];
+        w.rec_dev = c->w.rec_dev + g.first;
+        w.rec_base = 0;
+        if (exporting) {
+            { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, s); }
+            bool moments = false;
+            for (u32 q = 0; q < g.count; ++q)
+                moments = moments || c->h_ddesc[g.first + q].cm != nullptr || c->h_ddesc[g.first + q].cv != nullptr;
+            {
+                StageTimer t(c, ST_DECODE_PREP);
+                launch_decode_count(w, g.count, g.ntiles, 0, s);
+                launch_decode_scan(w, g.count, 0, s);
+                if (moments) {
+                    launch_decode_count(w, g.count, g.ntiles, 1, s);
+                    launch_decode_scan(w, g.count, 1, s);
+                }
+            }
+            { StageTimer t(c, ST_EXPORT_DENSE); launch_export_dense(w, g.count, g.ntiles, moments, s); }
+        } else {
+            { StageTimer t(c, ST_MISC); launch_dense_parse(w, g.count, s); }
+            { StageTimer t(c, ST_DECODE_DENSE); launch_decode_dense(w, g.count, g.ntiles, s); }
+        }
+        { StageTimer t(c, ST_MISC); launch_decode_finish(w, g.count, s); }
+    }
+    if (count) {
+        if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
+            return EXCP_E_HIP;
+    }
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
+    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    c->pending = 2;
+    c->pending_count = count;
+    return EXCP_OK;
 }
 
 }  // namespace
@@ -434,6 +502,7 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
             DDesc &d = c->h_ddesc[g.first + q];
             d.Wp = b.W_prev_recon; d.blob = (const unsigned char *)b.blob; d.blob_bytes = b.blob_bytes; d.n = b.n;
             d.W_out = b.W_recon_out; d.m_out = b.m_out; d.v_out = b.v_out;
+            d.cw = d.cm = d.cv = d.head = nullptr;
             d.tile_begin = tile; d.tile_count = (u32)((b.n + EXCP_TILE - 1) / EXCP_TILE);
             c->h_tile_begin[tb_off + q] = tile;
             tile += d.tile_count;
@@ -471,6 +540,47 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
     c->pending = 2;
     c->pending_count = count;
     return EXCP_OK;
+}
+
+uint64_t excp_dense_bytes(uint64_t n, int nbits) { return nbits <= 4 ? (n + 1) / 2 : n; }
+uint64_t excp_head_bytes(int nbits) { return (nbits < 2 || nbits > 8) ? 0 : EXCP_HEADER + 12ull * (1ull << nbits); }
+
+int excp_export_dense(excp_ctx *c, int count, const excp_dense_export *items) {
+    if (!c || count < 0 || (count && !items)) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+    for (int i = 0; i < count; ++i) {
+        const excp_dense_export &e = items[i];
+        if (e.n > c->max_tensor) return EXCP_E_ARG;
+        if (!e.blob || ((uintptr_t)e.blob & 15u)) return EXCP_E_ARG;
+        if (((uintptr_t)e.head | (uintptr_t)e.codes_w | (uintptr_t)e.codes_m | (uintptr_t)e.codes_v) & 15u) return EXCP_E_ARG;
+    }
+    return run_dense(c, count, true, [&](u32 i, DDesc &d) {
+        const excp_dense_export &e = items[i];
+        d.Wp = nullptr; d.blob = (const unsigned char *)e.blob; d.blob_bytes = e.blob_bytes; d.n = e.n;
+        d.W_out = d.m_out = d.v_out = nullptr;
+        d.cw = e.codes_w; d.cm = e.codes_m; d.cv = e.codes_v; d.head = (unsigned char *)e.head;
+    });
+}
+
+int excp_decompress_dense(excp_ctx *c, int count, const excp_dense_blob *items) {
+    if (!c || count < 0 || (count && !items)) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
+    for (int i = 0; i < count; ++i) {
+        const excp_dense_blob &e = items[i];
+        if (e.n > c->max_tensor) return EXCP_E_ARG;
+        if (!e.head || ((uintptr_t)e.head & 15u)) return EXCP_E_ARG;
+        if (((uintptr_t)e.codes_w | (uintptr_t)e.codes_m | (uintptr_t)e.codes_v) & 15u) return EXCP_E_ARG;
+        if (e.n && e.W_recon_out && (!e.W_prev_recon || !e.codes_w)) return EXCP_E_ARG;
+        if (e.n && ((e.m_out && !e.codes_m) || (e.v_out && !e.codes_v))) return EXCP_E_ARG;
+    }
+    return run_dense(c, count, false, [&](u32 i, DDesc &d) {
+        const excp_dense_blob &e = items[i];
+        d.Wp = e.W_prev_recon; d.blob = (const unsigned char *)e.head; d.blob_bytes = e.head_bytes; d.n = e.n;
+        d.W_out = e.W_recon_out; d.m_out = e.m_out; d.v_out = e.v_out;
+        d.cw = (unsigned char *)e.codes_w; d.cm = (unsigned char *)e.codes_m; d.cv = (unsigned char *)e.codes_v; d.head = nullptr;
+    });
 }
 
 int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
@@ -521,6 +631,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
                 const bool last = j + 1 == ch.steps;
                 dd.Wp = nullptr; dd.blob = (const unsigned char *)ch.blobs[j]; dd.blob_bytes = ch.blob_bytes[j]; dd.n = ch.n;
                 dd.W_out = nullptr; dd.m_out = last ? ch.m_out : nullptr; dd.v_out = last ? ch.v_out : nullptr;
+                dd.cw = dd.cm = dd.cv = dd.head = nullptr;
                 dd.tile_begin = dtile; dd.tile_count = tiles;
                 c->h_tile_begin[g.tb_desc + d] = dtile;
                 dtile += tiles;

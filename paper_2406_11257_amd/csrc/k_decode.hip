@@ -30,6 +30,10 @@ __device__ __forceinline__ u32 popcount_range_lane(const u64 *__restrict__ bm, u
     return cnt;
 }
 
+__device__ __forceinline__ bool wants_moments(const DDesc &D) {
+    return D.m_out != nullptr || D.v_out != nullptr || D.cm != nullptr || D.cv != nullptr;
+}
+
 // Validate the header of every blob and derive the section offsets.
 __global__ void k_decode_parse(Workspace w, u32 ntensors) {
     const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_count(Workspace w, u32 
                     if (rem < 64) v &= (1ull << rem) - 1ull;
                     cnt = __popcll(v);
                 }
-            } else if (D.m_out != nullptr || D.v_out != nullptr) {      // only where moments are wanted
+            } else if (wants_moments(D)) {                              // only where moments are wanted
                 const u64 *bm = (const u64 *)(D.blob + S.off_bo);
                 u64 p0 = w.dec_cnt_w[tile];
                 u64 p1 = (tile + 1 < D.tile_begin + D.tile_count) ? (u64)w.dec_cnt_w[tile + 1] : S.pop_w;
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 n
     const DDesc &D = w.ddesc[t];
     DState &S = w.dst[t];
     u32 *cnt = (WHICH == 0 ? w.dec_cnt_w : w.dec_cnt_o) + D.tile_begin;
-    if (WHICH == 1 && D.m_out == nullptr && D.v_out == nullptr) return;    // bitmap_o is not used for this one
+    if (WHICH == 1 && !wants_moments(D)) return;    // bitmap_o is not used for this one
     u64 carry = 0;
     for (u32 base = 0; base < D.tile_count; base += EXCP_THREADS) {
         u32 i = base + tid;
@@ -146,14 +150,35 @@ __device__ __forceinline__ u32 window32(const u32 *s, u32 p) {
     return __builtin_amdgcn_alignbit(s[i + 1], s[i], p & 31u);
 }
 
+// The codes of four consecutive elements (the first has index e0, a multiple of 4; `left` of them
+// exist) into a per-element code tensor: half a byte each when nbits <= 4, else a byte each.
+__device__ __forceinline__ void store_codes4(unsigned char *dst, u64 e0, u32 left, u32 nbits, const u32 c[4]) {
+    if (left == 0u) return;
+    if (nbits <= 4u) {
+        const u32 v = c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12);
+        EXCP_GLOBAL unsigned char *p = gptr(dst) + (e0 >> 1);
+        if (left > 2u) *(EXCP_GLOBAL unsigned short *)p = (unsigned short)v;
+        else *p = (unsigned char)v;
+    } else {
+        const u32 v = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
+        EXCP_GLOBAL unsigned char *p = gptr(dst) + e0;
+        if (left >= 4u) *(EXCP_GLOBAL u32 *)p = v;
+        else for (u32 j = 0; j < left; ++j) p[j] = (unsigned char)(v >> (8u * j));
+    }
+}
+
 // One tile (4096 elements) per workgroup iteration.  Each wave scans the tile's 64 bitmap words,
 // the workgroup stages the tile's contiguous run of packed codes (and, for the moments, the run of
 // bitmap_o bits of its survivors with their prefix counts) in LDS, then every lane reconstructs four
 // consecutive elements: the codes of its survivors are consecutive fields of the staged stream, so
 // one 32-bit window read per lane holds all of them.
-template <bool MOMENTS>
-__global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
-    __shared__ float s_book[3 * 256];
+//
+// DENSE: the same walk writes, instead of the reconstructed values, the codes themselves as the
+// per-element code tensors of Sec. 4.2 (0 where pruned; two codes per byte when nbits <= 4, the
+// even element in the low four bits; one code per byte otherwise).
+template <bool MOMENTS, bool DENSE>
+__device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u32 ntiles) {
+    __shared__ float s_book[DENSE ? 1 : 3 * 256];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     __shared__ u32 s_cw[DEC_CODE_WORDS];
     __shared__ u32 s_cm[MOMENTS ? DEC_CODE_WORDS : 1], s_cv[MOMENTS ? DEC_CODE_WORDS : 1];
@@ -172,14 +197,15 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
         const u64 base = (u64)ltile * EXCP_TILE;
         const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;   // elements of this tile
         const unsigned char *blob = D.blob;
-        const bool has_w = D.W_out != nullptr;
-        const bool has_m = MOMENTS && D.m_out != nullptr, has_v = MOMENTS && D.v_out != nullptr;
+        const bool has_w = DENSE ? D.cw != nullptr : D.W_out != nullptr;
+        const bool has_m = MOMENTS && (DENSE ? D.cm != nullptr : D.m_out != nullptr);
+        const bool has_v = MOMENTS && (DENSE ? D.cv != nullptr : D.v_out != nullptr);
         const bool moments = has_m || has_v;
         if (!has_w && !moments) continue;                  // nothing to write for this one
 
         // previous weights of the lane's 4 x 4 elements: issued first, consumed last
         float wp[4][4];
-        if (has_w) {
+        if (!DENSE && has_w) {
             const EXCP_GLOBAL float *Wp = gptr(D.Wp) + base;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -224,7 +250,7 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
         }
 
         __syncthreads();                                   // the previous tile's LDS readers are done
-        if (t != cur_t) {
+        if (!DENSE && t != cur_t) {
             const EXCP_GLOBAL float *books = gptr((const float *)(blob + EXCP_HEADER));
             for (u32 i = tid; i < 3u * E; i += EXCP_THREADS) s_book[(i / E) * 256u + (i % E)] = books[i];
             cur_t = t;
@@ -270,7 +296,18 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
             const u32 nib = (u32)(word >> sub) & 15u;
             const u32 r = wex + __popcll(word & ((1ull << sub) - 1ull));   // tile rank of the lane's first survivor
             u32 f = window32(s_cw, woff + r * nbits);
-            if (has_w) {
+            if (DENSE) {
+                if (has_w) {
+                    u32 c[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const bool kept = (nib >> j) & 1u;
+                        c[j] = kept ? (f & cmask) : 0u;
+                        f = kept ? (f >> nbits) : f;
+                    }
+                    store_codes4(D.cw, base + off, rem - min(rem, off), nbits, c);
+                }
+            } else if (has_w) {
                 float out[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -295,6 +332,22 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
                 const u32 orank = s_oex[bi] + __popc(s_ow[bi] & ((1u << bsh) - 1u));
                 u32 fm = window32(s_cm, moff + orank * nbits);
                 u32 fv = window32(s_cv, moff + orank * nbits);
+                if (DENSE) {
+                    u32 cm4[4], cv4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const bool kept = (nib >> j) & 1u;
+                        const bool ko = kept && (obits & 1u);
+                        cm4[j] = ko ? (fm & cmask) : 0u;
+                        cv4[j] = ko ? (fv & cmask) : 0u;
+                        obits = kept ? (obits >> 1) : obits;
+                        fm = ko ? (fm >> nbits) : fm;
+                        fv = ko ? (fv >> nbits) : fv;
+                    }
+                    if (has_m) store_codes4(D.cm, base + off, rem - min(rem, off), nbits, cm4);
+                    if (has_v) store_codes4(D.cv, base + off, rem - min(rem, off), nbits, cv4);
+                    continue;
+                }
                 float om[4], ov[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -322,6 +375,15 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u3
             }
         }
     }
+}
+
+template <bool MOMENTS>
+__global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
+    decode_tiles<MOMENTS, false>(w, ntensors, ntiles);
+}
+template <bool MOMENTS>
+__global__ __launch_bounds__(EXCP_THREADS, 8) void k_export_dense(Workspace w, u32 ntensors, u32 ntiles) {
+    decode_tiles<MOMENTS, true>(w, ntensors, ntiles);
 }
 
 // Alg. 3: W_0 plus a chain of compressed checkpoints, oldest first, in ONE pass over the weights.
@@ -451,6 +513,132 @@ __global__ void k_decode_finish(Workspace w, u32 ntensors, u32 rec_base) {
     R.status = S.status; R.pad = 0;
 }
 
+// Export: header and codebooks of every well-formed blob, verbatim (one workgroup per tensor).
+__global__ void k_export_head(Workspace w, u32 ntensors) {
+    const u32 t = blockIdx.x;
+    const DDesc &D = w.ddesc[t];
+    const DState &S = w.dst[t];
+    if (S.status != 0 || D.head == nullptr) return;
+    const u32 words = (EXCP_HEADER + 12u * (1u << S.nbits)) / 4u;
+    const EXCP_GLOBAL u32 *src = gptr((const u32 *)D.blob);
+    EXCP_GLOBAL u32 *dst = gptr((u32 *)D.head);
+    for (u32 i = threadIdx.x; i < words; i += blockDim.x) dst[i] = src[i];
+}
+
+// Reconstruction from the per-element code tensors: here `blob` holds only header and codebooks.
+__global__ void k_dense_parse(Workspace w, u32 ntensors) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= ntensors) return;
+    const DDesc &D = w.ddesc[t];
+    DState &S = w.dst[t];
+    S.status = 0; S.pop_w = 0; S.pop_o = 0;
+    S.n_w = 0; S.n_o = 0; S.nbits = 4; S.blob_bytes = 0;
+    if (D.blob_bytes < EXCP_HEADER) { S.status = -4; return; }
+    const u32 *h = (const u32 *)D.blob;
+    const u64 *h64 = (const u64 *)D.blob;
+    const u32 nbits = h[2];
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 4u;
+    ok = ok && h64[2] == D.n && D.blob_bytes >= EXCP_HEADER + 12ull * (1u << (nbits & 15u));
+    if (!ok) { S.status = -4; return; }
+    S.n_w = h64[3]; S.n_o = h64[4]; S.nbits = nbits; S.blob_bytes = h64[8];
+}
+
+// Eight consecutive elements per lane and step: one 32-bit (or 64-bit) load of codes per tensor,
+// two 16-byte loads of the previous weights, two 16-byte stores per output.  Code 0 leaves the
+// weight untouched (not "+ 0.0": a negative zero stays) and gives a zero moment.  A code beyond the
+// codebook, or a set unused half of the last byte, marks the tensor as damaged.
+__global__ __launch_bounds__(EXCP_THREADS) void k_decode_dense(Workspace w, u32 ntensors, u32 ntiles) {
+    __shared__ float s_book[3 * 256];
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    const u32 tid = threadIdx.x;
+    u32 cur_t = 0xffffffffu;
+    load_tile_table(s_tiles, w.tile_begin, ntensors);
+    for (u32 tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const u32 t = find_owner(s_tiles, ntensors, tile);
+        const DDesc &D = w.ddesc[t];
+        DState &S = w.dst[t];
+        if (S.status != 0 && S.status != -40) continue;    // -40: damage found by another workgroup meanwhile
+        const u32 nbits = S.nbits, E = 1u << nbits;
+        const bool wide = nbits > 4u;
+        const u64 n = D.n;
+        const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
+        const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
+        if (t != cur_t) {
+            __syncthreads();
+            const EXCP_GLOBAL float *books = gptr((const float *)(D.blob + EXCP_HEADER));
+            for (u32 i = tid; i < 3u * E; i += EXCP_THREADS) s_book[(i / E) * 256u + (i % E)] = books[i];
+            cur_t = t;
+            __syncthreads();
+        }
+        bool bad = false;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const u32 off = (u32)k * 2048u + tid * 8u;
+            if (off >= rem) continue;
+            const u32 left = min(8u, rem - off);
+            const u64 e0 = base + off;
+            const unsigned char *src[3] = {D.cw, D.cm, D.cv};
+            float *dst[3] = {D.W_out, D.m_out, D.v_out};
+#pragma unroll
+            for (int q = 0; q < 3; ++q) {
+                if (dst[q] == nullptr) continue;
+                // the eight codes, one byte each
+                u64 c8 = 0;
+                if (wide) {
+                    const EXCP_GLOBAL unsigned char *p = gptr(src[q]) + e0;
+                    if (left == 8u) c8 = *(const EXCP_GLOBAL u64 *)p;
+                    else for (u32 j = 0; j < left; ++j) c8 |= (u64)p[j] << (8u * j);
+                } else {
+                    const EXCP_GLOBAL unsigned char *p = gptr(src[q]) + (e0 >> 1);
+                    u32 c4 = 0;
+                    if (left == 8u) c4 = *(const EXCP_GLOBAL u32 *)p;
+                    else {
+                        for (u32 j = 0; j < (left + 1u) / 2u; ++j) c4 |= (u32)p[j] << (8u * j);
+                        if ((left & 1u) && (c4 >> (4u * left))) bad = true;      // the unused half of the last byte
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) c8 |= (u64)((c4 >> (4 * j)) & 15u) << (8 * j);
+                }
+                float x[8];
+                EXCP_GLOBAL float *out = gptr(dst[q]) + e0;
+                if (q == 0) {
+                    const EXCP_GLOBAL float *Wp = gptr(D.Wp) + e0;
+                    if (left == 8u) {
+                        const f4u a = *(const EXCP_GLOBAL f4u *)Wp, b = *(const EXCP_GLOBAL f4u *)(Wp + 4);
+                        x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) x[j] = ((u32)j < left) ? Wp[j] : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const u32 c = (u32)(c8 >> (8 * j)) & 255u;
+                    if (c >= E) bad = true;
+                    const float centre = s_book[(u32)q * 256u + (c & (E - 1u))];
+                    if (q == 0) x[j] = c ? x[j] + centre : x[j];
+                    else x[j] = c ? centre : 0.f;
+                }
+                if (left == 8u) {
+                    f4u a, b;
+                    a.x = x[0]; a.y = x[1]; a.z = x[2]; a.w = x[3]; b.x = x[4]; b.y = x[5]; b.z = x[6]; b.w = x[7];
+                    *(EXCP_GLOBAL f4u *)out = a; *(EXCP_GLOBAL f4u *)(out + 4) = b;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) if ((u32)j < left) out[j] = x[j];
+                }
+            }
+        }
+        if (bad) S.status = -40;
+    }
+}
+
+// -40 (damage seen while decoding) becomes the public "damaged blob" status.
+__global__ void k_dense_status(Workspace w, u32 ntensors) {
+    const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < ntensors && w.dst[t].status == -40) w.dst[t].status = -4;
+}
+
 // Decode state for a blob the compress path has just written (no header parsing needed).
 __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -461,6 +649,7 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     DState &S = w.dst[t];
     D.Wp = C.Wp; D.blob = C.blob; D.blob_bytes = T.blob_bytes; D.n = C.n;
     D.W_out = C.W_out; D.m_out = nullptr; D.v_out = nullptr;
+    D.cw = nullptr; D.cm = nullptr; D.cv = nullptr; D.head = nullptr;
     D.tile_begin = C.tile_begin; D.tile_count = C.tile_count;
     S.n_w = T.n_w; S.n_o = T.n_o; S.blob_bytes = T.blob_bytes; S.nbits = (u32)g.nbits;
     S.off_bw = EXCP_HEADER + 12ull * (1u << g.nbits);
@@ -505,6 +694,28 @@ void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool momen
     if (blocks > ntiles) blocks = ntiles;
     if (moments) hipLaunchKernelGGL(k_decode_main<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
     else hipLaunchKernelGGL(k_decode_main<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+}
+void launch_export_dense(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
+    if (!ntensors) return;
+    hipLaunchKernelGGL(k_export_head, dim3(ntensors), dim3(EXCP_THREADS), 0, s, w, ntensors);
+    if (!ntiles) return;
+    u32 blocks = excp_grid(w, 64);
+    if (blocks > ntiles) blocks = ntiles;
+    if (moments) hipLaunchKernelGGL(k_export_dense<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    else hipLaunchKernelGGL(k_export_dense<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+}
+void launch_dense_parse(const Workspace &w, u32 ntensors, hipStream_t s) {
+    if (!ntensors) return;
+    hipLaunchKernelGGL(k_dense_parse, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors);
+}
+void launch_decode_dense(const Workspace &w, u32 ntensors, u32 ntiles, hipStream_t s) {
+    if (!ntensors) return;
+    if (ntiles) {
+        u32 blocks = excp_grid(w, 32);
+        if (blocks > ntiles) blocks = ntiles;
+        hipLaunchKernelGGL(k_decode_dense, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    }
+    hipLaunchKernelGGL(k_dense_status, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors);
 }
 void launch_decode_finish(const Workspace &w, u32 ntensors, hipStream_t s) {
     if (!ntensors) return;
