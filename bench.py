@@ -250,6 +250,32 @@ def main():
     torch.cuda.synchronize()
     dec3_ms = (time.perf_counter() - t3) * 1e3 / max(1, args.steps)
 
+    # ---- the stored layout of Sec. 4.2: export of the per-element code tensors, and Alg. 2 from them ----
+    hb = X.excp_head_bytes(nbits)
+    doffs, dtot = [], 0
+    for spec in cfg.tensors:
+        doffs.append(dtot)
+        dtot += (X.excp_dense_bytes(spec.n, nbits) + 15) & ~15
+    dense = [torch.empty(max(dtot, 16), dtype=torch.uint8, device=dev) for _ in range(3)]
+    heads = torch.empty((len(cfg.tensors), (hb + 15) & ~15), dtype=torch.uint8, device=dev)
+    dslice = lambda k, i: dense[k][doffs[i]:doffs[i] + X.excp_dense_bytes(cfg.tensors[i].n, nbits)]
+    exp = [(tensors[i][4], int(stats[i].blob_bytes), spec.n, heads[i], dslice(0, i), dslice(1, i), dslice(2, i))
+           for i, spec in enumerate(cfg.tensors)]
+    imp = [(flat[0][offs[i]:offs[i] + spec.n], heads[i], hb, spec.n, dslice(0, i), dslice(1, i), dslice(2, i),
+            flat[4][offs[i]:offs[i] + spec.n], flat[2][offs[i]:offs[i] + spec.n], flat[3][offs[i]:offs[i] + spec.n])
+           for i, spec in enumerate(cfg.tensors)]
+    dense_ms = {}
+    for name, call, arg in (("export", ctx.excp_export_dense, exp), ("decompress", ctx.excp_decompress_dense, imp)):
+        call(arg); ctx.excp_collect()
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        for _ in range(max(1, args.steps)):
+            call(arg)
+            ctx.excp_collect()
+        torch.cuda.synchronize()
+        dense_ms[name] = (time.perf_counter() - t5) * 1e3 / max(1, args.steps)
+    dense_bytes_total = len(cfg.tensors) * hb + 3 * sum(X.excp_dense_bytes(spec.n, nbits) for spec in cfg.tensors)
+
     out = {
         "metric": "checkpoint params compressed/sec and % of HBM roofline, 7B-shaped step",
         "value": params_per_s, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -267,6 +293,8 @@ def main():
         "decompress_ms": dec_ms, "decompress_params_per_s": N / (dec_ms * 1e-3),
         "decompress_with_moments_ms": dec3_ms,
         "reconstruct_chain_ms": {"checkpoints": chain_len, "ms": chain_ms, "one_by_one_ms": chain_len * dec_ms},
+        "dense_layout": {"bytes": dense_bytes_total, "ratio": 12.0 * N / dense_bytes_total,
+                         "export_ms": dense_ms["export"], "decompress_with_moments_ms": dense_ms["decompress"]},
         "workspace_GB": ctx.workspace_bytes / 1e9,
         "roofline": roofline,
         "cpu_baseline": cpu,

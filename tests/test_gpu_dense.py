@@ -200,3 +200,21 @@ def test_damage_and_argument_errors(ctx):
         ctx.excp_decompress_dense([(to_dev(Wps[0]), b[0], hb, n, None, None, None, Wout, None, None)])
     with pytest.raises(X.ExcpError):
         ctx.excp_decompress_dense([(to_dev(Wps[0]), b[0], hb, n, b[1], None, None, None, Wout, None)])
+
+
+@pytest.mark.parametrize("layout", ["dense", "blob"])
+def test_archive_round_trip_through_the_gpu(ctx, layout):
+    from paper_2406_11257_amd import archive as A
+    sizes = [0, 5, 4097, 250001]
+    cases = [case(n, 900 + i) for i, n in enumerate(sizes)]
+    rc, outs = gpu_compress(ctx, cases, 5e-5, 2.0, 4, 3)
+    assert rc == 0
+    named = [(f"t{i}", o["blob_dev"], int(o["stats"].blob_bytes), n) for i, (o, n) in enumerate(zip(outs, sizes))]
+    data = A.save_checkpoint(ctx, named, 4, layout=layout, preset=6, threads=4)
+    assert len(data) < 12 * sum(sizes) / 8                  # far below the fp32 state it stands for
+    back = A.load_checkpoint(ctx, data, {f"t{i}": to_dev(c[0]) for i, c in enumerate(cases)}, threads=4)
+    for i, (c, o) in enumerate(zip(cases, outs)):
+        W, m, v = back[f"t{i}"]
+        ref = O.decompress_step(c[0], o["blob"])
+        assert W.cpu().numpy().tobytes() == ref[0].tobytes() == o["W_recon"].tobytes()
+        assert m.cpu().numpy().tobytes() == ref[1].tobytes() and v.cpu().numpy().tobytes() == ref[2].tobytes()
