@@ -36,7 +36,8 @@ from dataclasses import dataclass, field
 import numpy as np
 
 __all__ = [
-    "MAGIC", "VERSION", "HEADER_BYTES", "FLAG_MEDIAN_OF_WEIGHTS", "FLAG_NO_M2W",
+    "MAGIC", "VERSION", "HEADER_BYTES", "FLAG_MEDIAN_OF_WEIGHTS", "FLAG_NO_M2W", "FLAG_NO_QUANT", "FLAG_NO_W2M",
+    "RAW_BITS",
     "residual", "lower_median_abs", "exact_mean_abs", "weight_mask",
     "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
     "pack_bitmap", "pack_codes", "unpack_bitmap", "unpack_codes",
@@ -47,6 +48,9 @@ __all__ = [
 
 FLAG_MEDIAN_OF_WEIGHTS = 1
 FLAG_NO_M2W = 2
+FLAG_NO_QUANT = 4           # Table "abl", "prune" without "quant": the survivors are stored as they are (fp32)
+FLAG_NO_W2M = 8             # Table "vit", no weights-to-momentum check: M_o does not depend on M_w
+RAW_BITS = 32               # the "code" width written into the header of a blob without quantisation
 MAGIC = 0x50435845          # bytes "EXCP" read as a little-endian u32
 VERSION = 1
 HEADER_BYTES = 80
@@ -248,11 +252,12 @@ def _pad16(nbytes: int) -> int:
     return (nbytes + 15) // 16 * 16
 
 
-def blob_size(n: int, n_w: int, n_o: int, nbits: int) -> int:
-    """Closed-form size of one compressed tensor (bytes)."""
-    size = HEADER_BYTES + 3 * 4 * (1 << nbits)
+def blob_size(n: int, n_w: int, n_o: int, nbits: int, flags: int = 0) -> int:
+    """Closed-form size of one compressed tensor (bytes).  nbits = RAW_BITS: no codebooks, fp32 values
+    in place of codes; FLAG_NO_W2M: the second bitmap covers all n elements, not the n_w survivors."""
+    size = HEADER_BYTES + (0 if nbits == RAW_BITS else 3 * 4 * (1 << nbits))
     size += _pad16(8 * ((n + 63) // 64))
-    size += _pad16(8 * ((n_w + 63) // 64))
+    size += _pad16(8 * (((n if flags & FLAG_NO_W2M else n_w) + 63) // 64))
     size += _pad16(8 * ((n_w * nbits + 63) // 64))
     size += 2 * _pad16(8 * ((n_o * nbits + 63) // 64))
     return size
@@ -267,7 +272,8 @@ def build_blob(*, n, nbits, flags, iters, alpha, beta, med, mean32, t_w, r_o,
                Cw, Cm, Cv, Mw, Mo_over_survivors, codes_w, codes_m, codes_v) -> bytes:
     n_w = int(Mw.sum())
     n_o = int(Mo_over_survivors.sum())
-    total = blob_size(n, n_w, n_o, nbits)
+    assert Mo_over_survivors.size == (n if flags & FLAG_NO_W2M else n_w)
+    total = blob_size(n, n_w, n_o, nbits, flags)
     head = struct.pack("<IIIIQQQffffffQII",
                        MAGIC, VERSION, nbits, flags, n, n_w, n_o,
                        float(f32(alpha)), float(f32(beta)), float(med), float(mean32),
@@ -275,6 +281,8 @@ def build_blob(*, n, nbits, flags, iters, alpha, beta, med, mean32, t_w, r_o,
     assert len(head) == HEADER_BYTES
     parts = [head]
     for C in (Cw, Cm, Cv):
+        if nbits == RAW_BITS:
+            break                                            # nothing is quantised: no codebooks
         book = np.concatenate([np.zeros(1, dtype=f32), C.astype(f32)])
         parts.append(book.astype("<f4").tobytes())
     parts.append(_section(pack_bitmap(Mw)))
@@ -296,17 +304,18 @@ def parse_blob(blob: bytes, n_expected: int | None = None) -> dict:
         raise BlobError("bad magic")
     if version != VERSION:
         raise BlobError("bad version")
-    if not 2 <= nbits <= 8:
-        raise BlobError("nbits out of range")
-    if flags > 3:
+    if flags > 15:
         raise BlobError("unknown flags")
+    if not (2 <= nbits <= 8 or (nbits == RAW_BITS and flags & FLAG_NO_QUANT)) or \
+            (nbits != RAW_BITS and flags & FLAG_NO_QUANT):
+        raise BlobError("nbits out of range")
     if n_expected is not None and n != n_expected:
         raise BlobError("element count mismatch")
-    if not (n_o <= n_w <= n):
+    if not (n_w <= n and n_o <= (n if flags & FLAG_NO_W2M else n_w)):
         raise BlobError("inconsistent counts")
-    if total != blob_size(n, n_w, n_o, nbits) or len(blob) < total:
+    if total != blob_size(n, n_w, n_o, nbits, flags) or len(blob) < total:
         raise BlobError("inconsistent size")
-    E = 1 << nbits
+    E = 0 if nbits == RAW_BITS else 1 << nbits
     off = HEADER_BYTES
     books = []
     for _ in range(3):
@@ -320,7 +329,7 @@ def parse_blob(blob: bytes, n_expected: int | None = None) -> dict:
         return arr
 
     bw = take((n + 63) // 64)
-    bo = take((n_w + 63) // 64)
+    bo = take(((n if flags & FLAG_NO_W2M else n_w) + 63) // 64)
     cw = take((n_w * nbits + 63) // 64)
     cm = take((n_o * nbits + 63) // 64)
     cv = take((n_o * nbits + 63) // 64)
@@ -368,7 +377,9 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
     v = np.ascontiguousarray(v, dtype=f32).ravel()
     n = W.size
     assert W_prev.size == n and m.size == n and v.size == n
-    assert 2 <= nbits <= 8 and iters >= 0 and 0 <= flags <= 3
+    assert 2 <= nbits <= 8 and iters >= 0 and 0 <= flags <= 15
+    raw = bool(flags & FLAG_NO_QUANT)
+    stored_bits = RAW_BITS if raw else nbits
     for arr in (W_prev, W, m, v):
         if not np.all(np.isfinite(arr)):
             raise NonFiniteError("NaN or Inf in an input")
@@ -379,7 +390,7 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
         zb = np.zeros(0, dtype=bool)
         zc = np.zeros(0, dtype=np.int64)
         C0 = np.zeros(K, dtype=f32)
-        blob = build_blob(n=0, nbits=nbits, flags=flags, iters=iters, alpha=alpha, beta=beta,
+        blob = build_blob(n=0, nbits=stored_bits, flags=flags, iters=iters, alpha=alpha, beta=beta,
                           med=f32(0), mean32=f32(0), t_w=f32(0), r_o=f32(0),
                           Cw=C0, Cm=C0, Cv=C0, Mw=zb, Mo_over_survivors=zb,
                           codes_w=zc, codes_m=zc, codes_v=zc)
@@ -396,26 +407,37 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
     med = lower_median_abs(W if flags & FLAG_MEDIAN_OF_WEIGHTS else d)      # Eq. r_w
     S, mean32 = exact_mean_abs(m)                             # Eq. r_o
     Mw, t_w = weight_mask(d, v, alpha, med, use_moment=not (flags & FLAG_NO_M2W))   # Eq. r_w
-    Mo, r_o = momentum_mask(m, Mw, beta, mean32)              # Eq. r_o
+    # bit 3: without the weights-to-momentum check the moment mask of Eq. r_o stands on its own
+    w2m = not (flags & FLAG_NO_W2M)
+    Mo, r_o = momentum_mask(m, Mw if w2m else np.ones(n, dtype=bool), beta, mean32)   # Eq. r_o
     xw, xm, xv = d[Mw], m[Mo], v[Mo]                          # survivors, index order
 
     C, A, O = {}, {}, {}
+    stored = {}
     for name, x in (("w", xw), ("m", xm), ("v", xv)):         # Alg. 1 steps 3-4
-        C[name], A[name] = lloyd(x, K, iters)
-        O[name] = objective(x, C[name], A[name])
+        if raw:                                               # bit 2: no quantisation, the values themselves
+            C[name], A[name], O[name] = np.zeros(0, dtype=f32), None, 0.0
+            stored[name] = x.copy()
+            codes = x.view(np.uint32).astype(np.int64)
+        else:
+            C[name], A[name] = lloyd(x, K, iters)
+            O[name] = objective(x, C[name], A[name])
+            stored[name] = C[name][A[name]]
+            codes = A[name] + 1
+        stored[name + "_codes"] = codes
 
-    blob = build_blob(n=n, nbits=nbits, flags=flags, iters=iters, alpha=alpha, beta=beta,
+    blob = build_blob(n=n, nbits=stored_bits, flags=flags, iters=iters, alpha=alpha, beta=beta,
                       med=med, mean32=mean32, t_w=t_w, r_o=r_o,
-                      Cw=C["w"], Cm=C["m"], Cv=C["v"], Mw=Mw, Mo_over_survivors=Mo[Mw],
-                      codes_w=A["w"] + 1, codes_m=A["m"] + 1, codes_v=A["v"] + 1)
+                      Cw=C["w"], Cm=C["m"], Cv=C["v"], Mw=Mw, Mo_over_survivors=Mo[Mw] if w2m else Mo,
+                      codes_w=stored["w_codes"], codes_m=stored["m_codes"], codes_v=stored["v_codes"])
 
     # Alg. 2 applied to what was just stored (the copy kept for the next step).
     W_rec = W_prev.copy()
-    W_rec[Mw] = (W_prev[Mw] + C["w"][A["w"]]).astype(f32)
+    W_rec[Mw] = (W_prev[Mw] + stored["w"]).astype(f32)
     m_rec = np.zeros(n, dtype=f32)
     v_rec = np.zeros(n, dtype=f32)
-    m_rec[Mo] = C["m"][A["m"]]
-    v_rec[Mo] = C["v"][A["v"]]
+    m_rec[Mo] = stored["m"]
+    v_rec[Mo] = stored["v"]
     return CompressResult(blob, W_rec, m_rec, v_rec, n, int(Mw.sum()), int(Mo.sum()),
                           med, S, mean32, t_w, r_o, Mw, Mo, C, A, O,
                           dict(w=xw, m=xm, v=xv))
@@ -428,22 +450,37 @@ def decompress_step(W_prev, blob: bytes):
     W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
     p = parse_blob(blob, n_expected=W_prev.size)
     n, n_w, n_o, nbits = p["n"], p["n_w"], p["n_o"], p["nbits"]
-    Mw = unpack_bitmap(p["bitmap_w"], n)
-    Mo_s = unpack_bitmap(p["bitmap_o"], n_w)
-    if int(Mw.sum()) != n_w or int(Mo_s.sum()) != n_o:
-        raise BlobError("bitmap population does not match the header")
-    cw = unpack_codes(p["codes_w"], n_w, nbits)
-    cm = unpack_codes(p["codes_m"], n_o, nbits)
-    cv = unpack_codes(p["codes_v"], n_o, nbits)
+    idx_w, idx_o = _kept_indices(p)
+    vals = []
+    for key, count in (("w", n_w), ("m", n_o), ("v", n_o)):
+        c = unpack_codes(p["codes_" + key], count, nbits)
+        if nbits == RAW_BITS:
+            vals.append(c.astype(np.uint32).view(f32))              # stored as they were
+        else:
+            vals.append(p["book_" + key][c])                        # Alg. 2 steps 2-3: codebook look-up
     W_rec = W_prev.copy()
-    idx_w = np.flatnonzero(Mw)
-    W_rec[idx_w] = (W_prev[idx_w] + p["book_w"][cw]).astype(f32)   # Alg. 2 steps 2 and 4
-    idx_o = idx_w[Mo_s]
+    W_rec[idx_w] = (W_prev[idx_w] + vals[0]).astype(f32)            # Alg. 2 step 4
     m_rec = np.zeros(n, dtype=f32)
     v_rec = np.zeros(n, dtype=f32)
-    m_rec[idx_o] = p["book_m"][cm]                                  # Alg. 2 step 3
-    v_rec[idx_o] = p["book_v"][cv]
+    m_rec[idx_o] = vals[1]
+    v_rec[idx_o] = vals[2]
     return W_rec, m_rec, v_rec
+
+
+def _kept_indices(p: dict):
+    """Element indices of the kept residuals and of the kept moment pairs of a parsed blob."""
+    n, n_w, n_o = p["n"], p["n_w"], p["n_o"]
+    Mw = unpack_bitmap(p["bitmap_w"], n)
+    idx_w = np.flatnonzero(Mw)
+    if p["flags"] & FLAG_NO_W2M:
+        Mo = unpack_bitmap(p["bitmap_o"], n)                        # over all elements
+        idx_o = np.flatnonzero(Mo)
+    else:
+        Mo = unpack_bitmap(p["bitmap_o"], n_w)                      # over the kept residuals
+        idx_o = idx_w[Mo[:idx_w.size]] if idx_w.size == n_w else idx_w[:0]
+    if idx_w.size != n_w or int(Mo.sum()) != n_o:
+        raise BlobError("bitmap population does not match the header")
+    return idx_w, idx_o
 
 
 def reconstruct_chain(W0, blobs):
@@ -500,12 +537,9 @@ def export_dense(blob: bytes):
     """Blob -> (head, codes_w, codes_m, codes_v): the per-element code tensors of Sec. 4.2."""
     p = parse_blob(blob)
     n, n_w, n_o, nbits = p["n"], p["n_w"], p["n_o"], p["nbits"]
-    Mw = unpack_bitmap(p["bitmap_w"], n)
-    Mo_s = unpack_bitmap(p["bitmap_o"], n_w)
-    if int(Mw.sum()) != n_w or int(Mo_s.sum()) != n_o:
-        raise BlobError("bitmap population does not match the header")
-    idx_w = np.flatnonzero(Mw)
-    idx_o = idx_w[Mo_s]
+    if nbits == RAW_BITS:
+        raise BlobError("a blob without quantisation has no codes to export")
+    idx_w, idx_o = _kept_indices(p)
     per_element = []
     for idx, words, count in ((idx_w, p["codes_w"], n_w), (idx_o, p["codes_m"], n_o), (idx_o, p["codes_v"], n_o)):
         e = np.zeros(n, dtype=np.int64)                      # pruned elements keep code 0
@@ -522,7 +556,7 @@ def decompress_dense(W_prev, head: bytes, codes_w, codes_m, codes_v):
     if len(head) < HEADER_BYTES:
         raise BlobError("shorter than a header")
     magic, version, nbits, flags, n_stored = struct.unpack("<IIIIQ", head[:24])
-    if magic != MAGIC or version != VERSION or not 2 <= nbits <= 8 or flags > 3 or n_stored != n:
+    if magic != MAGIC or version != VERSION or not 2 <= nbits <= 8 or flags > 15 or n_stored != n:
         raise BlobError("bad header")
     if len(head) < head_bytes(nbits):
         raise BlobError("codebooks missing")

@@ -627,3 +627,110 @@ def test_dense_layout_rejects_damage_and_keeps_minus_zero():
         O.decompress_dense(Wp, head, odd, cm, cv)
     with pytest.raises(O.BlobError):
         O.decompress_dense(Wp, b"XXXX" + head[4:], cw, cm, cv)
+
+
+# ---------------------------------------------------------------- the remaining ablation modes
+def test_prune_only_mode_stores_the_survivors_themselves():
+    # Table "abl", prune without quant: same masks, fp32 values in place of codes, no codebooks
+    Wp, W, m, v = small_case(3001, seed=21)
+    base = O.compress_step(Wp, W, m, v, alpha=5e-5, nbits=4, iters=3)
+    r = O.compress_step(Wp, W, m, v, alpha=5e-5, nbits=4, iters=3, flags=O.FLAG_NO_QUANT)
+    assert np.array_equal(r.Mw, base.Mw) and np.array_equal(r.Mo, base.Mo)
+    d = (W - Wp).astype(f32)
+    # reconstruction: previous weights plus the residual itself, one fp32 rounding; moments exact
+    want = Wp.copy()
+    for i in np.flatnonzero(r.Mw):
+        want[i] = f32(Wp[i] + d[i])
+    assert r.W_recon.tobytes() == want.tobytes()
+    assert np.array_equal(r.m_recon, np.where(r.Mo, m, 0)) and np.array_equal(r.v_recon, np.where(r.Mo, v, 0))
+    assert np.max(np.abs(r.W_recon[r.Mw].astype(np.float64) - W[r.Mw])) <= 2.0 ** -24 * np.max(np.abs(W)) * 2
+    # bytes: header, no codebooks, two bitmaps, then the three value streams as little-endian fp32
+    n, nw, no = 3001, r.n_w, r.n_o
+    pad = lambda b: (b + 15) // 16 * 16
+    off = 80 + pad(8 * ((n + 63) // 64)) + pad(8 * ((nw + 63) // 64))
+    assert struct.unpack("<I", r.blob[8:12])[0] == 32 and struct.unpack("<I", r.blob[12:16])[0] == 4
+    assert r.blob[off:off + 4 * nw] == d[r.Mw].astype("<f4").tobytes()
+    off += pad(8 * ((32 * nw + 63) // 64))
+    assert r.blob[off:off + 4 * no] == m[r.Mo].astype("<f4").tobytes()
+    off += pad(8 * ((32 * no + 63) // 64))
+    assert r.blob[off:off + 4 * no] == v[r.Mo].astype("<f4").tobytes()
+    assert off + pad(8 * ((32 * no + 63) // 64)) == len(r.blob) == O.blob_size(n, nw, no, 32)
+    got = O.decompress_step(Wp, r.blob)
+    assert got[0].tobytes() == r.W_recon.tobytes() and got[1].tobytes() == r.m_recon.tobytes()
+    assert got[2].tobytes() == r.v_recon.tobytes()
+    assert len(r.blob) > 3 * len(base.blob)                  # quantisation is where most of the ratio comes from
+    with pytest.raises(O.BlobError):
+        O.export_dense(r.blob)
+    bad = bytearray(r.blob); bad[12] = 0                     # 32-bit "codes" without the flag
+    with pytest.raises(O.BlobError):
+        O.parse_blob(bytes(bad))
+    bad = bytearray(base.blob); bad[12] = 4                  # the flag with a codebook width
+    with pytest.raises(O.BlobError):
+        O.parse_blob(bytes(bad))
+
+
+def test_no_weights_to_momentum_check():
+    # Table "vit", W2M "no check": M_o(i) = [|m_i| > r_o] whatever M_w says (exact rational brute force)
+    Wp, W, m, v = small_case(2500, seed=22)
+    base = O.compress_step(Wp, W, m, v, alpha=5e-5, beta=1.0, nbits=3, iters=2)
+    r = O.compress_step(Wp, W, m, v, alpha=5e-5, beta=1.0, nbits=3, iters=2, flags=O.FLAG_NO_W2M)
+    assert r.r_o == base.r_o and np.array_equal(r.Mw, base.Mw)
+    brute = np.array([Fraction(float(abs(x))) > Fraction(float(r.r_o)) for x in m])
+    assert np.array_equal(r.Mo, brute)
+    assert np.array_equal(base.Mo, brute & base.Mw) and r.n_o > base.n_o
+    assert np.any(r.Mo & ~r.Mw)                               # moments kept where the weight is pruned
+    # the residual stream is untouched; the moment streams are the larger selections
+    assert r.C["w"].tobytes() == base.C["w"].tobytes() and np.array_equal(r.assign["w"], base.assign["w"])
+    assert np.array_equal(r.x["m"], m[brute]) and np.array_equal(r.x["v"], v[brute])
+    p = O.parse_blob(r.blob)
+    assert p["flags"] == 8 and p["bitmap_o"].size == (2500 + 63) // 64
+    assert np.array_equal(O.unpack_bitmap(p["bitmap_o"], 2500), brute)
+    assert len(r.blob) == O.blob_size(2500, r.n_w, r.n_o, 3, flags=8)
+    got = O.decompress_step(Wp, r.blob)
+    for a, b in zip(got, (r.W_recon, r.m_recon, r.v_recon)):
+        assert a.tobytes() == b.tobytes()
+    assert np.array_equal(got[1] != 0, brute & (got[1] != 0)) and np.count_nonzero(got[2]) == r.n_o
+    # the stored layout of Sec. 4.2 carries it as well
+    head, cw, cm, cv = O.export_dense(r.blob)
+    codes_m = O.dense_unpack(cm, 2500, 3)
+    assert np.array_equal(codes_m != 0, brute)
+    back = O.decompress_dense(Wp, head, cw, cm, cv)
+    for a, b in zip(back, got):
+        assert a.tobytes() == b.tobytes()
+
+
+def test_hand_built_blob_without_the_weights_to_momentum_check():
+    # the five-element example: M_w = 1 0 1 1 1; r_o = 8 keeps only |m| = 9 (index 2) with the check.
+    # Lower beta to 0.5 (r_o = 2): |m| > 2 at indices 2 and 4 -- and make index 1 (pruned weight) large.
+    Wp = np.zeros(5, f32)
+    W = np.array([1.0, 0.0, -2.0, 4.0, 8.0], f32)
+    m = np.array([1.0, 6.0, 9.0, 1.0, 8.0], f32)          # mean 5, beta 0.5 -> r_o = 2.5
+    v = np.full(5, 1e30, f32)
+    r = O.compress_step(Wp, W, m, v, alpha=1.0, beta=0.5, nbits=2, iters=0, flags=O.FLAG_NO_W2M)
+    assert list(r.Mw) == [True, False, True, True, True] and list(r.Mo) == [False, True, True, False, True]
+    p = O.parse_blob(r.blob)
+    assert (p["n_w"], p["n_o"]) == (4, 3)
+    assert int(p["bitmap_w"][0]) == 0b11101 and int(p["bitmap_o"][0]) == 0b10110
+    # K = 3 centres from [6, 9, 8] sorted [6, 8, 9]: ranks (2k+1)*3//6 = 0, 1, 2 -> 6, 8, 9; codes 1, 3, 2
+    assert list(p["book_m"]) == [0.0, 6.0, 8.0, 9.0]
+    assert int(p["codes_m"][0]) == 1 | (3 << 2) | (2 << 4)
+    Wr, mr, vr = O.decompress_step(Wp, r.blob)
+    assert list(mr) == [0, 6.0, 9.0, 0, 8.0] and Wr[1] == 0.0
+
+
+@pytest.mark.parametrize("flags", range(16))
+def test_every_combination_of_switches_round_trips(flags):
+    Wp, W, m, v = small_case(777, seed=30 + flags)
+    alpha = 0.7 if flags & O.FLAG_NO_M2W else 5e-5
+    r = O.compress_step(Wp, W, m, v, alpha=alpha, beta=1.5, nbits=4, iters=2, flags=flags)
+    p = O.parse_blob(r.blob)
+    assert p["flags"] == flags and p["nbits"] == (32 if flags & 4 else 4)
+    assert len(r.blob) == O.blob_size(777, r.n_w, r.n_o, p["nbits"], flags)
+    got = O.decompress_step(Wp, r.blob)
+    assert got[0].tobytes() == r.W_recon.tobytes() and got[1].tobytes() == r.m_recon.tobytes()
+    assert got[2].tobytes() == r.v_recon.tobytes()
+    assert np.array_equal(got[1] != 0, r.Mo & (m != 0)) or not (flags & 4)
+    if flags & 8:
+        assert np.array_equal(r.Mo, np.abs(m) > r.r_o)
+    else:
+        assert not np.any(r.Mo & ~r.Mw)
