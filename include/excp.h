@@ -33,6 +33,9 @@
  *   reconstruct: W_hat[i] = W_prev_recon[i] + C_w[code] at M_w, else
  *   W_prev_recon[i]; m_hat, v_hat = C[code] at M_o, else +0.
  *
+ * The other modes of the paper's ablation tables need no switch: without the residual (Table "abl")
+ * pass zeros as W_prev_recon; without pruning pass alpha = beta = 0 (only exact zeros are dropped).
+ *
  * Compressed tensor ("blob"), little endian, every section padded to 16 B:
  *   header (80 B): u32 magic "EXCP", u32 version=1, u32 nbits, u32 flags,
  *                  u64 n, u64 n_w, u64 n_o, f32 alpha, beta, med, mean, t_w,
@@ -84,6 +87,12 @@ extern "C" {
 /* flags of the compress calls (stored in the blob header; decompress does not need them) */
 #define EXCP_FLAG_MEDIAN_OF_WEIGHTS 1u  /* med = lower median of |W_t| instead of |d| (the other reading of Eq. "r_w") */
 #define EXCP_FLAG_NO_M2W            2u  /* ablation of Table "vit": r_i = alpha * med for every i (no 1/sqrt(v_i))   */
+#define EXCP_FLAG_NO_QUANT          4u  /* Table "abl", prune without quantisation: the survivors are stored as the
+                                           fp32 values they are.  nbits and lloyd_iters are ignored; the header says
+                                           nbits = 32, the codebook section is empty, the three code sections hold
+                                           fp32 bit patterns (32-bit "codes" in the same bit order); reconstruction
+                                           adds the residual itself.  Size and bound: pass nbits = 32 below.
+                                           Such blobs are read by excp_decompress_tensors only (no chain, no export). */
 
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 
@@ -151,7 +160,8 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream,
                 uint64_t max_tensor_elems, uint64_t max_group_elems);
 void excp_destroy(excp_ctx *ctx);
 
-/* Worst-case compressed size of an n-element tensor (every element kept). */
+/* Worst-case compressed size of an n-element tensor (every element kept).  nbits in [2,8], or 32 for
+ * EXCP_FLAG_NO_QUANT; 0 for any other nbits. */
 uint64_t excp_blob_bound(uint64_t n, int nbits);
 /* Exact compressed size for given counts (the closed form of the layout above). */
 uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits);

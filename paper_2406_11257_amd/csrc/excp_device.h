@@ -112,6 +112,9 @@ struct GroupParams {
     u32 ntensors, ntiles;
 };
 
+#define EXCP_RAW_BITS    32u       // "code" width of a blob written without quantisation: fp32 values, no codebooks
+// bytes of the three codebooks that follow the header
+static __host__ __device__ inline u64 excp_books_bytes(u32 nbits) { return nbits >= EXCP_RAW_BITS ? 0ull : 12ull << nbits; }
 static __host__ __device__ inline u64 excp_pad16(u64 b) { return (b + 15ull) & ~15ull; }
 static __host__ __device__ inline u64 excp_words(u64 bits) { return (bits + 63ull) >> 6; }
 
@@ -172,7 +175,9 @@ void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s);
-void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s);
+void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s);
+void launch_decode_raw(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
+void launch_store_raw(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which, hipStream_t s);
 void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s);
 void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);

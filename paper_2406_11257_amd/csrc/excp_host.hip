@@ -91,7 +91,7 @@ struct StageTimer {
 };
 
 u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits) {
-    u64 s = EXCP_HEADER + 12ull * (1ull << nbits);
+    u64 s = EXCP_HEADER + excp_books_bytes((u32)nbits);
     s += excp_pad16(8 * excp_words(n));
     s += excp_pad16(8 * excp_words(nw));
     s += excp_pad16(8 * excp_words(nw * (u64)nbits));
@@ -132,6 +132,7 @@ void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32
     {
         StageTimer t(c, ST_DECODE_MAIN);
         launch_decode_main(w, ntensors, ntiles, moments, c->stream);
+        launch_decode_raw(w, ntensors, ntiles, moments, c->stream);     // blobs written without quantisation, if any
     }
 }
 
@@ -172,7 +173,7 @@ int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
         w.rec_dev = c->w.rec_dev + g.first;
         w.rec_base = 0;
         if (exporting) {
-            { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, s); }
+            { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, false, s); }
             bool moments = false;
             for (u32 q = 0; q < g.count; ++q)
                 moments = moments || c->h_ddesc[g.first + q].cm != nullptr || c->h_ddesc[g.first + q].cv != nullptr;
@@ -222,12 +223,12 @@ const char *excp_strerror(int code) {
 }
 
 uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits) {
-    if (nbits < 2 || nbits > 8 || n_w > n || n_o > n_w) return 0;
+    if (((nbits < 2 || nbits > 8) && nbits != (int)EXCP_RAW_BITS) || n_w > n || n_o > n_w) return 0;
     return blob_size_host(n, n_w, n_o, nbits);
 }
 
 uint64_t excp_blob_bound(uint64_t n, int nbits) {
-    if (nbits < 2 || nbits > 8) return 0;
+    if ((nbits < 2 || nbits > 8) && nbits != (int)EXCP_RAW_BITS) return 0;
     return blob_size_host(n, n, n, nbits);
 }
 
@@ -367,19 +368,21 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (c->pending) return EXCP_E_STATE;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
 #ifdef EXCP_TUNING
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xfcu) != 0) return EXCP_E_ARG;   // tuning build only
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xf8u) != 0) return EXCP_E_ARG;   // tuning build only
 #else
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~3u) != 0) return EXCP_E_ARG;
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~7u) != 0) return EXCP_E_ARG;
 #endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
-    const int K = (1 << nbits) - 1;
+    const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0;     // survivors stored as fp32: no codebook stage at all
+    if (raw) nbits = (int)EXCP_RAW_BITS;
+    const int K = raw ? 0 : (1 << nbits) - 1;
     for (int i = 0; i < count; ++i) {
         const excp_tensor &t = tensors[i];
         if (t.n > c->max_tensor) return EXCP_E_ARG;
         if (!t.blob || ((uintptr_t)t.blob & 15u)) return EXCP_E_ARG;
         if (t.n && (!t.W_prev_recon || !t.W_t || !t.m_t || !t.v_t)) return EXCP_E_ARG;
         // the part of the blob whose place does not depend on the data must fit
-        if (t.blob_cap < EXCP_HEADER + 12ull * (1ull << nbits) + excp_pad16(8 * excp_words(t.n))) return EXCP_E_CAP;
+        if (t.blob_cap < EXCP_HEADER + excp_books_bytes((u32)nbits) + excp_pad16(8 * excp_words(t.n))) return EXCP_E_CAP;
     }
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
     const u64 cap_elems = c->max_group;
@@ -446,26 +449,32 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         { StageTimer t(c, ST_MASK_SCAN); launch_mask_compact(w, p, 1, s); }
         { StageTimer t(c, ST_MASK_GATHER); launch_mask_compact(w, p, 2, s); }
         { StageTimer t(c, ST_LAYOUT); launch_layout(w, p, s); }
-        { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
-        { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }
-        { StageTimer t(c, ST_KM_SCAN); launch_km_partition(w, p, 2, s); }
-        { StageTimer t(c, ST_KM_SCATTER); launch_km_partition(w, p, 3, s); }
-        { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }
-        { StageTimer t(c, ST_KM_INIT); launch_km_init(w, p, s); }
-        for (int it = 0; it < lloyd_iters; ++it) {
-            // classification also moves the centres by the previous iteration's totals
-            { StageTimer t(c, ST_KM_CLASSIFY); launch_km_classify(w, p, it, s); }
-            { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, it, s); }
+        if (raw) {
+            StageTimer t(c, ST_ASSIGN_PACK); launch_store_raw(w, p, s);
+        } else {
+            { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
+            { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }
+            { StageTimer t(c, ST_KM_SCAN); launch_km_partition(w, p, 2, s); }
+            { StageTimer t(c, ST_KM_SCATTER); launch_km_partition(w, p, 3, s); }
+            { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }
+            { StageTimer t(c, ST_KM_INIT); launch_km_init(w, p, s); }
+            for (int it = 0; it < lloyd_iters; ++it) {
+                // classification also moves the centres by the previous iteration's totals
+                { StageTimer t(c, ST_KM_CLASSIFY); launch_km_classify(w, p, it, s); }
+                { StageTimer t(c, ST_KM_ITER); launch_km_iter(w, p, it, s); }
+            }
+            if (lloyd_iters > 0) { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
+            { StageTimer t(c, ST_ASSIGN_PACK); launch_assign_pack(w, p, s); }
         }
-        if (lloyd_iters > 0) { StageTimer t(c, ST_KM_UPDATE); launch_km_update(w, p, s); }
-        { StageTimer t(c, ST_ASSIGN_PACK); launch_assign_pack(w, p, s); }
         { StageTimer t(c, ST_FINALIZE); launch_finalize(w, p, s); }
         bool any_out = false;
         for (u32 q = 0; q < g.count; ++q) any_out = any_out || tensors[g.first + q].W_recon_out != nullptr;
         if (any_out) {
             // (the per-tile survivor counts come from the mask pass: no bitmap counting here)
             { StageTimer t(c, ST_MISC); launch_decode_from_compress(w, p, s); }
-            { StageTimer t(c, ST_DECODE_MAIN); launch_decode_main(w, g.count, g.ntiles, false, s); }
+            StageTimer t(c, ST_DECODE_MAIN);
+            if (raw) launch_decode_raw(w, g.count, g.ntiles, false, s);
+            else launch_decode_main(w, g.count, g.ntiles, false, s);
         }
     }
     if (count) {
@@ -524,7 +533,7 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
         w.tile_begin = c->tile_begin_all + tb_offsets[gi];
         w.rec_dev = c->w.rec_dev + g.first;
         w.rec_base = 0;
-        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, s); }
+        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.count, true, s); }
         bool moments = false;
         for (u32 q = 0; q < g.count; ++q)
             moments = moments || blobs[g.first + q].m_out != nullptr || blobs[g.first + q].v_out != nullptr;
@@ -663,7 +672,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
         bool moments = false;
         for (u32 q = 0; q < g.count; ++q)
             moments = moments || chains[g.first + q].m_out != nullptr || chains[g.first + q].v_out != nullptr;
-        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.ndescs, s); }
+        { StageTimer t(c, ST_MISC); launch_decode_parse(w, g.ndescs, false, s); }
         {
             StageTimer t(c, ST_DECODE_PREP);
             launch_decode_count(w, g.ndescs, dtiles, 0, s);

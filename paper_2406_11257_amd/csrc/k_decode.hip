@@ -35,7 +35,7 @@ __device__ __forceinline__ bool wants_moments(const DDesc &D) {
 }
 
 // Validate the header of every blob and derive the section offsets.
-__global__ void k_decode_parse(Workspace w, u32 ntensors) {
+__global__ void k_decode_parse(Workspace w, u32 ntensors, u32 allow_raw) {
     const u32 t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= ntensors) return;
     const DDesc &D = w.ddesc[t];
@@ -47,11 +47,13 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors) {
     const u64 *h64 = (const u64 *)D.blob;
     const u32 nbits = h[2];
     const u64 n = h64[2], nw = h64[3], no = h64[4], total = h64[8];
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 4u;
+    const bool raw = (h[3] & 4u) != 0u;                   // written without quantisation: fp32 values, no codebooks
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && h[3] < 8u;
+    ok = ok && (raw ? (nbits == EXCP_RAW_BITS && allow_raw != 0u) : (nbits >= 2u && nbits <= 8u));
     ok = ok && n == D.n && no <= nw && nw <= n;
     u64 off = EXCP_HEADER;
     if (ok) {
-        off += 12ull * (1u << nbits);
+        off += excp_books_bytes(nbits);
         S.off_bw = off; off += excp_pad16(8ull * excp_words(n));
         S.off_bo = off; off += excp_pad16(8ull * excp_words(nw));
         S.off_cw = off; off += excp_pad16(8ull * excp_words(nw * nbits));
@@ -176,12 +178,16 @@ __device__ __forceinline__ void store_codes4(unsigned char *dst, u64 e0, u32 lef
 // DENSE: the same walk writes, instead of the reconstructed values, the codes themselves as the
 // per-element code tensors of Sec. 4.2 (0 where pruned; two codes per byte when nbits <= 4, the
 // even element in the low four bits; one code per byte otherwise).
-template <bool MOMENTS, bool DENSE>
+//
+// RAW: blobs written without quantisation hold fp32 values where the others hold codes; a lane reads
+// its survivors' values straight from the blob (consecutive lanes, consecutive addresses).  Such
+// blobs are skipped by the other instantiations, and this one skips everything else.
+template <bool MOMENTS, bool DENSE, bool RAW>
 __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u32 ntiles) {
-    __shared__ float s_book[DENSE ? 1 : 3 * 256];
+    __shared__ float s_book[DENSE || RAW ? 1 : 3 * 256];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
-    __shared__ u32 s_cw[DEC_CODE_WORDS];
-    __shared__ u32 s_cm[MOMENTS ? DEC_CODE_WORDS : 1], s_cv[MOMENTS ? DEC_CODE_WORDS : 1];
+    __shared__ u32 s_cw[RAW ? 2 : DEC_CODE_WORDS];
+    __shared__ u32 s_cm[MOMENTS && !RAW ? DEC_CODE_WORDS : 2], s_cv[MOMENTS && !RAW ? DEC_CODE_WORDS : 2];
     __shared__ u32 s_ow[MOMENTS ? DEC_OBIT_WORDS : 1], s_oex[MOMENTS ? DEC_OBIT_WORDS : 1];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     u32 cur_t = 0xffffffffu;
@@ -191,7 +197,8 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
         const DDesc &D = w.ddesc[t];
         const DState &S = w.dst[t];
         if (S.status != 0) continue;                       // same decision for the whole workgroup
-        const u32 nbits = S.nbits, E = 1u << nbits, cmask = E - 1u;
+        if ((S.nbits == EXCP_RAW_BITS) != RAW) continue;
+        const u32 nbits = S.nbits, E = RAW ? 0u : 1u << (nbits & 15u), cmask = E - 1u;
         const u64 n = D.n;
         const u32 ltile = tile - D.tile_begin;
         const u64 base = (u64)ltile * EXCP_TILE;
@@ -250,17 +257,19 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
         }
 
         __syncthreads();                                   // the previous tile's LDS readers are done
-        if (!DENSE && t != cur_t) {
+        if (!DENSE && !RAW && t != cur_t) {
             const EXCP_GLOBAL float *books = gptr((const float *)(blob + EXCP_HEADER));
             for (u32 i = tid; i < 3u * E; i += EXCP_THREADS) s_book[(i / E) * 256u + (i % E)] = books[i];
             cur_t = t;
         }
-        stage_words(s_cw, gptr((const u32 *)(blob + S.off_cw)) + (wbit0 >> 5), (woff + cnt * nbits + 31u) >> 5);
+        if (!RAW) stage_words(s_cw, gptr((const u32 *)(blob + S.off_cw)) + (wbit0 >> 5), (woff + cnt * nbits + 31u) >> 5);
         if (MOMENTS && moments) {
             const u64 mbit0 = (u64)o_tile * nbits;
             const u32 mwords = (moff + ocnt * nbits + 31u) >> 5;
-            stage_words(s_cm, gptr((const u32 *)(blob + S.off_cm)) + (mbit0 >> 5), mwords);
-            stage_words(s_cv, gptr((const u32 *)(blob + S.off_cv)) + (mbit0 >> 5), mwords);
+            if (!RAW) {
+                stage_words(s_cm, gptr((const u32 *)(blob + S.off_cm)) + (mbit0 >> 5), mwords);
+                stage_words(s_cv, gptr((const u32 *)(blob + S.off_cv)) + (mbit0 >> 5), mwords);
+            }
             if (wave == 0) {
                 // bitmap_o bits [q_tile, q_tile + cnt) as u32 words, with the count of set bits before each word
                 const EXCP_GLOBAL u32 *bo = gptr((const u32 *)(blob + S.off_bo)) + (q_tile >> 5);
@@ -295,7 +304,8 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
             const u64 word = ((u64)whi << 32) | wlo;
             const u32 nib = (u32)(word >> sub) & 15u;
             const u32 r = wex + __popcll(word & ((1ull << sub) - 1ull));   // tile rank of the lane's first survivor
-            u32 f = window32(s_cw, woff + r * nbits);
+            u32 f = RAW ? 0u : window32(s_cw, woff + r * nbits);
+            const EXCP_GLOBAL float *xw = gptr((const float *)(blob + S.off_cw)) + q_tile + r;   // RAW: the lane's first survivor
             if (DENSE) {
                 if (has_w) {
                     u32 c[4];
@@ -312,7 +322,9 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const bool kept = (nib >> j) & 1u;
-                    const float c = s_book[f & cmask];
+                    float c;
+                    if (RAW) { c = kept ? *xw : 0.f; xw += kept; }
+                    else c = s_book[f & cmask];
                     out[j] = kept ? wp[k][j] + c : wp[k][j];
                     f = kept ? (f >> nbits) : f;
                 }
@@ -330,8 +342,10 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
                 const u32 bi = bpos >> 5, bsh = bpos & 31u;
                 u32 obits = __builtin_amdgcn_alignbit(s_ow[bi + 1], s_ow[bi], bsh);
                 const u32 orank = s_oex[bi] + __popc(s_ow[bi] & ((1u << bsh) - 1u));
-                u32 fm = window32(s_cm, moff + orank * nbits);
-                u32 fv = window32(s_cv, moff + orank * nbits);
+                u32 fm = RAW ? 0u : window32(s_cm, moff + orank * nbits);
+                u32 fv = RAW ? 0u : window32(s_cv, moff + orank * nbits);
+                const EXCP_GLOBAL float *xm = gptr((const float *)(blob + S.off_cm)) + o_tile + orank;   // RAW
+                const EXCP_GLOBAL float *xv = gptr((const float *)(blob + S.off_cv)) + o_tile + orank;
                 if (DENSE) {
                     u32 cm4[4], cv4[4];
 #pragma unroll
@@ -353,8 +367,13 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
                 for (int j = 0; j < 4; ++j) {
                     const bool kept = (nib >> j) & 1u;
                     const bool ko = kept && (obits & 1u);
-                    om[j] = ko ? s_book[256u + (fm & cmask)] : 0.f;
-                    ov[j] = ko ? s_book[512u + (fv & cmask)] : 0.f;
+                    if (RAW) {
+                        om[j] = ko ? *xm : 0.f; ov[j] = ko ? *xv : 0.f;
+                        xm += ko; xv += ko;
+                    } else {
+                        om[j] = ko ? s_book[256u + (fm & cmask)] : 0.f;
+                        ov[j] = ko ? s_book[512u + (fv & cmask)] : 0.f;
+                    }
                     obits = kept ? (obits >> 1) : obits;
                     fm = ko ? (fm >> nbits) : fm;
                     fv = ko ? (fv >> nbits) : fv;
@@ -379,11 +398,25 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
-    decode_tiles<MOMENTS, false>(w, ntensors, ntiles);
+    decode_tiles<MOMENTS, false, false>(w, ntensors, ntiles);
+}
+// Blobs written without quantisation.  Most batches hold none: leave at once then.
+template <bool MOMENTS>
+__global__ __launch_bounds__(EXCP_THREADS) void k_decode_raw(Workspace w, u32 ntensors, u32 ntiles) {
+    __shared__ u32 s_any;
+    if (threadIdx.x == 0) s_any = 0u;
+    __syncthreads();
+    bool mine = false;
+    for (u32 t = threadIdx.x; t < ntensors; t += EXCP_THREADS)
+        mine = mine || (w.dst[t].status == 0 && w.dst[t].nbits == EXCP_RAW_BITS);
+    if (mine) s_any = 1u;
+    __syncthreads();
+    if (s_any == 0u) return;
+    decode_tiles<MOMENTS, false, true>(w, ntensors, ntiles);
 }
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, 8) void k_export_dense(Workspace w, u32 ntensors, u32 ntiles) {
-    decode_tiles<MOMENTS, true>(w, ntensors, ntiles);
+    decode_tiles<MOMENTS, true, false>(w, ntensors, ntiles);
 }
 
 // Alg. 3: W_0 plus a chain of compressed checkpoints, oldest first, in ONE pass over the weights.
@@ -652,7 +685,7 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     D.cw = nullptr; D.cm = nullptr; D.cv = nullptr; D.head = nullptr;
     D.tile_begin = C.tile_begin; D.tile_count = C.tile_count;
     S.n_w = T.n_w; S.n_o = T.n_o; S.blob_bytes = T.blob_bytes; S.nbits = (u32)g.nbits;
-    S.off_bw = EXCP_HEADER + 12ull * (1u << g.nbits);
+    S.off_bw = EXCP_HEADER + excp_books_bytes((u32)g.nbits);
     S.off_bo = T.off_bo; S.off_cw = T.off_cw; S.off_cm = T.off_cm; S.off_cv = T.off_cv;
     S.status = (T.status == 0 && C.W_out != nullptr) ? 0 : 1;    // 1 = skip silently
     S.pop_w = 0; S.pop_o = 0;
@@ -667,9 +700,9 @@ __global__ void k_decode_counts_from_mask(Workspace w, u32 ntiles) {
 
 }  // namespace
 
-void launch_decode_parse(const Workspace &w, u32 ntensors, hipStream_t s) {
+void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s) {
     if (!ntensors) return;
-    hipLaunchKernelGGL(k_decode_parse, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors);
+    hipLaunchKernelGGL(k_decode_parse, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors, allow_raw ? 1u : 0u);
 }
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
@@ -694,6 +727,13 @@ void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool momen
     if (blocks > ntiles) blocks = ntiles;
     if (moments) hipLaunchKernelGGL(k_decode_main<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
     else hipLaunchKernelGGL(k_decode_main<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+}
+void launch_decode_raw(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
+    if (!ntiles) return;
+    u32 blocks = excp_grid(w, 32);
+    if (blocks > ntiles) blocks = ntiles;
+    if (moments) hipLaunchKernelGGL(k_decode_raw<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    else hipLaunchKernelGGL(k_decode_raw<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
 }
 void launch_export_dense(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
     if (!ntensors) return;

@@ -936,17 +936,51 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_assign_pack(Workspace w, Gr
     }
 }
 
+// ---------------------------------------------------------------- no quantisation: the streams as they are
+// Prune-only mode (Table "abl"): every survivor stream goes into its blob section as fp32, in index
+// order; the section's padding (up to 16 bytes) is zeroed.  One chunk of 8192 values per step.
+__global__ __launch_bounds__(EXCP_THREADS) void k_store_raw(Workspace w, GroupParams g) {
+    const u32 tid = threadIdx.x;
+    const u32 total = *w.chunk_total;
+    const u32 nseg = 3u * g.ntensors;
+    for (u32 c = blockIdx.x; c < total; c += gridDim.x) {
+        const u32 sidx = find_owner(w.seg_chunk_begin, nseg, c);
+        const SegState &S = w.seg[sidx];
+        const u32 t = sidx / 3u, which = sidx % 3u;
+        const TState &T = w.st[t];
+        const u64 len = S.len;
+        const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
+        const u64 off = which == 0 ? T.off_cw : (which == 1 ? T.off_cm : T.off_cv);
+        const EXCP_GLOBAL float *src = gptr(seg_data(w, sidx)) + base;
+        EXCP_GLOBAL float *dst = gptr((float *)(w.desc[t].blob + off)) + base;
+        const u32 padded = (clen + 3u) & ~3u;              // a chunk starts on a 16-byte boundary of the section
+        for (u32 i = tid * 4u; i < padded; i += EXCP_THREADS * 4u) {
+            f4u o;
+            if (i + 4u <= clen) {
+                const f4u q = *(const EXCP_GLOBAL f4u *)(src + i);
+                o = q;
+            } else {
+                o.x = i < clen ? src[i] : 0.f; o.y = i + 1u < clen ? src[i + 1u] : 0.f;
+                o.z = i + 2u < clen ? src[i + 2u] : 0.f; o.w = 0.f;
+            }
+            *(EXCP_GLOBAL f4u *)(dst + i) = o;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- header, codebooks, results
 __global__ __launch_bounds__(EXCP_THREADS) void k_finalize(Workspace w, GroupParams g, u32 rec_base) {
     __shared__ double s_obj[3];
     const u32 t = blockIdx.x, tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const TDesc &D = w.desc[t];
     TState &T = w.st[t];
-    const u32 E = 1u << g.nbits;
+    const bool raw = (u32)g.nbits >= EXCP_RAW_BITS;          // no quantisation: no codebooks, no objective
+    const u32 E = raw ? 0u : 1u << g.nbits;
     if (wave < 3) {
         const u32 sidx = 3u * t + wave;
         double acc = 0.0;
-        if (w.seg[sidx].len) {
+        if (!raw && w.seg[sidx].len) {
             const u32 c0 = w.seg[sidx].chunk_begin, c1 = w.seg_chunk_begin[sidx + 1];
             for (u32 c = c0 + lane; c < c1; c += 64) acc += w.part_obj[c];
         }
@@ -1020,6 +1054,11 @@ void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
 
 void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s) {
     hipLaunchKernelGGL(k_assign_pack, dim3(excp_grid(w, 5)), dim3(EXCP_THREADS), 0, s, w, g);
+}
+
+void launch_store_raw(const Workspace &w, const GroupParams &g, hipStream_t s) {
+    if (!g.ntensors) return;
+    hipLaunchKernelGGL(k_store_raw, dim3(excp_grid(w, 16)), dim3(EXCP_THREADS), 0, s, w, g);
 }
 
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s) {

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
         }
         // keep bitmap of the residual: one ballot per 64 elements
         {
-            u64 *bm = (u64 *)(D.blob + EXCP_HEADER + 12ull * (1u << g.nbits));
+            u64 *bm = (u64 *)(D.blob + EXCP_HEADER + excp_books_bytes((u32)g.nbits));
             const u64 nwords = excp_words(n);
             u64 mine = 0;
 #pragma unroll
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_bitmap_o(Workspace w, Gro
         const u32 nwo = (u32)excp_words(n_w), padded = nwo + (nwo & 1u);   // section length, zero-padded to 16 bytes
         if (64u * b >= padded) continue;
         const TDesc &D = w.desc[t];
-        const u64 off_bo = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(D.n));
+        const u64 off_bo = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * excp_words(D.n));
         const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
         const u32 sb = 2u * s_tiles[t], se = 2u * s_tiles[t + 1];
         const u32 Q0 = 4096u * b;
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParam
         const TDesc &D = w.desc[t];
         if (which == 0) {
             const u64 n = D.n, nw = S.n_w, no = S.n_o, nb = (u64)g.nbits;
-            u64 off = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n));
+            u64 off = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * excp_words(n));
             S.off_bo = off; off += excp_pad16(8ull * excp_words(nw));
             S.off_cw = off; off += excp_pad16(8ull * excp_words(nw * nb));
             S.off_cm = off; off += excp_pad16(8ull * excp_words(no * nb));
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParam
         const TDesc &D = w.desc[t];
         {
             const u64 n = D.n, nw = S.n_w, no = S.n_o, nb = (u64)g.nbits;
-            u64 off = EXCP_HEADER + 12ull * (1u << g.nbits) + excp_pad16(8ull * excp_words(n));
+            u64 off = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * excp_words(n));
             off += excp_pad16(8ull * excp_words(nw)) + excp_pad16(8ull * excp_words(nw * nb)) +
                    2ull * excp_pad16(8ull * excp_words(no * nb));
             if (off > D.blob_cap || S.nonfinite) len = 0;

@@ -12,19 +12,19 @@ def to_dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def gpu_compress(ctx, cases, alpha=5e-5, beta=2.0, nbits=4, iters=10, want_recon=True, blob_cap=None):
+def gpu_compress(ctx, cases, alpha=5e-5, beta=2.0, nbits=4, iters=10, want_recon=True, blob_cap=None, flags=0):
     """cases: list of (Wp, W, m, v) numpy arrays.  Returns list of dicts (blob bytes, stats, W_recon)."""
     dev, keep = [], []
     for (Wp, W, m, v) in cases:
         n = W.size
-        cap = X.excp_blob_bound(n, nbits) if blob_cap is None else blob_cap
+        cap = X.excp_blob_bound(n, 32 if flags & 4 else nbits) if blob_cap is None else blob_cap
         blob = torch.zeros(cap + 64, dtype=torch.uint8, device="cuda")
         blob[cap:] = 0xAB                       # canary behind the capacity
         Wout = torch.full((n,), 7.0, dtype=torch.float32, device="cuda") if want_recon else None
         t = (to_dev(Wp), to_dev(W), to_dev(m), to_dev(v), blob[:cap], Wout)
         dev.append(t)
         keep.append((blob, cap))
-    ctx.excp_compress_tensors(dev, alpha, beta, nbits, iters, 0)
+    ctx.excp_compress_tensors(dev, alpha, beta, nbits, iters, flags)
     rc, stats = ctx.excp_collect(check=False)
     out = []
     for (t, (blob, cap), st) in zip(dev, keep, stats):
