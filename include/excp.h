@@ -42,7 +42,8 @@
  *                  r_o, u64 blob_bytes, u32 lloyd_iters, u32 0
  *   3 codebooks  : 2^nbits fp32 each (weights, m, v); entry 0 = +0.0
  *   bitmap_w     : ceil(n/64)   u64, bit (i & 63) of word (i >> 6) = M_w(i)
- *   bitmap_o     : ceil(n_w/64) u64 over the M_w survivors in index order
+ *   bitmap_o     : ceil(n_w/64) u64 over the M_w survivors in index order (with EXCP_FLAG_NO_W2M:
+ *                  ceil(n/64) u64 over all elements)
  *   codes_w/m/v  : nbits-wide codes, element j in bits [j*nbits, (j+1)*nbits)
  *                  of a little-endian bit stream stored as u64 words
  *
@@ -93,6 +94,9 @@ extern "C" {
                                            fp32 bit patterns (32-bit "codes" in the same bit order); reconstruction
                                            adds the residual itself.  Size and bound: pass nbits = 32 below.
                                            Such blobs are read by excp_decompress_tensors only (no chain, no export). */
+#define EXCP_FLAG_NO_W2M            8u  /* ablation of Table "vit", no weights-to-momentum check: M_o(i) = |m_i| > r_o
+                                           whether or not the weight is kept.  bitmap_o then has one bit per ELEMENT
+                                           (ceil(n/64) words) and n_o may exceed n_w; everything else is unchanged. */
 
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 
@@ -165,6 +169,9 @@ void excp_destroy(excp_ctx *ctx);
 uint64_t excp_blob_bound(uint64_t n, int nbits);
 /* Exact compressed size for given counts (the closed form of the layout above). */
 uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits);
+/* The same for a blob written with `flags` (nbits = 32 with EXCP_FLAG_NO_QUANT; the larger second
+ * bitmap with EXCP_FLAG_NO_W2M); 0 for inconsistent arguments. */
+uint64_t excp_blob_size_ex(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits, uint32_t flags);
 
 /* Alg. 1 (minus the archive step) for `count` tensors; asynchronous.  flags: 0 or EXCP_FLAG_* ORed. */
 int excp_compress_tensors(excp_ctx *ctx, int count, const excp_tensor *tensors,

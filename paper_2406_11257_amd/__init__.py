@@ -7,5 +7,5 @@ There is no CPU fallback: loading fails loudly if the library is not built.
 from .binding import (  # noqa: F401
     EXCP_OK, EXCP_E_ARG, EXCP_E_CAP, EXCP_E_NONFINITE, EXCP_E_BLOB, EXCP_E_HIP, EXCP_E_STATE,
     EXCP_E_INTERNAL, ExcpError, ExcpStats, Context, lib, lib_path,
-    excp_blob_bound, excp_blob_size, excp_dense_bytes, excp_head_bytes, excp_strerror,
+    excp_blob_bound, excp_blob_size, excp_blob_size_ex, excp_dense_bytes, excp_head_bytes, excp_strerror,
 )

@@ -59,6 +59,7 @@ SYMBOLS = {
     "excp_reconstruct_chain": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "excp_blob_bound": (C.c_uint64, [C.c_uint64, C.c_int]),
     "excp_blob_size": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int]),
+    "excp_blob_size_ex": (C.c_uint64, [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int, C.c_uint32]),
     "excp_compress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpTensor), C.c_float, C.c_float,
                                         C.c_int, C.c_int, C.c_uint32]),
     "excp_decompress_tensors": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(ExcpBlob)]),
@@ -115,6 +116,10 @@ def excp_blob_bound(n: int, nbits: int) -> int:
 
 def excp_blob_size(n: int, n_w: int, n_o: int, nbits: int) -> int:
     return int(lib().excp_blob_size(n, n_w, n_o, nbits))
+
+
+def excp_blob_size_ex(n: int, n_w: int, n_o: int, nbits: int, flags: int) -> int:
+    return int(lib().excp_blob_size_ex(n, n_w, n_o, nbits, flags))
 
 
 def excp_dense_bytes(n: int, nbits: int) -> int:

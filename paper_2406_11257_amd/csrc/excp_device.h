@@ -84,6 +84,8 @@ struct DState {
     u32 nbits;
     int status;
     u64 pop_w, pop_o;           // bitmap populations found while scanning
+    u32 flags;                  // the blob's flags (bit 3: bitmap_o covers all elements)
+    u32 pad;
 };
 
 // Host-filled description of one tensor of a chain reconstruction: its decode descriptors (one per

@@ -90,10 +90,10 @@ struct StageTimer {
     }
 };
 
-u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits) {
+u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits, u32 flags = 0) {
     u64 s = EXCP_HEADER + excp_books_bytes((u32)nbits);
     s += excp_pad16(8 * excp_words(n));
-    s += excp_pad16(8 * excp_words(nw));
+    s += excp_pad16(8 * excp_words((flags & EXCP_FLAG_NO_W2M) ? n : nw));
     s += excp_pad16(8 * excp_words(nw * (u64)nbits));
     s += 2 * excp_pad16(8 * excp_words(no * (u64)nbits));
     return s;
@@ -225,6 +225,13 @@ const char *excp_strerror(int code) {
 uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits) {
     if (((nbits < 2 || nbits > 8) && nbits != (int)EXCP_RAW_BITS) || n_w > n || n_o > n_w) return 0;
     return blob_size_host(n, n_w, n_o, nbits);
+}
+
+uint64_t excp_blob_size_ex(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits, uint32_t flags) {
+    const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0, nw2m = (flags & EXCP_FLAG_NO_W2M) != 0;
+    if (flags > 15u || (raw ? nbits != (int)EXCP_RAW_BITS : (nbits < 2 || nbits > 8))) return 0;
+    if (n_w > n || n_o > (nw2m ? n : n_w)) return 0;
+    return blob_size_host(n, n_w, n_o, nbits, flags);
 }
 
 uint64_t excp_blob_bound(uint64_t n, int nbits) {
@@ -368,9 +375,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (c->pending) return EXCP_E_STATE;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
 #ifdef EXCP_TUNING
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xf8u) != 0) return EXCP_E_ARG;   // tuning build only
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xf0u) != 0) return EXCP_E_ARG;   // tuning build only
 #else
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~7u) != 0) return EXCP_E_ARG;
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~15u) != 0) return EXCP_E_ARG;
 #endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
     const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0;     // survivors stored as fp32: no codebook stage at all

@@ -41,28 +41,29 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors, u32 allow_raw) {
     const DDesc &D = w.ddesc[t];
     DState &S = w.dst[t];
     S.status = 0; S.pop_w = 0; S.pop_o = 0;
-    S.n_w = 0; S.n_o = 0; S.nbits = 4; S.blob_bytes = 0;
+    S.n_w = 0; S.n_o = 0; S.nbits = 4; S.blob_bytes = 0; S.flags = 0; S.pad = 0;
     if (D.blob_bytes < EXCP_HEADER) { S.status = -4; return; }
     const u32 *h = (const u32 *)D.blob;
     const u64 *h64 = (const u64 *)D.blob;
     const u32 nbits = h[2];
     const u64 n = h64[2], nw = h64[3], no = h64[4], total = h64[8];
     const bool raw = (h[3] & 4u) != 0u;                   // written without quantisation: fp32 values, no codebooks
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && h[3] < 8u;
+    const bool nw2m = (h[3] & 8u) != 0u;                  // bitmap_o over all elements, not over the kept residuals
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && h[3] < 16u;
     ok = ok && (raw ? (nbits == EXCP_RAW_BITS && allow_raw != 0u) : (nbits >= 2u && nbits <= 8u));
-    ok = ok && n == D.n && no <= nw && nw <= n;
+    ok = ok && n == D.n && nw <= n && no <= (nw2m ? n : nw);
     u64 off = EXCP_HEADER;
     if (ok) {
         off += excp_books_bytes(nbits);
         S.off_bw = off; off += excp_pad16(8ull * excp_words(n));
-        S.off_bo = off; off += excp_pad16(8ull * excp_words(nw));
+        S.off_bo = off; off += excp_pad16(8ull * excp_words(nw2m ? n : nw));
         S.off_cw = off; off += excp_pad16(8ull * excp_words(nw * nbits));
         S.off_cm = off; off += excp_pad16(8ull * excp_words(no * nbits));
         S.off_cv = off; off += excp_pad16(8ull * excp_words(no * nbits));
         ok = (off == total) && (total <= D.blob_bytes);
     }
     if (!ok) { S.status = -4; return; }
-    S.n_w = nw; S.n_o = no; S.nbits = nbits; S.blob_bytes = total;
+    S.n_w = nw; S.n_o = no; S.nbits = nbits; S.blob_bytes = total; S.flags = h[3];
 }
 
 // which == 0: per-tile popcount of bitmap_w.  which == 1: per-tile popcount of the bitmap_o bits
@@ -96,6 +97,10 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_count(Workspace w, u32 
                 u64 p1 = (tile + 1 < D.tile_begin + D.tile_count) ? (u64)w.dec_cnt_w[tile + 1] : S.pop_w;
                 if (p1 > S.n_w) p1 = S.n_w;          // damaged blob: stay inside the bitmap
                 if (p0 > p1) p0 = p1;
+                if (S.flags & 8u) {                  // one bit per element: the tile's own range
+                    p0 = (u64)ltile * EXCP_TILE;
+                    p1 = (D.n - p0 < (u64)EXCP_TILE) ? D.n : p0 + EXCP_TILE;
+                }
                 cnt = popcount_range_lane(bm, p0, p1, lane);
             }
             cnt = wave_sum_u32(cnt);
@@ -248,12 +253,13 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
         const u64 wbit0 = (u64)q_tile * nbits;
         const u32 woff = (u32)(wbit0 & 31ull);
         u32 o_tile = 0, ocnt = 0, moff = 0, ooff = 0;
+        const bool nw2m = MOMENTS && (S.flags & 8u) != 0u;    // M_o bits per element instead of per kept residual
         if (MOMENTS && moments) {
             o_tile = w.dec_cnt_o[tile];
             const u32 o_next = (ltile + 1u < D.tile_count) ? w.dec_cnt_o[tile + 1] : (u32)S.pop_o;
             ocnt = o_next - o_tile;
             moff = (u32)(((u64)o_tile * nbits) & 31ull);
-            ooff = q_tile & 31u;
+            ooff = nw2m ? 0u : q_tile & 31u;
         }
 
         __syncthreads();                                   // the previous tile's LDS readers are done
@@ -272,14 +278,16 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
             }
             if (wave == 0) {
                 // bitmap_o bits [q_tile, q_tile + cnt) as u32 words, with the count of set bits before each word
-                const EXCP_GLOBAL u32 *bo = gptr((const u32 *)(blob + S.off_bo)) + (q_tile >> 5);
-                const u32 owords = (ooff + cnt + 31u) >> 5;        // <= 129
+                const EXCP_GLOBAL u32 *bo = gptr((const u32 *)(blob + S.off_bo)) + (nw2m ? ltile * (EXCP_TILE / 32u) : q_tile >> 5);
+                const u32 obits_total = nw2m ? rem : ooff + cnt;
+                const u32 owords = (obits_total + 31u) >> 5;       // <= 129
                 u32 carry = 0;
 #pragma unroll
                 for (int c = 0; c < 3; ++c) {
                     const u32 i = lane + 64u * (u32)c;
                     u32 word = (i < owords) ? bo[i] : 0u;
                     if (i == 0u) word &= ~((1u << ooff) - 1u);     // bits of earlier tiles' survivors
+                    if (nw2m && i + 1u == owords && (obits_total & 31u)) word &= (1u << (obits_total & 31u)) - 1u;   // bits past the last element
                     const u32 opc = __popc(word);
                     u32 oincl = opc;
 #pragma unroll
@@ -338,7 +346,7 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
                 }
             }
             if (MOMENTS && moments) {
-                const u32 bpos = ooff + r;                                // the first survivor's bit in the staged bitmap_o
+                const u32 bpos = nw2m ? off : ooff + r;                   // the first survivor's (element's) bit in the staged bitmap_o
                 const u32 bi = bpos >> 5, bsh = bpos & 31u;
                 u32 obits = __builtin_amdgcn_alignbit(s_ow[bi + 1], s_ow[bi], bsh);
                 const u32 orank = s_oex[bi] + __popc(s_ow[bi] & ((1u << bsh) - 1u));
@@ -351,10 +359,10 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const bool kept = (nib >> j) & 1u;
-                        const bool ko = kept && (obits & 1u);
+                        const bool ko = (kept || nw2m) && (obits & 1u);
                         cm4[j] = ko ? (fm & cmask) : 0u;
                         cv4[j] = ko ? (fv & cmask) : 0u;
-                        obits = kept ? (obits >> 1) : obits;
+                        obits = (kept || nw2m) ? (obits >> 1) : obits;
                         fm = ko ? (fm >> nbits) : fm;
                         fv = ko ? (fv >> nbits) : fv;
                     }
@@ -366,7 +374,7 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const bool kept = (nib >> j) & 1u;
-                    const bool ko = kept && (obits & 1u);
+                    const bool ko = (kept || nw2m) && (obits & 1u);
                     if (RAW) {
                         om[j] = ko ? *xm : 0.f; ov[j] = ko ? *xv : 0.f;
                         xm += ko; xv += ko;
@@ -374,7 +382,7 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
                         om[j] = ko ? s_book[256u + (fm & cmask)] : 0.f;
                         ov[j] = ko ? s_book[512u + (fv & cmask)] : 0.f;
                     }
-                    obits = kept ? (obits >> 1) : obits;
+                    obits = (kept || nw2m) ? (obits >> 1) : obits;
                     fm = ko ? (fm >> nbits) : fm;
                     fv = ko ? (fv >> nbits) : fv;
                 }
@@ -565,12 +573,12 @@ __global__ void k_dense_parse(Workspace w, u32 ntensors) {
     const DDesc &D = w.ddesc[t];
     DState &S = w.dst[t];
     S.status = 0; S.pop_w = 0; S.pop_o = 0;
-    S.n_w = 0; S.n_o = 0; S.nbits = 4; S.blob_bytes = 0;
+    S.n_w = 0; S.n_o = 0; S.nbits = 4; S.blob_bytes = 0; S.flags = 0; S.pad = 0;
     if (D.blob_bytes < EXCP_HEADER) { S.status = -4; return; }
     const u32 *h = (const u32 *)D.blob;
     const u64 *h64 = (const u64 *)D.blob;
     const u32 nbits = h[2];
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 4u;
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 16u;
     ok = ok && h64[2] == D.n && D.blob_bytes >= EXCP_HEADER + 12ull * (1u << (nbits & 15u));
     if (!ok) { S.status = -4; return; }
     S.n_w = h64[3]; S.n_o = h64[4]; S.nbits = nbits; S.blob_bytes = h64[8];
@@ -688,7 +696,7 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     S.off_bw = EXCP_HEADER + excp_books_bytes((u32)g.nbits);
     S.off_bo = T.off_bo; S.off_cw = T.off_cw; S.off_cm = T.off_cm; S.off_cv = T.off_cv;
     S.status = (T.status == 0 && C.W_out != nullptr) ? 0 : 1;    // 1 = skip silently
-    S.pop_w = 0; S.pop_o = 0;
+    S.pop_w = 0; S.pop_o = 0; S.flags = g.flags; S.pad = 0;
 }
 
 // The compress path already knows how many survivors precede every tile: the exclusive scan of its

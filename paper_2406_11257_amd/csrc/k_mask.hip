@@ -33,6 +33,11 @@ struct Regs {
 
 // sub-tile s of the group -> (tensor, first element); slots live in the partition arrays, which are
 // free until the codebook stage
+//
+// NW2M (Table "vit", no weights-to-momentum check): M_o(i) = |m_i| > r_o for every element, kept
+// weight or not.  The moment survivors are then compacted from the elements themselves, and the
+// sub-tile's M_o words are indexed by element.
+template <bool NW2M>
 __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, GroupParams g) {
     __shared__ float l_w[SUB], l_m[SUB], l_v[SUB];      // compacted survivors of one sub-tile
     __shared__ u32 s_w[4], s_o[4];
@@ -137,7 +142,8 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
             const bool kw = (mw >> lane) & 1ull;
             const u32 rk = pw + __popcll(mw & lt_mask);
             if (kw) {
-                l_w[rk] = R.w[j]; l_m[rk] = R.m[j]; l_v[rk] = R.v[j];
+                l_w[rk] = R.w[j];
+                if (!NW2M) { l_m[rk] = R.m[j]; l_v[rk] = R.v[j]; }
             }
             pw += __popcll(mw);
         }
@@ -151,10 +157,16 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
         for (int j = 0; j < NBATCH; ++j) {
             const u32 p = (wave * NBATCH + j) * 64 + lane;       // survivor position in the sub-tile
             const bool in = p < tw;
-            mm[j] = in ? l_m[p] : 0.f;
-            vv2[j] = in ? l_v[p] : 0.f;
             if (in) sw[p] = l_w[p];
-            bo[j] = ballot64(in && fabsf(mm[j]) > r_o);
+            if (NW2M) {
+                // p is also this lane's element of batch j
+                mm[j] = R.m[j]; vv2[j] = R.v[j];
+                bo[j] = ballot64((FULL || p < rem) && fabsf(mm[j]) > r_o);
+            } else {
+                mm[j] = in ? l_m[p] : 0.f;
+                vv2[j] = in ? l_v[p] : 0.f;
+                bo[j] = ballot64(in && fabsf(mm[j]) > r_o);
+            }
             co += __popcll(bo[j]);
         }
         if (lane < NBATCH) {
@@ -162,7 +174,7 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
 #pragma unroll
             for (int j = 0; j < NBATCH; ++j) if (lane == (u32)j) mine = bo[j];
             const u32 wordi = wave * NBATCH + lane;
-            if (wordi < ((tw + 63u) >> 6)) w.mask_bo[(u64)sub * BO_WORDS + wordi] = mine;
+            if (NW2M || wordi < ((tw + 63u) >> 6)) w.mask_bo[(u64)sub * BO_WORDS + wordi] = mine;
         }
         if (lane == 0) s_o[wave] = co;
         __syncthreads();
@@ -284,8 +296,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
         __syncthreads();
         for (u32 j = wave; j < GATHER_SUBS; j += 4) {
             const u32 tw = s_tw[j], to = s_to[j];
-            if (tw == 0) continue;
-            const u32 sub = sub0 + j, t = s_t[j];
+            if (tw == 0 && to == 0) continue;
             const u32 pw = s_pw[j], po = s_po[j];
             const u64 slot = s_slot[j], eoff = s_eoff[j];
             const EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
@@ -380,6 +391,26 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_bitmap_o(Workspace w, Gro
     }
 }
 
+// bitmap_o without the weights-to-momentum check: one bit per element, so the sub-tiles' words are
+// already the section's words, 32 per sub-tile.
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_bitmap_o_elems(Workspace w, GroupParams g) {
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
+    for (u32 blk = blockIdx.x * 4 + wave; blk < g.ntiles; blk += gridDim.x * 4) {
+        const u32 t = find_owner(s_tiles, g.ntensors, blk);
+        const u32 b = blk - s_tiles[t];                     // the tensor's b-th tile = 64 words
+        const TDesc &D = w.desc[t];
+        const u64 nwo = excp_words(D.n), padded = nwo + (nwo & 1ull);
+        const u64 widx = 64ull * b + lane;
+        if (widx >= padded) continue;
+        const u64 off_bo = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * nwo);
+        const u64 cap_words = (D.blob_cap > off_bo) ? (D.blob_cap - off_bo) >> 3 : 0ull;
+        const u64 word = widx < nwo ? w.mask_bo[(2ull * blk + (lane >> 5)) * BO_WORDS + (lane & 31u)] : 0ull;
+        if (widx < cap_words) ((u64 *)(D.blob + off_bo))[widx] = word;
+    }
+}
+
 // After the masks: blob section offsets, capacity check, survivor stream lengths and the chunk
 // list of the survivor passes.  One workgroup; tensors and streams are few.
 __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParams g, u32 *seg_chunk_begin) {
@@ -397,7 +428,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParam
         if (which == 0) {
             const u64 n = D.n, nw = S.n_w, no = S.n_o, nb = (u64)g.nbits;
             u64 off = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * excp_words(n));
-            S.off_bo = off; off += excp_pad16(8ull * excp_words(nw));
+            S.off_bo = off; off += excp_pad16(8ull * excp_words((g.flags & 8u) ? n : nw));
             S.off_cw = off; off += excp_pad16(8ull * excp_words(nw * nb));
             S.off_cm = off; off += excp_pad16(8ull * excp_words(no * nb));
             S.off_cv = off; off += excp_pad16(8ull * excp_words(no * nb));
@@ -419,7 +450,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_layout(Workspace w, GroupParam
         {
             const u64 n = D.n, nw = S.n_w, no = S.n_o, nb = (u64)g.nbits;
             u64 off = EXCP_HEADER + excp_books_bytes((u32)g.nbits) + excp_pad16(8ull * excp_words(n));
-            off += excp_pad16(8ull * excp_words(nw)) + excp_pad16(8ull * excp_words(nw * nb)) +
+            off += excp_pad16(8ull * excp_words((g.flags & 8u) ? n : nw)) + excp_pad16(8ull * excp_words(nw * nb)) +
                    2ull * excp_pad16(8ull * excp_words(no * nb));
             if (off > D.blob_cap || S.nonfinite) len = 0;
         }
@@ -453,7 +484,8 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
     if (phase == 0) {
         u32 grid = excp_grid(w, 20);
         if (grid > nsub) grid = nsub;
-        hipLaunchKernelGGL(k_mask_slots, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        if (g.flags & 8u) hipLaunchKernelGGL(k_mask_slots<true>, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        else hipLaunchKernelGGL(k_mask_slots<false>, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     } else if (phase == 1) {
         hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
     } else {
@@ -462,7 +494,8 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
         hipLaunchKernelGGL(k_mask_gather, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
         u32 grid_o = (g.ntiles + 3) / 4;
         if (grid_o > excp_grid(w, 16)) grid_o = excp_grid(w, 16);
-        hipLaunchKernelGGL(k_mask_bitmap_o, dim3(grid_o), dim3(EXCP_THREADS), 0, s, w, g);
+        if (g.flags & 8u) hipLaunchKernelGGL(k_mask_bitmap_o_elems, dim3(grid_o), dim3(EXCP_THREADS), 0, s, w, g);
+        else hipLaunchKernelGGL(k_mask_bitmap_o, dim3(grid_o), dim3(EXCP_THREADS), 0, s, w, g);
     }
 }
 

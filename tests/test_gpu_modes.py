@@ -108,3 +108,67 @@ def test_no_residual_and_no_pruning_need_no_switch(ctx):
     assert refs[0].median == np.sort(np.abs(W))[(n - 1) // 2]            # the "residual" is the weight itself
     outs, refs = check_mode(ctx, [(Wp, W, m, v)], 0.0, 0.0, 4, 5, 0)
     assert refs[0].n_w == np.count_nonzero(W - Wp) and refs[0].n_o == np.count_nonzero((W - Wp != 0) & (m != 0))
+
+
+@pytest.mark.parametrize("flags", [8, 9, 10, 12, 15])
+def test_moment_mask_without_the_weights_to_momentum_check(ctx, flags):
+    cases = [case(n, 400 + i) for i, n in enumerate(SIZES)]
+    alpha = 0.7 if flags & 2 else 5e-5
+    outs, refs = check_mode(ctx, cases, alpha, 1.0, 4, 3, flags)
+    for c, o, r in zip(cases, outs, refs):
+        assert o["stats"].blob_bytes == X.excp_blob_size_ex(c[0].size, r.n_w, r.n_o, 32 if flags & 4 else 4, flags)
+    big = refs[-1]
+    assert np.any(big.Mo & ~big.Mw) and big.n_o > 0
+
+
+@pytest.mark.parametrize("alpha,beta,nbits", [(1.0, 0.0, 2), (0.0, 3.0, 8), (2e-4, 0.5, 5), (1.0, 0.5, 3)])
+def test_no_w2m_from_no_weights_kept_to_all_moments_kept(ctx, alpha, beta, nbits):
+    # alpha = 1 prunes (nearly) every weight while the moments stay: n_o far above n_w
+    cases = [case(n, 440 + i) for i, n in enumerate([7, 4097, 262145])]
+    outs, refs = check_mode(ctx, cases, alpha, beta, nbits, 2, 8)
+    if alpha == 1.0:
+        assert refs[-1].n_o > refs[-1].n_w
+
+
+def test_no_w2m_through_the_stored_layout_and_the_chain(ctx):
+    from test_gpu_dense import export, dense_decode
+    n = 150001
+    cases = [case(n, 460), case(4097, 461)]
+    rc, outs = gpu_compress(ctx, cases, 5e-5, 1.0, 4, 2, flags=8)
+    assert rc == 0
+    rc, stats, res, bufs = export(ctx, outs, 4)
+    assert rc == 0
+    for o, (head, cw, cm, cv) in zip(outs, res):
+        ref = O.export_dense(o["blob"])
+        assert head.tobytes() == ref[0] and cw.tobytes() == ref[1].tobytes()
+        assert cm.tobytes() == ref[2].tobytes() and cv.tobytes() == ref[3].tobytes()
+    rc, stats, dec = dense_decode(ctx, [c[0] for c in cases], bufs, [n, 4097])
+    assert rc == 0
+    for c, o, d in zip(cases, outs, dec):
+        ref = O.decompress_step(c[0], o["blob"])
+        assert d[0].tobytes() == ref[0].tobytes() and d[1].tobytes() == ref[1].tobytes() and d[2].tobytes() == ref[2].tobytes()
+    # a chain of two such checkpoints: the moments are those of the last one
+    Wp, W, m, v = cases[0]
+    r1 = O.compress_step(Wp, W, m, v, 5e-5, 1.0, 4, 2, flags=8)
+    W2 = (W + np.random.default_rng(1).laplace(0, 1e-4, n).astype(f32)).astype(f32)
+    rc, out2 = gpu_compress(ctx, [(r1.W_recon, W2, m, v)], 5e-5, 1.0, 4, 2, flags=8)
+    Wout, mout, vout = (torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3))
+    ctx.excp_reconstruct_chain([(to_dev(Wp), [outs[0]["blob_dev"], out2[0]["blob_dev"]],
+                                 [int(outs[0]["stats"].blob_bytes), int(out2[0]["stats"].blob_bytes)], Wout, mout, vout)])
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    ref = O.reconstruct_chain(Wp, [outs[0]["blob"], out2[0]["blob"]])
+    assert Wout.cpu().numpy().tobytes() == ref[0].tobytes() and mout.cpu().numpy().tobytes() == ref[1].tobytes()
+    assert vout.cpu().numpy().tobytes() == ref[2].tobytes()
+    # damage: a count that only the other layout allows, and a flipped moment bit
+    good = bytearray(outs[0]["blob"])
+    b = bytearray(good); b[12] = 0                         # same bytes read as the default layout: sizes disagree
+    rc, _ = gpu_decompress(ctx, Wp, bytes(b), n)
+    assert rc == X.EXCP_E_BLOB
+    p = O.parse_blob(bytes(good))
+    off_bo = 80 + 12 * 16 + (8 * ((n + 63) // 64) + 15) // 16 * 16
+    b = bytearray(good); b[off_bo + 5] ^= 0x04
+    rc, _ = gpu_decompress(ctx, Wp, bytes(b), n)
+    assert rc == X.EXCP_E_BLOB
+    with pytest.raises(X.ExcpError):
+        ctx.excp_compress_tensors([], 5e-5, 2.0, 4, 2, 16)
