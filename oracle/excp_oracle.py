@@ -36,7 +36,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 __all__ = [
-    "MAGIC", "VERSION", "HEADER_BYTES", "FLAG_MEDIAN_OF_WEIGHTS", "FLAG_NO_M2W", "FLAG_NO_QUANT", "FLAG_NO_W2M",
+    "MAGIC", "VERSION", "HEADER_BYTES", "FLAG_MEDIAN_OF_WEIGHTS", "FLAG_NO_M2W", "FLAG_NO_QUANT", "FLAG_NO_W2M", "FLAG_W_F16", "FLAG_W_BF16", "widen", "narrow",
     "RAW_BITS",
     "residual", "lower_median_abs", "exact_mean_abs", "weight_mask",
     "momentum_mask", "kmeans_init", "nearest_centre", "lloyd", "objective",
@@ -50,6 +50,9 @@ FLAG_MEDIAN_OF_WEIGHTS = 1
 FLAG_NO_M2W = 2
 FLAG_NO_QUANT = 4           # Table "abl", "prune" without "quant": the survivors are stored as they are (fp32)
 FLAG_NO_W2M = 8             # Table "vit", no weights-to-momentum check: M_o does not depend on M_w
+FLAG_W_F16 = 16             # the weights (previous, current, reconstructed) are IEEE binary16 (Sec. 4.3: PanGu)
+FLAG_W_BF16 = 32            # ... or bfloat16, held as uint16 bit patterns
+FLAGS_ALL = 63
 RAW_BITS = 32               # the "code" width written into the header of a blob without quantisation
 MAGIC = 0x50435845          # bytes "EXCP" read as a little-endian u32
 VERSION = 1
@@ -64,6 +67,42 @@ class BlobError(ValueError):
 
 class NonFiniteError(ValueError):
     """An input array holds NaN or Inf."""
+
+
+# --------------------------------------------------------------------------
+# Weights stored in 16 bits.  The method itself is unchanged: every weight is widened to fp32
+# (exact), all arithmetic is the fp32 arithmetic described above, and a reconstructed weight is the
+# fp32 sum rounded once more, to nearest even, into the storage format.  Pruned positions keep the
+# previous weight's bits.
+# --------------------------------------------------------------------------
+def _check_flags(flags: int) -> None:
+    if not 0 <= flags <= FLAGS_ALL or (flags & FLAG_W_F16 and flags & FLAG_W_BF16):
+        raise ValueError("unknown or contradictory flags")
+
+
+def widen(a, flags: int) -> np.ndarray:
+    if flags & FLAG_W_F16:
+        a = np.ascontiguousarray(a).ravel()
+        assert a.dtype == np.float16
+        return a.astype(f32)
+    if flags & FLAG_W_BF16:
+        a = np.ascontiguousarray(a).ravel()
+        assert a.dtype == np.uint16
+        return (a.astype(np.uint32) << np.uint32(16)).view(f32)
+    return np.ascontiguousarray(a, dtype=f32).ravel()
+
+
+def narrow(x: np.ndarray, flags: int) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=f32)
+    if flags & FLAG_W_F16:
+        with np.errstate(over="ignore"):
+            return x.astype(np.float16)                       # IEEE round to nearest even
+    if flags & FLAG_W_BF16:
+        b = x.view(np.uint32).astype(np.uint64)
+        assert not np.any(np.isnan(x))
+        # drop 16 bits, nearest even: add half of the dropped range minus one, plus the kept lsb
+        return ((b + 0x7FFF + ((b >> 16) & 1)) >> 16).astype(np.uint16)
+    return x
 
 
 # --------------------------------------------------------------------------
@@ -304,7 +343,7 @@ def parse_blob(blob: bytes, n_expected: int | None = None) -> dict:
         raise BlobError("bad magic")
     if version != VERSION:
         raise BlobError("bad version")
-    if flags > 15:
+    if flags > FLAGS_ALL or (flags & FLAG_W_F16 and flags & FLAG_W_BF16):
         raise BlobError("unknown flags")
     if not (2 <= nbits <= 8 or (nbits == RAW_BITS and flags & FLAG_NO_QUANT)) or \
             (nbits != RAW_BITS and flags & FLAG_NO_QUANT):
@@ -371,13 +410,15 @@ class CompressResult:
 # --------------------------------------------------------------------------
 def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
                   flags=0) -> CompressResult:
-    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
-    W = np.ascontiguousarray(W, dtype=f32).ravel()
+    _check_flags(flags)
+    W_prev_stored = np.ascontiguousarray(W_prev).ravel()
+    W_prev = widen(W_prev, flags)
+    W = widen(W, flags)
     m = np.ascontiguousarray(m, dtype=f32).ravel()
     v = np.ascontiguousarray(v, dtype=f32).ravel()
     n = W.size
     assert W_prev.size == n and m.size == n and v.size == n
-    assert 2 <= nbits <= 8 and iters >= 0 and 0 <= flags <= 15
+    assert 2 <= nbits <= 8 and iters >= 0
     raw = bool(flags & FLAG_NO_QUANT)
     stored_bits = RAW_BITS if raw else nbits
     for arr in (W_prev, W, m, v):
@@ -394,7 +435,7 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
                           med=f32(0), mean32=f32(0), t_w=f32(0), r_o=f32(0),
                           Cw=C0, Cm=C0, Cv=C0, Mw=zb, Mo_over_survivors=zb,
                           codes_w=zc, codes_m=zc, codes_v=zc)
-        return CompressResult(blob, z, z, z, 0, 0, 0, f32(0), 0.0, f32(0), f32(0), f32(0),
+        return CompressResult(blob, narrow(z, flags), z, z, 0, 0, 0, f32(0), 0.0, f32(0), f32(0), f32(0),
                               zb, zb, dict(w=C0, m=C0, v=C0), dict(w=zc, m=zc, v=zc),
                               dict(w=0.0, m=0.0, v=0.0), dict(w=z, m=z, v=z))
 
@@ -432,8 +473,7 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
                       codes_w=stored["w_codes"], codes_m=stored["m_codes"], codes_v=stored["v_codes"])
 
     # Alg. 2 applied to what was just stored (the copy kept for the next step).
-    W_rec = W_prev.copy()
-    W_rec[Mw] = (W_prev[Mw] + stored["w"]).astype(f32)
+    W_rec = _apply_residual(W_prev_stored, W_prev, np.flatnonzero(Mw), stored["w"], flags)
     m_rec = np.zeros(n, dtype=f32)
     v_rec = np.zeros(n, dtype=f32)
     m_rec[Mo] = stored["m"]
@@ -443,11 +483,21 @@ def compress_step(W_prev, W, m, v, alpha=5e-5, beta=2.0, nbits=4, iters=10,
                           dict(w=xw, m=xm, v=xv))
 
 
+def _apply_residual(W_prev_stored, W_prev32, idx, values, flags):
+    """W_hat: the previous weights with `values` added at `idx` (fp32 addition, then the storage
+    format's rounding when the weights are 16-bit); everything else keeps its bits."""
+    out = np.array(W_prev_stored, copy=True)
+    out[idx] = narrow((W_prev32[idx] + values).astype(f32), flags)
+    return out
+
+
 # --------------------------------------------------------------------------
 # Alg. 2 for one tensor, from the stored bytes alone.
 # --------------------------------------------------------------------------
 def decompress_step(W_prev, blob: bytes):
-    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
+    flags = parse_blob(blob)["flags"]
+    W_prev_stored = np.ascontiguousarray(W_prev).ravel()
+    W_prev = widen(W_prev, flags)
     p = parse_blob(blob, n_expected=W_prev.size)
     n, n_w, n_o, nbits = p["n"], p["n_w"], p["n_o"], p["nbits"]
     idx_w, idx_o = _kept_indices(p)
@@ -458,8 +508,7 @@ def decompress_step(W_prev, blob: bytes):
             vals.append(c.astype(np.uint32).view(f32))              # stored as they were
         else:
             vals.append(p["book_" + key][c])                        # Alg. 2 steps 2-3: codebook look-up
-    W_rec = W_prev.copy()
-    W_rec[idx_w] = (W_prev[idx_w] + vals[0]).astype(f32)            # Alg. 2 step 4
+    W_rec = _apply_residual(W_prev_stored, W_prev, idx_w, vals[0], flags)   # Alg. 2 step 4
     m_rec = np.zeros(n, dtype=f32)
     v_rec = np.zeros(n, dtype=f32)
     m_rec[idx_o] = vals[1]
@@ -487,7 +536,7 @@ def reconstruct_chain(W0, blobs):
     """Alg. 3: from the weights the chain starts with, apply the compressed checkpoints one after the
     other (each is Alg. 2 against the reconstruction before it).  Returns the last reconstruction and
     the moments stored in the last checkpoint."""
-    W = np.ascontiguousarray(W0, dtype=f32).ravel()
+    W = np.ascontiguousarray(W0).ravel()
     m = v = None
     for blob in blobs:
         W, m, v = decompress_step(W, blob)
@@ -551,12 +600,15 @@ def export_dense(blob: bytes):
 def decompress_dense(W_prev, head: bytes, codes_w, codes_m, codes_v):
     """Alg. 2 from the stored layout of Sec. 4.2: look every element's code up in its codebook; code 0
     leaves the previous weight untouched and gives a zero moment."""
-    W_prev = np.ascontiguousarray(W_prev, dtype=f32).ravel()
-    n = W_prev.size
     if len(head) < HEADER_BYTES:
         raise BlobError("shorter than a header")
     magic, version, nbits, flags, n_stored = struct.unpack("<IIIIQ", head[:24])
-    if magic != MAGIC or version != VERSION or not 2 <= nbits <= 8 or flags > 15 or n_stored != n:
+    if flags > FLAGS_ALL or (flags & FLAG_W_F16 and flags & FLAG_W_BF16):
+        raise BlobError("bad header")
+    W_prev_stored = np.ascontiguousarray(W_prev).ravel()
+    W_prev = widen(W_prev, flags)
+    n = W_prev.size
+    if magic != MAGIC or version != VERSION or not 2 <= nbits <= 8 or n_stored != n:
         raise BlobError("bad header")
     if len(head) < head_bytes(nbits):
         raise BlobError("codebooks missing")
@@ -569,8 +621,7 @@ def decompress_dense(W_prev, head: bytes, codes_w, codes_m, codes_v):
             raise BlobError("code beyond the codebook")
         kept = c != 0
         if k == 0:
-            r = W_prev.copy()
-            r[kept] = (W_prev[kept] + books[0][c[kept]]).astype(f32)
+            r = _apply_residual(W_prev_stored, W_prev, np.flatnonzero(kept), books[0][c[kept]], flags)
         else:
             r = np.zeros(n, dtype=f32)
             r[kept] = books[k][c[kept]]

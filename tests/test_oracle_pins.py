@@ -734,3 +734,111 @@ def test_every_combination_of_switches_round_trips(flags):
         assert np.array_equal(r.Mo, np.abs(m) > r.r_o)
     else:
         assert not np.any(r.Mo & ~r.Mw)
+
+
+# ---------------------------------------------------------------- weights stored in 16 bits
+def nearest_even_in_format(x: float, mant_bits: int, emin: int, emax: int):
+    """Exact round-to-nearest-even of a finite double into a binary format with `mant_bits` explicit
+    mantissa bits, minimum normal exponent emin and maximum exponent emax; returns a Fraction or
+    +-inf.  Plain rational arithmetic, no floating-point conversion involved."""
+    if x == 0:
+        return Fraction(0)
+    q = Fraction(x)
+    s = -1 if q < 0 else 1
+    q = abs(q)
+    e = max(math.floor(math.log2(q)), emin)
+    while Fraction(2) ** (e + 1) <= q:
+        e += 1
+    while e > emin and Fraction(2) ** e > q:
+        e -= 1
+    ulp = Fraction(2) ** (e - mant_bits)
+    k = q / ulp
+    lo = math.floor(k)
+    rem = k - lo
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    r = lo * ulp
+    if r >= Fraction(2) ** (emax + 1):
+        return s * math.inf
+    return s * r
+
+
+def sixteen_bit_test_values():
+    g = np.random.default_rng(77)
+    x = np.concatenate([
+        g.standard_normal(300) * 0.02, g.standard_normal(100) * 1e-6, g.standard_normal(50) * 1e4,
+        g.standard_normal(50) * 1e-41,                               # fp32 denormals
+        np.array([0.0, -0.0, 1.0, 65504.0, 65519.9, 65520.0, 6.1e-5, 5.96e-8, 2.98e-8, 2.9802322e-8, 3e-8,
+                  3.3895314e38, 3.4e38, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -9, 1.0 + 3 * 2.0 ** -9, 1.0 + 2.0 ** -11,
+                  1.0 + 3 * 2.0 ** -11, -1.0 - 2.0 ** -8, 2.0 ** -126, 2.0 ** -133, 2.0 ** -134 * 1.5]),
+    ]).astype(f32)
+    return x
+
+
+def test_narrowing_to_fp16_and_bf16_is_round_to_nearest_even():
+    x = sixteen_bit_test_values()
+    h = O.narrow(x, O.FLAG_W_F16)
+    b = O.narrow(x, O.FLAG_W_BF16)
+    assert h.dtype == np.float16 and b.dtype == np.uint16
+    hw, bw = O.widen(h, O.FLAG_W_F16), O.widen(b, O.FLAG_W_BF16)
+    for xi, hi, bi in zip(x.tolist(), hw.tolist(), bw.tolist()):
+        want_h = nearest_even_in_format(xi, 10, -14, 15)
+        want_b = nearest_even_in_format(xi, 7, -126, 127)
+        assert (Fraction(hi) if math.isfinite(hi) else hi) == want_h, (xi, hi, want_h)
+        assert (Fraction(bi) if math.isfinite(bi) else bi) == want_b, (xi, bi, want_b)
+    assert np.array_equal(np.signbit(hw), np.signbit(x)) and np.array_equal(np.signbit(bw), np.signbit(x))
+    # widening is exact and narrowing what was widened gives the same bits back
+    all16 = np.arange(65536, dtype=np.uint16)
+    finite_b = all16[(all16 & 0x7F80) != 0x7F80]
+    assert np.array_equal(O.narrow(O.widen(finite_b, O.FLAG_W_BF16), O.FLAG_W_BF16), finite_b)
+    finite_h = all16[(all16 & 0x7C00) != 0x7C00].view(np.float16)
+    assert np.array_equal(O.narrow(O.widen(finite_h, O.FLAG_W_F16), O.FLAG_W_F16).view(np.uint16), finite_h.view(np.uint16))
+    assert O.widen(np.array([0x3F80, 0xC000, 0x0001], np.uint16), O.FLAG_W_BF16).tolist() == [1.0, -2.0, 2.0 ** -133]
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_sixteen_bit_weights_are_the_fp32_method_on_widened_values(kind):
+    flag = O.FLAG_W_F16 if kind == "f16" else O.FLAG_W_BF16
+    g = np.random.default_rng(5)
+    n = 4001
+    Wp32 = (g.standard_normal(n) * 0.02).astype(f32)
+    Wp = O.narrow(Wp32, flag)
+    W = O.narrow((O.widen(Wp, flag) + g.laplace(0, 3e-4, n).astype(f32)).astype(f32), flag)
+    Wp[:7] = O.narrow(np.full(7, -0.0, f32), flag)
+    W[:7] = Wp[:7]                                                # pruned, and must stay -0.0
+    m = (g.standard_normal(n) * 5e-5).astype(f32)
+    v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+    r16 = O.compress_step(Wp, W, m, v, nbits=4, iters=3, flags=flag)
+    r32 = O.compress_step(O.widen(Wp, flag), O.widen(W, flag), m, v, nbits=4, iters=3)
+    # same masks, codebooks and codes: only the flags field of the header differs
+    assert r16.blob[:12] == r32.blob[:12] and r16.blob[16:] == r32.blob[16:]
+    assert struct.unpack("<I", r16.blob[12:16])[0] == flag
+    # many residuals are zero (the weights did not move by one unit of the 16-bit format): pruned
+    assert 0 < r16.n_w < n
+    # reconstruction: the fp32 result rounded once into the storage format; pruned positions keep their bits
+    want = O.narrow(r32.W_recon, flag)
+    assert r16.W_recon.dtype == Wp.dtype
+    assert r16.W_recon.view(np.uint16).tobytes() == np.where(r16.Mw, want.view(np.uint16), Wp.view(np.uint16)).astype(np.uint16).tobytes()
+    assert np.all(r16.W_recon.view(np.uint16)[:7] == Wp.view(np.uint16)[:7])
+    for i in np.flatnonzero(r16.Mw)[:200]:
+        s = f32(O.widen(Wp[i:i + 1], flag)[0] + r32.C["w"][r32.assign["w"][np.count_nonzero(r16.Mw[:i])]])
+        fmt = (10, -14, 15) if kind == "f16" else (7, -126, 127)
+        assert Fraction(float(O.widen(r16.W_recon[i:i + 1], flag)[0])) == nearest_even_in_format(float(s), *fmt)
+    got = O.decompress_step(Wp, r16.blob)
+    assert got[0].dtype == Wp.dtype and got[0].view(np.uint16).tobytes() == r16.W_recon.view(np.uint16).tobytes()
+    assert got[1].tobytes() == r16.m_recon.tobytes() and got[2].tobytes() == r16.v_recon.tobytes()
+    head, cw, cm, cv = O.export_dense(r16.blob)
+    back = O.decompress_dense(Wp, head, cw, cm, cv)
+    assert back[0].view(np.uint16).tobytes() == r16.W_recon.view(np.uint16).tobytes()
+    # a second step against the reconstruction, then the chain from the start
+    W2 = O.narrow((O.widen(W, flag) + g.laplace(0, 3e-4, n).astype(f32)).astype(f32), flag)
+    r2 = O.compress_step(r16.W_recon, W2, m, v, nbits=4, iters=3, flags=flag)
+    end = O.reconstruct_chain(Wp, [r16.blob, r2.blob])
+    assert end[0].view(np.uint16).tobytes() == r2.W_recon.view(np.uint16).tobytes()
+    err = np.abs(O.widen(end[0], flag).astype(np.float64) - O.widen(W2, flag))
+    assert np.median(err) < 1e-3
+    with pytest.raises(ValueError):
+        O.compress_step(Wp, W, m, v, flags=O.FLAG_W_F16 | O.FLAG_W_BF16)
+    bad = bytearray(r16.blob); bad[12] = 48
+    with pytest.raises(O.BlobError):
+        O.parse_blob(bytes(bad))
