@@ -43,7 +43,7 @@ def survey_step_bytes_per_param(p_w, p_o):
     return 32.2 + 58.5 * s + 8.0
 
 
-STAGE_KERNEL = {"stats_stream": "k_stats_stream", "mask_slots": "k_mask_slots<false>", "mask_gather": "k_mask_gather",
+STAGE_KERNEL = {"stats_stream": "k_stats_stream<false>", "mask_slots": "k_mask_slots<false, false>", "mask_gather": "k_mask_gather",
                 "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats",
                 "assign_pack": "k_assign_pack", "decode_main": "k_decode_main<false>"}
 

@@ -48,7 +48,7 @@
  *                  of a little-endian bit stream stored as u64 words
  *
  * Memory and ownership.  Every tensor pointer below is DEVICE memory on the
- * context's GPU (4-byte aligned is enough); blobs are DEVICE memory, 16-byte
+ * context's GPU (4-byte aligned is enough; weights are fp32 unless EXCP_FLAG_W_* says otherwise); blobs are DEVICE memory, 16-byte
  * aligned.  The caller owns all of them and the HIP stream.  The context owns
  * only its workspace, allocated in excp_create; no entry point allocates
  * afterwards.  stats / blob_bytes outputs are HOST memory.
@@ -98,32 +98,45 @@ extern "C" {
                                            whether or not the weight is kept.  bitmap_o then has one bit per ELEMENT
                                            (ceil(n/64) words) and n_o may exceed n_w; everything else is unchanged. */
 
+#define EXCP_FLAG_W_F16             16u /* the WEIGHT arrays (W_prev_recon, W_t, W_recon_out; W0 / W_out of a chain)   */
+#define EXCP_FLAG_W_BF16            32u /* hold IEEE binary16 / bfloat16 instead of fp32 (Sec. 4.3: checkpoints saved
+                                           in 16 bits); at most one of the two.  2-byte aligned is enough (8-byte
+                                           aligned arrays are read and written in wider pieces).  A weight is widened
+                                           exactly, all arithmetic is the fp32 arithmetic above, and a reconstructed
+                                           weight is the fp32 sum rounded to nearest even into the storage format;
+                                           pruned positions keep their bits.  The moments stay fp32.  The header
+                                           records the storage, and every reader takes it from there. */
+
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 
 typedef struct excp_ctx excp_ctx;
 
 /* One tensor of a compress batch (Alg. 1 inputs). */
 typedef struct {
-    const float *W_prev_recon;   /* device, n: reconstructed weights of the previous checkpoint */
-    const float *W_t;            /* device, n: current weights                                    */
+    const void  *W_prev_recon;   /* device, n weights: reconstructed weights of the previous checkpoint */
+    const void  *W_t;            /* device, n weights: current weights                            */
     const float *m_t;            /* device, n: Adam first moment                                  */
     const float *v_t;            /* device, n: Adam second moment                                 */
     uint64_t     n;              /* elements; 0 is allowed (header-only blob)                     */
     void        *blob;           /* device, 16-B aligned: receives the compressed tensor          */
     uint64_t     blob_cap;       /* bytes available at blob (excp_blob_bound never fails)         */
-    float       *W_recon_out;    /* device, n, nullable: reconstructed weights of THIS checkpoint;
-                                    may be the same pointer as W_prev_recon (in-place update)      */
+    void        *W_recon_out;    /* device, n weights, nullable: reconstructed weights of THIS
+                                    checkpoint; may be the same pointer as W_prev_recon (in place) */
 } excp_tensor;
 
 /* One tensor of a decompress batch (Alg. 2 inputs). */
 typedef struct {
-    const float *W_prev_recon;   /* device, n */
+    const void  *W_prev_recon;   /* device, n weights in the storage the blob's header names */
     const void  *blob;           /* device, 16-B aligned */
     uint64_t     blob_bytes;     /* bytes readable at blob */
     uint64_t     n;              /* must equal the n stored in the blob */
-    float       *W_recon_out;    /* device, n, nullable; may equal W_prev_recon */
+    void        *W_recon_out;    /* device, n weights, nullable; may equal W_prev_recon */
     float       *m_out;          /* device, n, nullable */
     float       *v_out;          /* device, n, nullable */
+    uint32_t     flags;          /* storage of the weight arrays passed here: 0 (fp32), EXCP_FLAG_W_F16 or
+                                    EXCP_FLAG_W_BF16.  Must be what the blob's header says (EXCP_E_BLOB
+                                    otherwise), so that no array is ever read with the wrong element size. */
+    uint32_t     reserved;       /* 0 */
 } excp_blob;
 
 /* One tensor of a chain reconstruction (Alg. 3): the weights the chain starts from and `steps`
@@ -132,14 +145,17 @@ typedef struct {
  * device memory, 16-B aligned. */
 #define EXCP_MAX_CHAIN 16
 typedef struct {
-    const float       *W0;          /* device, n: seed-initialised (or fully stored) weights      */
+    const void        *W0;          /* device, n weights: seed-initialised (or fully stored)      */
     uint64_t           n;
     int                steps;       /* 1 .. EXCP_MAX_CHAIN; longer chains: call again from W_out  */
     const void *const *blobs;       /* host array of device pointers                              */
     const uint64_t    *blob_bytes;  /* host array: bytes readable at each blob                    */
-    float             *W_out;       /* device, n, nullable; may equal W0                          */
+    void              *W_out;       /* device, n weights, nullable; may equal W0                  */
     float             *m_out;       /* device, n, nullable: moments stored in the LAST checkpoint */
     float             *v_out;
+    uint32_t           flags;       /* storage of W0 / W_out, as in excp_blob; every checkpoint of the
+                                       chain must have been written with the same storage            */
+    uint32_t           reserved;    /* 0 */
 } excp_chain;
 
 /* Per-tensor results (host). */
@@ -209,16 +225,18 @@ typedef struct {
 
 /* One tensor of a reconstruction from that layout (Alg. 2 on per-element codes). */
 typedef struct {
-    const float   *W_prev_recon; /* device, n; needed when W_recon_out is given */
+    const void    *W_prev_recon; /* device, n weights; needed when W_recon_out is given */
     const void    *head;         /* device, 16-B aligned: header and codebooks */
     uint64_t       head_bytes;   /* bytes readable at head */
     uint64_t       n;            /* must equal the n stored in the header */
     const uint8_t *codes_w;      /* device, 16-B aligned; each needed when its output is given */
     const uint8_t *codes_m;
     const uint8_t *codes_v;
-    float         *W_recon_out;  /* device, n, nullable; may equal W_prev_recon */
+    void          *W_recon_out;  /* device, n weights, nullable; may equal W_prev_recon */
     float         *m_out;        /* device, n, nullable */
     float         *v_out;        /* device, n, nullable */
+    uint32_t       flags;        /* storage of the weight arrays, as in excp_blob */
+    uint32_t       reserved;     /* 0 */
 } excp_dense_blob;
 
 /* Blob -> the layout of Sec. 4.2, for `count` tensors; asynchronous, results by excp_collect (n,
@@ -237,14 +255,15 @@ int excp_decompress_dense(excp_ctx *ctx, int count, const excp_dense_blob *items
 int excp_collect(excp_ctx *ctx, excp_stats *stats);
 
 /* Single-tensor forms (Alg. 1 / Alg. 2 argument lists); they wait for completion.
- * blob_bytes and stats are host pointers and may be NULL. */
+ * blob_bytes and stats are host pointers and may be NULL.  The flags of excp_decompress_step are
+ * those of excp_blob (the storage of the weight arrays). */
 int excp_compress_step(excp_ctx *ctx,
-                       const float *W_prev_recon, const float *W_t, const float *m_t, const float *v_t,
+                       const void *W_prev_recon, const void *W_t, const float *m_t, const float *v_t,
                        uint64_t n, float alpha, float beta, int nbits, int lloyd_iters, uint32_t flags,
                        void *blob_out, uint64_t blob_cap, uint64_t *blob_bytes,
-                       float *W_recon_out, excp_stats *stats);
-int excp_decompress_step(excp_ctx *ctx, const float *W_prev_recon, const void *blob, uint64_t blob_bytes,
-                         uint64_t n, float *W_recon_out, float *m_out, float *v_out);
+                       void *W_recon_out, excp_stats *stats);
+int excp_decompress_step(excp_ctx *ctx, const void *W_prev_recon, const void *blob, uint64_t blob_bytes,
+                         uint64_t n, void *W_recon_out, float *m_out, float *v_out, uint32_t flags);
 
 /* Per-stage timing.  When enabled, HIP events bracket every kernel stage of the next batches;
  * after excp_collect, excp_stage_ms returns the summed milliseconds and launches of stage `i`

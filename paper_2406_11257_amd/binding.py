@@ -8,6 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 EXCP_OK, EXCP_E_ARG, EXCP_E_CAP, EXCP_E_NONFINITE = 0, -1, -2, -3
 EXCP_E_BLOB, EXCP_E_HIP, EXCP_E_STATE, EXCP_E_INTERNAL = -4, -5, -6, -7
+EXCP_FLAG_MEDIAN_OF_WEIGHTS, EXCP_FLAG_NO_M2W, EXCP_FLAG_NO_QUANT, EXCP_FLAG_NO_W2M = 1, 2, 4, 8
+EXCP_FLAG_W_F16, EXCP_FLAG_W_BF16 = 16, 32
 
 
 class ExcpTensor(C.Structure):
@@ -19,13 +21,14 @@ class ExcpTensor(C.Structure):
 class ExcpChain(C.Structure):
     _fields_ = [("W0", C.c_void_p), ("n", C.c_uint64), ("steps", C.c_int),
                 ("blobs", C.POINTER(C.c_void_p)), ("blob_bytes", C.POINTER(C.c_uint64)),
-                ("W_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p)]
+                ("W_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ExcpBlob(C.Structure):
     _fields_ = [("W_prev_recon", C.c_void_p), ("blob", C.c_void_p), ("blob_bytes", C.c_uint64),
                 ("n", C.c_uint64), ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p),
-                ("v_out", C.c_void_p)]
+                ("v_out", C.c_void_p), ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ExcpDenseExport(C.Structure):
@@ -36,7 +39,8 @@ class ExcpDenseExport(C.Structure):
 class ExcpDenseBlob(C.Structure):
     _fields_ = [("W_prev_recon", C.c_void_p), ("head", C.c_void_p), ("head_bytes", C.c_uint64),
                 ("n", C.c_uint64), ("codes_w", C.c_void_p), ("codes_m", C.c_void_p), ("codes_v", C.c_void_p),
-                ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p)]
+                ("W_recon_out", C.c_void_p), ("m_out", C.c_void_p), ("v_out", C.c_void_p),
+                ("flags", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ExcpStats(C.Structure):
@@ -72,7 +76,7 @@ SYMBOLS = {
                                      C.c_float, C.c_float, C.c_int, C.c_int, C.c_uint32, C.c_void_p,
                                      C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p, C.POINTER(ExcpStats)]),
     "excp_decompress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
-                                       C.c_void_p, C.c_void_p, C.c_void_p]),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]),
     "excp_set_profiling": (C.c_int, [C.c_void_p, C.c_int]),
     "excp_stage_count": (C.c_int, []),
     "excp_stage_name": (C.c_char_p, [C.c_int]),
@@ -134,10 +138,34 @@ def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
 
-def _check_f32(t, name, device):
+_WEIGHT_NAMES = ("W_prev_recon", "W_t", "W_recon_out", "W0", "W_out")
+
+
+def _check_f32(t, name, device, flags=None):
+    """Moments are float32.  Weight tensors are float32, or float16 / bfloat16 with EXCP_FLAG_W_F16 /
+    EXCP_FLAG_W_BF16; where no flags are at hand (reading a blob) the blob's header names the storage
+    and the caller passes tensors of that type."""
     import torch
-    if t.dtype != torch.float32 or not t.is_contiguous() or t.device != device:
-        raise TypeError(f"{name} must be a contiguous float32 tensor on {device}")
+    allowed = (torch.float32,)
+    if name in _WEIGHT_NAMES:
+        if flags is None:
+            allowed = (torch.float32, torch.float16, torch.bfloat16)
+        elif flags & EXCP_FLAG_W_F16:
+            allowed = (torch.float16,)
+        elif flags & EXCP_FLAG_W_BF16:
+            allowed = (torch.bfloat16,)
+    if t.dtype not in allowed or not t.is_contiguous() or t.device != device:
+        raise TypeError(f"{name} must be a contiguous tensor on {device} of type {' / '.join(str(a) for a in allowed)}")
+
+
+def _wflags(*tensors) -> int:
+    """The storage flag that says what the given weight tensors hold (they must agree)."""
+    import torch
+    kinds = {t.dtype for t in tensors if t is not None}
+    if len(kinds) > 1:
+        raise TypeError("the weight tensors of one item differ in type")
+    kind = kinds.pop() if kinds else torch.float32
+    return {torch.float32: 0, torch.float16: EXCP_FLAG_W_F16, torch.bfloat16: EXCP_FLAG_W_BF16}[kind]
 
 
 class Context:
@@ -176,12 +204,12 @@ class Context:
         arr = (ExcpTensor * max(len(tensors), 1))()
         for i, (Wp, W, m, v, blob, Wout) in enumerate(tensors):
             for t, nm in ((Wp, "W_prev_recon"), (W, "W_t"), (m, "m_t"), (v, "v_t")):
-                _check_f32(t, nm, self.device)
+                _check_f32(t, nm, self.device, flags)
             n = W.numel()
             if not (Wp.numel() == n == m.numel() == v.numel()):
                 raise ValueError("tensor lengths differ")
             if Wout is not None:
-                _check_f32(Wout, "W_recon_out", self.device)
+                _check_f32(Wout, "W_recon_out", self.device, flags)
                 if Wout.numel() != n:
                     raise ValueError("W_recon_out length differs")
             arr[i] = ExcpTensor(Wp.data_ptr(), W.data_ptr(), m.data_ptr(), v.data_ptr(), n,
@@ -210,7 +238,7 @@ class Context:
             arr[i] = ExcpBlob(Wp.data_ptr(), blob.data_ptr(), nbytes, n,
                               0 if Wout is None else Wout.data_ptr(),
                               0 if mout is None else mout.data_ptr(),
-                              0 if vout is None else vout.data_ptr())
+                              0 if vout is None else vout.data_ptr(), _wflags(Wp, Wout), 0)
         rc = lib().excp_decompress_tensors(self._h, len(blobs), arr)
         if rc != EXCP_OK:
             raise ExcpError(rc, "excp_decompress_tensors")
@@ -249,7 +277,8 @@ class Context:
             if hbytes > head.numel() * head.element_size():
                 raise ValueError("head_bytes exceeds the head tensor")
             arr[i] = ExcpDenseBlob(0 if Wp is None else Wp.data_ptr(), head.data_ptr(), hbytes, n,
-                                   *[0 if t is None else t.data_ptr() for t in (cw, cm, cv, Wout, mout, vout)])
+                                   *[0 if t is None else t.data_ptr() for t in (cw, cm, cv, Wout, mout, vout)],
+                                   _wflags(Wp, Wout), 0)
         rc = lib().excp_decompress_dense(self._h, len(items), arr)
         if rc != EXCP_OK:
             raise ExcpError(rc, "excp_decompress_dense")
@@ -280,7 +309,7 @@ class Context:
                                C.cast(nbs, C.POINTER(C.c_uint64)),
                                0 if Wout is None else Wout.data_ptr(),
                                0 if mout is None else mout.data_ptr(),
-                               0 if vout is None else vout.data_ptr())
+                               0 if vout is None else vout.data_ptr(), _wflags(W0, Wout), 0)
         rc = lib().excp_reconstruct_chain(self._h, len(chains), arr)
         if rc != EXCP_OK:
             raise ExcpError(rc, "excp_reconstruct_chain")
@@ -300,12 +329,12 @@ class Context:
     def excp_compress_step(self, Wp, W, m, v, blob, alpha=5e-5, beta=2.0, nbits=4, lloyd_iters=10,
                            flags=0, W_recon_out=None, check=True):
         for t, nm in ((Wp, "W_prev_recon"), (W, "W_t"), (m, "m_t"), (v, "v_t")):
-            _check_f32(t, nm, self.device)
+            _check_f32(t, nm, self.device, flags)
         n = W.numel()
         if not (Wp.numel() == n == m.numel() == v.numel()):
             raise ValueError("tensor lengths differ")
         if W_recon_out is not None:
-            _check_f32(W_recon_out, "W_recon_out", self.device)
+            _check_f32(W_recon_out, "W_recon_out", self.device, flags)
         nbytes = C.c_uint64(0)
         st = ExcpStats()
         rc = lib().excp_compress_step(self._h, _ptr(Wp), _ptr(W), _ptr(m), _ptr(v), n, alpha, beta, nbits,
@@ -324,7 +353,7 @@ class Context:
                 if t.numel() != n:
                     raise ValueError(nm + " length differs")
         rc = lib().excp_decompress_step(self._h, _ptr(Wp), _ptr(blob), blob_bytes, n, _ptr(W_recon_out),
-                                        _ptr(m_out), _ptr(v_out))
+                                        _ptr(m_out), _ptr(v_out), _wflags(Wp, W_recon_out))
         if check and rc != EXCP_OK:
             raise ExcpError(rc, "excp_decompress_step")
         return rc

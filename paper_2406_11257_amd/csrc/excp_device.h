@@ -76,6 +76,8 @@ struct DDesc {
     unsigned char *cw, *cm, *cv;
     unsigned char *head;        // export: receives header and codebooks (nullable)
     u32 tile_begin, tile_count;
+    u32 wtype;                  // storage of the caller's weight arrays (0 fp32, 1 fp16, 2 bf16): the blob must
+    u32 pad;                    // say the same; 3 = no weight arrays are involved
 };
 
 struct DState {
@@ -178,6 +180,7 @@ void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s)
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s);
+void launch_decode_main16(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_decode_raw(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_store_raw(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which, hipStream_t s);

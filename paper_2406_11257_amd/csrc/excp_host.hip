@@ -132,6 +132,7 @@ void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32
     {
         StageTimer t(c, ST_DECODE_MAIN);
         launch_decode_main(w, ntensors, ntiles, moments, c->stream);
+        launch_decode_main16(w, ntensors, ntiles, moments, c->stream);  // blobs of 16-bit weights, if any
         launch_decode_raw(w, ntensors, ntiles, moments, c->stream);     // blobs written without quantisation, if any
     }
 }
@@ -229,7 +230,7 @@ uint64_t excp_blob_size(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits) {
 
 uint64_t excp_blob_size_ex(uint64_t n, uint64_t n_w, uint64_t n_o, int nbits, uint32_t flags) {
     const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0, nw2m = (flags & EXCP_FLAG_NO_W2M) != 0;
-    if (flags > 15u || (raw ? nbits != (int)EXCP_RAW_BITS : (nbits < 2 || nbits > 8))) return 0;
+    if (flags > 63u || (flags & 0x30u) == 0x30u || (raw ? nbits != (int)EXCP_RAW_BITS : (nbits < 2 || nbits > 8))) return 0;
     if (n_w > n || n_o > (nw2m ? n : n_w)) return 0;
     return blob_size_host(n, n_w, n_o, nbits, flags);
 }
@@ -375,9 +376,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (c->pending) return EXCP_E_STATE;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
 #ifdef EXCP_TUNING
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xf0u) != 0) return EXCP_E_ARG;   // tuning build only
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xc0u) != 0 || (flags & 0x30u) == 0x30u) return EXCP_E_ARG;   // tuning build only
 #else
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~15u) != 0) return EXCP_E_ARG;
+    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~63u) != 0 || (flags & 0x30u) == 0x30u) return EXCP_E_ARG;
 #endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
     const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0;     // survivors stored as fp32: no codebook stage at all
@@ -405,8 +406,8 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         for (u32 q = 0; q < g.count; ++q) {
             const excp_tensor &t = tensors[g.first + q];
             TDesc &d = c->h_desc[g.first + q];
-            d.Wp = t.W_prev_recon; d.W = t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
-            d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = t.W_recon_out;
+            d.Wp = (const float *)t.W_prev_recon; d.W = (const float *)t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
+            d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = (float *)t.W_recon_out;
             d.elem_off = elem_off; d.tile_begin = tile;
             d.cand_off = cand_off; d.cand_cap = t.n / 12 + 4096;
             cand_off += d.cand_cap;
@@ -481,6 +482,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
             { StageTimer t(c, ST_MISC); launch_decode_from_compress(w, p, s); }
             StageTimer t(c, ST_DECODE_MAIN);
             if (raw) launch_decode_raw(w, g.count, g.ntiles, false, s);
+            else if (flags & 0x30u) launch_decode_main16(w, g.count, g.ntiles, false, s);
             else launch_decode_main(w, g.count, g.ntiles, false, s);
         }
     }
@@ -501,6 +503,7 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     for (int i = 0; i < count; ++i) {
         const excp_blob &b = blobs[i];
+        if ((b.flags & ~0x30u) || (b.flags & 0x30u) == 0x30u) return EXCP_E_ARG;
         if (b.n > c->max_tensor) return EXCP_E_ARG;
         if (!b.blob || ((uintptr_t)b.blob & 15u)) return EXCP_E_ARG;
         if (b.n && !b.W_prev_recon) return EXCP_E_ARG;
@@ -516,9 +519,9 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
         for (u32 q = 0; q < g.count; ++q) {
             const excp_blob &b = blobs[g.first + q];
             DDesc &d = c->h_ddesc[g.first + q];
-            d.Wp = b.W_prev_recon; d.blob = (const unsigned char *)b.blob; d.blob_bytes = b.blob_bytes; d.n = b.n;
-            d.W_out = b.W_recon_out; d.m_out = b.m_out; d.v_out = b.v_out;
-            d.cw = d.cm = d.cv = d.head = nullptr;
+            d.Wp = (const float *)b.W_prev_recon; d.blob = (const unsigned char *)b.blob; d.blob_bytes = b.blob_bytes; d.n = b.n;
+            d.W_out = (float *)b.W_recon_out; d.m_out = b.m_out; d.v_out = b.v_out;
+            d.cw = d.cm = d.cv = d.head = nullptr; d.wtype = (b.flags >> 4) & 3u; d.pad = 0;
             d.tile_begin = tile; d.tile_count = (u32)((b.n + EXCP_TILE - 1) / EXCP_TILE);
             c->h_tile_begin[tb_off + q] = tile;
             tile += d.tile_count;
@@ -576,6 +579,7 @@ int excp_export_dense(excp_ctx *c, int count, const excp_dense_export *items) {
         d.Wp = nullptr; d.blob = (const unsigned char *)e.blob; d.blob_bytes = e.blob_bytes; d.n = e.n;
         d.W_out = d.m_out = d.v_out = nullptr;
         d.cw = e.codes_w; d.cm = e.codes_m; d.cv = e.codes_v; d.head = (unsigned char *)e.head;
+        d.wtype = 3u; d.pad = 0;
     });
 }
 
@@ -585,6 +589,7 @@ int excp_decompress_dense(excp_ctx *c, int count, const excp_dense_blob *items) 
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     for (int i = 0; i < count; ++i) {
         const excp_dense_blob &e = items[i];
+        if ((e.flags & ~0x30u) || (e.flags & 0x30u) == 0x30u) return EXCP_E_ARG;
         if (e.n > c->max_tensor) return EXCP_E_ARG;
         if (!e.head || ((uintptr_t)e.head & 15u)) return EXCP_E_ARG;
         if (((uintptr_t)e.codes_w | (uintptr_t)e.codes_m | (uintptr_t)e.codes_v) & 15u) return EXCP_E_ARG;
@@ -593,9 +598,10 @@ int excp_decompress_dense(excp_ctx *c, int count, const excp_dense_blob *items) 
     }
     return run_dense(c, count, false, [&](u32 i, DDesc &d) {
         const excp_dense_blob &e = items[i];
-        d.Wp = e.W_prev_recon; d.blob = (const unsigned char *)e.head; d.blob_bytes = e.head_bytes; d.n = e.n;
-        d.W_out = e.W_recon_out; d.m_out = e.m_out; d.v_out = e.v_out;
+        d.Wp = (const float *)e.W_prev_recon; d.blob = (const unsigned char *)e.head; d.blob_bytes = e.head_bytes; d.n = e.n;
+        d.W_out = (float *)e.W_recon_out; d.m_out = e.m_out; d.v_out = e.v_out;
         d.cw = (unsigned char *)e.codes_w; d.cm = (unsigned char *)e.codes_m; d.cv = (unsigned char *)e.codes_v; d.head = nullptr;
+        d.wtype = (e.flags >> 4) & 3u; d.pad = 0;
     });
 }
 
@@ -606,6 +612,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
     u64 total_descs = 0;
     for (int i = 0; i < count; ++i) {
         const excp_chain &ch = chains[i];
+        if ((ch.flags & ~0x30u) || (ch.flags & 0x30u) == 0x30u) return EXCP_E_ARG;
         if (ch.n > c->max_tensor || ch.steps < 1 || ch.steps > EXCP_MAX_CHAIN) return EXCP_E_ARG;
         if (!ch.blobs || !ch.blob_bytes) return EXCP_E_ARG;
         if (ch.n && !ch.W0) return EXCP_E_ARG;
@@ -638,7 +645,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
             const excp_chain &ch = chains[g.first + q];
             const u32 tiles = (u32)((ch.n + EXCP_TILE - 1) / EXCP_TILE);
             CDesc &cd = c->h_cdesc[g.first + q];
-            cd.W0 = ch.W0; cd.W_out = ch.W_out; cd.n = ch.n; cd.first_desc = d; cd.steps = (u32)ch.steps;
+            cd.W0 = (const float *)ch.W0; cd.W_out = (float *)ch.W_out; cd.n = ch.n; cd.first_desc = d; cd.steps = (u32)ch.steps;
             cd.tile_begin = ctile; cd.tile_count = tiles;
             c->h_tile_begin[g.tb_chain + q] = ctile;
             ctile += tiles;
@@ -647,7 +654,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
                 const bool last = j + 1 == ch.steps;
                 dd.Wp = nullptr; dd.blob = (const unsigned char *)ch.blobs[j]; dd.blob_bytes = ch.blob_bytes[j]; dd.n = ch.n;
                 dd.W_out = nullptr; dd.m_out = last ? ch.m_out : nullptr; dd.v_out = last ? ch.v_out : nullptr;
-                dd.cw = dd.cm = dd.cv = dd.head = nullptr;
+                dd.cw = dd.cm = dd.cv = dd.head = nullptr; dd.wtype = (ch.flags >> 4) & 3u; dd.pad = 0;
                 dd.tile_begin = dtile; dd.tile_count = tiles;
                 c->h_tile_begin[g.tb_desc + d] = dtile;
                 dtile += tiles;
@@ -687,7 +694,11 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
             if (moments) { launch_decode_count(w, g.ndescs, dtiles, 1, s); launch_decode_scan(w, g.ndescs, 1, s); }
         }
         { StageTimer t(c, ST_DECODE_MAIN); launch_decode_chain(w, g.count, g.ntiles, s); }
-        if (moments) { StageTimer t(c, ST_DECODE_MAIN); launch_decode_main(w, g.ndescs, dtiles, true, s); }   // the last checkpoints' moments
+        if (moments) {      // the last checkpoints' moments
+            StageTimer t(c, ST_DECODE_MAIN);
+            launch_decode_main(w, g.ndescs, dtiles, true, s);
+            launch_decode_main16(w, g.ndescs, dtiles, true, s);
+        }
         { StageTimer t(c, ST_MISC); launch_chain_finish(w, g.count, s); }
     }
     if (count) {
@@ -740,10 +751,10 @@ int excp_collect(excp_ctx *c, excp_stats *stats) {
     return first;
 }
 
-int excp_compress_step(excp_ctx *c, const float *W_prev_recon, const float *W_t, const float *m_t,
+int excp_compress_step(excp_ctx *c, const void *W_prev_recon, const void *W_t, const float *m_t,
                        const float *v_t, uint64_t n, float alpha, float beta, int nbits, int lloyd_iters,
                        uint32_t flags, void *blob_out, uint64_t blob_cap, uint64_t *blob_bytes,
-                       float *W_recon_out, excp_stats *stats) {
+                       void *W_recon_out, excp_stats *stats) {
     excp_tensor t{W_prev_recon, W_t, m_t, v_t, n, blob_out, blob_cap, W_recon_out};
     int rc = excp_compress_tensors(c, 1, &t, alpha, beta, nbits, lloyd_iters, flags);
     if (rc != EXCP_OK) return rc;
@@ -754,9 +765,9 @@ int excp_compress_step(excp_ctx *c, const float *W_prev_recon, const float *W_t,
     return rc;
 }
 
-int excp_decompress_step(excp_ctx *c, const float *W_prev_recon, const void *blob, uint64_t blob_bytes,
-                         uint64_t n, float *W_recon_out, float *m_out, float *v_out) {
-    excp_blob b{W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out};
+int excp_decompress_step(excp_ctx *c, const void *W_prev_recon, const void *blob, uint64_t blob_bytes,
+                         uint64_t n, void *W_recon_out, float *m_out, float *v_out, uint32_t flags) {
+    excp_blob b{W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out, flags, 0};
     int rc = excp_decompress_tensors(c, 1, &b);
     if (rc != EXCP_OK) return rc;
     return excp_collect(c, nullptr);

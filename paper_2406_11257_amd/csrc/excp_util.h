@@ -55,6 +55,31 @@ __device__ __forceinline__ const EXCP_GLOBAL T *gptr(const T *p) { return (const
 template <class T>
 __device__ __forceinline__ EXCP_GLOBAL T *gptr(T *p) { return (EXCP_GLOBAL T *)(uintptr_t)p; }
 
+// Weights stored in 16 bits (flags bits 4-5 of a compress call or a blob header: 1 = IEEE binary16,
+// 2 = bfloat16).  Widening is exact; narrowing rounds to nearest even (a finite fp32 beyond the
+// format's range becomes infinity, as IEEE conversion does).  All arithmetic stays fp32.
+__device__ __forceinline__ u32 excp_wtype(u32 flags) { return (flags >> 4) & 3u; }
+__device__ __forceinline__ float w16_widen(u32 h, bool bf) {
+    const float half = (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    return bf ? u2f(h << 16) : half;
+}
+__device__ __forceinline__ u32 w16_narrow(float x, bool bf) {
+    const u32 b = f2u(x);
+    const u32 bf_bits = (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;       // never a NaN here: inputs are finite
+    const u32 half_bits = (u32)__builtin_bit_cast(unsigned short, (_Float16)x);
+    return bf ? bf_bits : half_bits;
+}
+typedef unsigned short us4 __attribute__((ext_vector_type(4), aligned(8)));
+// One weight at index idx of an array whose element type is given by wt (0 = fp32).
+__device__ __forceinline__ float load_weight(const float *p, u64 idx, u32 wt) {
+    if (wt == 0u) return p[idx];
+    return w16_widen(((const unsigned short *)p)[idx], wt == 2u);
+}
+__device__ __forceinline__ void store_weight(float *p, u64 idx, u32 wt, float x) {
+    if (wt == 0u) p[idx] = x;
+    else ((unsigned short *)p)[idx] = (unsigned short)w16_narrow(x, wt == 2u);
+}
+
 // Copy of a tile table in LDS (the per-tile owner search then costs no global round trips).
 #define EXCP_MAX_GROUP_TENSORS 1024
 __device__ __forceinline__ void load_tile_table(u32 *dst, const u32 *__restrict__ src, u32 count) {

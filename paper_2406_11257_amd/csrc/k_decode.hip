@@ -49,9 +49,10 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors, u32 allow_raw) {
     const u64 n = h64[2], nw = h64[3], no = h64[4], total = h64[8];
     const bool raw = (h[3] & 4u) != 0u;                   // written without quantisation: fp32 values, no codebooks
     const bool nw2m = (h[3] & 8u) != 0u;                  // bitmap_o over all elements, not over the kept residuals
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && h[3] < 16u;
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && h[3] < 64u && (h[3] & 0x30u) != 0x30u;
     ok = ok && (raw ? (nbits == EXCP_RAW_BITS && allow_raw != 0u) : (nbits >= 2u && nbits <= 8u));
     ok = ok && n == D.n && nw <= n && no <= (nw2m ? n : nw);
+    ok = ok && (D.wtype == 3u || D.wtype == excp_wtype(h[3]));      // the caller's arrays are what the blob expects
     u64 off = EXCP_HEADER;
     if (ok) {
         off += excp_books_bytes(nbits);
@@ -187,7 +188,11 @@ __device__ __forceinline__ void store_codes4(unsigned char *dst, u64 e0, u32 lef
 // RAW: blobs written without quantisation hold fp32 values where the others hold codes; a lane reads
 // its survivors' values straight from the blob (consecutive lanes, consecutive addresses).  Such
 // blobs are skipped by the other instantiations, and this one skips everything else.
-template <bool MOMENTS, bool DENSE, bool RAW>
+//
+// WMODE: which weight storage this instantiation takes (blob flags bits 4-5): 0 = fp32 blobs only,
+// 1 = blobs of 16-bit weights only (fp16 / bf16: widened exactly, the sum rounded to nearest even
+// into the format, pruned positions keep their bits), 2 = both, decided per tensor.
+template <bool MOMENTS, bool DENSE, bool RAW, int WMODE>
 __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u32 ntiles) {
     __shared__ float s_book[DENSE || RAW ? 1 : 3 * 256];
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
@@ -203,6 +208,10 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
         const DState &S = w.dst[t];
         if (S.status != 0) continue;                       // same decision for the whole workgroup
         if ((S.nbits == EXCP_RAW_BITS) != RAW) continue;
+        const u32 wt = WMODE == 0 ? 0u : excp_wtype(S.flags);
+        if (WMODE == 0 && excp_wtype(S.flags) != 0u) continue;
+        if (WMODE == 1 && wt == 0u) continue;
+        const bool bf = wt == 2u;
         const u32 nbits = S.nbits, E = RAW ? 0u : 1u << (nbits & 15u), cmask = E - 1u;
         const u64 n = D.n;
         const u32 ltile = tile - D.tile_begin;
@@ -217,7 +226,20 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 
         // previous weights of the lane's 4 x 4 elements: issued first, consumed last
         float wp[4][4];
-        if (!DENSE && has_w) {
+        us4 hp[4];                                         // 16-bit weights stay as they are until the sum
+        if (!DENSE && has_w && WMODE != 0 && wt != 0u) {
+            const EXCP_GLOBAL unsigned short *Hp = gptr((const unsigned short *)D.Wp) + base;
+            const bool vec = ((uintptr_t)D.Wp & 7u) == 0u;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+                if (vec && off + 4u <= rem) hp[k] = *(const EXCP_GLOBAL us4 *)(Hp + off);
+                else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) hp[k][j] = (off + (u32)j < rem) ? Hp[off + (u32)j] : (unsigned short)0;
+                }
+            }
+        } else if (!DENSE && has_w) {
             const EXCP_GLOBAL float *Wp = gptr(D.Wp) + base;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -325,6 +347,24 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
                     }
                     store_codes4(D.cw, base + off, rem - min(rem, off), nbits, c);
                 }
+            } else if (has_w && WMODE != 0 && wt != 0u) {
+                us4 o16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool kept = (nib >> j) & 1u;
+                    float c;
+                    if (RAW) { c = kept ? *xw : 0.f; xw += kept; }
+                    else c = s_book[f & cmask];
+                    const u32 h = hp[k][j];
+                    o16[j] = (unsigned short)(kept ? w16_narrow(w16_widen(h, bf) + c, bf) : h);
+                    f = kept ? (f >> nbits) : f;
+                }
+                EXCP_GLOBAL unsigned short *Ho = gptr((unsigned short *)D.W_out) + base;
+                if (((uintptr_t)D.W_out & 7u) == 0u && off + 4u <= rem) *(EXCP_GLOBAL us4 *)(Ho + off) = o16;
+                else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) if (off + (u32)j < rem) Ho[off + (u32)j] = o16[j];
+                }
             } else if (has_w) {
                 float out[4];
 #pragma unroll
@@ -406,7 +446,21 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
-    decode_tiles<MOMENTS, false, false>(w, ntensors, ntiles);
+    decode_tiles<MOMENTS, false, false, 0>(w, ntensors, ntiles);
+}
+// The same for blobs of 16-bit weights.  Most batches hold none: leave at once then.
+template <bool MOMENTS>
+__global__ __launch_bounds__(EXCP_THREADS) void k_decode_main16(Workspace w, u32 ntensors, u32 ntiles) {
+    __shared__ u32 s_any;
+    if (threadIdx.x == 0) s_any = 0u;
+    __syncthreads();
+    bool mine = false;
+    for (u32 t = threadIdx.x; t < ntensors; t += EXCP_THREADS)
+        mine = mine || (w.dst[t].status == 0 && w.dst[t].nbits != EXCP_RAW_BITS && excp_wtype(w.dst[t].flags) != 0u);
+    if (mine) s_any = 1u;
+    __syncthreads();
+    if (s_any == 0u) return;
+    decode_tiles<MOMENTS, false, false, 1>(w, ntensors, ntiles);
 }
 // Blobs written without quantisation.  Most batches hold none: leave at once then.
 template <bool MOMENTS>
@@ -420,11 +474,11 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_raw(Workspace w, u32 nt
     if (mine) s_any = 1u;
     __syncthreads();
     if (s_any == 0u) return;
-    decode_tiles<MOMENTS, false, true>(w, ntensors, ntiles);
+    decode_tiles<MOMENTS, false, true, 2>(w, ntensors, ntiles);
 }
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, 8) void k_export_dense(Workspace w, u32 ntensors, u32 ntiles) {
-    decode_tiles<MOMENTS, true, false>(w, ntensors, ntiles);
+    decode_tiles<MOMENTS, true, false, 2>(w, ntensors, ntiles);
 }
 
 // Alg. 3: W_0 plus a chain of compressed checkpoints, oldest first, in ONE pass over the weights.
@@ -442,14 +496,17 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u
         const CDesc &C = w.cdesc[t];
         if (C.W_out == nullptr) continue;
         bool good = true;                                  // every checkpoint of the chain parsed and counted fine
-        for (u32 j = 0; j < C.steps; ++j) good = good && w.dst[C.first_desc + j].status == 0;
+        const u32 wt = excp_wtype(w.dst[C.first_desc].flags);      // ... and all store their weights alike
+        for (u32 j = 0; j < C.steps; ++j)
+            good = good && w.dst[C.first_desc + j].status == 0 && excp_wtype(w.dst[C.first_desc + j].flags) == wt;
         if (!good) continue;                               // same decision for the whole workgroup
+        const bool bf = wt == 2u;
         const u64 n = C.n;
         const u32 ltile = tile - C.tile_begin;
         const u64 base = (u64)ltile * EXCP_TILE;
         const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
         float wp[4][4];
-        {
+        if (wt == 0u) {
             const EXCP_GLOBAL float *W0 = gptr(C.W0) + base;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -461,6 +518,15 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u
 #pragma unroll
                     for (int j = 0; j < 4; ++j) wp[k][j] = (off + (u32)j < rem) ? W0[off + (u32)j] : 0.f;
                 }
+            }
+        }
+        if (wt != 0u) {                                    // 16-bit weights: the registers hold the widened values
+            const EXCP_GLOBAL unsigned short *H0 = gptr((const unsigned short *)C.W0) + base;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wp[k][j] = (off + (u32)j < rem) ? w16_widen(H0[off + (u32)j], bf) : 0.f;
             }
         }
         for (u32 step = 0; step < C.steps; ++step) {
@@ -508,10 +574,23 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u
                 for (int j = 0; j < 4; ++j) {
                     const bool kept = (nib >> j) & 1u;
                     const float c = s_book[f & cmask];
-                    wp[k][j] = kept ? wp[k][j] + c : wp[k][j];
+                    float sum = wp[k][j] + c;
+                    if (wt != 0u) sum = w16_widen(w16_narrow(sum, bf), bf);   // every checkpoint rounds into the storage format
+                    wp[k][j] = kept ? sum : wp[k][j];
                     f = kept ? (f >> nbits) : f;
                 }
             }
+        }
+        if (wt != 0u) {
+            EXCP_GLOBAL unsigned short *Ho = gptr((unsigned short *)C.W_out) + base;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (off + (u32)j < rem) Ho[off + (u32)j] = (unsigned short)w16_narrow(wp[k][j], bf);
+            }
+            continue;
         }
         EXCP_GLOBAL float *Wo = gptr(C.W_out) + base;
 #pragma unroll
@@ -534,7 +613,10 @@ __global__ void k_chain_finish(Workspace w, u32 ntensors, u32 rec_base) {
     if (t >= ntensors) return;
     const CDesc &C = w.cdesc[t];
     int status = 0;
-    for (u32 j = 0; j < C.steps && status == 0; ++j) status = w.dst[C.first_desc + j].status;
+    for (u32 j = 0; j < C.steps && status == 0; ++j) {
+        status = w.dst[C.first_desc + j].status;
+        if (status == 0 && excp_wtype(w.dst[C.first_desc + j].flags) != excp_wtype(w.dst[C.first_desc].flags)) status = -4;
+    }
     const DState &S = w.dst[C.first_desc + C.steps - 1u];
     HostRec &R = w.rec_dev[rec_base + t];
     R.n = C.n; R.n_w = S.n_w; R.n_o = S.n_o; R.blob_bytes = S.blob_bytes; R.nonfinite = 0;
@@ -578,10 +660,11 @@ __global__ void k_dense_parse(Workspace w, u32 ntensors) {
     const u32 *h = (const u32 *)D.blob;
     const u64 *h64 = (const u64 *)D.blob;
     const u32 nbits = h[2];
-    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 16u;
+    bool ok = h[0] == EXCP_MAGIC && h[1] == EXCP_VERSION && nbits >= 2u && nbits <= 8u && h[3] < 64u && (h[3] & 0x30u) != 0x30u;
     ok = ok && h64[2] == D.n && D.blob_bytes >= EXCP_HEADER + 12ull * (1u << (nbits & 15u));
+    ok = ok && (D.wtype == 3u || D.wtype == excp_wtype(h[3]));
     if (!ok) { S.status = -4; return; }
-    S.n_w = h64[3]; S.n_o = h64[4]; S.nbits = nbits; S.blob_bytes = h64[8];
+    S.n_w = h64[3]; S.n_o = h64[4]; S.nbits = nbits; S.blob_bytes = h64[8]; S.flags = h[3];
 }
 
 // Eight consecutive elements per lane and step: one 32-bit (or 64-bit) load of codes per tensor,
@@ -601,6 +684,8 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_dense(Workspace w, u32 
         if (S.status != 0 && S.status != -40) continue;    // -40: damage found by another workgroup meanwhile
         const u32 nbits = S.nbits, E = 1u << nbits;
         const bool wide = nbits > 4u;
+        const u32 wt = excp_wtype(S.flags);                // 16-bit weights: widen, add, round into the format
+        const bool bf = wt == 2u;
         const u64 n = D.n;
         const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
         const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
@@ -642,6 +727,23 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_dense(Workspace w, u32 
                 }
                 float x[8];
                 EXCP_GLOBAL float *out = gptr(dst[q]) + e0;
+                if (q == 0 && wt != 0u) {
+                    const EXCP_GLOBAL unsigned short *Hp = gptr((const unsigned short *)D.Wp) + e0;
+                    EXCP_GLOBAL unsigned short *Ho = gptr((unsigned short *)D.W_out) + e0;
+                    u32 h[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) h[j] = ((u32)j < left) ? Hp[j] : 0u;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const u32 c = (u32)(c8 >> (8 * j)) & 255u;
+                        if (c >= E) bad = true;
+                        const float centre = s_book[c & (E - 1u)];
+                        if (c) h[j] = w16_narrow(w16_widen(h[j], bf) + centre, bf);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) if ((u32)j < left) Ho[j] = (unsigned short)h[j];
+                    continue;
+                }
                 if (q == 0) {
                     const EXCP_GLOBAL float *Wp = gptr(D.Wp) + e0;
                     if (left == 8u) {
@@ -690,7 +792,7 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     DState &S = w.dst[t];
     D.Wp = C.Wp; D.blob = C.blob; D.blob_bytes = T.blob_bytes; D.n = C.n;
     D.W_out = C.W_out; D.m_out = nullptr; D.v_out = nullptr;
-    D.cw = nullptr; D.cm = nullptr; D.cv = nullptr; D.head = nullptr;
+    D.cw = nullptr; D.cm = nullptr; D.cv = nullptr; D.head = nullptr; D.wtype = excp_wtype(g.flags); D.pad = 0;
     D.tile_begin = C.tile_begin; D.tile_count = C.tile_count;
     S.n_w = T.n_w; S.n_o = T.n_o; S.blob_bytes = T.blob_bytes; S.nbits = (u32)g.nbits;
     S.off_bw = EXCP_HEADER + excp_books_bytes((u32)g.nbits);
@@ -735,6 +837,13 @@ void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool momen
     if (blocks > ntiles) blocks = ntiles;
     if (moments) hipLaunchKernelGGL(k_decode_main<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
     else hipLaunchKernelGGL(k_decode_main<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+}
+void launch_decode_main16(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
+    if (!ntiles) return;
+    u32 blocks = excp_grid(w, 64);
+    if (blocks > ntiles) blocks = ntiles;
+    if (moments) hipLaunchKernelGGL(k_decode_main16<true>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
+    else hipLaunchKernelGGL(k_decode_main16<false>, dim3(blocks), dim3(EXCP_THREADS), 0, s, w, ntensors, ntiles);
 }
 void launch_decode_raw(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
     if (!ntiles) return;

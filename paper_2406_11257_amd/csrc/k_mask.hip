@@ -37,7 +37,8 @@ struct Regs {
 // NW2M (Table "vit", no weights-to-momentum check): M_o(i) = |m_i| > r_o for every element, kept
 // weight or not.  The moment survivors are then compacted from the elements themselves, and the
 // sub-tile's M_o words are indexed by element.
-template <bool NW2M>
+// W16: the two weight arrays hold 16-bit values (fp16 or bf16 by the flags), widened as they arrive.
+template <bool NW2M, bool W16>
 __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, GroupParams g) {
     __shared__ float l_w[SUB], l_m[SUB], l_v[SUB];      // compacted survivors of one sub-tile
     __shared__ u32 s_w[4], s_o[4];
@@ -54,22 +55,27 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, Gro
         const TDesc &D = w.desc[t];
         const u64 n = D.n;
         const u64 base = (u64)(tile - s_tiles[t]) * EXCP_TILE + (u64)(sub & 1u) * SUB;
+        const bool bf = W16 && excp_wtype(g.flags) == 2u;
         if (base + SUB <= n) {
             // full sub-tile: one address per array and lane, the batches are immediate offsets
             const u64 first = base + (u64)(wave * (SUB / 4) + lane);
             const EXCP_GLOBAL float *gW = gptr(D.W) + first, *gP = gptr(D.Wp) + first;
+            const EXCP_GLOBAL unsigned short *hW = gptr((const unsigned short *)D.W) + first;
+            const EXCP_GLOBAL unsigned short *hP = gptr((const unsigned short *)D.Wp) + first;
             const EXCP_GLOBAL float *gM = gptr(D.m) + first, *gV = gptr(D.v) + first;
 #pragma unroll
             for (int j = 0; j < NBATCH; ++j) {
-                R.w[j] = gW[j * 64]; R.p[j] = gP[j * 64]; R.m[j] = gM[j * 64]; R.v[j] = gV[j * 64];
+                if (W16) { R.w[j] = w16_widen(hW[j * 64], bf); R.p[j] = w16_widen(hP[j * 64], bf); }
+                else { R.w[j] = gW[j * 64]; R.p[j] = gP[j * 64]; }
+                R.m[j] = gM[j * 64]; R.v[j] = gV[j * 64];
             }
         } else {
 #pragma unroll
             for (int j = 0; j < NBATCH; ++j) {
                 const u64 idx = base + (u64)((wave * NBATCH + j) * 64 + lane);
                 const bool ok = idx < n;
-                R.w[j] = ok ? D.W[idx] : 0.f;
-                R.p[j] = ok ? D.Wp[idx] : 0.f;
+                R.w[j] = ok ? load_weight(D.W, idx, W16 ? excp_wtype(g.flags) : 0u) : 0.f;
+                R.p[j] = ok ? load_weight(D.Wp, idx, W16 ? excp_wtype(g.flags) : 0u) : 0.f;
                 R.m[j] = ok ? D.m[idx] : 0.f;
                 R.v[j] = ok ? D.v[idx] : 1.f;
             }
@@ -484,8 +490,11 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
     if (phase == 0) {
         u32 grid = excp_grid(w, 20);
         if (grid > nsub) grid = nsub;
-        if (g.flags & 8u) hipLaunchKernelGGL(k_mask_slots<true>, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
-        else hipLaunchKernelGGL(k_mask_slots<false>, dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        const bool nw2m = (g.flags & 8u) != 0, w16 = (g.flags & 0x30u) != 0;
+        if (nw2m && w16) hipLaunchKernelGGL((k_mask_slots<true, true>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        else if (nw2m) hipLaunchKernelGGL((k_mask_slots<true, false>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        else if (w16) hipLaunchKernelGGL((k_mask_slots<false, true>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
+        else hipLaunchKernelGGL((k_mask_slots<false, false>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     } else if (phase == 1) {
         hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
     } else {

@@ -63,7 +63,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, Gro
         u32 k = 0xffffffffu;
         if (i < ns) {
             const u64 idx = n <= MED_SAMPLE ? (u64)i : ((u64)i * n) / MED_SAMPLE;
-            k = f2u((g.flags & 1u) ? D.W[idx] : D.W[idx] - D.Wp[idx]) & 0x7fffffffu;   // flag: median of |W_t|
+            const u32 wt = excp_wtype(g.flags);
+            const float wv = load_weight(D.W, idx, wt);
+            k = f2u((g.flags & 1u) ? wv : wv - load_weight(D.Wp, idx, wt)) & 0x7fffffffu;   // flag: median of |W_t|
             const u32 mb = f2u(D.m[idx]) & 0x7fffffffu;
             if (mb < 0x7f800000u) mmax = max(mmax, mb);
         }
@@ -95,6 +97,9 @@ typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 // The streaming pass: exact sum of |m|, non-finite check, count of keys below the bracket and
 // collection of the keys inside it.  Persistent workgroups over contiguous tile ranges; a lane
 // takes four consecutive elements of each of four 256-element rows of its wave's quarter tile.
+// W16: the weights are 16-bit (fp16 or bf16 by the flags), four to an 8-byte load where the arrays
+// allow it; they are widened on arrival and everything after that is the fp32 code.
+template <bool W16>
 __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, GroupParams g) {
     __shared__ u64 bins[EXCP_ABSM_BINS];
     __shared__ u32 l_cand[4][2 * CAND_PER_WAVE + 1];   // per wave: staged candidates, plus a spare slot
@@ -179,13 +184,25 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
         const bool of_weights = (g.flags & 1u) != 0;       // the median is that of |W_t|, not of the residual
         {
             const EXCP_GLOBAL float *gW = gptr(D.W) + base, *gP = gptr(D.Wp) + base, *gM = gptr(D.m) + base;
-            if (rem == EXCP_TILE) {
+            const u32 wt = W16 ? excp_wtype(g.flags) : 0u;
+            const bool bf = wt == 2u;
+            const EXCP_GLOBAL unsigned short *hW = gptr((const unsigned short *)D.W) + base;
+            const EXCP_GLOBAL unsigned short *hP = gptr((const unsigned short *)D.Wp) + base;
+            const bool vec16 = W16 && (((uintptr_t)D.W | (uintptr_t)D.Wp) & 7u) == 0u;   // 8-byte loads need 8-byte alignment
+            if (rem == EXCP_TILE && (!W16 || vec16)) {
                 f4u a[4], p[4], mm[4];
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
-                    a[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gW + off));
-                    p[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gP + off));
+                    if (W16) {
+                        const us4 ha = __builtin_nontemporal_load((const EXCP_GLOBAL us4 *)(hW + off));
+                        const us4 hp = __builtin_nontemporal_load((const EXCP_GLOBAL us4 *)(hP + off));
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) { a[k][j] = w16_widen(ha[j], bf); p[k][j] = w16_widen(hp[j], bf); }
+                    } else {
+                        a[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gW + off));
+                        p[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gP + off));
+                    }
                     mm[k] = __builtin_nontemporal_load((const EXCP_GLOBAL f4u *)(gM + off));
                 }
 #pragma unroll
@@ -204,7 +221,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
                 for (int j = 0; j < 16; ++j) {
                     const u32 off = wave * 1024u + (u32)(j >> 2) * 256u + lane * 4u + (u32)(j & 3);
                     const bool ok = off < rem;
-                    const float av = ok ? gW[off] : 0.f, pv = ok ? gP[off] : 0.f, mv = ok ? gM[off] : 0.f;
+                    float av = 0.f, pv = 0.f;
+                    if (ok) {
+                        av = W16 ? w16_widen(hW[off], bf) : gW[off];
+                        pv = W16 ? w16_widen(hP[off], bf) : gP[off];
+                    }
+                    const float mv = ok ? gM[off] : 0.f;
                     const u32 dk = f2u(av - pv) & 0x7fffffffu, wk = f2u(av) & 0x7fffffffu;
                     mb[j] = f2u(mv) & 0x7fffffffu;
                     worst = max(max(worst, dk), max(mb[j], max(wk, f2u(pv) & 0x7fffffffu)));
@@ -402,7 +424,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_full_hist(Workspace w, GroupPa
         for (int j = 0; j < 16; ++j) {
             const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
             if (idx < n) {
-                const u32 k = f2u((g.flags & 1u) ? D.W[idx] : D.W[idx] - D.Wp[idx]) & 0x7fffffffu;
+                const u32 wt = excp_wtype(g.flags);
+                const float wv = load_weight(D.W, idx, wt);
+                const u32 k = f2u((g.flags & 1u) ? wv : wv - load_weight(D.Wp, idx, wt)) & 0x7fffffffu;
                 if (PASS == 0) atomicAdd(&hist[k >> 20], 1u);
                 if (PASS == 1) { if ((k >> 20) == prefix) atomicAdd(&hist[(k >> 9) & 2047u], 1u); }
                 if (PASS == 2) { if ((k >> 9) == prefix) atomicAdd(&hist[k & 511u], 1u); }
@@ -541,7 +565,11 @@ void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream
     const dim3 stream_grid(excp_grid(w, 8));
     switch (phase) {
         case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, block, 0, s, w, g); break;
-        case 1: if (g.ntiles) hipLaunchKernelGGL(k_stats_stream, stream_grid, block, 0, s, w, g); break;
+        case 1:
+            if (!g.ntiles) break;
+            if (g.flags & 0x30u) hipLaunchKernelGGL(k_stats_stream<true>, stream_grid, block, 0, s, w, g);
+            else hipLaunchKernelGGL(k_stats_stream<false>, stream_grid, block, 0, s, w, g);
+            break;
         case 2: hipLaunchKernelGGL(k_cand_begin, small, dim3(256), 0, s, w, g); break;
         case 3: if (g.ntiles) hipLaunchKernelGGL(k_cand_hist, dim3((g.ntiles + CAND_TILES - 1) / CAND_TILES), block, 0, s, w, g); break;
         case 4: hipLaunchKernelGGL(k_cand_resolve, per_tensor, block, 0, s, w, g); break;

@@ -171,4 +171,4 @@ def test_no_w2m_through_the_stored_layout_and_the_chain(ctx):
     rc, _ = gpu_decompress(ctx, Wp, bytes(b), n)
     assert rc == X.EXCP_E_BLOB
     with pytest.raises(X.ExcpError):
-        ctx.excp_compress_tensors([], 5e-5, 2.0, 4, 2, 16)
+        ctx.excp_compress_tensors([], 5e-5, 2.0, 4, 2, 64)

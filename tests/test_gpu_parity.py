@@ -465,7 +465,7 @@ def test_ablation_switches(ctx, flags, alpha):
         assert t[4][:int(st.blob_bytes)].cpu().numpy().tobytes() == ref.blob
         assert np.array_equal(t[5].cpu().numpy().view(np.uint32), ref.W_recon.view(np.uint32))
     with pytest.raises(X.ExcpError):
-        ctx.excp_compress_tensors(dev[:1], alpha, 2.0, 4, 5, 16)
+        ctx.excp_compress_tensors(dev[:1], alpha, 2.0, 4, 5, 64)
 
 
 def test_errors_are_reported_not_faulted(ctx):
@@ -496,7 +496,7 @@ def test_errors_are_reported_not_faulted(ctx):
     d = [to_dev(a) for a in (Wp, W, m, v)]
     blob = torch.zeros(X.excp_blob_bound(Wp.size, 4), dtype=torch.uint8, device="cuda")
     for kw in (dict(nbits=1), dict(nbits=9), dict(lloyd_iters=-1), dict(alpha=-1.0), dict(beta=float("nan")),
-               dict(flags=16)):
+               dict(flags=64)):
         rc, _, _ = ctx.excp_compress_step(*d, blob, check=False, **kw)
         assert rc == X.EXCP_E_ARG, kw
     # damaged blobs

@@ -1,0 +1,240 @@
+"""GPU parity for weights stored in 16 bits (fp16 / bf16; the paper's PanGu checkpoints are fp16):
+blob for blob and bit for bit against the oracle, through compress, Alg. 2, Alg. 3 and the stored
+layout of Sec. 4.2."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import paper_2406_11257_amd as X
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+F16, BF16 = O.FLAG_W_F16, O.FLAG_W_BF16
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = X.Context(4 << 20, 6 << 20)
+    yield c
+    c.close()
+
+
+def w_to_dev(a, flag):
+    """numpy storage array (float32 / float16 / uint16 bit patterns of bf16) -> torch CUDA tensor."""
+    a = np.ascontiguousarray(a)
+    if flag & BF16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def w_to_host(t, flag):
+    if flag & BF16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint16 if a.dtype.itemsize == 2 else np.uint32)
+
+
+def case16(n, seed, flag, scale=3e-4, still=0.0):
+    """A checkpoint pair in 16-bit storage; `still` = fraction of weights that did not move at all."""
+    g = np.random.default_rng(seed)
+    Wp = O.narrow((g.standard_normal(n) * 0.02).astype(f32), flag)
+    step = g.laplace(0, scale, n).astype(f32)
+    if still:
+        step[g.random(n) < still] = 0
+    W = O.narrow((O.widen(Wp, flag) + step).astype(f32), flag)
+    m = (g.standard_normal(n) * 5e-5).astype(f32)
+    v = (m.astype(np.float64) ** 2 * g.lognormal(0, 1, n) + 1e-16).astype(f32)
+    return Wp, W, m, v
+
+
+def compress16(ctx, cases, flags, alpha=5e-5, beta=2.0, nbits=4, iters=3, shift=0):
+    """shift: start every weight array `shift` elements into its allocation (2-byte alignment only)."""
+    dev = []
+    for (Wp, W, m, v) in cases:
+        n = W.size
+        pad = lambda a: np.concatenate([np.zeros(shift, a.dtype), a])
+        blob = torch.zeros(X.excp_blob_bound(n, 32 if flags & 4 else nbits), dtype=torch.uint8, device="cuda")
+        Wout = torch.zeros(n + shift, dtype=w_to_dev(pad(Wp), flags).dtype, device="cuda")
+        dev.append((w_to_dev(pad(Wp), flags)[shift:], w_to_dev(pad(W), flags)[shift:],
+                    torch.from_numpy(m).cuda(), torch.from_numpy(v).cuda(), blob, Wout[shift:]))
+    ctx.excp_compress_tensors(dev, alpha, beta, nbits, iters, flags)
+    rc, stats = ctx.excp_collect(check=False)
+    return rc, stats, dev
+
+
+def check16(ctx, cases, flags, alpha=5e-5, beta=2.0, nbits=4, iters=3, shift=0):
+    rc, stats, dev = compress16(ctx, cases, flags, alpha, beta, nbits, iters, shift)
+    assert rc == 0
+    out = []
+    for c, t, st in zip(cases, dev, stats):
+        ref = O.compress_step(*c, alpha, beta, nbits, iters, flags=flags)
+        n = c[0].size
+        assert st.status == 0 and (st.n, st.n_w, st.n_o) == (n, ref.n_w, ref.n_o)
+        assert bits(np.array([st.median_abs_dw], f32))[0] == bits(np.array([ref.median], f32))[0]
+        blob = t[4][:int(st.blob_bytes)].cpu().numpy().tobytes()
+        assert blob == ref.blob
+        got = w_to_host(t[5], flags)
+        assert got.dtype == ref.W_recon.dtype and bits(got).tobytes() == bits(ref.W_recon).tobytes()
+        # Alg. 2 from the blob, with moments, into fresh outputs
+        Wout = torch.zeros_like(t[5])
+        mout = torch.empty(n, dtype=torch.float32, device="cuda")
+        vout = torch.empty(n, dtype=torch.float32, device="cuda")
+        ctx.excp_decompress_tensors([(t[0], t[4], int(st.blob_bytes), n, Wout, mout, vout)])
+        rc2, _ = ctx.excp_collect(check=False)
+        assert rc2 == 0
+        assert bits(w_to_host(Wout, flags)).tobytes() == bits(ref.W_recon).tobytes()
+        assert mout.cpu().numpy().tobytes() == ref.m_recon.tobytes() and vout.cpu().numpy().tobytes() == ref.v_recon.tobytes()
+        out.append((ref, t, st))
+    return out
+
+
+SIZES = [0, 1, 2, 3, 5, 63, 64, 65, 2047, 2049, 4095, 4097, 8193, 70001, (1 << 20) + 3]
+
+
+@pytest.mark.parametrize("flag", [F16, BF16])
+def test_sizes_with_ragged_tails(ctx, flag):
+    check16(ctx, [case16(n, 600 + i, flag) for i, n in enumerate(SIZES)], flag)
+
+
+@pytest.mark.parametrize("flag", [F16, BF16])
+def test_arrays_that_are_only_two_byte_aligned(ctx, flag):
+    check16(ctx, [case16(n, 620 + i, flag) for i, n in enumerate([5, 4097, 300001])], flag, shift=1)
+    check16(ctx, [case16(n, 630 + i, flag) for i, n in enumerate([4099, 150001])], flag, shift=3)
+
+
+@pytest.mark.parametrize("flags,alpha", [(F16 | 1, 5e-5), (BF16 | 2, 0.7), (F16 | 4, 5e-5), (BF16 | 8, 5e-5),
+                                         (F16 | 15, 0.01), (BF16 | 12, 5e-5)])
+def test_with_the_other_switches(ctx, flags, alpha):
+    check16(ctx, [case16(n, 640 + i, flags) for i, n in enumerate([7, 4097, 262145])], flags, alpha=alpha, beta=1.0)
+
+
+@pytest.mark.parametrize("flag", [F16, BF16])
+def test_most_weights_did_not_move(ctx, flag):
+    # 16-bit weights late in training: most residuals are exactly zero and the rest are a handful of
+    # distinct values.  The median is zero (the sample bracket cannot hold it: full selection), and the
+    # k-means streams are heavily tied.
+    cases = [case16(n, 660 + i, flag, scale=2e-5, still=0.6) for i, n in enumerate([4097, 1 << 20, (1 << 21) + 5])]
+    res = check16(ctx, cases, flag, alpha=5e-5, nbits=4, iters=10)
+    assert all(r.median == 0 for r, _, _ in res) and all(r.n_w > 0 for r, _, _ in res)
+    check16(ctx, cases[:2], flag, alpha=5e-5, nbits=2, iters=10)
+    check16(ctx, cases[:2], flag, alpha=5e-5, nbits=8, iters=4)
+
+
+@pytest.mark.parametrize("flag", [F16, BF16])
+def test_chain_of_checkpoints_rounds_at_every_step(ctx, flag):
+    n = 200003
+    Wp, W, m, v = case16(n, 680, flag)
+    g = np.random.default_rng(3)
+    blobs, devs, cur, start = [], [], Wp, Wp
+    for step in range(4):
+        W = O.narrow((O.widen(cur, flag) + g.laplace(0, 3e-4, n).astype(f32)).astype(f32), flag)
+        (ref, t, st), = check16(ctx, [(cur, W, m, v)], flag)
+        blobs.append(ref.blob)
+        devs.append((t[4], int(st.blob_bytes)))
+        cur = ref.W_recon
+    Wout = torch.zeros_like(w_to_dev(start, flag))
+    mout = torch.empty(n, dtype=torch.float32, device="cuda")
+    vout = torch.empty(n, dtype=torch.float32, device="cuda")
+    ctx.excp_reconstruct_chain([(w_to_dev(start, flag), [b for b, _ in devs], [s for _, s in devs], Wout, mout, vout)])
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    ref = O.reconstruct_chain(start, blobs)
+    assert bits(w_to_host(Wout, flag)).tobytes() == bits(ref[0]).tobytes() == bits(cur).tobytes()
+    assert mout.cpu().numpy().tobytes() == ref[1].tobytes() and vout.cpu().numpy().tobytes() == ref[2].tobytes()
+    # a chain whose checkpoints disagree about the storage is refused
+    other = BF16 if flag == F16 else F16
+    (r2, t2, st2), = check16(ctx, [case16(n, 681, other)], other)
+    ctx.excp_reconstruct_chain([(w_to_dev(start, flag), [devs[0][0], t2[4]], [devs[0][1], int(st2.blob_bytes)], Wout, None, None)])
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == X.EXCP_E_BLOB
+
+
+@pytest.mark.parametrize("flag", [F16, BF16])
+def test_stored_layout_and_mixed_batches(ctx, flag):
+    n = 90001
+    c16 = case16(n, 700, flag)
+    (ref, t, st), = check16(ctx, [c16], flag)
+    hb, db = X.excp_head_bytes(4), X.excp_dense_bytes(n, 4)
+    head = torch.zeros(hb, dtype=torch.uint8, device="cuda")
+    codes = [torch.zeros(db + 16, dtype=torch.uint8, device="cuda") for _ in range(3)]
+    ctx.excp_export_dense([(t[4], int(st.blob_bytes), n, head, *codes)])
+    rc, _ = ctx.excp_collect(check=False)
+    assert rc == 0
+    want = O.export_dense(ref.blob)
+    assert head.cpu().numpy().tobytes() == want[0]
+    for got, w in zip(codes, want[1:]):
+        assert got[:db].cpu().numpy().tobytes() == w.tobytes()
+    Wout = torch.zeros_like(t[5])
+    mout = torch.empty(n, dtype=torch.float32, device="cuda")
+    ctx.excp_decompress_dense([(t[0], head, hb, n, codes[0], codes[1], None, Wout, mout, None)])
+    rc, _ = ctx.excp_collect(check=False)
+    assert rc == 0
+    assert bits(w_to_host(Wout, flag)).tobytes() == bits(ref.W_recon).tobytes()
+    assert mout.cpu().numpy().tobytes() == ref.m_recon.tobytes()
+    # one Alg. 2 batch with fp32, 16-bit and unquantised 16-bit blobs side by side
+    (rr, tr, sr), = check16(ctx, [case16(n, 701, flag)], flag | 4)
+    g = np.random.default_rng(9)
+    Wp32 = (g.standard_normal(n) * 0.02).astype(f32)
+    W32 = (Wp32 + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+    r32 = O.compress_step(Wp32, W32, c16[2], c16[3], nbits=4, iters=3)
+    b32 = torch.zeros(X.excp_blob_bound(n, 4), dtype=torch.uint8, device="cuda")
+    d32 = torch.from_numpy(Wp32).cuda()
+    ctx.excp_compress_tensors([(d32, torch.from_numpy(W32).cuda(), t[2], t[3], b32, None)], 5e-5, 2.0, 4, 3, 0)
+    rc, s32 = ctx.excp_collect(check=False)
+    outs = [torch.zeros_like(t[5]), torch.zeros(n, dtype=torch.float32, device="cuda"), torch.zeros_like(tr[5])]
+    ctx.excp_decompress_tensors([(t[0], t[4], int(st.blob_bytes), n, outs[0], None, None),
+                                 (d32, b32, int(s32[0].blob_bytes), n, outs[1], None, None),
+                                 (tr[0], tr[4], int(sr.blob_bytes), n, outs[2], None, None)])
+    rc, _ = ctx.excp_collect(check=False)
+    assert rc == 0
+    assert bits(w_to_host(outs[0], flag)).tobytes() == bits(ref.W_recon).tobytes()
+    assert outs[1].cpu().numpy().tobytes() == r32.W_recon.tobytes()
+    assert bits(w_to_host(outs[2], flag)).tobytes() == bits(rr.W_recon).tobytes()
+
+
+def test_errors(ctx):
+    n = 5000
+    Wp, W, m, v = case16(n, 720, F16)
+    W[1234] = np.float16(np.inf)
+    rc, stats, dev = compress16(ctx, [(Wp, W, m, v)], F16)
+    assert rc == X.EXCP_E_NONFINITE and stats[0].status == X.EXCP_E_NONFINITE
+    d = dev[0]
+    with pytest.raises(X.ExcpError):
+        ctx.excp_compress_tensors([d], 5e-5, 2.0, 4, 3, F16 | BF16)
+    with pytest.raises(TypeError):
+        ctx.excp_compress_tensors([d], 5e-5, 2.0, 4, 3, 0)             # float16 tensors without the flag
+    with pytest.raises(X.ExcpError):
+        ctx.excp_compress_tensors([d], 5e-5, 2.0, 4, 3, F16 | 64)
+
+
+def test_arrays_of_the_wrong_storage_are_refused_not_read(ctx):
+    n = 30001
+    (ref, t, st), = check16(ctx, [case16(n, 730, F16)], F16)
+    nb = int(st.blob_bytes)
+    # fp32 and bf16 arrays against a blob of fp16 weights, and fp16 arrays against an fp32 blob
+    for dt in (torch.float32, torch.bfloat16):
+        Wp = torch.zeros(n, dtype=dt, device="cuda")
+        Wout = torch.full((n,), 5.0, dtype=dt, device="cuda")
+        ctx.excp_decompress_tensors([(Wp, t[4], nb, n, Wout, None, None)])
+        rc, stats = ctx.excp_collect(check=False)
+        assert rc == X.EXCP_E_BLOB and stats[0].status == X.EXCP_E_BLOB
+        assert torch.all(Wout == 5.0)
+        ctx.excp_reconstruct_chain([(Wp, [t[4]], [nb], Wout, None, None)])
+        rc, stats = ctx.excp_collect(check=False)
+        assert rc == X.EXCP_E_BLOB and torch.all(Wout == 5.0)
+    g = np.random.default_rng(4)
+    Wp32 = (g.standard_normal(n) * 0.02).astype(f32)
+    W32 = (Wp32 + g.laplace(0, 1e-4, n).astype(f32)).astype(f32)
+    b32 = torch.zeros(X.excp_blob_bound(n, 4), dtype=torch.uint8, device="cuda")
+    ctx.excp_compress_tensors([(torch.from_numpy(Wp32).cuda(), torch.from_numpy(W32).cuda(), t[2], t[3], b32, None)],
+                              5e-5, 2.0, 4, 3, 0)
+    rc, s32 = ctx.excp_collect(check=False)
+    assert rc == 0
+    guard = torch.full((2 * n,), 7.0, dtype=torch.float16, device="cuda")       # the output is its first half
+    ctx.excp_decompress_tensors([(t[0], b32, int(s32[0].blob_bytes), n, guard[:n], None, None)])
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == X.EXCP_E_BLOB and torch.all(guard == 7.0)
