@@ -21,30 +21,33 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
 
-def stage_bytes_per_param(p_w, p_o, nbits, iters):
-    """Algorithmic HBM bytes per parameter of each kernel stage (what the method must move)."""
+def stage_bytes_per_param(p_w, p_o, nbits, iters, wb=4.0):
+    """Algorithmic HBM bytes per parameter of each kernel stage (what the method must move); wb = bytes
+    of one stored weight (4, or 2 for fp16 / bf16 checkpoints)."""
     s = p_w + 2.0 * p_o
     bitmaps = 0.125 * (1.0 + p_w)
     return {
-        "stats_stream": 12.0,                              # read W_prev, W, m
-        "mask_slots": 16.0 + 0.125 + 4.0 * s,              # read all four arrays; write keep bitmap + survivor slots
+        "stats_stream": 2.0 * wb + 4.0,                    # read W_prev, W, m
+        "mask_slots": 2.0 * wb + 8.0 + 0.125 + 4.0 * s,    # read all four arrays; write keep bitmap + survivor slots
         "mask_gather": 8.0 * s + 0.25 * p_w,               # slots -> dense survivor arrays; local M_o bits -> bitmap_o
         "km_count": 4.0 * s,                               # read the survivors, count per bucket
         "km_scatter": 8.0 * s,                             # read the survivors, write them bucket by bucket
         "km_bucket_stats": 4.0 * s,                        # read the partitioned survivors once
         "assign_pack": 4.0 * s + s * nbits / 8.0,          # read survivors, write codes
-        "decode_main": 4.0 + bitmaps + s * nbits / 8.0 + 4.0,   # read W_prev, bitmaps, codes; write W_hat
+        "decode_main": wb + bitmaps + s * nbits / 8.0 + wb,     # read W_prev, bitmaps, codes; write W_hat
     }
 
 
-def survey_step_bytes_per_param(p_w, p_o):
-    """Step-level accounting used for the '% of HBM roofline' headline: 32.2 + 58.5 s (+ 8 for W_hat)."""
+def survey_step_bytes_per_param(p_w, p_o, wb=4.0):
+    """Step-level accounting used for the '% of HBM roofline' headline: 32.2 + 58.5 s (+ 8 for W_hat) for
+    fp32 weights; of the 32.2, sixteen bytes are the two passes over W_prev and W, and the 8 are W_prev
+    read and W_hat written: those scale with the stored weight size."""
     s = p_w + 2.0 * p_o
-    return 32.2 + 58.5 * s + 8.0
+    return 32.2 - 16.0 * (1.0 - wb / 4.0) + 58.5 * s + 8.0 * wb / 4.0
 
 
 STAGE_KERNEL = {"stats_stream": "k_stats_stream<false>", "mask_slots": "k_mask_slots<false, false>", "mask_gather": "k_mask_gather",
-                "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats",
+                "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats<4u>",
                 "assign_pack": "k_assign_pack", "decode_main": "k_decode_main<false>"}
 
 
@@ -70,6 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=-1, help="workload config id (default: largest that fits)")
     ap.add_argument("--groups", type=int, default=2, help="tensor groups a large checkpoint is processed in")
+    ap.add_argument("--weights", choices=("f32", "f16", "bf16"), default="f32",
+                    help="storage of W_prev, W and W_hat (the headline workload is f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -87,6 +92,9 @@ def main():
     dev = torch.device("cuda", 0)
     free, total_mem = torch.cuda.mem_get_info()
     alpha, beta, nbits, iters = synth.ALPHA, synth.BETA, synth.NBITS, synth.LLOYD_ITERS
+    wdtype = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.weights]
+    wflags = {"f32": 0, "f16": X.EXCP_FLAG_W_F16, "bf16": X.EXCP_FLAG_W_BF16}[args.weights]
+    wb = 4.0 if args.weights == "f32" else 2.0
 
     def need_bytes(cfg, group):
         N = cfg.total
@@ -110,7 +118,8 @@ def main():
 
     # ---- inputs resident in HBM: four flat arrays, one view per tensor -------------------------
     t0 = time.time()
-    flat = [torch.empty(N, dtype=torch.float32, device=dev) for _ in range(5)]   # Wp, W, m, v, W_hat
+    flat = [torch.empty(N, dtype=wdtype if k in (0, 1, 4) else torch.float32, device=dev)
+            for k in range(5)]                                                    # Wp, W, m, v, W_hat
     offs, o = [], 0
     for i, spec in enumerate(cfg.tensors):
         Wp, W, m, v = synth.torch_draw_tensor(cid, i, spec, dev)
@@ -133,7 +142,7 @@ def main():
                         blob_flat[int(boffs[i]):int(boffs[i + 1])], flat[4][a:b]))
 
     def step():
-        ctx.excp_compress_tensors(tensors, alpha, beta, nbits, iters, 0)
+        ctx.excp_compress_tensors(tensors, alpha, beta, nbits, iters, wflags)
         return ctx.excp_collect()[1]
 
     for _ in range(args.warmup):
@@ -168,7 +177,7 @@ def main():
     params_per_s = N / (ms_per_step * 1e-3)
 
     # ---- roofline of the dominant kernel ----------------------------------------------------------
-    per_param = stage_bytes_per_param(p_w, p_o, nbits, iters)
+    per_param = stage_bytes_per_param(p_w, p_o, nbits, iters, wb)
     stage_report = {}
     for k, (ms, launches) in stage_tot.items():
         if launches == 0:
@@ -186,7 +195,7 @@ def main():
                 "avg_launch_ms": d["ms_per_step"] / d["launches_per_step"],
                 "algorithmic_bytes_per_launch": per_param[dominant] * N / d["launches_per_step"],
                 "algorithmic_bytes_per_param": per_param[dominant]}
-    step_bytes = survey_step_bytes_per_param(p_w, p_o) * N
+    step_bytes = survey_step_bytes_per_param(p_w, p_o, wb) * N
     step_frac = step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     # ---- decompress (Alg. 2) timing, reported beside the headline --------------------------------
@@ -203,7 +212,7 @@ def main():
     dec_ms = (time.perf_counter() - t1) * 1e3 / max(1, args.steps)
 
     # one plain copy of known size (1 GiB read + 1 GiB written): calibrates profiler byte counters
-    probe = min(N * 4, 1 << 30) & ~15
+    probe = min(N * int(wb), 1 << 30) & ~15
     ctx.excp_copy_probe(flat[4], flat[0], probe)
     torch.cuda.synchronize()
 
@@ -228,9 +237,10 @@ def main():
         big = [i for i in range(len(cfg.tensors)) if cfg.tensors[i].n >= 1_000_000] or list(range(len(cfg.tensors)))
         pick = min(big, key=lambda i: (cfg.tensors[i].n, i))
         a, b = offs[pick], offs[pick] + min(cfg.tensors[pick].n, budget_elems)
-        host = [f[a:b].cpu().numpy() for f in flat[:4]]
+        host = [(f[a:b].view(torch.int16).cpu().numpy().view(np.uint16) if f.dtype == torch.bfloat16
+                 else f[a:b].cpu().numpy()) for f in flat[:4]]
         t2 = time.perf_counter()
-        ref = O.compress_step(*host, alpha, beta, nbits, iters)
+        ref = O.compress_step(*host, alpha, beta, nbits, iters, flags=wflags)
         cpu_s = time.perf_counter() - t2
         cpu = {"value": (b - a) / cpu_s, "unit": "params/s", "cores": 1, "kind": "oracle",
                "sample": f"first {b - a} elements of tensor {pick} ({cfg.tensors[pick].name}) of the same "
@@ -282,18 +292,18 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cid}: {cfg.name}-shaped checkpoint, {len(cfg.tensors)} tensors, {N} fp32 "
-                               f"params x (W_prev, W, m, v) resident in HBM; alpha={alpha}, beta={beta}, nbits={nbits}, "
+                               f"params x (W_prev, W, m, v) resident in HBM, weights stored as {args.weights}; alpha={alpha}, beta={beta}, nbits={nbits}, "
                                f"{iters} Lloyd iterations; W_hat emitted",
                    "params": N, "tensors": len(cfg.tensors), "group_elems": group},
-        "state_GBs": 16.0 * N / (ms_per_step * 1e-3) / 1e9,
+        "state_GBs": (8.0 + 2.0 * wb) * N / (ms_per_step * 1e-3) / 1e9,
         "hbm_roofline_pct_step": 100.0 * step_frac,
-        "step_algorithmic_bytes_per_param": survey_step_bytes_per_param(p_w, p_o),
+        "step_algorithmic_bytes_per_param": survey_step_bytes_per_param(p_w, p_o, wb),
         "keep_fractions": {"p_w": p_w, "p_o": p_o},
-        "compression_ratio": 12.0 * N / blob_bytes,
+        "compression_ratio": (8.0 + wb) * N / blob_bytes,
         "decompress_ms": dec_ms, "decompress_params_per_s": N / (dec_ms * 1e-3),
         "decompress_with_moments_ms": dec3_ms,
         "reconstruct_chain_ms": {"checkpoints": chain_len, "ms": chain_ms, "one_by_one_ms": chain_len * dec_ms},
-        "dense_layout": {"bytes": dense_bytes_total, "ratio": 12.0 * N / dense_bytes_total,
+        "dense_layout": {"bytes": dense_bytes_total, "ratio": (8.0 + wb) * N / dense_bytes_total,
                          "export_ms": dense_ms["export"], "decompress_with_moments_ms": dense_ms["decompress"]},
         "workspace_GB": ctx.workspace_bytes / 1e9,
         "roofline": roofline,

@@ -36,6 +36,23 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int m) {
     return __longlong_as_double((long long)shfl_xor_u64((u64)__double_as_longlong(v), m));
 }
 
+// Histogram increment in LDS for data that may be heavily tied (then most lanes of a wave hit the same
+// bin, and plain atomics take turns): up to two groups of lanes that share a bin are added by one lane
+// each, whoever is left adds for itself.  Every lane of the wave must call it.
+__device__ __forceinline__ void hist_add_tied(u32 *hist, u32 bin, bool active) {
+    u64 todo = ballot64(active);
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        if (todo == 0ull) break;                            // the same in every lane
+        const u32 leader = (u32)__ffsll((long long)todo) - 1u;
+        const u32 lb = (u32)__shfl((int)bin, (int)leader, WAVE);
+        const u64 same = ballot64(active && bin == lb) & todo;
+        if (lane_id() == leader) atomicAdd(&hist[lb], (u32)__popcll(same));
+        todo &= ~same;
+    }
+    if ((todo >> lane_id()) & 1ull) atomicAdd(&hist[bin], 1u);
+}
+
 // Largest t with begin[t] <= x (begin is non-decreasing, begin[0] == 0, count+1 entries,
 // begin[count] > x).  Entries may repeat (empty items); the item found is never empty.
 __device__ __forceinline__ u32 find_owner(const u32 *__restrict__ begin, u32 count, u32 x) {
@@ -78,6 +95,24 @@ __device__ __forceinline__ float load_weight(const float *p, u64 idx, u32 wt) {
 __device__ __forceinline__ void store_weight(float *p, u64 idx, u32 wt, float x) {
     if (wt == 0u) p[idx] = x;
     else ((unsigned short *)p)[idx] = (unsigned short)w16_narrow(x, wt == 2u);
+}
+
+// Four consecutive weights of a tile: elements [off, off + 4) of the tile that starts at `tile0` (an
+// element pointer into an array of type wt), of which `rem` exist; one 16-byte (fp32) or 8-byte
+// (16-bit, if the array is 8-byte aligned) load where all four exist, else one by one; missing ones are 0.
+typedef float f4w __attribute__((ext_vector_type(4), aligned(4)));
+__device__ __forceinline__ void load_weights4(const float *arr, u64 tile0, u32 off, u32 rem, u32 wt, float (&out)[4]) {
+    if (off + 4u <= rem && wt == 0u) {
+        const f4w q = *(const EXCP_GLOBAL f4w *)(gptr(arr) + tile0 + off);
+        out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
+    } else if (off + 4u <= rem && ((uintptr_t)arr & 7u) == 0u) {
+        const us4 q = *(const EXCP_GLOBAL us4 *)(gptr((const unsigned short *)arr) + tile0 + off);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = w16_widen(q[j], wt == 2u);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) out[j] = (off + (u32)j < rem) ? load_weight(arr, tile0 + off + (u32)j, wt) : 0.f;
+    }
 }
 
 // Copy of a tile table in LDS (the per-tile owner search then costs no global round trips).

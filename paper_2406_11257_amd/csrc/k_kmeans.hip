@@ -413,13 +413,16 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
 }
 
 // ---------------------------------------------------------------- P4: exact totals per bucket
-// One workgroup per four buckets of a stream; its four waves share every bucket (a quarter each),
-// so that one very large bucket does not leave a single wave working alone.  Values of a bucket
+// One workgroup per four buckets of a stream; its four or sixteen waves share every bucket,
+// so that one very large bucket (tied values) does not leave a single wave working alone.  Values of a bucket
 // are neighbours in value, hence in exponent: a window of 40 bit positions placed from the first
 // values met holds practically all of them; inside it a lane adds shifted mantissas as integers
 // (low and high 32-bit halves in separate 64-bit counters, magnitudes of all values and of the
 // negative ones) with no cross-lane traffic; the rest (rare) is filed one by one.
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_bucket_stats(Workspace w, GroupParams g) {
+// (sixteen for 16-bit weights, whose residuals are heavily tied; four otherwise, which is faster when
+// the buckets are even)
+template <u32 BS_WAVES>
+__global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, GroupParams g) {
     __shared__ u64 bins[4][EXCP_ABSM_BINS];
     __shared__ u32 s_min[4], s_max[4];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
@@ -435,8 +438,8 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_bucket_stats(Workspace w, G
     const EXCP_GLOBAL float *part = gptr(seg_part(w, sidx));
     for (u32 j = 0; j < 4; ++j) {
         const u32 q0 = begin[b0 + j], q1 = begin[b0 + j + 1];
-        // this wave's quarter, cut at multiples of 256 values from the bucket's start
-        const u32 blocks = (q1 - q0 + 255u) >> 8, per = (blocks + 3u) >> 2;
+        // this wave's share, cut at multiples of 256 values from the bucket's start
+        const u32 blocks = (q1 - q0 + 255u) >> 8, per = (blocks + BS_WAVES - 1u) / BS_WAVES;
         const u32 p0 = min(q0 + wave * per * 256u, q1), p1 = min(p0 + per * 256u, q1);
         if (p0 >= p1) continue;
         u64 *mybins = bins[j];
@@ -512,7 +515,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_bucket_stats(Workspace w, G
 // ---------------------------------------------------------------- P6: initial centres
 // One workgroup per (stream, rank): radix select inside the bucket that holds the rank; the bits
 // that the bucket's minimum and maximum key share are known and skipped.
-__global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupParams g) {
+// (1024 threads for 16-bit weights: a bucket of tied values can be most of a stream; 256 otherwise)
+template <u32 INIT_THREADS>
+__global__ __launch_bounds__(INIT_THREADS) void k_km_init(Workspace w, GroupParams g) {
     __shared__ u32 hist[256];
     __shared__ u32 s_pick[2];
     const u32 K = (u32)g.K;
@@ -537,23 +542,31 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_init(Workspace w, GroupPara
     while (top >= 0) {
         const int width = top + 1 < 8 ? top + 1 : 8;
         const int shift = top + 1 - width;
-        hist[tid] = 0;
+        if (tid < 256u) hist[tid] = 0;
         __syncthreads();
-        auto tally = [&](float xv) {
+        // A bucket far above the average size holds tied values (a continuous distribution fills the
+        // buckets evenly): its lanes mostly hit the same bin, and the increments are grouped per wave.
+        const bool crowded = (u64)(p1 - p0) > 8ull * (len / NBKT + 1ull);
+        auto tally = [&](float xv, bool in) {
             const u32 key = key_of(xv);
-            const bool match = (top == 31) ? true : ((key >> (top + 1)) == prefix);
-            if (match) atomicAdd(&hist[(key >> shift) & ((1u << width) - 1u)], 1u);
+            const bool match = in && ((top == 31) ? true : ((key >> (top + 1)) == prefix));
+            const u32 bin = (key >> shift) & ((1u << width) - 1u);
+            if (crowded) hist_add_tied(hist, bin, match);
+            else if (match) atomicAdd(&hist[bin], 1u);
         };
-        // 4096 values per round, sixteen per thread, every load of a round issued before its use
-        for (u32 q0 = p0; q0 < p1; q0 += 16u * EXCP_THREADS) {
-            if (q0 + 16u * EXCP_THREADS <= p1) {
+        // sixteen values per thread and round, every load of a round issued before its use
+        for (u32 q0 = p0; q0 < p1; q0 += 16u * INIT_THREADS) {
+            if (q0 + 16u * INIT_THREADS <= p1) {
                 f4u q[4];
 #pragma unroll
-                for (u32 j = 0; j < 4; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(gpart + q0 + (j * EXCP_THREADS + tid) * 4u);
+                for (u32 j = 0; j < 4; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(gpart + q0 + (j * INIT_THREADS + tid) * 4u);
 #pragma unroll
-                for (u32 j = 0; j < 4; ++j) { tally(q[j].x); tally(q[j].y); tally(q[j].z); tally(q[j].w); }
+                for (u32 j = 0; j < 4; ++j) { tally(q[j].x, true); tally(q[j].y, true); tally(q[j].z, true); tally(q[j].w, true); }
             } else {
-                for (u32 p = q0 + tid; p < p1; p += EXCP_THREADS) tally(gpart[p]);
+                for (u32 pp = q0; pp < p1; pp += INIT_THREADS) {       // the same trip count in every lane
+                    const u32 p = pp + tid;
+                    tally(p < p1 ? gpart[p] : 0.f, p < p1);
+                }
             }
         }
         __syncthreads();
@@ -1026,14 +1039,18 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
         case 1: hipLaunchKernelGGL(k_km_count, dim3(excp_grid(w, 30)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 2: hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(1024), 0, s, w, g); break;
         case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 96)), dim3(EXCP_THREADS), 0, s, w, g); break;
-        case 4: hipLaunchKernelGGL(k_km_bucket_stats, dim3(nseg * (NBKT / 4)), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 4:
+            if (g.flags & 0x30u) hipLaunchKernelGGL(k_km_bucket_stats<16>, dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
+            else hipLaunchKernelGGL(k_km_bucket_stats<4>, dim3(nseg * (NBKT / 4)), dim3(256), 0, s, w, g);
+            break;
         default: break;
     }
 }
 
 void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_init, dim3(3 * g.ntensors * (u32)g.K), dim3(EXCP_THREADS), 0, s, w, g);
+    if (g.flags & 0x30u) hipLaunchKernelGGL(k_km_init<1024>, dim3(3 * g.ntensors * (u32)g.K), dim3(1024), 0, s, w, g);
+    else hipLaunchKernelGGL(k_km_init<256>, dim3(3 * g.ntensors * (u32)g.K), dim3(256), 0, s, w, g);
 }
 
 void launch_km_classify(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s) {

@@ -125,7 +125,10 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             u32 at = 0;
             if (lane == 0) at = atomicAdd(&w.st[tt].cand_count, wcount);
             at = __shfl(at, 0, WAVE);
-            if ((u64)at + wcount <= w.desc[tt].cand_cap) {
+            if (w.st[tt].br_lo == w.st[tt].br_hi) {
+                // a bracket of one value (heavily tied data, e.g. 16-bit weights that did not move):
+                // every candidate is that value, so their number is all that is needed
+            } else if ((u64)at + wcount <= w.desc[tt].cand_cap) {
                 EXCP_GLOBAL u32 *dst = gptr(w.cand) + w.desc[tt].cand_off + at;
                 for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
             } else if (lane == 0) {
@@ -292,6 +295,11 @@ __global__ void k_cand_begin(Workspace w, GroupParams g) {
     const u64 n = w.desc[t].n;
     const u64 r = (n - 1) >> 1;
     const u64 below = S.c_lt, cnt = S.cand_count;
+    if (S.br_hi == S.br_lo) {              // one-value bracket: only counted, never listed
+        if (r >= below && r < below + cnt) { S.med_bits = S.br_lo; S.med_state = MED_KNOWN; }
+        else S.med_state = MED_FALLBACK;
+        return;
+    }
     if (S.cand_overflow || cnt > w.desc[t].cand_cap || r < below || r >= below + cnt) {
         S.med_state = MED_FALLBACK;
         return;
@@ -420,16 +428,23 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_full_hist(Workspace w, GroupPa
         const u64 n = D.n;
         const u64 base = (u64)(tile - D.tile_begin) * EXCP_TILE;
         const u32 prefix = PASS > 0 ? w.st[t].sel_base : 0u;
-#pragma unroll 4
-        for (int j = 0; j < 16; ++j) {
-            const u64 idx = base + (u64)((wave * 16 + j) * 64 + lane);
-            if (idx < n) {
-                const u32 wt = excp_wtype(g.flags);
-                const float wv = load_weight(D.W, idx, wt);
-                const u32 k = f2u((g.flags & 1u) ? wv : wv - load_weight(D.Wp, idx, wt)) & 0x7fffffffu;
-                if (PASS == 0) atomicAdd(&hist[k >> 20], 1u);
-                if (PASS == 1) { if ((k >> 20) == prefix) atomicAdd(&hist[(k >> 9) & 2047u], 1u); }
-                if (PASS == 2) { if ((k >> 9) == prefix) atomicAdd(&hist[k & 511u], 1u); }
+        // (this path is taken for heavily tied data above all: see hist_add_tied)
+        const u32 rem = (n - base < (u64)EXCP_TILE) ? (u32)(n - base) : EXCP_TILE;
+        const u32 wt = excp_wtype(g.flags);
+        const bool of_weights = (g.flags & 1u) != 0u;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u32 off = wave * 1024u + (u32)q * 256u + lane * 4u;
+            float a[4], pv[4] = {0.f, 0.f, 0.f, 0.f};
+            load_weights4(D.W, base, off, rem, wt, a);
+            if (!of_weights) load_weights4(D.Wp, base, off, rem, wt, pv);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool act = off + (u32)j < rem;
+                const u32 k = f2u(a[j] - pv[j]) & 0x7fffffffu;
+                if (PASS == 0) hist_add_tied(hist, k >> 20, act);
+                if (PASS == 1) hist_add_tied(hist, (k >> 9) & 2047u, act && (k >> 20) == prefix);
+                if (PASS == 2) hist_add_tied(hist, k & 511u, act && (k >> 9) == prefix);
             }
         }
     }
