@@ -52,6 +52,10 @@ struct TState {
     float mean32, t_w, r_o;
     int status;
     u32 absm_base;              // lowest bit position of the 24-position window used for the exact sum of |m|
+    // tied data (16-bit weights): values inside the median bracket that the sample shows to be heavily
+    // repeated are counted, not listed among the candidates
+    u32 natoms, atom_key[4], atom_cnt[4];
+    u32 pad2[2];
 };
 
 // One survivor stream (3 per tensor: residual, m, v) during codebook construction.

@@ -84,9 +84,25 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, Gro
             S.med_bits = key[(n - 1) >> 1];
             S.med_state = MED_KNOWN;
         } else {
-            S.br_lo = key[MED_SAMPLE / 2 - MED_HALF_WIDTH];
-            S.br_hi = key[MED_SAMPLE / 2 + MED_HALF_WIDTH];
+            const u32 a = MED_SAMPLE / 2 - MED_HALF_WIDTH, b = MED_SAMPLE / 2 + MED_HALF_WIDTH;
+            S.br_lo = key[a];
+            S.br_hi = key[b];
             S.med_state = MED_PENDING;
+            // 16-bit weights: residuals are few distinct values.  Up to four values of the bracket
+            // that fill at least 32 places of the sorted sample (0.4 % of the tensor) are counted
+            // during the streaming pass instead of being listed one by one.
+            u32 na = 0;
+            if ((g.flags & 0x30u) && key[a] != key[b]) {
+                for (u32 i = a; i <= b && na < 4u;) {
+                    const u32 kv = key[i];
+                    u32 j0 = i, j1 = i;
+                    while (j0 > 0u && key[j0 - 1u] == kv) --j0;
+                    while (j1 + 1u < MED_SAMPLE && key[j1 + 1u] == kv) ++j1;
+                    if (j1 - j0 + 1u >= 32u) S.atom_key[na++] = kv;
+                    i = j1 + 1u;
+                }
+            }
+            S.natoms = na;
         }
     }
 }
@@ -118,8 +134,14 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
     u64 accL = 0, accH = 0;        // this lane's in-window units: sum of low / high 32-bit halves
     u32 B = w.st[t].absm_base;     // window = bit positions [B, B + 24)
 
+    u32 acnt[4] = {0u, 0u, 0u, 0u};   // W16: elements equal to the tensor's counted bracket values (same in every lane)
     u32 wcount = 0;                // candidates this wave has staged in LDS (same in every lane)
     auto flush_cand = [&](u32 tt) {
+        if (W16 && lane == 0) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) if (acnt[q]) atomicAdd(&w.st[tt].atom_cnt[q], acnt[q]);
+        }
+        if (W16) { acnt[0] = acnt[1] = acnt[2] = acnt[3] = 0u; }
         // the staged candidates go to the tensor's list: one reservation for many tiles
         if (wcount) {
             u32 at = 0;
@@ -246,11 +268,20 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             }
             if (nf == 0 && worst >= 0x7f800000u) nf = 1;
         }
+        const u32 natoms = W16 ? S.natoms : 0u;
+        const u32 ak0 = S.atom_key[0], ak1 = S.atom_key[1], ak2 = S.atom_key[2], ak3 = S.atom_key[3];
         if (pending && !TUNE(16)) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 clt += __popcll(ballot64(key[j] < klo));
-                const bool cand = key[j] - klo <= kspan;      // klo <= key <= khi (a padded key wraps far above)
+                bool cand = key[j] - klo <= kspan;            // klo <= key <= khi (a padded key wraps far above)
+                if (W16 && natoms) {
+                    const bool e0 = key[j] == ak0, e1 = natoms > 1u && key[j] == ak1;
+                    const bool e2 = natoms > 2u && key[j] == ak2, e3 = natoms > 3u && key[j] == ak3;
+                    acnt[0] += __popcll(ballot64(e0)); acnt[1] += __popcll(ballot64(e1));
+                    acnt[2] += __popcll(ballot64(e2)); acnt[3] += __popcll(ballot64(e3));
+                    cand = cand && !(e0 || e1 || e2 || e3);
+                }
                 const u64 bal = ballot64(cand);
                 // branch-free: the others write to a spare slot past the end
                 const u32 below = __builtin_amdgcn_mbcnt_hi((u32)(bal >> 32), __builtin_amdgcn_mbcnt_lo((u32)bal, 0u));
@@ -300,7 +331,9 @@ __global__ void k_cand_begin(Workspace w, GroupParams g) {
         else S.med_state = MED_FALLBACK;
         return;
     }
-    if (S.cand_overflow || cnt > w.desc[t].cand_cap || r < below || r >= below + cnt) {
+    u64 counted = 0;                       // bracket values that were counted instead of listed
+    for (u32 q = 0; q < S.natoms; ++q) counted += S.atom_cnt[q];
+    if (S.cand_overflow || cnt > w.desc[t].cand_cap || r < below || r >= below + cnt + counted) {
         S.med_state = MED_FALLBACK;
         return;
     }
@@ -369,6 +402,14 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_cand_resolve(Workspace w, Grou
     if (S.med_state != MED_PENDING || S.sel_width == 0) return;
     u32 *H = w.med_hist + (u64)t * 2048u;
     const u32 width = S.sel_width, shift = width > 11u ? width - 11u : 0u, rank = S.sel_rank, base = S.sel_base;
+    if (tid == 0) {
+        // the counted bracket values join the listed candidates, each with its multiplicity
+        for (u32 q = 0; q < S.natoms; ++q) {
+            const u32 rel = S.atom_key[q] - base;
+            if ((u64)rel < (1ull << width)) H[rel >> shift] += S.atom_cnt[q];
+        }
+    }
+    __syncthreads();
     u32 c[8], local = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) { c[i] = H[tid * 8 + i]; local += c[i]; H[tid * 8 + i] = 0; }
