@@ -16,7 +16,7 @@ import sys
 
 def short(name: str):
     m = re.search(r"(k_[a-z0-9_]+(<[^>]*>)?)", name)
-    return m.group(1) if m else None
+    return m.group(1).replace(" ", "") if m else None        # no blanks: the tables are split on them
 
 
 def stats(directory: str) -> None:
