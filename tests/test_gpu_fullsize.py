@@ -129,3 +129,62 @@ def test_largest_tensor_properties_and_sampled_elements(batch):
     # exactly is that every centre lies inside its stream's range and the objective is consistent
     assert st.obj_w > 0 and st.obj_m > 0 and st.obj_v > 0
     assert abs(12.0 * n / nbytes - 28.8) < 0.5                   # same ratio as every other tensor of this recipe
+
+
+def test_sixteen_bit_weights_at_full_size(batch):
+    """A 16.8 M-element tensor stored as fp16 with the moment mask on its own (flags F16 | NO_W2M) against
+    the whole oracle, and a 45 M-element bf16 tensor against independent device-side routines; the same
+    context as above, so the benchmark's launch configuration."""
+    ctx, cfg, items = batch
+    dev = torch.device("cuda", 0)
+    (Wp, W, m, v), _, _, _, _ = items[1]
+    Wp16, W16 = Wp.half(), W.half()
+    n = Wp.numel()
+    flags = X.EXCP_FLAG_W_F16 | X.EXCP_FLAG_NO_W2M
+    blob = torch.zeros(X.excp_blob_bound(n, 4), dtype=torch.uint8, device=dev)
+    Wout = torch.empty(n, dtype=torch.float16, device=dev)
+    # second tensor of the batch: bf16, default masks
+    (Wp2, W2, m2, v2), _, _, _, _ = items[5]
+    Wpb, Wb = Wp2.bfloat16(), W2.bfloat16()
+    n2 = Wp2.numel()
+    ctx.excp_compress_tensors([(Wp16, W16, m, v, blob, Wout)], synth.ALPHA, synth.BETA, 4, synth.LLOYD_ITERS, flags)
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    st = stats[0]
+    ref = O.compress_step(Wp16.cpu().numpy(), W16.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy(),
+                          synth.ALPHA, synth.BETA, 4, synth.LLOYD_ITERS, flags=flags)
+    print("16.8M fp16: n_w", st.n_w, "n_o", st.n_o, "median", st.median_abs_dw, flush=True)
+    assert (st.n_w, st.n_o) == (ref.n_w, ref.n_o)
+    assert blob[:int(st.blob_bytes)].cpu().numpy().tobytes() == ref.blob
+    assert Wout.cpu().numpy().view(np.uint16).tobytes() == ref.W_recon.view(np.uint16).tobytes()
+    outs = [torch.empty(n, dtype=torch.float16, device=dev)] + [torch.empty(n, dtype=torch.float32, device=dev) for _ in range(2)]
+    ctx.excp_decompress_step(Wp16, blob, int(st.blob_bytes), *outs)
+    assert torch.equal(outs[0], Wout)
+    assert outs[1].cpu().numpy().tobytes() == ref.m_recon.tobytes() and outs[2].cpu().numpy().tobytes() == ref.v_recon.tobytes()
+    # bf16, 45 M elements
+    blob2 = torch.zeros(X.excp_blob_bound(n2, 4), dtype=torch.uint8, device=dev)
+    Wout2 = torch.empty(n2, dtype=torch.bfloat16, device=dev)
+    ctx.excp_compress_tensors([(Wpb, Wb, m2, v2, blob2, Wout2)], synth.ALPHA, synth.BETA, 4, synth.LLOYD_ITERS, X.EXCP_FLAG_W_BF16)
+    rc, stats = ctx.excp_collect(check=False)
+    assert rc == 0
+    st2 = stats[0]
+    d = Wb.float() - Wpb.float()
+    kth = torch.kthvalue(d.abs(), (n2 - 1) // 2 + 1).values.item()
+    assert f32(kth).tobytes() == f32(st2.median_abs_dw).tobytes()
+    t_w = f32(f32(synth.ALPHA) * f32(st2.median_abs_dw))
+    r = torch.tensor(t_w, device=dev) / torch.sqrt(v2)
+    keep = d.abs() > r
+    assert int(keep.sum().item()) == st2.n_w
+    r_o = f32(f32(synth.BETA) * f32(st2.mean_abs_m))
+    assert int((keep & (m2.abs() > float(r_o))).sum().item()) == st2.n_o
+    print("45M bf16: n_w", st2.n_w, "n_o", st2.n_o, "median", st2.median_abs_dw, flush=True)
+    nb2 = int(st2.blob_bytes)
+    assert nb2 == X.excp_blob_size(n2, st2.n_w, st2.n_o, 4)
+    W3 = torch.empty(n2, dtype=torch.bfloat16, device=dev)
+    ctx.excp_decompress_step(Wpb, blob2, nb2, W3, None, None)
+    assert torch.equal(W3, Wout2)
+    assert torch.equal(Wout2[~keep], Wpb[~keep])                  # pruned positions keep their bits
+    # every kept weight moved to the nearest-even bf16 of (previous + a centre of the stored codebook)
+    book = torch.from_numpy(np.frombuffer(blob2[80:80 + 64].cpu().numpy().tobytes(), dtype="<f4").copy()).to(dev)
+    cand = (Wpb.float()[keep][:2_000_000, None] + book[None, 1:]).bfloat16()
+    assert bool((cand == Wout2[keep][:2_000_000, None]).any(dim=1).all())
