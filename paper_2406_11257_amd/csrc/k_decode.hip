@@ -445,7 +445,7 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 }
 
 template <bool MOMENTS>
-__global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
+__global__ __launch_bounds__(EXCP_THREADS, MOMENTS ? 6 : 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
     decode_tiles<MOMENTS, false, false, 0>(w, ntensors, ntiles);
 }
 // The same for blobs of 16-bit weights.  Most batches hold none: leave at once then.
