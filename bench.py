@@ -215,6 +215,18 @@ def main():
     probe = min(N * int(wb), 1 << 30) & ~15
     ctx.excp_copy_probe(flat[4], flat[0], probe)
     torch.cuda.synchronize()
+    # the rate of a plain device-to-device copy on this GPU (torch's own copy kernel over up to 16 GiB):
+    # what mixed read + write traffic reaches in practice, as a reference next to the 8 TB/s nominal peak
+    cbytes = min(N * int(wb), 16 << 30)
+    csrc, cdst = flat[0].view(torch.uint8)[:cbytes], flat[4].view(torch.uint8)[:cbytes]
+    cdst.copy_(csrc)
+    ce0, ce1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ce0.record()
+    for _ in range(3):
+        cdst.copy_(csrc)
+    ce1.record()
+    torch.cuda.synchronize()
+    copy_GBs = 2.0 * cbytes * 3 / (ce0.elapsed_time(ce1) * 1e-3) / 1e9
 
     # ---- Alg. 3: a chain of 8 checkpoints in one pass (the same blob eight times: a valid chain) ------
     chain_len = 8
@@ -306,7 +318,7 @@ def main():
         "dense_layout": {"bytes": dense_bytes_total, "ratio": (8.0 + wb) * N / dense_bytes_total,
                          "export_ms": dense_ms["export"], "decompress_with_moments_ms": dense_ms["decompress"]},
         "workspace_GB": ctx.workspace_bytes / 1e9,
-        "roofline": roofline,
+        "roofline": dict(roofline, plain_copy_GBs_same_gpu=copy_GBs),
         "cpu_baseline": cpu,
         "stages": stage_report,
     }
