@@ -139,8 +139,8 @@ def save_checkpoint(ctx, named_blobs, nbits: int, layout: str = "dense", preset:
 
 
 def load_checkpoint(ctx, data: bytes, W_prev, want_moments: bool = True, threads: int = 8):
-    """Inverse of save_checkpoint: W_prev maps tensor name -> previous reconstructed weights (device,
-    fp32).  Returns name -> (W_hat, m_hat, v_hat) device tensors (moments None unless wanted)."""
+    """Inverse of save_checkpoint: W_prev maps tensor name -> previous reconstructed weights (device;
+    fp32, or fp16 / bf16 if the checkpoint was compressed from such weights).  Returns name -> (W_hat, m_hat, v_hat) device tensors (moments None unless wanted)."""
     import numpy as np
     import torch
     from . import binding as B
@@ -155,7 +155,7 @@ def load_checkpoint(ctx, data: bytes, W_prev, want_moments: bool = True, threads
             padded = bytes(sec) + b"\0" * (max(16, (len(sec) + 15) // 16 * 16) - len(sec))
             dev.append(torch.from_numpy(np.frombuffer(padded, dtype=np.uint8).copy()).to(Wp.device))
         keep.append(dev)
-        W = torch.empty(n, dtype=torch.float32, device=Wp.device)
+        W = torch.empty(n, dtype=Wp.dtype, device=Wp.device)        # the storage the blob was written for
         m = torch.empty(n, dtype=torch.float32, device=Wp.device) if want_moments else None
         v = torch.empty(n, dtype=torch.float32, device=Wp.device) if want_moments else None
         out[e["name"]] = (W, m, v)

@@ -238,3 +238,19 @@ def test_arrays_of_the_wrong_storage_are_refused_not_read(ctx):
     ctx.excp_decompress_tensors([(t[0], b32, int(s32[0].blob_bytes), n, guard[:n], None, None)])
     rc, stats = ctx.excp_collect(check=False)
     assert rc == X.EXCP_E_BLOB and torch.all(guard == 7.0)
+
+
+@pytest.mark.parametrize("layout", ["dense", "blob"])
+def test_archive_round_trip_with_sixteen_bit_weights(ctx, layout):
+    from paper_2406_11257_amd import archive as A
+    sizes = [5, 4097, 120001]
+    cases = [case16(n, 760 + i, BF16) for i, n in enumerate(sizes)]
+    res = check16(ctx, cases, BF16)
+    named = [(f"t{i}", t[4], int(st.blob_bytes), n) for i, ((ref, t, st), n) in enumerate(zip(res, sizes))]
+    data = A.save_checkpoint(ctx, named, 4, layout=layout, preset=3, threads=4)
+    back = A.load_checkpoint(ctx, data, {f"t{i}": t[0] for i, (ref, t, st) in enumerate(res)}, threads=4)
+    for i, (ref, t, st) in enumerate(res):
+        W, m, v = back[f"t{i}"]
+        assert W.dtype == torch.bfloat16
+        assert bits(w_to_host(W, BF16)).tobytes() == bits(ref.W_recon).tobytes()
+        assert m.cpu().numpy().tobytes() == ref.m_recon.tobytes() and v.cpu().numpy().tobytes() == ref.v_recon.tobytes()
