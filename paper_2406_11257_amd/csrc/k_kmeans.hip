@@ -214,11 +214,21 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupPa
     __syncthreads();
     for (u32 i = tid; i < ns; i += EXCP_THREADS) atomicAdd(&cnt[cell_of(smp[i], s_map)], 1u);
     __syncthreads();
-    // exclusive scan over the cells (16 consecutive cells per thread), then bucket = share of the sample below
+    // Exclusive scan over the cells (16 consecutive cells per thread), then bucket = share of the sample
+    // below.  A cell that alone holds more than 1/64 of the sample is a tied value (a continuous
+    // distribution never fills one of 4096 cells like that): it gets a bucket of its own, so that a bucket
+    // is either one repeated value -- which neither the initial order statistics nor the Lloyd
+    // iterations ever have to read again -- or an even share of the rest.  With H such cells the others
+    // are spread over S = 255 - 2 H buckets; a heavy cell sits one above the light cells before it and
+    // one below those after it.
     constexpr u32 PER = EXCP_KM_CELLS / EXCP_THREADS;     // 16
-    u32 local[PER], sum = 0;
+    const u32 heavy_min = max(ns / 64u, 32u);
+    u32 local[PER], sum = 0;                               // sum: heavy cells << 16 | samples in light cells
 #pragma unroll
-    for (u32 q = 0; q < PER; ++q) { local[q] = cnt[tid * PER + q]; sum += local[q]; }
+    for (u32 q = 0; q < PER; ++q) {
+        local[q] = cnt[tid * PER + q];
+        sum += local[q] >= heavy_min ? (1u << 16) : local[q];
+    }
     s_part[tid] = sum;
     __syncthreads();
     for (u32 off = 1; off < EXCP_THREADS; off <<= 1) {
@@ -227,6 +237,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupPa
         s_part[tid] += v;
         __syncthreads();
     }
+    const u32 total = s_part[EXCP_THREADS - 1];
+    const u32 H = total >> 16, ns_light = total & 0xffffu;
+    const u32 S = NBKT - 1u - 2u * H;                      // H <= 64, so S >= 127
     u32 run = s_part[tid] - sum;
     u32 *out = w.km_split + (u64)sidx * EXCP_KM_MAP_WORDS;
     if (tid < 4) out[tid] = s_map[tid];
@@ -235,9 +248,13 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupPa
         u32 word = 0;
 #pragma unroll
         for (u32 q = 0; q < 4; ++q) {
-            const u32 bkt = min((u32)(((u64)run * NBKT) / ns), NBKT - 1u);
+            const u32 c = local[q4 * 4 + q];
+            const bool heavy = c >= heavy_min;
+            const u32 light_before = run & 0xffffu, heavy_before = run >> 16;
+            const u32 share = ns_light ? min((u32)(((u64)light_before * S) / ns_light), S - 1u) : 0u;
+            const u32 bkt = share + 2u * heavy_before + (heavy ? 1u : 0u);
             word |= bkt << (8u * q);
-            run += local[q4 * 4 + q];
+            run += heavy ? (1u << 16) : c;
         }
         out[4 + tid * (PER / 4) + q4] = word;
     }
