@@ -552,6 +552,42 @@ __global__ __launch_bounds__(INIT_THREADS) void k_km_init(Workspace w, GroupPara
     const EXCP_GLOBAL float *gpart = gptr(seg_part(w, sidx));
     u32 diff = kmin ^ kmax;
     if (diff == 0) { if (tid == 0) S.C[k] = val_of(kmin); return; }
+    // A bucket far above the average size holds tied values (a continuous distribution fills the
+    // buckets evenly).  Such a bucket is mostly ONE value, its smallest or its largest key, with a few
+    // strays beside it: one cheap pass counts the two extremes, and if the rank falls among them the
+    // answer is known without any digit-by-digit selection.
+    const bool crowded = (u64)(p1 - p0) > 3ull * (len / NBKT + 1ull);
+    if (crowded) {
+        __shared__ u32 s_ext[2];
+        if (tid == 0) { s_ext[0] = 0u; s_ext[1] = 0u; }
+        __syncthreads();
+        u32 c_lo = 0, c_hi = 0;
+        for (u32 q0 = p0; q0 < p1; q0 += 16u * INIT_THREADS) {
+            if (q0 + 16u * INIT_THREADS <= p1) {
+                f4u q[4];
+#pragma unroll
+                for (u32 j = 0; j < 4; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(gpart + q0 + (j * INIT_THREADS + tid) * 4u);
+#pragma unroll
+                for (u32 j = 0; j < 4; ++j) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const u32 key = key_of(q[j][e]);
+                        c_lo += key == kmin; c_hi += key == kmax;
+                    }
+                }
+            } else {
+                for (u32 p = q0 + tid; p < p1; p += INIT_THREADS) {
+                    const u32 key = key_of(gpart[p]);
+                    c_lo += key == kmin; c_hi += key == kmax;
+                }
+            }
+        }
+        c_lo = wave_sum_u32(c_lo); c_hi = wave_sum_u32(c_hi);
+        if ((tid & 63u) == 0u) { atomicAdd(&s_ext[0], c_lo); atomicAdd(&s_ext[1], c_hi); }
+        __syncthreads();
+        if (rank < s_ext[0]) { if (tid == 0) S.C[k] = val_of(kmin); return; }
+        if (rank >= (p1 - p0) - s_ext[1]) { if (tid == 0) S.C[k] = val_of(kmax); return; }
+    }
     int hb = 31 - __clz((int)diff);          // highest bit in which keys of this bucket differ
     u32 prefix = kmin >> (hb + 1 > 31 ? 31 : hb + 1);
     if (hb == 31) prefix = 0;
@@ -561,9 +597,7 @@ __global__ __launch_bounds__(INIT_THREADS) void k_km_init(Workspace w, GroupPara
         const int shift = top + 1 - width;
         if (tid < 256u) hist[tid] = 0;
         __syncthreads();
-        // A bucket far above the average size holds tied values (a continuous distribution fills the
-        // buckets evenly): its lanes mostly hit the same bin, and the increments are grouped per wave.
-        const bool crowded = (u64)(p1 - p0) > 8ull * (len / NBKT + 1ull);
+        // (in a crowded bucket the lanes mostly hit the same bin: the increments are grouped per wave)
         auto tally = [&](float xv, bool in) {
             const u32 key = key_of(xv);
             const bool match = in && ((top == 31) ? true : ((key >> (top + 1)) == prefix));
