@@ -471,8 +471,17 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
         const u32 B = pm + 4u > 39u ? pm + 4u - 39u : 0u;
         u64 aL = 0, aH = 0, nL = 0, nH = 0;
         u32 kmin = 0xffffffffu, kmax = 0;
+        // Tied data (the sixteen-wave form): a large bucket is mostly one value.  The wave takes its
+        // first value as that one and only counts its repetitions; count times value joins the sums
+        // at the end.
+        u32 dom = 0xffffffffu, ndom = 0;                   // bit pattern of the repeated value; this lane's count
+        if (BS_WAVES == 16u) {
+            const u32 first = f2u(part[p0]), fe = (first & 0x7fffffffu) >> 23;
+            if (((fe ? fe : 1u) - 1u) - B < 40u && (first & 0x7fffffffu)) dom = first;     // inside the window, not zero
+        }
         auto take = [&](float xv) {
             const u32 u = f2u(xv), mb = u & 0x7fffffffu, e = mb >> 23;
+            if (BS_WAVES == 16u && u == dom) { ++ndom; return; }
             const u32 k = key_of(xv);
             kmin = min(kmin, k); kmax = max(kmax, k);
             const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
@@ -497,6 +506,16 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
 #pragma unroll
                 for (u32 e = 0; e < 4; ++e) if (i + e < p1) take(part[i + e]);
             }
+        }
+        if (BS_WAVES == 16u && ndom) {
+            const u32 mb = dom & 0x7fffffffu, e = mb >> 23;
+            const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+            const u64 term = (u64)mant << (((e ? e : 1u) - 1u) - B);
+            const u64 tl = (term & 0xffffffffull) * ndom, th = (term >> 32) * ndom;      // a lane sees < 2^20 values
+            aL += tl; aH += th;
+            if (dom >> 31) { nL += tl; nH += th; }
+            const u32 k = key_of(u2f(dom));
+            kmin = min(kmin, k); kmax = max(kmax, k);
         }
         // wave totals: magnitudes of all values (+) and twice those of the negative ones (-)
         aL = wave_sum_u64(aL); aH = wave_sum_u64(aH);
