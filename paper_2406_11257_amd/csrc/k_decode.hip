@@ -450,7 +450,7 @@ __global__ __launch_bounds__(EXCP_THREADS, MOMENTS ? 6 : 8) void k_decode_main(W
 }
 // The same for blobs of 16-bit weights.  Most batches hold none: leave at once then.
 template <bool MOMENTS>
-__global__ __launch_bounds__(EXCP_THREADS) void k_decode_main16(Workspace w, u32 ntensors, u32 ntiles) {
+__global__ __launch_bounds__(EXCP_THREADS, MOMENTS ? 6 : 8) void k_decode_main16(Workspace w, u32 ntensors, u32 ntiles) {
     __shared__ u32 s_any;
     if (threadIdx.x == 0) s_any = 0u;
     __syncthreads();
