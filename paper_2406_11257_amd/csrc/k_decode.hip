@@ -521,13 +521,8 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u
             }
         }
         if (wt != 0u) {                                    // 16-bit weights: the registers hold the widened values
-            const EXCP_GLOBAL unsigned short *H0 = gptr((const unsigned short *)C.W0) + base;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) wp[k][j] = (off + (u32)j < rem) ? w16_widen(H0[off + (u32)j], bf) : 0.f;
-            }
+            for (int k = 0; k < 4; ++k) load_weights4(C.W0, base, wave * 1024u + (u32)k * 256u + lane * 4u, rem, wt, wp[k]);
         }
         for (u32 step = 0; step < C.steps; ++step) {
             const DDesc &D = w.ddesc[C.first_desc + step];
@@ -583,12 +578,18 @@ __global__ __launch_bounds__(EXCP_THREADS, 8) void k_decode_chain(Workspace w, u
         }
         if (wt != 0u) {
             EXCP_GLOBAL unsigned short *Ho = gptr((unsigned short *)C.W_out) + base;
+            const bool vec = ((uintptr_t)C.W_out & 7u) == 0u;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const u32 off = wave * 1024u + (u32)k * 256u + lane * 4u;
+                us4 o16;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (off + (u32)j < rem) Ho[off + (u32)j] = (unsigned short)w16_narrow(wp[k][j], bf);
+                for (int j = 0; j < 4; ++j) o16[j] = (unsigned short)w16_narrow(wp[k][j], bf);
+                if (vec && off + 4u <= rem) *(EXCP_GLOBAL us4 *)(Ho + off) = o16;
+                else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) if (off + (u32)j < rem) Ho[off + (u32)j] = o16[j];
+                }
             }
             continue;
         }
