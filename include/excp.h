@@ -80,12 +80,14 @@ extern "C" {
                                   lloyd_iters < 0, unknown flags, tensor larger than the context allows */
 #define EXCP_E_CAP        -2   /* blob_cap smaller than the compressed tensor */
 #define EXCP_E_NONFINITE  -3   /* NaN or Inf in an input, or the residual overflows fp32 */
-#define EXCP_E_BLOB       -4   /* decompress: bad magic / version / sizes / bitmap population */
+#define EXCP_E_BLOB       -4   /* decompress: bad magic / version / sizes / bitmap population, a blob of another
+                                  weight storage than the arrays passed, or of a kind the call does not read */
 #define EXCP_E_HIP        -5   /* a HIP call failed, or the device could not be used */
 #define EXCP_E_STATE      -6   /* call order violated (batch pending / nothing to collect) */
 #define EXCP_E_INTERNAL   -7   /* an internal work list overflowed (should not happen) */
 
-/* flags of the compress calls (stored in the blob header; decompress does not need them) */
+/* flags of the compress calls (stored in the blob header, which is where the readers take them from;
+ * only the storage of the weight arrays is stated again by whoever reads a blob, see excp_blob) */
 #define EXCP_FLAG_MEDIAN_OF_WEIGHTS 1u  /* med = lower median of |W_t| instead of |d| (the other reading of Eq. "r_w") */
 #define EXCP_FLAG_NO_M2W            2u  /* ablation of Table "vit": r_i = alpha * med for every i (no 1/sqrt(v_i))   */
 #define EXCP_FLAG_NO_QUANT          4u  /* Table "abl", prune without quantisation: the survivors are stored as the
@@ -105,7 +107,8 @@ extern "C" {
                                            exactly, all arithmetic is the fp32 arithmetic above, and a reconstructed
                                            weight is the fp32 sum rounded to nearest even into the storage format;
                                            pruned positions keep their bits.  The moments stay fp32.  The header
-                                           records the storage, and every reader takes it from there. */
+                                           records the storage; a reader passes arrays of that storage and says
+                                           so (excp_blob.flags), and a mismatch is EXCP_E_BLOB. */
 
 #define EXCP_MAX_TENSOR_ELEMS 2147479552ull   /* per-tensor element limit (2^31 - 4096) */
 
