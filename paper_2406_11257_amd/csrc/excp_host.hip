@@ -302,6 +302,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     // per-tile survivor counts of decode; a chain reconstruction keeps those of all its checkpoints
     ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles * EXCP_MAX_CHAIN);
     ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles * EXCP_MAX_CHAIN);
+    ok = ok && dev_alloc(c, &w.dec_kinds, 4);
     ok = ok && dev_alloc(c, &w.err_flag, 4);
     ok = ok && dev_alloc(c, &w.rec_dev, kMaxBatchTensors);
     w.max_chunks = (u32)(chunks_group > 0xffffffffull ? 0xffffffffull : chunks_group);

@@ -30,6 +30,12 @@ __device__ __forceinline__ u32 popcount_range_lane(const u64 *__restrict__ bm, u
     return cnt;
 }
 
+// Which decoder takes a blob: 1 = codes and fp32 weights, 2 = codes and 16-bit weights, 4 = written
+// without quantisation (either weight storage).
+__device__ __forceinline__ u32 blob_kind(u32 nbits, u32 flags) {
+    return nbits == EXCP_RAW_BITS ? 4u : (excp_wtype(flags) != 0u ? 2u : 1u);
+}
+
 __device__ __forceinline__ bool wants_moments(const DDesc &D) {
     return D.m_out != nullptr || D.v_out != nullptr || D.cm != nullptr || D.cv != nullptr;
 }
@@ -65,6 +71,7 @@ __global__ void k_decode_parse(Workspace w, u32 ntensors, u32 allow_raw) {
     }
     if (!ok) { S.status = -4; return; }
     S.n_w = nw; S.n_o = no; S.nbits = nbits; S.blob_bytes = total; S.flags = h[3];
+    atomicOr(w.dec_kinds, blob_kind(nbits, h[3]));
 }
 
 // which == 0: per-tile popcount of bitmap_w.  which == 1: per-tile popcount of the bitmap_o bits
@@ -446,34 +453,19 @@ __device__ __forceinline__ void decode_tiles(const Workspace &w, u32 ntensors, u
 
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, MOMENTS ? 6 : 8) void k_decode_main(Workspace w, u32 ntensors, u32 ntiles) {
+    if ((*w.dec_kinds & 1u) == 0u) return;                 // no blob of fp32 weights in this group
     decode_tiles<MOMENTS, false, false, 0>(w, ntensors, ntiles);
 }
-// The same for blobs of 16-bit weights.  Most batches hold none: leave at once then.
+// The same for blobs of 16-bit weights (most batches hold none).
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS, MOMENTS ? 6 : 8) void k_decode_main16(Workspace w, u32 ntensors, u32 ntiles) {
-    __shared__ u32 s_any;
-    if (threadIdx.x == 0) s_any = 0u;
-    __syncthreads();
-    bool mine = false;
-    for (u32 t = threadIdx.x; t < ntensors; t += EXCP_THREADS)
-        mine = mine || (w.dst[t].status == 0 && w.dst[t].nbits != EXCP_RAW_BITS && excp_wtype(w.dst[t].flags) != 0u);
-    if (mine) s_any = 1u;
-    __syncthreads();
-    if (s_any == 0u) return;
+    if ((*w.dec_kinds & 2u) == 0u) return;
     decode_tiles<MOMENTS, false, false, 1>(w, ntensors, ntiles);
 }
-// Blobs written without quantisation.  Most batches hold none: leave at once then.
+// Blobs written without quantisation (most batches hold none).
 template <bool MOMENTS>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_raw(Workspace w, u32 ntensors, u32 ntiles) {
-    __shared__ u32 s_any;
-    if (threadIdx.x == 0) s_any = 0u;
-    __syncthreads();
-    bool mine = false;
-    for (u32 t = threadIdx.x; t < ntensors; t += EXCP_THREADS)
-        mine = mine || (w.dst[t].status == 0 && w.dst[t].nbits == EXCP_RAW_BITS);
-    if (mine) s_any = 1u;
-    __syncthreads();
-    if (s_any == 0u) return;
+    if ((*w.dec_kinds & 4u) == 0u) return;
     decode_tiles<MOMENTS, false, true, 2>(w, ntensors, ntiles);
 }
 template <bool MOMENTS>
@@ -800,6 +792,7 @@ __global__ void k_decode_from_compress(Workspace w, GroupParams g) {
     S.off_bo = T.off_bo; S.off_cw = T.off_cw; S.off_cm = T.off_cm; S.off_cv = T.off_cv;
     S.status = (T.status == 0 && C.W_out != nullptr) ? 0 : 1;    // 1 = skip silently
     S.pop_w = 0; S.pop_o = 0; S.flags = g.flags; S.pad = 0;
+    if (t == 0) *w.dec_kinds = blob_kind((u32)g.nbits, g.flags);
 }
 
 // The compress path already knows how many survivors precede every tile: the exclusive scan of its
@@ -813,6 +806,7 @@ __global__ void k_decode_counts_from_mask(Workspace w, u32 ntiles) {
 
 void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s) {
     if (!ntensors) return;
+    launch_zero_u32(w.dec_kinds, 1, s);
     hipLaunchKernelGGL(k_decode_parse, dim3((ntensors + 255) / 256), dim3(256), 0, s, w, ntensors, allow_raw ? 1u : 0u);
 }
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s) {
