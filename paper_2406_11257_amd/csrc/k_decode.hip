@@ -724,8 +724,15 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_dense(Workspace w, u32 
                     const EXCP_GLOBAL unsigned short *Hp = gptr((const unsigned short *)D.Wp) + e0;
                     EXCP_GLOBAL unsigned short *Ho = gptr((unsigned short *)D.W_out) + e0;
                     u32 h[8];
+                    const bool vec = left == 8u && (((uintptr_t)D.Wp | (uintptr_t)D.W_out) & 7u) == 0u;
+                    if (vec) {
+                        const us4 a = *(const EXCP_GLOBAL us4 *)Hp, b = *(const EXCP_GLOBAL us4 *)(Hp + 4);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) h[j] = ((u32)j < left) ? Hp[j] : 0u;
+                        for (int j = 0; j < 4; ++j) { h[j] = a[j]; h[4 + j] = b[j]; }
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) h[j] = ((u32)j < left) ? Hp[j] : 0u;
+                    }
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const u32 c = (u32)(c8 >> (8 * j)) & 255u;
@@ -733,8 +740,15 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_dense(Workspace w, u32 
                         const float centre = s_book[c & (E - 1u)];
                         if (c) h[j] = w16_narrow(w16_widen(h[j], bf) + centre, bf);
                     }
+                    if (vec) {
+                        us4 a, b;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) if ((u32)j < left) Ho[j] = (unsigned short)h[j];
+                        for (int j = 0; j < 4; ++j) { a[j] = (unsigned short)h[j]; b[j] = (unsigned short)h[4 + j]; }
+                        *(EXCP_GLOBAL us4 *)Ho = a; *(EXCP_GLOBAL us4 *)(Ho + 4) = b;
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) if ((u32)j < left) Ho[j] = (unsigned short)h[j];
+                    }
                     continue;
                 }
                 if (q == 0) {
