@@ -328,7 +328,7 @@ __global__ __launch_bounds__(1024) void k_km_scan(Workspace w, GroupParams g) {
     const u32 a0 = min(c0 + q * nq, c1), a1 = min(a0 + nq, c1);
     u32 *cnt = w.km_cnt;
     u32 s = 0;
-#pragma unroll 8
+#pragma unroll 16
     for (u32 c = a0; c < a1; ++c) s += cnt[(u64)c * NBKT + b];
     tot[q][b] = s;
     __syncthreads();
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(1024) void k_km_scan(Workspace w, GroupParams g) {
     }
     u32 run = begin[b];
     for (u32 qq = 0; qq < q; ++qq) run += tot[qq][b];
-#pragma unroll 4
+#pragma unroll 16
     for (u32 c = a0; c < a1; ++c) {
         u32 v = cnt[(u64)c * NBKT + b];
         cnt[(u64)c * NBKT + b] = run;
