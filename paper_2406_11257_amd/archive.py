@@ -9,8 +9,9 @@ Archive file (little endian):
     8 B   magic "EXCPARC1"
     8 B   u64 length L of the index
     L B   index, UTF-8 JSON: {"tensors": [{"name", "n", "nbits", "layout", "sections":
-          [{"raw", "packed", "crc"} ...]} ...]}
-    ...   the packed sections, back to back, in index order; each one is a raw LZMA2 stream
+          [{"raw", "packed", "crc"} ...]} ...], "preset", "codec"}
+    ...   the packed sections, back to back, in index order; each one is a raw LZMA2 stream (or, for
+          the comparison of Table "compact", a zlib or bzip2 stream)
 
 Layouts: "dense" = head, codes_w, codes_m, codes_v (the paper's stored layout, one code per
 element); "blob" = the compressed tensor of the C ABI as one section (bitmaps + packed codes).
@@ -19,6 +20,7 @@ interpreter lock) and a single tensor can be read back without the others.
 """
 from __future__ import annotations
 
+import bz2
 import json
 import lzma
 import struct
@@ -27,20 +29,42 @@ from concurrent.futures import ThreadPoolExecutor
 
 MAGIC = b"EXCPARC1"
 DEFAULT_PRESET = 9 | lzma.PRESET_EXTREME
+CODECS = ("lzma2", "deflate", "bzip2", "none")      # Table "compact" compares 7z with zip and bz2
 
 
 def _filters(preset: int):
     return [{"id": lzma.FILTER_LZMA2, "preset": preset}]
 
 
-def _pack_one(args):
-    raw, preset = args
-    return lzma.compress(raw, format=lzma.FORMAT_RAW, filters=_filters(preset))
+def _encode(raw: bytes, codec: str, preset: int) -> bytes:
+    if codec == "lzma2":
+        return lzma.compress(raw, format=lzma.FORMAT_RAW, filters=_filters(preset))
+    if codec == "deflate":
+        return zlib.compress(raw, 9)
+    if codec == "bzip2":
+        return bz2.compress(raw, 9)
+    if codec == "none":
+        return raw
+    raise ValueError("unknown codec " + codec)
 
 
-def pack(tensors, preset: int = DEFAULT_PRESET, threads: int = 8) -> bytes:
+def _decode(packed: bytes, codec: str, preset: int) -> bytes:
+    if codec == "lzma2":
+        return lzma.decompress(packed, format=lzma.FORMAT_RAW, filters=_filters(preset))
+    if codec == "deflate":
+        return zlib.decompress(packed)
+    if codec == "bzip2":
+        return bz2.decompress(packed)
+    if codec == "none":
+        return packed
+    raise ValueError("unknown codec " + codec)
+
+
+def pack(tensors, preset: int = DEFAULT_PRESET, threads: int = 8, codec: str = "lzma2") -> bytes:
     """tensors: sequence of dicts {"name", "n", "nbits", "layout", "sections": [bytes-like, ...]}.
-    Returns the archive."""
+    codec: "lzma2" (the paper's choice), "deflate", "bzip2" or "none".  Returns the archive."""
+    if codec not in CODECS:
+        raise ValueError("unknown codec " + str(codec))
     jobs = []
     for t in tensors:
         if t["layout"] not in ("dense", "blob"):
@@ -50,8 +74,8 @@ def pack(tensors, preset: int = DEFAULT_PRESET, threads: int = 8) -> bytes:
         for s in t["sections"]:
             jobs.append((bytes(s), preset))
     with ThreadPoolExecutor(max_workers=max(1, threads)) as pool:
-        packed = list(pool.map(_pack_one, jobs))
-    index, k = {"preset": preset, "tensors": []}, 0
+        packed = list(pool.map(lambda job: _encode(job[0], codec, job[1]), jobs))
+    index, k = {"preset": preset, "codec": codec, "tensors": []}, 0
     for t in tensors:
         secs = []
         for s in t["sections"]:
@@ -77,7 +101,9 @@ def read_index(data: bytes) -> tuple[dict, int]:
 def unpack(data: bytes, threads: int = 8):
     """Inverse of pack(): the list of tensors with their raw sections (bytes); verifies lengths and CRCs."""
     index, off = read_index(data)
-    preset = index["preset"]
+    preset, codec = index["preset"], index.get("codec", "lzma2")
+    if codec not in CODECS:
+        raise ValueError("unknown codec " + str(codec))
     jobs = []
     for t in index["tensors"]:
         for s in t["sections"]:
@@ -88,7 +114,7 @@ def unpack(data: bytes, threads: int = 8):
 
     def one(job):
         blob, s = job
-        raw = lzma.decompress(blob, format=lzma.FORMAT_RAW, filters=_filters(preset))
+        raw = _decode(blob, codec, preset)
         if len(raw) != s["raw"] or zlib.crc32(raw) != s["crc"]:
             raise ValueError("a section does not match its index entry")
         return raw
@@ -108,7 +134,7 @@ def unpack(data: bytes, threads: int = 8):
 # GPU <-> archive.  `ctx` is a paper_2406_11257_amd.Context; blobs are what its compress calls wrote.
 # ---------------------------------------------------------------------------------------------
 def save_checkpoint(ctx, named_blobs, nbits: int, layout: str = "dense", preset: int = DEFAULT_PRESET,
-                    threads: int = 8) -> bytes:
+                    threads: int = 8, codec: str = "lzma2") -> bytes:
     """named_blobs: sequence of (name, blob device tensor, blob_bytes, n).  Exports the paper's stored
     layout on the GPU (layout "dense") or takes the blobs as they are ("blob"), copies to the host
     and packs.  Returns the archive bytes."""
@@ -135,7 +161,7 @@ def save_checkpoint(ctx, named_blobs, nbits: int, layout: str = "dense", preset:
                             "sections": [blob[:nbytes].cpu().numpy().tobytes()]})
     else:
         raise ValueError("unknown layout " + layout)
-    return pack(tensors, preset, threads)
+    return pack(tensors, preset, threads, codec)
 
 
 def load_checkpoint(ctx, data: bytes, W_prev, want_moments: bool = True, threads: int = 8):
@@ -204,11 +230,12 @@ def _report(cid: int, preset: int, threads: int, max_tensors: int | None) -> Non
     print(f"  blob (bitmaps + packed codes): {blob_bytes} B  ratio {raw / blob_bytes:.2f}")
     print(f"  per-element codes (Sec. 4.2):   {dense_bytes} B  ratio {raw / dense_bytes:.2f}")
     for layout in ("dense", "blob"):
-        t0 = time.time()
-        data = save_checkpoint(ctx, named, synth.NBITS, layout=layout, preset=preset, threads=threads)
-        dt = time.time() - t0
-        print(f"  {layout:5s} + LZMA2 (preset {preset & 15}{'e' if preset & lzma.PRESET_EXTREME else ''}, {threads} threads): "
-              f"{len(data)} B  ratio {raw / len(data):.2f}  ({dt:.1f} s)", flush=True)
+        for codec in ("lzma2", "bzip2", "deflate"):
+            t0 = time.time()
+            data = save_checkpoint(ctx, named, synth.NBITS, layout=layout, preset=preset, threads=threads, codec=codec)
+            dt = time.time() - t0
+            how = f"LZMA2 (preset {preset & 15}{'e' if preset & lzma.PRESET_EXTREME else ''})" if codec == "lzma2" else codec
+            print(f"  {layout:5s} + {how}, {threads} threads: {len(data)} B  ratio {raw / len(data):.2f}  ({dt:.1f} s)", flush=True)
     ctx.close()
 
 

@@ -48,6 +48,22 @@ def test_round_trip_of_both_layouts_and_reconstruction():
     assert len(data) < raw
 
 
+@pytest.mark.parametrize("codec", ["lzma2", "deflate", "bzip2", "none"])
+def test_every_codec_round_trips(codec):
+    Wp, W, m, v = small(5000, 3)
+    r = O.compress_step(Wp, W, m, v, nbits=4, iters=2)
+    head, cw, cm, cv = O.export_dense(r.blob)
+    entries = [{"name": "a", "n": 5000, "nbits": 4, "layout": "dense", "sections": [head, cw.tobytes(), cm.tobytes(), cv.tobytes()]},
+               {"name": "b", "n": 5000, "nbits": 4, "layout": "blob", "sections": [r.blob]}]
+    data = A.pack(entries, preset=2, threads=2, codec=codec)
+    back = A.unpack(data, threads=2)
+    assert A.read_index(data)[0]["codec"] == codec
+    for a, b in zip(entries, back):
+        assert [bytes(x) for x in a["sections"]] == b["sections"]
+    with pytest.raises(ValueError):
+        A.pack(entries, codec="rar")
+
+
 def test_container_checks():
     e = [{"name": "x", "n": 4, "nbits": 4, "layout": "blob", "sections": [b"abcd" * 100]}]
     data = A.pack(e, preset=1, threads=1)
