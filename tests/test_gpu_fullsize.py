@@ -188,3 +188,63 @@ def test_sixteen_bit_weights_at_full_size(batch):
     book = torch.from_numpy(np.frombuffer(blob2[80:80 + 64].cpu().numpy().tobytes(), dtype="<f4").copy()).to(dev)
     cand = (Wpb.float()[keep][:2_000_000, None] + book[None, 1:]).bfloat16()
     assert bool((cand == Wout2[keep][:2_000_000, None]).any(dim=1).all())
+
+
+def test_tensor_at_the_element_limit():
+    """One tensor of 2^31 - 4096 elements, the most a context accepts: thresholds and counts against
+    independent device-side routines, the keep bitmap word by word at both ends and in the middle,
+    Alg. 2 against what compress kept, and the last elements' codes against the oracle's rule."""
+    dev = torch.device("cuda", 0)
+    n = 2147479552
+    if torch.cuda.mem_get_info()[0] < 150 * 2**30:
+        pytest.skip("needs about 130 GiB of free device memory")
+    g = torch.Generator(device=dev)
+    g.manual_seed(1234)
+    Wp = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 0.02, generator=g)
+    W = torch.empty(n, dtype=torch.float32, device=dev).uniform_(-0.5, 0.5, generator=g)
+    W = -1e-4 * torch.sign(W) * torch.log1p(-2.0 * W.abs().clamp_(max=0.49999997))     # Laplace(0, 1e-4)
+    W += Wp
+    m = torch.empty(n, dtype=torch.float32, device=dev).normal_(0, 5e-5, generator=g)
+    v = torch.empty(n, dtype=torch.float32, device=dev).normal_(generator=g).exp_()
+    v.mul_(m).mul_(m).add_(1e-16)
+    ctx = X.Context(n, n)
+    blob = torch.empty(X.excp_blob_bound(n, 4), dtype=torch.uint8, device=dev)
+    Wout = torch.empty(n, dtype=torch.float32, device=dev)
+    ctx.excp_compress_tensors([(Wp, W, m, v, blob, Wout)], synth.ALPHA, synth.BETA, 4, synth.LLOYD_ITERS, 0)
+    rc, stats = ctx.excp_collect(check=False)
+    st = stats[0]
+    print("2^31 - 4096 elements: n_w", st.n_w, "n_o", st.n_o, "bytes", st.blob_bytes, flush=True)
+    assert rc == 0 and st.status == 0 and st.n == n
+    d = W - Wp
+    ad = d.abs()
+    kth = torch.kthvalue(ad, (n - 1) // 2 + 1).values.item()
+    del ad
+    assert f32(kth).tobytes() == f32(st.median_abs_dw).tobytes()
+    mean64 = m.abs().double().sum().item() / n
+    assert f32(mean64).tobytes() == f32(st.mean_abs_m).tobytes()
+    t_w = f32(f32(synth.ALPHA) * f32(st.median_abs_dw))
+    r_o = f32(f32(synth.BETA) * f32(st.mean_abs_m))
+    keep = d.abs() > (torch.tensor(t_w, device=dev) / torch.sqrt(v))
+    assert int(keep.sum().item()) == st.n_w
+    assert int((keep & (m.abs() > float(r_o))).sum().item()) == st.n_o
+    assert st.blob_bytes == X.excp_blob_size(n, st.n_w, st.n_o, 4)
+    words = (n + 63) // 64
+    bm = blob[80 + 192: 80 + 192 + 8 * words].view(torch.int64)
+    for w0 in (0, words // 2 - 500, words - 1000):
+        kk = keep[w0 * 64:(w0 + 1000) * 64].view(1000, 64).to(torch.int64)
+        ref = (kk << torch.arange(64, device=dev, dtype=torch.int64)).sum(dim=1)
+        assert torch.equal(bm[w0:w0 + 1000], ref), w0
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    ctx.excp_decompress_tensors([(Wp, blob, int(st.blob_bytes), n, out, None, None)])
+    rc, _ = ctx.excp_collect(check=False)
+    assert rc == 0 and torch.equal(out, Wout)
+    assert torch.equal(Wout[~keep], Wp[~keep])
+    book = np.frombuffer(blob[80:80 + 64].cpu().numpy().tobytes(), dtype="<f4").copy()
+    tail = torch.arange(n - 200000, n, device=dev)
+    hd = (W[tail] - Wp[tail]).cpu().numpy()
+    hk = keep[tail].cpu().numpy()
+    want = O.nearest_centre(hd[hk], book[1:]) + 1
+    got = Wout[tail].cpu().numpy()[hk]
+    expect = (Wp[tail].cpu().numpy()[hk] + book[want]).astype(f32)
+    assert np.array_equal(got.view(np.uint32), expect.view(np.uint32))
+    ctx.close()
