@@ -118,6 +118,7 @@ struct GroupParams {
     int nbits, K, iters;
     u32 flags;
     u32 ntensors, ntiles;
+    u32 wide;                   // launch the per-bucket kernels with sixteen waves: tied data, or one very large tensor
 };
 
 #define EXCP_RAW_BITS    32u       // "code" width of a blob written without quantisation: fp32 values, no codebooks
@@ -146,6 +147,7 @@ struct Workspace {
     u32 *km_split;            // [segment][EXCP_KM_MAP_WORDS] value -> bucket map: 4 parameters, then 4096 bucket bytes
     u32 *km_cnt;              // [chunk][256] bucket counts, then positions, of every chunk
     u32 *km_begin;            // [segment][257] first position of every bucket
+    u32 *km_part;             // [segment][16][256] bucket counts, then first positions, of each sixteenth of a stream's chunks
     u64 *km_bsum;             // [segment][256][EXCP_ABSM_BINS] exact signed sum of every bucket
     u32 *km_min, *km_max;     // [segment][256] smallest / largest key of every bucket
     u64 *km_acc;              // [segment][EXCP_MAX_K][EXCP_ABSM_BINS + 1] per-centre exact sum and count

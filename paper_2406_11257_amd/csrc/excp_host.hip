@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <new>
+#include <algorithm>
 #include <vector>
 
 #include "../../include/excp.h"
@@ -290,6 +291,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.km_split, nseg_max * EXCP_KM_MAP_WORDS);
     ok = ok && dev_alloc(c, &w.km_cnt, chunks_group * 256);
     ok = ok && dev_alloc(c, &w.km_begin, nseg_max * 257);
+    ok = ok && dev_alloc(c, &w.km_part, nseg_max * 16 * 256);
     ok = ok && dev_alloc(c, &w.km_bsum, nseg_max * 256 * EXCP_ABSM_BINS);
     ok = ok && dev_alloc(c, &w.km_min, nseg_max * 256);
     ok = ok && dev_alloc(c, &w.km_max, nseg_max * 256);
@@ -439,6 +441,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         GroupParams p{};
         p.alpha = alpha; p.beta = beta; p.nbits = nbits; p.K = K; p.iters = lloyd_iters; p.flags = flags;
         p.ntensors = g.count; p.ntiles = g.ntiles;
+        u64 largest = 0;
+        for (u32 q = 0; q < g.count; ++q) largest = std::max<u64>(largest, tensors[g.first + q].n);
+        p.wide = ((flags & 0x30u) != 0 || largest >= (1ull << 28)) ? 1u : 0u;
 #ifdef EXCP_TUNING
         w.tune_wgs = (flags >> 24) & 0xffu;
 #endif

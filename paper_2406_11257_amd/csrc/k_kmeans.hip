@@ -316,42 +316,85 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_count(Workspace w, Group
 }
 
 // ---------------------------------------------------------------- P2: offsets of every (chunk, bucket)
-// 1024 threads: thread (q, b) owns bucket b over one quarter of the stream's chunks.
-__global__ __launch_bounds__(1024) void k_km_scan(Workspace w, GroupParams g) {
-    __shared__ u32 tot[4][NBKT];
-    __shared__ u32 begin[NBKT + 1];
-    const u32 sidx = blockIdx.x, tid = threadIdx.x, q = tid >> 8, b = tid & 255u;
-    const u64 len = w.seg[sidx].len;
-    if (len == 0) return;
+// A stream's chunks are cut into sixteen parts so that sixteen workgroups share the walk over a long
+// stream's count table: (a) per-bucket totals of every part, (b) per stream: bucket totals, their
+// scan, and the first position of every (part, bucket), (c) per part: counts -> positions.
+constexpr u32 SCAN_PARTS = 16;
+
+__device__ __forceinline__ void scan_part_range(const Workspace &w, u32 sidx, u32 part, u32 &a0, u32 &a1) {
     const u32 c0 = w.seg[sidx].chunk_begin, c1 = w.seg_chunk_begin[sidx + 1];
-    const u32 nq = (c1 - c0 + 3) / 4;
-    const u32 a0 = min(c0 + q * nq, c1), a1 = min(a0 + nq, c1);
+    const u32 per = (c1 - c0 + SCAN_PARTS - 1u) / SCAN_PARTS;
+    a0 = min(c0 + part * per, c1);
+    a1 = min(a0 + per, c1);
+}
+
+// 1024 threads: thread (q, b) owns bucket b over one quarter of the part's chunks.
+__global__ __launch_bounds__(1024) void k_km_scan_parts(Workspace w, GroupParams g) {
+    __shared__ u32 tot[4][NBKT];
+    const u32 sidx = blockIdx.x / SCAN_PARTS, part = blockIdx.x % SCAN_PARTS;
+    const u32 tid = threadIdx.x, q = tid >> 8, b = tid & 255u;
+    if (w.seg[sidx].len == 0) return;
+    u32 p0, p1;
+    scan_part_range(w, sidx, part, p0, p1);
+    const u32 nq = (p1 - p0 + 3u) / 4u;
+    const u32 a0 = min(p0 + q * nq, p1), a1 = min(a0 + nq, p1);
+    const u32 *cnt = w.km_cnt;
+    u32 s = 0;
+#pragma unroll 16
+    for (u32 c = a0; c < a1; ++c) s += cnt[(u64)c * NBKT + b];
+    tot[q][b] = s;
+    __syncthreads();
+    if (q == 0) w.km_part[((u64)sidx * SCAN_PARTS + part) * NBKT + b] = tot[0][b] + tot[1][b] + tot[2][b] + tot[3][b];
+}
+
+// One workgroup of 256 threads per stream; thread b owns bucket b.
+__global__ __launch_bounds__(NBKT) void k_km_scan(Workspace w, GroupParams g) {
+    __shared__ u32 begin[NBKT + 1];
+    const u32 sidx = blockIdx.x, b = threadIdx.x;
+    if (w.seg[sidx].len == 0) return;
+    u32 *part = w.km_part + (u64)sidx * SCAN_PARTS * NBKT;
+    u32 pt[SCAN_PARTS], total = 0;
+#pragma unroll
+    for (u32 p = 0; p < SCAN_PARTS; ++p) { pt[p] = part[p * NBKT + b]; total += pt[p]; }
+    begin[b + 1] = total;
+    if (b == 0) begin[0] = 0;
+    __syncthreads();
+    // inclusive scan of begin[1..256]
+    for (u32 off = 1; off < NBKT; off <<= 1) {
+        const u32 v = b >= off ? begin[b + 1 - off] : 0u;
+        __syncthreads();
+        begin[b + 1] += v;
+        __syncthreads();
+    }
+    w.km_begin[(u64)sidx * (NBKT + 1) + b + 1] = begin[b + 1];
+    if (b == 0) w.km_begin[(u64)sidx * (NBKT + 1)] = 0;
+    u32 run = begin[b];
+#pragma unroll
+    for (u32 p = 0; p < SCAN_PARTS; ++p) { part[p * NBKT + b] = run; run += pt[p]; }
+}
+
+// 1024 threads: thread (q, b) turns the counts of bucket b into positions over one quarter of the
+// part's chunks (its start: the part's first position plus the quarters before it).
+__global__ __launch_bounds__(1024) void k_km_scan_apply(Workspace w, GroupParams g) {
+    __shared__ u32 tot[4][NBKT];
+    const u32 sidx = blockIdx.x / SCAN_PARTS, part = blockIdx.x % SCAN_PARTS;
+    const u32 tid = threadIdx.x, q = tid >> 8, b = tid & 255u;
+    if (w.seg[sidx].len == 0) return;
+    u32 p0, p1;
+    scan_part_range(w, sidx, part, p0, p1);
+    const u32 nq = (p1 - p0 + 3u) / 4u;
+    const u32 a0 = min(p0 + q * nq, p1), a1 = min(a0 + nq, p1);
     u32 *cnt = w.km_cnt;
     u32 s = 0;
 #pragma unroll 16
     for (u32 c = a0; c < a1; ++c) s += cnt[(u64)c * NBKT + b];
     tot[q][b] = s;
     __syncthreads();
-    if (q == 0) begin[b + 1] = tot[0][b] + tot[1][b] + tot[2][b] + tot[3][b];
-    if (tid == 0) begin[0] = 0;
-    __syncthreads();
-    // inclusive scan of begin[1..256] by the first 256 threads
-    for (u32 off = 1; off < NBKT; off <<= 1) {
-        u32 v = 0;
-        if (q == 0 && b >= off) v = begin[b + 1 - off];
-        __syncthreads();
-        if (q == 0) begin[b + 1] += v;
-        __syncthreads();
-    }
-    if (q == 0) {
-        w.km_begin[(u64)sidx * (NBKT + 1) + b + 1] = begin[b + 1];
-        if (b == 0) w.km_begin[(u64)sidx * (NBKT + 1)] = 0;
-    }
-    u32 run = begin[b];
+    u32 run = w.km_part[((u64)sidx * SCAN_PARTS + part) * NBKT + b];
     for (u32 qq = 0; qq < q; ++qq) run += tot[qq][b];
 #pragma unroll 16
     for (u32 c = a0; c < a1; ++c) {
-        u32 v = cnt[(u64)c * NBKT + b];
+        const u32 v = cnt[(u64)c * NBKT + b];
         cnt[(u64)c * NBKT + b] = run;
         run += v;
     }
@@ -436,8 +479,9 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
 // values met holds practically all of them; inside it a lane adds shifted mantissas as integers
 // (low and high 32-bit halves in separate 64-bit counters, magnitudes of all values and of the
 // negative ones) with no cross-lane traffic; the rest (rare) is filed one by one.
-// (sixteen for 16-bit weights, whose residuals are heavily tied; four otherwise, which is faster when
-// the buckets are even)
+// (sixteen for 16-bit weights, whose residuals are heavily tied, and for groups with a tensor so large
+// that its buckets alone are millions of values; four otherwise, which is faster when the buckets are
+// small and even)
 template <u32 BS_WAVES>
 __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, GroupParams g) {
     __shared__ u64 bins[4][EXCP_ABSM_BINS];
@@ -551,7 +595,8 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
 // ---------------------------------------------------------------- P6: initial centres
 // One workgroup per (stream, rank): radix select inside the bucket that holds the rank; the bits
 // that the bucket's minimum and maximum key share are known and skipped.
-// (1024 threads for 16-bit weights: a bucket of tied values can be most of a stream; 256 otherwise)
+// (1024 threads for 16-bit weights -- a bucket of tied values can be most of a stream -- and for very
+// large tensors; 256 otherwise)
 template <u32 INIT_THREADS>
 __global__ __launch_bounds__(INIT_THREADS) void k_km_init(Workspace w, GroupParams g) {
     __shared__ u32 hist[256];
@@ -1107,10 +1152,14 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
     switch (phase) {
         case 0: hipLaunchKernelGGL(k_km_sample, dim3(nseg), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 1: hipLaunchKernelGGL(k_km_count, dim3(excp_grid(w, 30)), dim3(EXCP_THREADS), 0, s, w, g); break;
-        case 2: hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(1024), 0, s, w, g); break;
+        case 2:
+            hipLaunchKernelGGL(k_km_scan_parts, dim3(nseg * SCAN_PARTS), dim3(1024), 0, s, w, g);
+            hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(NBKT), 0, s, w, g);
+            hipLaunchKernelGGL(k_km_scan_apply, dim3(nseg * SCAN_PARTS), dim3(1024), 0, s, w, g);
+            break;
         case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 96)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 4:
-            if (g.flags & 0x30u) hipLaunchKernelGGL(k_km_bucket_stats<16>, dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
+            if (g.wide) hipLaunchKernelGGL(k_km_bucket_stats<16>, dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
             else hipLaunchKernelGGL(k_km_bucket_stats<4>, dim3(nseg * (NBKT / 4)), dim3(256), 0, s, w, g);
             break;
         default: break;
@@ -1119,7 +1168,7 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
 
 void launch_km_init(const Workspace &w, const GroupParams &g, hipStream_t s) {
     if (!g.ntensors) return;
-    if (g.flags & 0x30u) hipLaunchKernelGGL(k_km_init<1024>, dim3(3 * g.ntensors * (u32)g.K), dim3(1024), 0, s, w, g);
+    if (g.wide) hipLaunchKernelGGL(k_km_init<1024>, dim3(3 * g.ntensors * (u32)g.K), dim3(1024), 0, s, w, g);
     else hipLaunchKernelGGL(k_km_init<256>, dim3(3 * g.ntensors * (u32)g.K), dim3(256), 0, s, w, g);
 }
 
