@@ -31,6 +31,8 @@ struct TDesc {
     u64 elem_off;      // start of this tensor's survivor slots in the group workspace
     u64 cand_off;      // start and capacity of this tensor's median-candidate list
     u64 cand_cap;
+    u32 cand_lists;    // the candidate list of a very large tensor is cut into this many lists (1 .. 16), each with a
+    u32 pad0;          // counter of its own, so that thousands of waves do not queue at one address
     u32 tile_begin;    // first tile of this tensor in the group's tile list
     u32 tile_count;
 };
@@ -136,6 +138,7 @@ struct Workspace {
     // median select
     u32 *med_hist;            // [tensor][2048]
     u32 *cand;                // median candidates (keys inside the sample bracket), per tensor
+    u32 *cand_ctr;            // [tensor][16][32] per list: [0] slots asked for, [1] end of the slots granted (128 B apart)
     // mask pass
     u64 *tile_status;         // per 2048-element sub-tile: survivors << 32 | moment survivors
     u64 *mask_prefix;         // exclusive scan of tile_status within each tensor

@@ -37,7 +37,7 @@ struct excp_ctx {
     u64 max_tensor = 0, max_group = 0, max_tiles = 0;
     Workspace w{};
     // per-batch arrays (device) and their pinned staging (host)
-    TDesc *desc_all = nullptr; TState *st_all = nullptr;
+    TDesc *desc_all = nullptr; TState *st_all = nullptr; u32 *cand_ctr_all = nullptr;
     DDesc *ddesc_all = nullptr; DState *dst_all = nullptr;
     CDesc *cdesc_all = nullptr; CDesc *h_cdesc = nullptr;
     u32 *tile_begin_all = nullptr;
@@ -268,6 +268,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     bool ok = true;
     ok = ok && dev_alloc(c, &c->desc_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->st_all, kMaxBatchTensors);
+    ok = ok && dev_alloc(c, &c->cand_ctr_all, (u64)kMaxBatchTensors * 512);
     ok = ok && dev_alloc(c, &c->ddesc_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->dst_all, kMaxBatchTensors);
     ok = ok && dev_alloc(c, &c->cdesc_all, kMaxBatchTensors);
@@ -412,7 +413,8 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
             d.Wp = (const float *)t.W_prev_recon; d.W = (const float *)t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
             d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = (float *)t.W_recon_out;
             d.elem_off = elem_off; d.tile_begin = tile;
-            d.cand_off = cand_off; d.cand_cap = t.n / 12 + 4096;
+            d.cand_lists = (u32)std::min<u64>(std::max<u64>(t.n >> 26, 1), 16); d.pad0 = 0;
+            d.cand_off = cand_off; d.cand_cap = (t.n / 12 + 4096 + d.cand_lists - 1) / d.cand_lists * d.cand_lists;
             cand_off += d.cand_cap;
             d.tile_count = (u32)((t.n + EXCP_TILE - 1) / EXCP_TILE);
             c->h_tile_begin[tb_off + q] = tile;
@@ -427,12 +429,14 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
             hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
             return EXCP_E_HIP;
         launch_zero_u32((u32 *)c->st_all, (u64)count * sizeof(TState) / 4, s);
+        launch_zero_u32(c->cand_ctr_all, (u64)count * 512, s);
     }
     for (size_t gi = 0; gi < groups.size(); ++gi) {
         const Group &g = groups[gi];
         Workspace w = c->w;
         w.desc = c->desc_all + g.first;
         w.st = c->st_all + g.first;
+        w.cand_ctr = c->cand_ctr_all + (u64)g.first * 512;
         w.ddesc = c->ddesc_all + g.first;
         w.dst = c->dst_all + g.first;
         w.tile_begin = c->tile_begin_all + tb_offsets[gi];

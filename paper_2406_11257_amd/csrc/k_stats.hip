@@ -144,17 +144,42 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
         if (W16) { acnt[0] = acnt[1] = acnt[2] = acnt[3] = 0u; }
         // the staged candidates go to the tensor's list: one reservation for many tiles
         if (wcount) {
-            u32 at = 0;
-            if (lane == 0) at = atomicAdd(&w.st[tt].cand_count, wcount);
-            at = __shfl(at, 0, WAVE);
-            if (w.st[tt].br_lo == w.st[tt].br_hi) {
-                // a bracket of one value (heavily tied data, e.g. 16-bit weights that did not move):
-                // every candidate is that value, so their number is all that is needed
-            } else if ((u64)at + wcount <= w.desc[tt].cand_cap) {
-                EXCP_GLOBAL u32 *dst = gptr(w.cand) + w.desc[tt].cand_off + at;
-                for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
-            } else if (lane == 0) {
-                atomicOr(&w.st[tt].cand_overflow, 1u);
+            const TDesc &D = w.desc[tt];
+            const u32 L = D.cand_lists;
+            const bool one_value = w.st[tt].br_lo == w.st[tt].br_hi;
+            if (L == 1u) {
+                u32 at = 0;
+                if (lane == 0) at = atomicAdd(&w.st[tt].cand_count, wcount);
+                at = __shfl(at, 0, WAVE);
+                if (one_value) {
+                    // a bracket of one value (heavily tied data, e.g. 16-bit weights that did not move):
+                    // every candidate is that value, so their number is all that is needed
+                } else if ((u64)at + wcount <= D.cand_cap) {
+                    EXCP_GLOBAL u32 *dst = gptr(w.cand) + D.cand_off + at;
+                    for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
+                } else if (lane == 0) {
+                    atomicOr(&w.st[tt].cand_overflow, 1u);
+                }
+            } else {
+                // a very large tensor: L lists with a counter each; a wave starts at "its" list and moves
+                // on to the next when one is full, so the lists fail only when all of them are full
+                u32 *ctr = w.cand_ctr + (u64)tt * 512u;
+                const u32 cap = (u32)(D.cand_cap / L);
+                u32 j = (blockIdx.x * 4u + wave) % L;
+                bool placed = false;
+                for (u32 attempt = 0; attempt < L && !placed; ++attempt, j = (j + 1u == L ? 0u : j + 1u)) {
+                    u32 at = 0;
+                    if (lane == 0) at = atomicAdd(&ctr[j * 32u], wcount);
+                    at = __shfl(at, 0, WAVE);
+                    if (one_value) { placed = true; break; }            // counted only
+                    if ((u64)at + wcount <= cap) {
+                        EXCP_GLOBAL u32 *dst = gptr(w.cand) + D.cand_off + (u64)j * cap + at;
+                        for (u32 i = lane; i < wcount; i += 64) dst[i] = l_cand[wave][i];
+                        if (lane == 0) atomicMax(&ctr[j * 32u + 1u], at + wcount);
+                        placed = true;
+                    }
+                }
+                if (!placed && lane == 0) atomicOr(&w.st[tt].cand_overflow, 1u);
             }
             wcount = 0;
         }
@@ -325,7 +350,15 @@ __global__ void k_cand_begin(Workspace w, GroupParams g) {
     if (S.med_state != MED_PENDING) return;
     const u64 n = w.desc[t].n;
     const u64 r = (n - 1) >> 1;
-    const u64 below = S.c_lt, cnt = S.cand_count;
+    const u32 L = w.desc[t].cand_lists;
+    u64 cnt = S.cand_count;
+    if (L > 1u) {                          // several lists: slots asked for (counting only) or granted (listed)
+        const u32 *ctr = w.cand_ctr + (u64)t * 512u;
+        cnt = 0;
+        for (u32 j = 0; j < L; ++j) cnt += ctr[j * 32u + (S.br_hi == S.br_lo ? 0u : 1u)];
+        S.cand_count = (u32)cnt;
+    }
+    const u64 below = S.c_lt;
     if (S.br_hi == S.br_lo) {              // one-value bracket: only counted, never listed
         if (r >= below && r < below + cnt) { S.med_bits = S.br_lo; S.med_state = MED_KNOWN; }
         else S.med_state = MED_FALLBACK;
@@ -363,25 +396,29 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_cand_hist(Workspace w, GroupPa
         const u32 a1 = min(te, hi);                       // this workgroup's tiles of tensor t: [a0, a1)
         const TState &S = w.st[t];
         if (a1 > a0 && S.med_state == MED_PENDING && S.sel_width != 0) {
-            const u32 cnt = S.cand_count, base = S.sel_base, width = S.sel_width;
+            const u32 base = S.sel_base, width = S.sel_width;
             const u32 shift = width > 11u ? width - 11u : 0u;
             const u64 limit = 1ull << width;
             const u32 tc = te - tb;
-            const u32 i0 = (u32)(((u64)cnt * (a0 - tb)) / tc), i1 = (u32)(((u64)cnt * (a1 - tb)) / tc);
-            const EXCP_GLOBAL u32 *c = gptr(w.cand) + w.desc[t].cand_off;
+            const u32 L = w.desc[t].cand_lists, cap = (u32)(w.desc[t].cand_cap / L);
             auto tally = [&](u32 key) {
                 const u32 rel = key - base;               // keys below base wrap around and drop out
                 if ((u64)rel < limit) atomicAdd(&hist[rel >> shift], 1u);
             };
-            for (u32 q0 = i0; q0 < i1; q0 += 4u * EXCP_THREADS) {
-                if (q0 + 4u * EXCP_THREADS <= i1) {
-                    u32 k[4];
+            for (u32 j = 0; j < L; ++j) {                 // (one list, except for very large tensors)
+                const u32 cnt = L == 1u ? S.cand_count : w.cand_ctr[(u64)t * 512u + j * 32u + 1u];
+                const u32 i0 = (u32)(((u64)cnt * (a0 - tb)) / tc), i1 = (u32)(((u64)cnt * (a1 - tb)) / tc);
+                const EXCP_GLOBAL u32 *c = gptr(w.cand) + w.desc[t].cand_off + (u64)j * cap;
+                for (u32 q0 = i0; q0 < i1; q0 += 4u * EXCP_THREADS) {
+                    if (q0 + 4u * EXCP_THREADS <= i1) {
+                        u32 k[4];
 #pragma unroll
-                    for (u32 j = 0; j < 4; ++j) k[j] = c[q0 + j * EXCP_THREADS + tid];
+                        for (u32 jj = 0; jj < 4; ++jj) k[jj] = c[q0 + jj * EXCP_THREADS + tid];
 #pragma unroll
-                    for (u32 j = 0; j < 4; ++j) tally(k[j]);
-                } else {
-                    for (u32 i = q0 + tid; i < i1; i += EXCP_THREADS) tally(c[i]);
+                        for (u32 jj = 0; jj < 4; ++jj) tally(k[jj]);
+                    } else {
+                        for (u32 i = q0 + tid; i < i1; i += EXCP_THREADS) tally(c[i]);
+                    }
                 }
             }
             __syncthreads();
