@@ -142,6 +142,7 @@ struct Workspace {
     // mask pass
     u64 *tile_status;         // per 2048-element sub-tile: survivors << 32 | moment survivors
     u64 *mask_prefix;         // exclusive scan of tile_status within each tensor
+    u64 *mask_part;           // [tensor][16] packed counts of each sixteenth of a tensor's sub-tiles
     u64 *mask_bo;             // [sub-tile][32] M_o bits of the sub-tile's survivors, local positions
     // survivor passes
     u32 *chunk_total;         // [1]

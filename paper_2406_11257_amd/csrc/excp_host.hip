@@ -281,6 +281,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.cand, G / 12 + 4096ull * kMaxGroupTensors + 16);
     ok = ok && dev_alloc(c, &w.tile_status, 2 * max_tiles);      // one word per 2048-element sub-tile
     ok = ok && dev_alloc(c, &w.mask_prefix, 2 * max_tiles);
+    ok = ok && dev_alloc(c, &w.mask_part, (u64)kMaxGroupTensors * 16);
     ok = ok && dev_alloc(c, &w.mask_bo, 2 * max_tiles * 32);
     ok = ok && dev_alloc(c, &w.chunk_total, 4);
     ok = ok && dev_alloc(c, &w.seg_chunk_begin, 3ull * kMaxGroupTensors + 4);

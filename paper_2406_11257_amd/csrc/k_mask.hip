@@ -232,22 +232,54 @@ __device__ __forceinline__ void store_batch(EXCP_GLOBAL float *dst, const float 
     }
 }
 
-// Exclusive scan of the sub-tile counts of one tensor (one workgroup per tensor); the totals are
-// the tensor's n_w and n_o.  Counts are packed (survivors << 32 | moment survivors).
+// Exclusive scan of the sub-tile counts of every tensor; the totals are the tensor's n_w and n_o.
+// Counts are packed (survivors << 32 | moment survivors).  A tensor's sub-tiles are cut into sixteen
+// parts, one workgroup each: first the parts' totals, then every workgroup scans its own part from the
+// sum of the parts before it.
+constexpr u32 MSCAN_PARTS = 16;
+
+__device__ __forceinline__ void mscan_range(u32 nsub, u32 part, u32 &s0, u32 &s1) {
+    const u32 per = ((nsub + MSCAN_PARTS - 1u) / MSCAN_PARTS + 3u) & ~3u;
+    s0 = min(part * per, nsub);
+    s1 = min(s0 + per, nsub);
+}
+
+__global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan_parts(Workspace w, GroupParams g) {
+    __shared__ u64 s_sum[EXCP_THREADS / 64];
+    const u32 t = blockIdx.x / MSCAN_PARTS, part = blockIdx.x % MSCAN_PARTS, tid = threadIdx.x;
+    const TDesc &D = w.desc[t];
+    u32 s0, s1;
+    mscan_range(2u * D.tile_count, part, s0, s1);
+    const u64 *cnt = w.tile_status + 2ull * D.tile_begin;
+    u64 local = 0;
+    for (u32 i = s0 + tid; i < s1; i += EXCP_THREADS) local += cnt[i];
+    local = wave_sum_u64(local);
+    if ((tid & 63u) == 0u) s_sum[tid >> 6] = local;
+    __syncthreads();
+    if (tid == 0) w.mask_part[(u64)t * MSCAN_PARTS + part] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+}
+
 __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupParams g) {
     __shared__ u64 s_sum[EXCP_THREADS];
-    const u32 t = blockIdx.x, tid = threadIdx.x;
+    const u32 t = blockIdx.x / MSCAN_PARTS, part = blockIdx.x % MSCAN_PARTS, tid = threadIdx.x;
     const TDesc &D = w.desc[t];
     const u32 nsub = 2u * D.tile_count;
+    u32 s0, s1;
+    mscan_range(nsub, part, s0, s1);
     u64 *cnt = w.tile_status + 2ull * D.tile_begin;
     u64 carry = 0;
-    for (u32 base = 0; base < nsub; base += EXCP_THREADS * 4) {
+    for (u32 q = 0; q < part; ++q) carry += w.mask_part[(u64)t * MSCAN_PARTS + q];
+    if (part == MSCAN_PARTS - 1u && tid == 0) {
+        const u64 total = carry + w.mask_part[(u64)t * MSCAN_PARTS + part];
+        w.st[t].n_w = total >> 32; w.st[t].n_o = total & 0xffffffffull;
+    }
+    for (u32 base = s0; base < s1; base += EXCP_THREADS * 4) {
         // four consecutive sub-tiles per thread
         u64 v[4], local = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             u32 i = base + tid * 4 + q;
-            v[q] = (i < nsub) ? cnt[i] : 0ull;
+            v[q] = (i < s1) ? cnt[i] : 0ull;
             local += v[q];
         }
         s_sum[tid] = local;
@@ -262,13 +294,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupPa
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             u32 i = base + tid * 4 + q;
-            if (i < nsub) w.mask_prefix[2ull * D.tile_begin + i] = run;
+            if (i < s1) w.mask_prefix[2ull * D.tile_begin + i] = run;
             run += v[q];
         }
         carry += s_sum[EXCP_THREADS - 1];
         __syncthreads();
     }
-    if (tid == 0) { w.st[t].n_w = carry >> 32; w.st[t].n_o = carry & 0xffffffffull; }
 }
 
 // Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays.  A workgroup takes 32
@@ -496,7 +527,8 @@ void launch_mask_compact(const Workspace &w, const GroupParams &g, int phase, hi
         else if (w16) hipLaunchKernelGGL((k_mask_slots<false, true>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
         else hipLaunchKernelGGL((k_mask_slots<false, false>), dim3(grid), dim3(EXCP_THREADS), 0, s, w, g);
     } else if (phase == 1) {
-        hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors), dim3(EXCP_THREADS), 0, s, w, g);
+        hipLaunchKernelGGL(k_mask_scan_parts, dim3(g.ntensors * MSCAN_PARTS), dim3(EXCP_THREADS), 0, s, w, g);
+        hipLaunchKernelGGL(k_mask_scan, dim3(g.ntensors * MSCAN_PARTS), dim3(EXCP_THREADS), 0, s, w, g);
     } else {
         u32 grid = (nsub + 31) / 32;
         if (grid > excp_grid(w, 48)) grid = excp_grid(w, 48);
