@@ -164,6 +164,7 @@ struct Workspace {
     DDesc *ddesc; DState *dst;
     CDesc *cdesc; u32 *chain_tile_begin;   // chain reconstruction: tensors and their tile table
     u32 *dec_cnt_w, *dec_cnt_o;   // per tile counts -> exclusive bases
+    u64 *dec_part;                // [descriptor][16] tile-count totals of each sixteenth of a tensor's tiles
     u32 *dec_kinds;               // [1] kinds of blob in the group being decoded: 1 fp32 weights, 2 16-bit weights, 4 unquantised
     // flags
     int *err_flag;

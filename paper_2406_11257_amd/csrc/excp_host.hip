@@ -307,6 +307,7 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     ok = ok && dev_alloc(c, &w.dec_cnt_w, max_tiles * EXCP_MAX_CHAIN);
     ok = ok && dev_alloc(c, &w.dec_cnt_o, max_tiles * EXCP_MAX_CHAIN);
     ok = ok && dev_alloc(c, &w.dec_kinds, 4);
+    ok = ok && dev_alloc(c, &w.dec_part, (u64)kMaxGroupTensors * 16);
     ok = ok && dev_alloc(c, &w.err_flag, 4);
     ok = ok && dev_alloc(c, &w.rec_dev, kMaxBatchTensors);
     w.max_chunks = (u32)(chunks_group > 0xffffffffull ? 0xffffffffull : chunks_group);

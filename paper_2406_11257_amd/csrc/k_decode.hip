@@ -117,19 +117,54 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_count(Workspace w, u32 
     }
 }
 
-// Exclusive scan of the per-tile counts of one tensor (one workgroup per tensor).
+// Exclusive scan of the per-tile counts of every tensor.  A tensor's tiles are cut into sixteen parts,
+// one workgroup each: first the parts' totals, then every workgroup scans its own part from the sum of
+// the parts before it.
+constexpr u32 DSCAN_PARTS = 16;
+
+__device__ __forceinline__ void dscan_range(u32 ntiles, u32 part, u32 &s0, u32 &s1) {
+    const u32 per = (ntiles + DSCAN_PARTS - 1u) / DSCAN_PARTS;
+    s0 = min(part * per, ntiles);
+    s1 = min(s0 + per, ntiles);
+}
+
+template <int WHICH>
+__global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan_parts(Workspace w, u32 ntensors) {
+    __shared__ u64 s_sum[EXCP_THREADS / 64];
+    const u32 t = blockIdx.x / DSCAN_PARTS, part = blockIdx.x % DSCAN_PARTS, tid = threadIdx.x;
+    const DDesc &D = w.ddesc[t];
+    if (WHICH == 1 && !wants_moments(D)) return;
+    const u32 *cnt = (WHICH == 0 ? w.dec_cnt_w : w.dec_cnt_o) + D.tile_begin;
+    u32 s0, s1;
+    dscan_range(D.tile_count, part, s0, s1);
+    u64 local = 0;
+    for (u32 i = s0 + tid; i < s1; i += EXCP_THREADS) local += cnt[i];
+    local = wave_sum_u64(local);
+    if ((tid & 63u) == 0u) s_sum[tid >> 6] = local;
+    __syncthreads();
+    if (tid == 0) w.dec_part[(u64)t * DSCAN_PARTS + part] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+}
+
 template <int WHICH>
 __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 ntensors) {
     __shared__ u32 s_sum[EXCP_THREADS];
-    const u32 t = blockIdx.x, tid = threadIdx.x;
+    const u32 t = blockIdx.x / DSCAN_PARTS, part = blockIdx.x % DSCAN_PARTS, tid = threadIdx.x;
     const DDesc &D = w.ddesc[t];
     DState &S = w.dst[t];
     u32 *cnt = (WHICH == 0 ? w.dec_cnt_w : w.dec_cnt_o) + D.tile_begin;
     if (WHICH == 1 && !wants_moments(D)) return;    // bitmap_o is not used for this one
+    u32 s0, s1;
+    dscan_range(D.tile_count, part, s0, s1);
     u64 carry = 0;
-    for (u32 base = 0; base < D.tile_count; base += EXCP_THREADS) {
+    for (u32 q = 0; q < part; ++q) carry += w.dec_part[(u64)t * DSCAN_PARTS + q];
+    if (part == DSCAN_PARTS - 1u && tid == 0) {
+        const u64 total = carry + w.dec_part[(u64)t * DSCAN_PARTS + part];
+        if (WHICH == 0) { S.pop_w = total; if (S.status == 0 && total != S.n_w) S.status = -4; }
+        else { S.pop_o = total; if (S.status == 0 && total != S.n_o) S.status = -4; }
+    }
+    for (u32 base = s0; base < s1; base += EXCP_THREADS) {
         u32 i = base + tid;
-        u32 v = (i < D.tile_count) ? cnt[i] : 0u;
+        u32 v = (i < s1) ? cnt[i] : 0u;
         s_sum[tid] = v;
         __syncthreads();
         for (int off = 1; off < EXCP_THREADS; off <<= 1) {
@@ -138,13 +173,9 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_decode_scan(Workspace w, u32 n
             s_sum[tid] += a;
             __syncthreads();
         }
-        if (i < D.tile_count) cnt[i] = (u32)(carry + s_sum[tid] - v);
+        if (i < s1) cnt[i] = (u32)(carry + s_sum[tid] - v);
         carry += s_sum[EXCP_THREADS - 1];
         __syncthreads();
-    }
-    if (tid == 0) {
-        if (WHICH == 0) { S.pop_w = carry; if (S.status == 0 && carry != S.n_w) S.status = -4; }
-        else { S.pop_o = carry; if (S.status == 0 && carry != S.n_o) S.status = -4; }
     }
 }
 
@@ -837,8 +868,14 @@ void launch_decode_count(const Workspace &w, u32 ntensors, u32 ntiles, int which
 }
 void launch_decode_scan(const Workspace &w, u32 ntensors, int which, hipStream_t s) {
     if (!ntensors) return;
-    if (which == 0) hipLaunchKernelGGL(k_decode_scan<0>, dim3(ntensors), dim3(EXCP_THREADS), 0, s, w, ntensors);
-    else hipLaunchKernelGGL(k_decode_scan<1>, dim3(ntensors), dim3(EXCP_THREADS), 0, s, w, ntensors);
+    const dim3 grid(ntensors * DSCAN_PARTS), block(EXCP_THREADS);
+    if (which == 0) {
+        hipLaunchKernelGGL(k_decode_scan_parts<0>, grid, block, 0, s, w, ntensors);
+        hipLaunchKernelGGL(k_decode_scan<0>, grid, block, 0, s, w, ntensors);
+    } else {
+        hipLaunchKernelGGL(k_decode_scan_parts<1>, grid, block, 0, s, w, ntensors);
+        hipLaunchKernelGGL(k_decode_scan<1>, grid, block, 0, s, w, ntensors);
+    }
 }
 void launch_decode_main(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s) {
     if (!ntiles) return;
