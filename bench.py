@@ -47,7 +47,7 @@ def survey_step_bytes_per_param(p_w, p_o, wb=4.0):
 
 
 STAGE_KERNEL = {"stats_stream": "k_stats_stream<false>", "mask_slots": "k_mask_slots<false,false>", "mask_gather": "k_mask_gather",
-                "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats<4u>",
+                "km_count": "k_km_count", "km_scatter": "k_km_scatter", "km_bucket_stats": "k_km_bucket_stats<4u,4u>",
                 "assign_pack": "k_assign_pack", "decode_main": "k_decode_main<false>"}
 
 

@@ -120,7 +120,8 @@ struct GroupParams {
     int nbits, K, iters;
     u32 flags;
     u32 ntensors, ntiles;
-    u32 wide;                   // launch the per-bucket kernels with sixteen waves: tied data, or one very large tensor
+    u32 wide;                   // per-bucket kernels with sixteen waves: 1 = tied data (16-bit weights), 2 = a very large
+                                // tensor in the group (then also one bucket per workgroup)
 };
 
 #define EXCP_RAW_BITS    32u       // "code" width of a blob written without quantisation: fp32 values, no codebooks

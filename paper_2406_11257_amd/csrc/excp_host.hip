@@ -449,7 +449,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         p.ntensors = g.count; p.ntiles = g.ntiles;
         u64 largest = 0;
         for (u32 q = 0; q < g.count; ++q) largest = std::max<u64>(largest, tensors[g.first + q].n);
-        p.wide = ((flags & 0x30u) != 0 || largest >= (1ull << 28)) ? 1u : 0u;
+        p.wide = largest >= (1ull << 28) ? 2u : ((flags & 0x30u) != 0 ? 1u : 0u);
 #ifdef EXCP_TUNING
         w.tune_wgs = (flags >> 24) & 0xffu;
 #endif

@@ -473,7 +473,7 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
 }
 
 // ---------------------------------------------------------------- P4: exact totals per bucket
-// One workgroup per four buckets of a stream; its four or sixteen waves share every bucket,
+// One workgroup per four buckets of a stream (per bucket in the sixteen-wave form); its waves share every bucket,
 // so that one very large bucket (tied values) does not leave a single wave working alone.  Values of a bucket
 // are neighbours in value, hence in exponent: a window of 40 bit positions placed from the first
 // values met holds practically all of them; inside it a lane adds shifted mantissas as integers
@@ -482,22 +482,22 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
 // (sixteen for 16-bit weights, whose residuals are heavily tied, and for groups with a tensor so large
 // that its buckets alone are millions of values; four otherwise, which is faster when the buckets are
 // small and even)
-template <u32 BS_WAVES>
+template <u32 BS_WAVES, u32 BPW>
 __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, GroupParams g) {
-    __shared__ u64 bins[4][EXCP_ABSM_BINS];
-    __shared__ u32 s_min[4], s_max[4];
+    __shared__ u64 bins[BPW][EXCP_ABSM_BINS];
+    __shared__ u32 s_min[BPW], s_max[BPW];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 nseg = 3u * g.ntensors;
-    const u64 first = (u64)blockIdx.x * 4;                 // first of this workgroup's buckets
+    const u64 first = (u64)blockIdx.x * BPW;               // first of this workgroup's buckets
     if (first >= (u64)nseg * NBKT) return;
     const u32 sidx = (u32)(first / NBKT), b0 = (u32)(first % NBKT);
     if (w.seg[sidx].len == 0) return;
-    if (tid < 4 * EXCP_ABSM_BINS) (&bins[0][0])[tid] = 0;
-    if (tid < 4) { s_min[tid] = 0xffffffffu; s_max[tid] = 0; }
+    if (tid < BPW * EXCP_ABSM_BINS) (&bins[0][0])[tid] = 0;
+    if (tid < BPW) { s_min[tid] = 0xffffffffu; s_max[tid] = 0; }
     __syncthreads();
     const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
     const EXCP_GLOBAL float *part = gptr(seg_part(w, sidx));
-    for (u32 j = 0; j < 4; ++j) {
+    for (u32 j = 0; j < BPW; ++j) {
         const u32 q0 = begin[b0 + j], q1 = begin[b0 + j + 1];
         // this wave's share, cut at multiples of 256 values from the bucket's start
         const u32 blocks = (q1 - q0 + 255u) >> 8, per = (blocks + BS_WAVES - 1u) / BS_WAVES;
@@ -587,9 +587,9 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
         }
     }
     __syncthreads();
-    if (tid < 4 * EXCP_ABSM_BINS)
+    if (tid < BPW * EXCP_ABSM_BINS)
         w.km_bsum[((u64)sidx * NBKT + b0) * EXCP_ABSM_BINS + tid] = (&bins[0][0])[tid];
-    if (tid < 4) { w.km_min[(u64)sidx * NBKT + b0 + tid] = s_min[tid]; w.km_max[(u64)sidx * NBKT + b0 + tid] = s_max[tid]; }
+    if (tid < BPW) { w.km_min[(u64)sidx * NBKT + b0 + tid] = s_min[tid]; w.km_max[(u64)sidx * NBKT + b0 + tid] = s_max[tid]; }
 }
 
 // ---------------------------------------------------------------- P6: initial centres
@@ -1159,8 +1159,9 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
             break;
         case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 96)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 4:
-            if (g.wide) hipLaunchKernelGGL(k_km_bucket_stats<16>, dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
-            else hipLaunchKernelGGL(k_km_bucket_stats<4>, dim3(nseg * (NBKT / 4)), dim3(256), 0, s, w, g);
+            if (g.wide == 2u) hipLaunchKernelGGL((k_km_bucket_stats<16, 1>), dim3(nseg * NBKT), dim3(1024), 0, s, w, g);
+            else if (g.wide) hipLaunchKernelGGL((k_km_bucket_stats<16, 4>), dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
+            else hipLaunchKernelGGL((k_km_bucket_stats<4, 4>), dim3(nseg * (NBKT / 4)), dim3(256), 0, s, w, g);
             break;
         default: break;
     }
