@@ -38,7 +38,7 @@ def stage_bytes_per_param(p_w, p_o, nbits, iters, wb=4.0):
     }
 
 
-def survey_step_bytes_per_param(p_w, p_o, wb=4.0):
+def step_bytes_per_param(p_w, p_o, wb=4.0):
     """Step-level accounting used for the '% of HBM roofline' headline: 32.2 + 58.5 s (+ 8 for W_hat) for
     fp32 weights; of the 32.2, sixteen bytes are the two passes over W_prev and W, and the 8 are W_prev
     read and W_hat written: those scale with the stored weight size."""
@@ -195,7 +195,7 @@ def main():
                 "avg_launch_ms": d["ms_per_step"] / d["launches_per_step"],
                 "algorithmic_bytes_per_launch": per_param[dominant] * N / d["launches_per_step"],
                 "algorithmic_bytes_per_param": per_param[dominant]}
-    step_bytes = survey_step_bytes_per_param(p_w, p_o, wb) * N
+    step_bytes = step_bytes_per_param(p_w, p_o, wb) * N
     step_frac = step_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9)
 
     # ---- decompress (Alg. 2) timing, reported beside the headline --------------------------------
@@ -258,6 +258,14 @@ def main():
                "sample": f"first {b - a} elements of tensor {pick} ({cfg.tensors[pick].name}) of the same "
                          f"checkpoint, {cpu_s:.1f} s; numpy, single thread; host has {os.cpu_count()} cores",
                "keep_fractions": [ref.n_w / (b - a), ref.n_o / (b - a)]}
+        # the library on the same sample (untimed): its blob must be the oracle's, byte for byte
+        sblob = torch.empty(X.excp_blob_bound(b - a, nbits), dtype=torch.uint8, device=dev)
+        ctx.excp_compress_tensors([(flat[0][a:b], flat[1][a:b], flat[2][a:b], flat[3][a:b], sblob, None)],
+                                  alpha, beta, nbits, iters, wflags)
+        sst = ctx.excp_collect()[1][0]
+        cpu["gpu_blob_identical"] = bool(sst.blob_bytes == len(ref.blob) and
+                                         sblob[:int(sst.blob_bytes)].cpu().numpy().tobytes() == ref.blob)
+        del sblob
 
     # ---- Alg. 2 with all three outputs (overwrites the m and v inputs: nothing needs them any more) ----
     dec3 = [(flat[0][offs[i]:offs[i] + spec.n], tensors[i][4], int(stats[i].blob_bytes), spec.n,
@@ -309,7 +317,7 @@ def main():
                    "params": N, "tensors": len(cfg.tensors), "group_elems": group},
         "state_GBs": (8.0 + 2.0 * wb) * N / (ms_per_step * 1e-3) / 1e9,
         "hbm_roofline_pct_step": 100.0 * step_frac,
-        "step_algorithmic_bytes_per_param": survey_step_bytes_per_param(p_w, p_o, wb),
+        "step_algorithmic_bytes_per_param": step_bytes_per_param(p_w, p_o, wb),
         "keep_fractions": {"p_w": p_w, "p_o": p_o},
         "compression_ratio": (8.0 + wb) * N / blob_bytes,
         "decompress_ms": dec_ms, "decompress_params_per_s": N / (dec_ms * 1e-3),
