@@ -18,14 +18,15 @@ rounding per operation (numpy float32 scalars/arrays), denormals preserved.
 Pins.  Every function below is pinned by tests that do not re-use its own
 formula: full-sort / counting invariants for the median, rational arithmetic
 for the mean, element-by-element pure-Python brute force for the masks,
-exhaustive nearest-centre search and a monotone objective for Lloyd, textbook
-Lloyd-Max levels, uniform-data fixed points, byte-level hand-built blobs and
-the size identities of the paper's result tables.  The paper does not specify
-k-means initialisation, iteration count, tie handling or empty-cluster
-handling (Sec. 3.3 says only "K-means algorithm"): the choices made in
-``kmeans_init`` / ``lloyd`` are this build's reading, so the *values* of the
-codebooks are "parity unpinned" by the paper itself; they are pinned only by
-the mathematical properties listed above.
+exhaustive nearest-centre search and a monotone objective for Lloyd, the
+Lloyd iterations of two libraries started from the same centres (scipy's
+kmeans2, scikit-learn's KMeans), textbook Lloyd-Max levels, uniform-data fixed
+points, byte-level hand-built blobs and the size identities of the paper's
+result tables.  The paper does not specify k-means initialisation, iteration
+count, tie handling or empty-cluster handling (Sec. 3.3 says only "K-means
+algorithm"): the choices made in ``kmeans_init`` / ``lloyd`` are this build's
+reading, so which codebook is the right one is "parity unpinned" by the paper
+itself; under that reading the values are pinned as listed above.
 """
 from __future__ import annotations
 

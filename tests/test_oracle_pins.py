@@ -296,6 +296,29 @@ def test_lloyd_objective_never_increases_and_centres_stay_ordered(K):
             assert C[k] == C_prev[k]
 
 
+@pytest.mark.parametrize("K,iters,n", [(3, 7, 5000), (15, 10, 20000), (255, 4, 60000)])
+def test_lloyd_against_library_lloyd_loops_from_the_same_start(K, iters, n):
+    """Two independent implementations of Lloyd's algorithm, run in fp64 for the same number of
+    updates from the same initial centres, end at the oracle's centres (which round to fp32 after
+    every update, hence the tolerance).  Continuous data: no ties, no empty clusters."""
+    from scipy.cluster.vq import kmeans2
+    from sklearn.cluster import KMeans
+    g = np.random.default_rng(500 + K)
+    x = np.concatenate([g.laplace(0, 1e-4, n), g.standard_normal(n // 4) * 1e-3]).astype(f32)
+    C, _ = O.lloyd(x, K, iters)
+    start = O.kmeans_init(x, K).astype(np.float64)[:, None]
+    data = x.astype(np.float64)[:, None]
+    scale = float(np.abs(C).max())
+    book, _ = kmeans2(data, start, iter=iters, minit="matrix", missing="raise")
+    assert np.max(np.abs(book[:, 0] - C)) < 1e-6 * scale
+    km = KMeans(n_clusters=K, init=start, n_init=1, max_iter=iters, tol=0.0, algorithm="lloyd").fit(data)
+    assert km.n_iter_ == iters
+    assert np.max(np.abs(km.cluster_centers_[:, 0] - C)) < 1e-6 * scale
+    # a planted mistake is seen: one update fewer moves the centres by far more than the tolerance
+    C_short, _ = O.lloyd(x, K, iters - 1)
+    assert np.max(np.abs(C_short - C)) > 1e-4 * scale
+
+
 def test_lloyd_is_lossless_when_values_fit_the_codebook():
     x = np.array([5e-4, -2e-4, 5e-4, 1e-3, -2e-4, 7e-5], f32)
     C, a = O.lloyd(x, 15, 10)
