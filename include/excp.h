@@ -26,10 +26,12 @@
  *   streams: d at M_w (n_w values), m and v at M_o (n_o values each), in
  *   index order; each stream is clustered on its own: K = 2^nbits - 1 centres
  *   start at the order statistics of rank ((2k+1) len)/(2K), then exactly
- *   `lloyd_iters` updates (nearest centre by squared fp64 distance, ties to the
- *   lower index; centre = fp32(fp64 sum / count); empty clusters keep their
- *   centre; the centres are re-sorted ascending after every update, which only
- *   matters for heavily tied data); code = 1 + index of the nearest final centre.
+ *   `lloyd_iters` updates (nearest centre: of the two centres that bracket a
+ *   value the upper one wins only if its fp64 distance is strictly smaller, and
+ *   of equal centres the lowest index is taken; centre = fp32(exact sum rounded
+ *   once to fp64 / count); empty clusters keep their centre; the centres are
+ *   re-sorted ascending after every update, which only matters for heavily tied
+ *   data); code = 1 + index of the nearest final centre.
  *   reconstruct: W_hat[i] = W_prev_recon[i] + C_w[code] at M_w, else
  *   W_prev_recon[i]; m_hat, v_hat = C[code] at M_o, else +0.
  *
