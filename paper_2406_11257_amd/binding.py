@@ -168,6 +168,15 @@ def _wflags(*tensors) -> int:
     return {torch.float32: 0, torch.float16: EXCP_FLAG_W_F16, torch.bfloat16: EXCP_FLAG_W_BF16}[kind]
 
 
+class PreparedBatch:
+    """A marshalled batch (Context.prepare_*): the argument array of one of the batched calls and the
+    tensors it points into, kept alive with it.  A job that passes the same tensors again and again
+    builds the array once, as a C caller would, and hands it to the call in place of the sequence."""
+
+    def __init__(self, kind, arr, count, keep, wflags=0):
+        self.kind, self.arr, self.count, self.keep, self.wflags = kind, arr, count, keep, wflags
+
+
 class Context:
     """Owns one excp_ctx.  Tensors are torch CUDA tensors; blobs are uint8 CUDA tensors."""
 
@@ -199,8 +208,25 @@ class Context:
         return int(lib().excp_workspace_bytes(self._h))
 
     # -- batched -----------------------------------------------------------------
-    def excp_compress_tensors(self, tensors, alpha=5e-5, beta=2.0, nbits=4, lloyd_iters=10, flags=0):
-        """tensors: sequence of (W_prev_recon, W_t, m_t, v_t, blob, W_recon_out-or-None)."""
+    def _batch(self, items, kind, make):
+        if not isinstance(items, PreparedBatch):
+            return make()
+        if items.kind != kind:
+            raise TypeError(f"a batch prepared for {items.kind} was passed to a {kind} call")
+        return items
+
+    def _submit(self, fn, name, batch):
+        rc = fn(self._h, batch.count, batch.arr)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, name)
+        self._keep = batch
+        self._count = batch.count
+
+    def prepare_compress(self, tensors, flags=0):
+        """Marshals a compress batch once: sequence of (W_prev_recon, W_t, m_t, v_t, blob,
+        W_recon_out-or-None) -> a PreparedBatch that excp_compress_tensors accepts in place of the
+        sequence, as often as wanted (a job that checkpoints the same tensors again and again builds
+        its argument array once, as a C caller would).  `flags` names the weight storage."""
         arr = (ExcpTensor * max(len(tensors), 1))()
         for i, (Wp, W, m, v, blob, Wout) in enumerate(tensors):
             for t, nm in ((Wp, "W_prev_recon"), (W, "W_t"), (m, "m_t"), (v, "v_t")):
@@ -215,14 +241,28 @@ class Context:
             arr[i] = ExcpTensor(Wp.data_ptr(), W.data_ptr(), m.data_ptr(), v.data_ptr(), n,
                                 blob.data_ptr(), blob.numel() * blob.element_size(),
                                 0 if Wout is None else Wout.data_ptr())
-        rc = lib().excp_compress_tensors(self._h, len(tensors), arr, alpha, beta, nbits, lloyd_iters, flags)
+        return PreparedBatch("compress", arr, len(tensors), tensors, flags & (EXCP_FLAG_W_F16 | EXCP_FLAG_W_BF16))
+
+    def excp_compress_tensors(self, tensors, alpha=5e-5, beta=2.0, nbits=4, lloyd_iters=10, flags=0):
+        """tensors: sequence of (W_prev_recon, W_t, m_t, v_t, blob, W_recon_out-or-None), or the
+        PreparedBatch that prepare_compress made of one."""
+        batch = self._batch(tensors, "compress", lambda: self.prepare_compress(tensors, flags))
+        if batch.wflags != flags & (EXCP_FLAG_W_F16 | EXCP_FLAG_W_BF16):
+            raise TypeError("the batch was prepared for another weight storage")
+        rc = lib().excp_compress_tensors(self._h, batch.count, batch.arr, alpha, beta, nbits, lloyd_iters, flags)
         if rc != EXCP_OK:
             raise ExcpError(rc, "excp_compress_tensors")
-        self._keep = (tensors, arr)
-        self._count = len(tensors)
+        self._keep = batch
+        self._count = batch.count
 
     def excp_decompress_tensors(self, blobs):
-        """blobs: sequence of (W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out)."""
+        """blobs: sequence of (W_prev_recon, blob, blob_bytes, n, W_recon_out, m_out, v_out), or the
+        PreparedBatch that prepare_decompress made of one."""
+        self._submit(lib().excp_decompress_tensors, "excp_decompress_tensors",
+                     self._batch(blobs, "decompress", lambda: self.prepare_decompress(blobs)))
+
+    def prepare_decompress(self, blobs):
+        """Marshals a decompress batch once (see prepare_compress)."""
         arr = (ExcpBlob * max(len(blobs), 1))()
         for i, (Wp, blob, nbytes, n, Wout, mout, vout) in enumerate(blobs):
             _check_f32(Wp, "W_prev_recon", self.device)
@@ -239,30 +279,32 @@ class Context:
                               0 if Wout is None else Wout.data_ptr(),
                               0 if mout is None else mout.data_ptr(),
                               0 if vout is None else vout.data_ptr(), _wflags(Wp, Wout), 0)
-        rc = lib().excp_decompress_tensors(self._h, len(blobs), arr)
-        if rc != EXCP_OK:
-            raise ExcpError(rc, "excp_decompress_tensors")
-        self._keep = (blobs, arr)
-        self._count = len(blobs)
+        return PreparedBatch("decompress", arr, len(blobs), blobs)
 
     def excp_export_dense(self, items):
         """items: sequence of (blob, blob_bytes, n, head, codes_w, codes_m, codes_v); the last four are
-        uint8 device tensors or None."""
+        uint8 device tensors or None; or the PreparedBatch that prepare_export_dense made of one."""
+        self._submit(lib().excp_export_dense, "excp_export_dense",
+                     self._batch(items, "export_dense", lambda: self.prepare_export_dense(items)))
+
+    def prepare_export_dense(self, items):
+        """Marshals an export batch once (see prepare_compress)."""
         arr = (ExcpDenseExport * max(len(items), 1))()
         for i, (blob, nbytes, n, head, cw, cm, cv) in enumerate(items):
             if nbytes > blob.numel() * blob.element_size():
                 raise ValueError("blob_bytes exceeds the blob tensor")
             arr[i] = ExcpDenseExport(blob.data_ptr(), nbytes, n, *[0 if t is None else t.data_ptr()
                                                                      for t in (head, cw, cm, cv)])
-        rc = lib().excp_export_dense(self._h, len(items), arr)
-        if rc != EXCP_OK:
-            raise ExcpError(rc, "excp_export_dense")
-        self._keep = (items, arr)
-        self._count = len(items)
+        return PreparedBatch("export_dense", arr, len(items), items)
 
     def excp_decompress_dense(self, items):
         """items: sequence of (W_prev_recon, head, head_bytes, n, codes_w, codes_m, codes_v,
-        W_recon_out, m_out, v_out)."""
+        W_recon_out, m_out, v_out), or the PreparedBatch that prepare_decompress_dense made of one."""
+        self._submit(lib().excp_decompress_dense, "excp_decompress_dense",
+                     self._batch(items, "decompress_dense", lambda: self.prepare_decompress_dense(items)))
+
+    def prepare_decompress_dense(self, items):
+        """Marshals a batch of reconstructions from the stored layout once (see prepare_compress)."""
         arr = (ExcpDenseBlob * max(len(items), 1))()
         for i, (Wp, head, hbytes, n, cw, cm, cv, Wout, mout, vout) in enumerate(items):
             if Wp is not None:
@@ -279,14 +321,16 @@ class Context:
             arr[i] = ExcpDenseBlob(0 if Wp is None else Wp.data_ptr(), head.data_ptr(), hbytes, n,
                                    *[0 if t is None else t.data_ptr() for t in (cw, cm, cv, Wout, mout, vout)],
                                    _wflags(Wp, Wout), 0)
-        rc = lib().excp_decompress_dense(self._h, len(items), arr)
-        if rc != EXCP_OK:
-            raise ExcpError(rc, "excp_decompress_dense")
-        self._keep = (items, arr)
-        self._count = len(items)
+        return PreparedBatch("decompress_dense", arr, len(items), items)
 
     def excp_reconstruct_chain(self, chains):
-        """chains: sequence of (W0, [blob tensors, oldest first], [blob_bytes], W_out, m_out, v_out)."""
+        """chains: sequence of (W0, [blob tensors, oldest first], [blob_bytes], W_out, m_out, v_out), or
+        the PreparedBatch that prepare_chain made of one."""
+        self._submit(lib().excp_reconstruct_chain, "excp_reconstruct_chain",
+                     self._batch(chains, "chain", lambda: self.prepare_chain(chains)))
+
+    def prepare_chain(self, chains):
+        """Marshals a batch of chains once (see prepare_compress)."""
         arr = (ExcpChain * max(len(chains), 1))()
         keep = []
         for i, (W0, blobs, sizes, Wout, mout, vout) in enumerate(chains):
@@ -310,11 +354,7 @@ class Context:
                                0 if Wout is None else Wout.data_ptr(),
                                0 if mout is None else mout.data_ptr(),
                                0 if vout is None else vout.data_ptr(), _wflags(W0, Wout), 0)
-        rc = lib().excp_reconstruct_chain(self._h, len(chains), arr)
-        if rc != EXCP_OK:
-            raise ExcpError(rc, "excp_reconstruct_chain")
-        self._keep = (chains, arr, keep)
-        self._count = len(chains)
+        return PreparedBatch("chain", arr, len(chains), (chains, keep))
 
     def excp_collect(self, check=True):
         stats = (ExcpStats * max(self._count, 1))()

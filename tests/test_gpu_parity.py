@@ -161,6 +161,44 @@ def test_runs_are_deterministic(ctx):
     assert blobs[0] == blobs[1] == blobs[2]
 
 
+def test_a_prepared_batch_is_reusable_and_follows_the_data(ctx):
+    # the argument array is marshalled once; what the tensors hold at call time is what gets compressed
+    cases = [case(300001, 81), case(5000, 82)]
+    dev = []
+    for (Wp, W, m, v) in cases:
+        blob = torch.zeros(X.excp_blob_bound(W.size, 4), dtype=torch.uint8, device="cuda")
+        dev.append((to_dev(Wp), to_dev(W), to_dev(m), to_dev(v), blob, torch.zeros(W.size, device="cuda")))
+    batch = ctx.prepare_compress(dev)
+    assert isinstance(batch, X.PreparedBatch) and batch.count == 2
+    for rep in range(3):
+        if rep == 2:                                   # new weights in the same buffers
+            cases = [case(300001, 83), case(5000, 84)]
+            for t, c in zip(dev, cases):
+                for k in range(4):
+                    t[k].copy_(torch.from_numpy(c[k]))
+        ctx.excp_compress_tensors(batch, 5e-5, 2.0, 4, 3)
+        rc, stats = ctx.excp_collect()
+        for c, t, st in zip(cases, dev, stats):
+            ref = O.compress_step(*c, 5e-5, 2.0, 4, 3)
+            assert t[4][:int(st.blob_bytes)].cpu().numpy().tobytes() == ref.blob, rep
+            assert np.array_equal(t[5].cpu().numpy().view(np.uint32), ref.W_recon.view(np.uint32)), rep
+    with pytest.raises(TypeError):
+        ctx.excp_compress_tensors(batch, 5e-5, 2.0, 4, 3, X.EXCP_FLAG_W_F16)
+    with pytest.raises(TypeError):
+        ctx.excp_decompress_tensors(batch)
+    # Alg. 2 from a prepared batch, twice
+    outs = [torch.zeros(t[1].numel(), device="cuda") for t in dev]
+    dec = ctx.prepare_decompress([(t[0], t[4], int(st.blob_bytes), t[1].numel(), o, None, None)
+                                  for t, st, o in zip(dev, stats, outs)])
+    for rep in range(2):
+        for o in outs:
+            o.zero_()
+        ctx.excp_decompress_tensors(dec)
+        ctx.excp_collect()
+        for t, o in zip(dev, outs):
+            assert torch.equal(o, t[5])
+
+
 def test_reconstruction_is_stable_over_repeated_multi_tensor_batches(ctx):
     # the reconstruction written by compress must equal Alg. 2 applied to the blob, every time,
     # also when the same device buffers are reused by later batches
