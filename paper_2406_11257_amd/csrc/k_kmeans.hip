@@ -116,48 +116,55 @@ __device__ __forceinline__ void wave_exact_add(const float (&x)[N], const bool (
 }
 
 // Signed bins -> the exact sum rounded once (to nearest, ties to even) to fp64.
+// Everything stays in registers (fixed indices after unrolling): this runs once per centre and
+// iteration on the critical path between two small kernels.
 __device__ double signed_bins_to_double(const u64 *bins) {
-    u32 limb[14];
-    for (int i = 0; i < 14; ++i) limb[i] = 0;
+    // base-256 digits of the sum (bin g has weight 2^(8g)), what is left over in a signed top word
+    u64 W[6] = {0, 0, 0, 0, 0, 0};
+    long long carry = 0;
+#pragma unroll
     for (int g = 0; g < EXCP_ABSM_BINS; ++g) {
-        long long c = (long long)bins[g];
-        if (!c) continue;
-        // sign-extended 64-bit value shifted left by 8g, added into a 448-bit two's complement number
-        u32 bit = 8u * g, li = bit >> 5, sh = bit & 31u;
-        u32 ext = c < 0 ? 0xffffffffu : 0u;
-        u64 uc = (u64)c;
-        u64 carry = 0;
-        for (u32 q = 0; li + q < 14; ++q) {
-            // 32-bit slice q of (sign-extended c) << sh
-            u32 lo_part, hi_part;
-            auto word = [&](int idx) -> u32 { return idx < 0 ? 0u : (idx == 0 ? (u32)uc : (idx == 1 ? (u32)(uc >> 32) : ext)); };
-            lo_part = word((int)q);
-            hi_part = word((int)q - 1);
-            u32 slice = sh ? ((lo_part << sh) | (hi_part >> (32 - sh))) : lo_part;
-            u64 s = (u64)limb[li + q] + slice + carry;
-            limb[li + q] = (u32)s;
-            carry = s >> 32;
-        }
+        const u64 b = bins[g];
+        const long long t = (long long)(b & 255ull) + carry;       // |carry| < 2^57: no overflow
+        carry = (t >> 8) + ((long long)b >> 8);
+        W[g >> 3] |= (u64)(t & 255) << (8 * (g & 7));
     }
-    const bool neg = limb[13] >> 31;
-    if (neg) {                                  // magnitude = two's complement negation
-        u64 carry = 1;
-        for (int i = 0; i < 14; ++i) { u64 s = (u64)(~limb[i]) + carry; limb[i] = (u32)s; carry = s >> 32; }
+    W[5] = (u64)carry;
+    const bool neg = carry < 0;
+    if (neg) {                                  // magnitude = two's complement negation of the 384 bits
+        u64 c = 1;
+#pragma unroll
+        for (int i = 0; i < 6; ++i) { const u64 v = ~W[i] + c; c = (c && v == 0) ? 1ull : 0ull; W[i] = v; }
     }
-    int top = -1;
-    for (int i = 13; i >= 0; --i) if (limb[i]) { top = i; break; }
-    if (top < 0) return 0.0;
-    int msb = 32 * top + (31 - __clz((int)limb[top]));
-    auto bit_at = [&](int p) -> u32 { return p < 0 ? 0u : (limb[p >> 5] >> (p & 31)) & 1u; };
+    // the top non-zero word, the word below it, and whether anything lies below those
+    u64 hi = 0, lo = 0, rest = 0; int wi = -1;
+#pragma unroll
+    for (int i = 5; i >= 0; --i) {
+        if (wi < 0) { if (W[i]) { wi = i; hi = W[i]; } }
+        else if (wi == i + 1) lo = W[i];
+        else rest |= W[i];
+    }
+    if (wi < 0) return 0.0;
+    const int top = 63 - __clzll((long long)hi), msb = 64 * wi + top;
     double mag;
     if (msb <= 52) {
-        u64 x = (u64)limb[0] | ((u64)limb[1] << 32);
-        mag = ldexp((double)x, -149);
+        mag = ldexp((double)hi, -149);          // wi == 0: the value itself, exactly
     } else {
-        u64 mant = 0;
-        for (int p = msb; p >= msb - 52; --p) mant = (mant << 1) | bit_at(p);
-        u32 guard = bit_at(msb - 53), sticky = 0;
-        for (int p = msb - 54; p >= 0 && !sticky; --p) sticky |= bit_at(p);
+        // the 53 bits from msb down, out of hi:lo; sh = number of bits of hi:lo below them
+        const int sh = top + 12;                // 64 + top - 52, in [12, 75]
+        u64 mant, guard, sticky;
+        if (sh < 64) {
+            mant = (hi << (64 - sh)) | (lo >> sh);
+            guard = (lo >> (sh - 1)) & 1ull;
+            sticky = lo & ((1ull << (sh - 1)) - 1ull);
+        } else if (sh == 64) {
+            mant = hi; guard = lo >> 63; sticky = lo & 0x7fffffffffffffffull;
+        } else {
+            mant = hi >> (sh - 64);
+            guard = (hi >> (sh - 65)) & 1ull;
+            sticky = (hi & ((1ull << (sh - 65)) - 1ull)) | lo;
+        }
+        sticky |= rest;
         if (guard && (sticky || (mant & 1ull))) mant += 1;
         mag = ldexp((double)mant, msb - 52 - 149);
     }
