@@ -165,12 +165,27 @@ __device__ __forceinline__ void compute_cut_keys(const float *C, int K, u32 *cut
     if (k == 0 || k > 255u) return;
     u32 res = 0xffffffffu;
     if ((int)k < K) {
-        u32 lo = 0x00800000u, hi = 0xff7fffffu;            // keys of -FLT_MAX and +FLT_MAX
-        if ((u32)nearest_centre(val_of(hi), C, K, nullptr) >= k) {
-            if ((u32)nearest_centre(val_of(lo), C, K, nullptr) >= k) hi = lo;
-            while (lo < hi) {                              // invariant: rule(hi) >= k
+        constexpr u32 KEY_LO = 0x00800000u, KEY_HI = 0xff7fffffu;          // keys of -FLT_MAX and +FLT_MAX
+        auto reaches = [&](u32 key) { return (u32)nearest_centre(val_of(key), C, K, nullptr) >= k; };
+        // The border between centres k-1 and k lies next to their midpoint, so a bracket of a few keys
+        // around the midpoint is probed first; whatever the probes say, the bisection below starts
+        // from a bracket they have proved (every key below lo stays below k, hi reaches k), so the
+        // result is that of a bisection over all finite keys.
+        const u32 mk = key_of((float)(0.5 * ((double)C[k - 1] + (double)C[k])));
+        const u32 p_lo = mk - KEY_LO > 2u ? mk - 2u : KEY_LO, p_hi = KEY_HI - mk > 2u ? mk + 2u : KEY_HI;
+        u32 lo = KEY_LO, hi = KEY_HI;
+        bool any = true;
+        if (reaches(p_hi)) {
+            if (reaches(p_lo)) hi = p_lo; else { lo = p_lo + 1u; hi = p_hi; }
+        } else if (p_hi < KEY_HI && reaches(KEY_HI)) {
+            lo = p_hi + 1u;
+        } else {
+            any = false;                                                   // no finite value reaches k
+        }
+        if (any) {
+            while (lo < hi) {                                              // invariant: hi reaches k
                 const u32 mid = lo + ((hi - lo) >> 1);
-                if ((u32)nearest_centre(val_of(mid), C, K, nullptr) >= k) hi = mid; else lo = mid + 1;
+                if (reaches(mid)) hi = mid; else lo = mid + 1u;
             }
             res = hi;
         }
