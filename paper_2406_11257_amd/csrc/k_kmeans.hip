@@ -495,20 +495,27 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
     __shared__ u32 s_min[BPW], s_max[BPW];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 nseg = 3u * g.ntensors;
-    const u64 first = (u64)blockIdx.x * BPW;               // first of this workgroup's buckets
-    if (first >= (u64)nseg * NBKT) return;
+    // a workgroup walks over sets of BPW buckets (many sets are tiny: one workgroup each would be
+    // bound by the rate at which workgroups can be started)
+    for (u64 first = (u64)blockIdx.x * BPW; first < (u64)nseg * NBKT; first += (u64)gridDim.x * BPW) {
     const u32 sidx = (u32)(first / NBKT), b0 = (u32)(first % NBKT);
-    if (w.seg[sidx].len == 0) return;
+    if (w.seg[sidx].len == 0) continue;                    // the same for the whole workgroup
+    __syncthreads();                                       // the previous set has left the LDS tables
     if (tid < BPW * EXCP_ABSM_BINS) (&bins[0][0])[tid] = 0;
     if (tid < BPW) { s_min[tid] = 0xffffffffu; s_max[tid] = 0; }
     __syncthreads();
     const u32 *begin = w.km_begin + (u64)sidx * (NBKT + 1);
     const EXCP_GLOBAL float *part = gptr(seg_part(w, sidx));
-    for (u32 j = 0; j < BPW; ++j) {
+    // Small buckets (the four together at most SOLO_MAX values: small tensors, small models): a wave
+    // takes a whole bucket, the four side by side, instead of four rounds of memory round trips.
+    constexpr u32 SOLO_MAX = 4096;
+    const bool solo = BS_WAVES == BPW && begin[b0 + BPW] - begin[b0] <= SOLO_MAX;
+    for (u32 jj = 0; jj < (solo ? 1u : BPW); ++jj) {
+        const u32 j = solo ? wave : jj;
         const u32 q0 = begin[b0 + j], q1 = begin[b0 + j + 1];
         // this wave's share, cut at multiples of 256 values from the bucket's start
         const u32 blocks = (q1 - q0 + 255u) >> 8, per = (blocks + BS_WAVES - 1u) / BS_WAVES;
-        const u32 p0 = min(q0 + wave * per * 256u, q1), p1 = min(p0 + per * 256u, q1);
+        const u32 p0 = solo ? q0 : min(q0 + wave * per * 256u, q1), p1 = solo ? q1 : min(p0 + per * 256u, q1);
         if (p0 >= p1) continue;
         u64 *mybins = bins[j];
         // window base from the first (up to) 64 values: top 4 binary orders above their largest
@@ -548,7 +555,17 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
                 atomicAdd(&mybins[pos >> 3], neg ? (u64)0 - d : d);
             }
         };
-        for (u32 p = p0; p < p1; p += 256u) {
+        // four 16-byte loads in flight per lane: the share of a wave in a large bucket is a chain of
+        // round trips otherwise
+        u32 p = p0;
+        for (; p + 1024u <= p1; p += 1024u) {
+            f4u q[4];
+#pragma unroll
+            for (u32 r = 0; r < 4; ++r) q[r] = *(const EXCP_GLOBAL f4u *)(part + p + r * 256u + lane * 4u);
+#pragma unroll
+            for (u32 r = 0; r < 4; ++r) { take(q[r].x); take(q[r].y); take(q[r].z); take(q[r].w); }
+        }
+        for (; p < p1; p += 256u) {
             const u32 i = p + lane * 4u;
             if (p + 256u <= p1) {
                 const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
@@ -597,6 +614,7 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
     if (tid < BPW * EXCP_ABSM_BINS)
         w.km_bsum[((u64)sidx * NBKT + b0) * EXCP_ABSM_BINS + tid] = (&bins[0][0])[tid];
     if (tid < BPW) { w.km_min[(u64)sidx * NBKT + b0 + tid] = s_min[tid]; w.km_max[(u64)sidx * NBKT + b0 + tid] = s_max[tid]; }
+    }
 }
 
 // ---------------------------------------------------------------- P6: initial centres
@@ -1168,7 +1186,7 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
         case 4:
             if (g.wide == 2u) hipLaunchKernelGGL((k_km_bucket_stats<16, 1>), dim3(nseg * NBKT), dim3(1024), 0, s, w, g);
             else if (g.wide) hipLaunchKernelGGL((k_km_bucket_stats<16, 4>), dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
-            else hipLaunchKernelGGL((k_km_bucket_stats<4, 4>), dim3(nseg * (NBKT / 4)), dim3(256), 0, s, w, g);
+            else hipLaunchKernelGGL((k_km_bucket_stats<4, 4>), dim3(std::min(nseg * (NBKT / 4), excp_grid(w, 32))), dim3(256), 0, s, w, g);
             break;
         default: break;
     }
