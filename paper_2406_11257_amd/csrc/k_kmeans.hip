@@ -858,7 +858,7 @@ __device__ __forceinline__ void file_total(u64 *bins, u64 L, u64 H, u32 B, bool 
     }
 }
 
-__global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
+__global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
     __shared__ u64 s_bins[ITEM_R][EXCP_ABSM_BINS + 1];
@@ -915,7 +915,17 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_iter(Workspace w, GroupP
                     atomicAdd(&acc[(u64)cl * (EXCP_ABSM_BINS + 1) + (pos >> 3)], neg ? (u64)0 - d : d);
                 }
             };
-            for (u32 p = p0; p < p1; p += 256u) {
+            // four 16-byte loads in flight per lane
+            constexpr u32 LOADS = 4;
+            u32 p = p0;
+            for (; p + LOADS * 256u <= p1; p += LOADS * 256u) {
+                f4u q[LOADS];
+#pragma unroll
+                for (u32 j = 0; j < LOADS; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(part + p + j * 256u + lane * 4u);
+#pragma unroll
+                for (u32 j = 0; j < LOADS; ++j) { take(q[j].x); take(q[j].y); take(q[j].z); take(q[j].w); }
+            }
+            for (; p < p1; p += 256u) {
                 const u32 i = p + lane * 4u;
                 if (p + 256u <= p1) {
                     const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
