@@ -27,6 +27,7 @@ namespace {
 constexpr u32 MED_SAMPLE = 8192;      // sample size (and the size up to which a tensor is simply sorted)
 constexpr u32 MED_HALF_WIDTH = 192;   // bracket = sample ranks 4096 -+ 192 (about 4.2 sigma of the sample rank)
 constexpr u32 CAND_PER_WAVE = 1024;
+constexpr u32 MED_THREADS = 1024;     // workgroup of the sampling kernel: one per tensor, so its own latency is the kernel's
 
 enum { MED_PENDING = 0, MED_KNOWN = 1, MED_FALLBACK = 2 };
 
@@ -34,7 +35,7 @@ __device__ __forceinline__ void sort_keys_lds(u32 *key, u32 count_pow2) {
     const u32 tid = threadIdx.x;
     for (u32 k = 2; k <= count_pow2; k <<= 1) {
         for (u32 j = k >> 1; j > 0; j >>= 1) {
-            for (u32 t = tid; t < count_pow2 / 2; t += EXCP_THREADS) {
+            for (u32 t = tid; t < count_pow2 / 2; t += MED_THREADS) {
                 u32 i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
                 u32 p = i | j;
                 u32 a = key[i], b = key[p];
@@ -47,7 +48,7 @@ __device__ __forceinline__ void sort_keys_lds(u32 *key, u32 count_pow2) {
 }
 
 // One workgroup per tensor: sample (or all) residual magnitudes, sorted.
-__global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, GroupParams g) {
+__global__ __launch_bounds__(MED_THREADS) void k_median_sample(Workspace w, GroupParams g) {
     __shared__ u32 key[MED_SAMPLE];
     __shared__ u32 s_mmax;
     const u32 t = blockIdx.x, tid = threadIdx.x;
@@ -59,7 +60,8 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_median_sample(Workspace w, Gro
     __syncthreads();
     const u32 ns = n < MED_SAMPLE ? (u32)n : MED_SAMPLE;
     u32 mmax = 0;                                   // largest finite |m| pattern of the sample
-    for (u32 i = tid; i < MED_SAMPLE; i += EXCP_THREADS) {
+#pragma unroll
+    for (u32 i = tid; i < MED_SAMPLE; i += MED_THREADS) {       // eight samples per thread, their loads side by side
         u32 k = 0xffffffffu;
         if (i < ns) {
             const u64 idx = n <= MED_SAMPLE ? (u64)i : ((u64)i * n) / MED_SAMPLE;
@@ -657,7 +659,7 @@ void launch_stats(const Workspace &w, const GroupParams &g, int phase, hipStream
     const dim3 block(EXCP_THREADS), per_tensor(g.ntensors), small((g.ntensors + 255) / 256);
     const dim3 stream_grid(excp_grid(w, 8));
     switch (phase) {
-        case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, block, 0, s, w, g); break;
+        case 0: hipLaunchKernelGGL(k_median_sample, per_tensor, dim3(MED_THREADS), 0, s, w, g); break;
         case 1:
             if (!g.ntiles) break;
             if (g.flags & 0x30u) hipLaunchKernelGGL(k_stats_stream<true>, stream_grid, block, 0, s, w, g);
