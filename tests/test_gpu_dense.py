@@ -218,3 +218,48 @@ def test_archive_round_trip_through_the_gpu(ctx, layout):
         ref = O.decompress_step(c[0], o["blob"])
         assert W.cpu().numpy().tobytes() == ref[0].tobytes() == o["W_recon"].tobytes()
         assert m.cpu().numpy().tobytes() == ref[1].tobytes() and v.cpu().numpy().tobytes() == ref[2].tobytes()
+
+
+def test_prepared_batches_of_the_other_calls(ctx):
+    # export, reconstruction from the stored layout and Alg. 3 from argument arrays marshalled once
+    cases = [case(150001, 911), case(4097, 912)]
+    rc, outs = gpu_compress(ctx, cases, iters=3)
+    assert rc == 0
+    items, bufs = [], []
+    for o in outs:
+        n = int(o["stats"].n)
+        b = [code_buffer(X.excp_head_bytes(4))] + [code_buffer(X.excp_dense_bytes(n, 4)) for _ in range(3)]
+        bufs.append(b)
+        items.append((o["blob_dev"], int(o["stats"].blob_bytes), n, *b))
+    exp = ctx.prepare_export_dense(items)
+    assert isinstance(exp, X.PreparedBatch) and exp.kind == "export_dense"
+    dec_items, dec_outs = [], []
+    for c, o, b in zip(cases, outs, bufs):
+        n = c[0].size
+        res = [torch.zeros(n, device="cuda") for _ in range(3)]
+        dec_outs.append(res)
+        dec_items.append((to_dev(c[0]), b[0], X.excp_head_bytes(4), n, b[1], b[2], b[3], *res))
+    dec = ctx.prepare_decompress_dense(dec_items)
+    chains = ctx.prepare_chain([(to_dev(c[0]), [o["blob_dev"]], [int(o["stats"].blob_bytes)],
+                                 torch.zeros(c[0].size, device="cuda"), None, None) for c, o in zip(cases, outs)])
+    for rep in range(2):
+        for b in bufs:
+            for t in b:
+                t.fill_(CANARY)
+        ctx.excp_export_dense(exp)
+        ctx.excp_collect()
+        ctx.excp_decompress_dense(dec)
+        ctx.excp_collect()
+        ctx.excp_reconstruct_chain(chains)
+        ctx.excp_collect()
+        for c, o, b, res, ch in zip(cases, outs, bufs, dec_outs, chains.keep[0]):
+            n = c[0].size
+            ref = O.export_dense(o["blob"])
+            for got, want in zip(b[1:], ref[1:]):
+                assert got[:X.excp_dense_bytes(n, 4)].cpu().numpy().tobytes() == want.tobytes(), rep
+            W2, m2, v2 = O.decompress_step(c[0], o["blob"])
+            assert res[0].cpu().numpy().tobytes() == W2.tobytes() and res[1].cpu().numpy().tobytes() == m2.tobytes()
+            assert res[2].cpu().numpy().tobytes() == v2.tobytes()
+            assert ch[3].cpu().numpy().tobytes() == W2.tobytes()
+    with pytest.raises(TypeError):
+        ctx.excp_export_dense(dec)
