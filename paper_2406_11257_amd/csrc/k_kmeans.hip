@@ -614,6 +614,7 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
     if (tid < BPW * EXCP_ABSM_BINS)
         w.km_bsum[((u64)sidx * NBKT + b0) * EXCP_ABSM_BINS + tid] = (&bins[0][0])[tid];
     if (tid < BPW) { w.km_min[(u64)sidx * NBKT + b0 + tid] = s_min[tid]; w.km_max[(u64)sidx * NBKT + b0 + tid] = s_max[tid]; }
+    if (BS_WAVES != 4u) break;                             // the sixteen-wave forms are launched one workgroup per set
     }
 }
 
