@@ -319,6 +319,34 @@ def test_lloyd_against_library_lloyd_loops_from_the_same_start(K, iters, n):
     assert np.max(np.abs(C_short - C)) > 1e-4 * scale
 
 
+def test_objective_is_the_exact_sum_of_squared_distances():
+    """objective() against rational arithmetic: the sum of (x_j - C[a_j])^2 with every difference and
+    square exact, rounded once at the end -- on values chosen so that an L1 sum, a sum of squared
+    VALUES, a missing square or an fp32 evaluation all give a different number."""
+    x = np.array([0.75, -1.5, 2.25, 1e-4, -3.0000002, 1e-3, 7.0, 7.0], f32)
+    C = np.array([-2.0, 0.5, 6.0], f32)
+    a = np.array([1, 0, 1, 1, 0, 1, 2, 2], np.int64)
+    exact = sum(((frac(t) - frac(C[k])) ** 2 for t, k in zip(x, a)), Fraction(0))
+    got = O.objective(x, C, a)
+    assert got == float(exact)                                  # correctly rounded: fsum of exact fp64 squares
+    l1 = float(sum((abs(frac(t) - frac(C[k])) for t, k in zip(x, a)), Fraction(0)))
+    assert abs(got - l1) > 0.1
+    assert abs(got - float(sum((frac(t) ** 2 for t in x), Fraction(0)))) > 1.0
+    # squares of fp32 differences are exact in fp64 only up to 48 bits: a term that is not -- the
+    # oracle's per-term rounding (fp64, one rounding per square) is what the rational sum must match
+    # within one unit of the result
+    g = np.random.default_rng(77)
+    x2 = g.laplace(0, 1e-4, 400).astype(f32)
+    C2, a2 = O.lloyd(x2, 7, 3)
+    exact2 = sum(((frac(t) - frac(C2[k])) ** 2 for t, k in zip(x2, a2)), Fraction(0))
+    assert abs(O.objective(x2, C2, a2) - float(exact2)) <= 2e-16 * float(exact2) * 400
+    # the assignment matters: moving one member to a farther centre raises it by exactly that term's change
+    b = a.copy(); b[0] = 2
+    delta = (frac(x[0]) - frac(C[2])) ** 2 - (frac(x[0]) - frac(C[1])) ** 2
+    assert O.objective(x, C, b) == float(exact + delta)
+    assert O.objective(np.zeros(0, f32), C, np.zeros(0, np.int64)) == 0.0
+
+
 def test_lloyd_is_lossless_when_values_fit_the_codebook():
     x = np.array([5e-4, -2e-4, 5e-4, 1e-3, -2e-4, 7e-5], f32)
     C, a = O.lloyd(x, 15, 10)
