@@ -52,8 +52,11 @@
  * Memory and ownership.  Every tensor pointer below is DEVICE memory on the
  * context's GPU (4-byte aligned is enough; weights are fp32 unless EXCP_FLAG_W_* says otherwise); blobs are DEVICE memory, 16-byte
  * aligned.  The caller owns all of them and the HIP stream.  The context owns
- * only its workspace, allocated in excp_create; no entry point allocates
- * afterwards.  stats / blob_bytes outputs are HOST memory.
+ * only its workspace and its bookkeeping lists, allocated in excp_create; the
+ * compress, decompress, export, chain and collect calls allocate nothing, on the
+ * device or on the host (the one later allocation is the event pool that the
+ * first excp_set_profiling(ctx, 1) creates, outside any step).  stats /
+ * blob_bytes outputs are HOST memory.
  *
  * Execution.  Work is enqueued on the context's stream.  excp_compress_tensors
  * and excp_decompress_tensors return after enqueueing; excp_collect waits for
@@ -84,7 +87,9 @@ extern "C" {
 #define EXCP_E_NONFINITE  -3   /* NaN or Inf in an input, or the residual overflows fp32 */
 #define EXCP_E_BLOB       -4   /* decompress: bad magic / version / sizes / bitmap population, a blob of another
                                   weight storage than the arrays passed, or of a kind the call does not read */
-#define EXCP_E_HIP        -5   /* a HIP call failed, or the device could not be used */
+#define EXCP_E_HIP        -5   /* a HIP call failed, or the device could not be used.  If it happens while a batch
+                                  is being enqueued, the call waits for what it had enqueued, and the context
+                                  refuses further work with this code: destroy it */
 #define EXCP_E_STATE      -6   /* call order violated (batch pending / nothing to collect) */
 #define EXCP_E_INTERNAL   -7   /* an internal work list overflowed (should not happen) */
 
@@ -278,9 +283,23 @@ int         excp_stage_count(void);
 const char *excp_stage_name(int i);
 int         excp_stage_ms(excp_ctx *ctx, int i, double *ms, int *launches);
 
-/* Measurement aid: a plain device-to-device copy of nbytes (multiple of 16, both pointers 16-B
- * aligned) on the context's stream, asynchronous.  Its HBM traffic is exactly nbytes read and
- * nbytes written, which calibrates a profiler's byte counters. */
+/* Size thresholds at which the library switches between forms of its kernels.  The forms compute the
+ * same bytes; the thresholds only decide which is faster, and the defaults are the measured ones.  They
+ * are settable so that the forms meant for very large tensors can be exercised -- and compared with a
+ * CPU reference -- on tensors a host can process.  value > 0; not while a batch is pending.
+ *   EXCP_PARAM_WIDE_ELEMS      (default 2^28): a group holding a tensor of at least this many elements
+ *                              computes the per-bucket totals and initial centres of Sec. 3.3 with
+ *                              sixteen waves and one workgroup per bucket.
+ *   EXCP_PARAM_CAND_LIST_ELEMS (default 2^26): a tensor's median candidates (Sec. 3.2) are filed in
+ *                              n / value lists (at least 1, at most 16), each with a counter of its own. */
+#define EXCP_PARAM_WIDE_ELEMS       1
+#define EXCP_PARAM_CAND_LIST_ELEMS  2
+int excp_set_param(excp_ctx *ctx, int param, uint64_t value);
+
+/* Measurement aid, not part of the method: a plain device-to-device copy of nbytes (multiple of 16,
+ * both pointers 16-B aligned) on the context's stream, asynchronous.  Its HBM traffic is exactly nbytes
+ * read and nbytes written, which is what bench.py and the profile summaries calibrate a profiler's byte
+ * counters with. */
 int excp_copy_probe(excp_ctx *ctx, void *dst, const void *src, uint64_t nbytes);
 
 /* Bytes of device workspace the context holds. */

@@ -10,6 +10,7 @@ EXCP_OK, EXCP_E_ARG, EXCP_E_CAP, EXCP_E_NONFINITE = 0, -1, -2, -3
 EXCP_E_BLOB, EXCP_E_HIP, EXCP_E_STATE, EXCP_E_INTERNAL = -4, -5, -6, -7
 EXCP_FLAG_MEDIAN_OF_WEIGHTS, EXCP_FLAG_NO_M2W, EXCP_FLAG_NO_QUANT, EXCP_FLAG_NO_W2M = 1, 2, 4, 8
 EXCP_FLAG_W_F16, EXCP_FLAG_W_BF16 = 16, 32
+EXCP_PARAM_WIDE_ELEMS, EXCP_PARAM_CAND_LIST_ELEMS = 1, 2
 
 
 class ExcpTensor(C.Structure):
@@ -78,6 +79,7 @@ SYMBOLS = {
     "excp_decompress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]),
     "excp_set_profiling": (C.c_int, [C.c_void_p, C.c_int]),
+    "excp_set_param": (C.c_int, [C.c_void_p, C.c_int, C.c_uint64]),
     "excp_stage_count": (C.c_int, []),
     "excp_stage_name": (C.c_char_p, [C.c_int]),
     "excp_stage_ms": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
@@ -402,6 +404,11 @@ class Context:
         rc = lib().excp_copy_probe(self._h, _ptr(dst), _ptr(src), nbytes)
         if rc != EXCP_OK:
             raise ExcpError(rc, "excp_copy_probe")
+
+    def excp_set_param(self, param: int, value: int):
+        rc = lib().excp_set_param(self._h, param, value)
+        if rc != EXCP_OK:
+            raise ExcpError(rc, "excp_set_param")
 
     # -- timing ----------------------------------------------------------------------
     def excp_set_profiling(self, enabled: bool):

@@ -172,12 +172,11 @@ struct Workspace {
     HostRec *rec_dev;
     u32 rec_base;             // index of this group's first tensor in rec_dev
     int cus;                  // compute units of the device
-    u32 tune_wgs;             // tuning builds only: workgroups per compute unit for every persistent kernel (0 = each kernel's own)
 };
 
 // Grid of a persistent kernel: `per_cu` workgroups per compute unit (each kernel's figure was
 // measured on its own).
-static inline u32 excp_grid(const Workspace &w, u32 per_cu) { return (u32)w.cus * (w.tune_wgs ? w.tune_wgs : per_cu); }
+static inline u32 excp_grid(const Workspace &w, u32 per_cu) { return (u32)w.cus * per_cu; }
 
 void launch_zero_u32(u32 *p, u64 count, hipStream_t s);
 void launch_copy_probe(const void *src, void *dst, u64 bytes, hipStream_t s);

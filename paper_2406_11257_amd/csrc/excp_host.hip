@@ -28,6 +28,10 @@ const char *kStageNames[ST_COUNT] = {
     "decode_prep", "decode_main", "export_dense", "decode_dense", "misc"};
 
 struct Span { int stage; hipEvent_t a, b; };
+struct Group { u32 first, count, ntiles; };
+struct CGroup { u32 first, count, first_desc, ndescs, ntiles, tb_desc, tb_chain; };
+
+constexpr size_t kEventPool = 8192;      // events made by excp_set_profiling: 4096 timed stages per batch
 
 }  // namespace
 
@@ -49,6 +53,14 @@ struct excp_ctx {
     // pending batch
     int pending = 0;      // 0 none, 1 compress, 2 decompress
     int pending_count = 0;
+    bool broken = false;  // a HIP call failed while a batch was being enqueued: the context takes no more work
+    // per-call lists; their storage is reserved in excp_create so that no call allocates
+    std::vector<Group> groups;
+    std::vector<CGroup> cgroups;
+    std::vector<u32> tb_offsets;
+    // size thresholds of the kernel forms (excp_set_param)
+    u64 wide_elems = 1ull << 28;        // a group with a tensor this large takes the sixteen-wave per-bucket kernels
+    u64 cand_list_elems = 1ull << 26;   // one median-candidate list per this many elements of a tensor (1 .. 16 lists)
     // profiling
     bool profiling = false;
     std::vector<Span> spans;
@@ -75,14 +87,12 @@ struct StageTimer {
     excp_ctx *c; int stage; hipEvent_t a = nullptr, b = nullptr;
     StageTimer(excp_ctx *ctx, int st) : c(ctx), stage(st) {
         if (!c->profiling) return;
-        auto get = [&]() {
-            hipEvent_t e = nullptr;
-            if (!c->free_events.empty()) { e = c->free_events.back(); c->free_events.pop_back(); }
-            else if (hipEventCreate(&e) != hipSuccess) e = nullptr;
-            return e;
-        };
-        a = get(); b = get();
-        if (a) (void)hipEventRecord(a, c->stream);
+        // events come from the pool excp_set_profiling made; a batch with more stages than the pool
+        // holds leaves the rest untimed rather than create events in the middle of a step
+        if (c->free_events.size() < 2) return;
+        a = c->free_events.back(); c->free_events.pop_back();
+        b = c->free_events.back(); c->free_events.pop_back();
+        (void)hipEventRecord(a, c->stream);
     }
     ~StageTimer() {
         if (!c->profiling || !a || !b) return;
@@ -90,6 +100,19 @@ struct StageTimer {
         c->spans.push_back({stage, a, b});
     }
 };
+
+// A HIP call failed after part of a batch was enqueued.  The copies already queued read the pinned
+// staging arrays, so the stream is drained before anything may overwrite them, and the context takes
+// no further work: what state the device tables are in is unknown.
+int enqueue_failed(excp_ctx *c) {
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipGetLastError();
+    for (auto &sp : c->spans) { c->free_events.push_back(sp.a); c->free_events.push_back(sp.b); }
+    c->spans.clear();
+    c->pending = 0;
+    c->broken = true;
+    return EXCP_E_HIP;
+}
 
 u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits, u32 flags = 0) {
     u64 s = EXCP_HEADER + excp_books_bytes((u32)nbits);
@@ -99,8 +122,6 @@ u64 blob_size_host(u64 n, u64 nw, u64 no, int nbits, u32 flags = 0) {
     s += 2 * excp_pad16(8 * excp_words(no * (u64)nbits));
     return s;
 }
-
-struct Group { u32 first, count, ntiles; };
 
 // Split [0, count) into groups: at most kMaxGroupTensors tensors, cap_elems elements, tcap tensors.
 template <class GetN>
@@ -143,10 +164,11 @@ void run_decode_prep_and_main(excp_ctx *c, const Workspace &w, u32 ntensors, u32
 template <class Fill>
 int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
-    std::vector<Group> groups;
+    std::vector<Group> &groups = c->groups;
+    std::vector<u32> &tb_offsets = c->tb_offsets;
+    groups.clear(); tb_offsets.clear();
     make_groups(count, c->max_group, kMaxGroupTensors, [&](u32 i) { DDesc d; fill(i, d); return (u64)d.n; }, groups);
     u32 tb_off = 0;
-    std::vector<u32> tb_offsets;
     for (const Group &g : groups) {
         u32 tile = 0;
         tb_offsets.push_back(tb_off);
@@ -164,7 +186,7 @@ int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
     if (count) {
         if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
     for (size_t gi = 0; gi < groups.size(); ++gi) {
         const Group &g = groups[gi];
@@ -197,10 +219,10 @@ int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
     }
     if (count) {
         if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
-    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
-    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return enqueue_failed(c);
+    if (hipGetLastError() != hipSuccess) return enqueue_failed(c);
     c->pending = 2;
     c->pending_count = count;
     return EXCP_OK;
@@ -259,6 +281,13 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
     c->stream = (hipStream_t)hip_stream;
     c->max_tensor = max_tensor_elems;
     c->max_group = max_group_elems;
+    try {                                     // every list a later call fills is reserved here, at its largest
+        c->groups.reserve(kMaxBatchTensors);
+        c->cgroups.reserve(kMaxBatchTensors);
+        c->tb_offsets.reserve(kMaxBatchTensors);
+        c->spans.reserve(kEventPool / 2);
+        c->free_events.reserve(kEventPool);
+    } catch (...) { delete c; return EXCP_E_HIP; }
     Workspace &w = c->w;
     const u64 G = max_group_elems;
     const u64 max_tiles = G / EXCP_TILE + kMaxGroupTensors + 1;
@@ -323,7 +352,6 @@ int excp_create(excp_ctx **out, int hip_device, void *hip_stream, uint64_t max_t
         hipDeviceProp_t prop;
         ok = hipGetDeviceProperties(&prop, hip_device) == hipSuccess && prop.multiProcessorCount > 0;
         w.cus = ok ? prop.multiProcessorCount : 0;
-        w.tune_wgs = 0;
     }
     if (ok) {
         launch_zero_u32(w.med_hist, (u64)kMaxGroupTensors * 2048, c->stream);
@@ -365,8 +393,28 @@ int excp_copy_probe(excp_ctx *c, void *dst, const void *src, uint64_t nbytes) {
 int excp_set_profiling(excp_ctx *c, int enabled) {
     if (!c) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
+    if (enabled && c->free_events.empty()) {
+        // the event pool is made here, once, so that no timed step creates events
+        if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
+        for (size_t i = 0; i < kEventPool; ++i) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreate(&e) != hipSuccess) return EXCP_E_HIP;
+            c->free_events.push_back(e);
+        }
+    }
     c->profiling = enabled != 0;
     return EXCP_OK;
+}
+
+int excp_set_param(excp_ctx *c, int param, uint64_t value) {
+    if (!c || value == 0) return EXCP_E_ARG;
+    if (c->pending) return EXCP_E_STATE;
+    switch (param) {
+        case EXCP_PARAM_WIDE_ELEMS: c->wide_elems = value; return EXCP_OK;
+        case EXCP_PARAM_CAND_LIST_ELEMS: c->cand_list_elems = value; return EXCP_OK;
+        default: return EXCP_E_ARG;
+    }
 }
 
 int excp_stage_ms(excp_ctx *c, int i, double *ms, int *launches) {
@@ -380,12 +428,9 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
                           int nbits, int lloyd_iters, uint32_t flags) {
     if (!c || count < 0 || (count && !tensors)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
-#ifdef EXCP_TUNING
-    if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & 0xc0u) != 0 || (flags & 0x30u) == 0x30u) return EXCP_E_ARG;   // tuning build only
-#else
     if (nbits < 2 || nbits > 8 || lloyd_iters < 0 || (flags & ~63u) != 0 || (flags & 0x30u) == 0x30u) return EXCP_E_ARG;
-#endif
     if (!(alpha >= 0.f) || !(beta >= 0.f) || isinf(alpha) || isinf(beta)) return EXCP_E_ARG;
     const bool raw = (flags & EXCP_FLAG_NO_QUANT) != 0;     // survivors stored as fp32: no codebook stage at all
     if (raw) nbits = (int)EXCP_RAW_BITS;
@@ -401,11 +446,12 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
     const u64 cap_elems = c->max_group;
     const u32 tcap = kMaxGroupTensors;
-    std::vector<Group> groups;
+    std::vector<Group> &groups = c->groups;
+    std::vector<u32> &tb_offsets = c->tb_offsets;
+    groups.clear(); tb_offsets.clear();
     make_groups(count, cap_elems, tcap, [&](u32 i) { return (u64)tensors[i].n; }, groups);
 
     u32 tb_off = 0;
-    std::vector<u32> tb_offsets;
     for (const Group &g : groups) {
         u64 elem_off = 0, cand_off = 0; u32 tile = 0;
         tb_offsets.push_back(tb_off);
@@ -415,7 +461,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
             d.Wp = (const float *)t.W_prev_recon; d.W = (const float *)t.W_t; d.m = t.m_t; d.v = t.v_t; d.n = t.n;
             d.blob = (unsigned char *)t.blob; d.blob_cap = t.blob_cap; d.W_out = (float *)t.W_recon_out;
             d.elem_off = elem_off; d.tile_begin = tile;
-            d.cand_lists = (u32)std::min<u64>(std::max<u64>(t.n >> 26, 1), 16); d.pad0 = 0;
+            d.cand_lists = (u32)std::min<u64>(std::max<u64>(t.n / c->cand_list_elems, 1), 16); d.pad0 = 0;
             d.cand_off = cand_off; d.cand_cap = (t.n / 12 + 4096 + d.cand_lists - 1) / d.cand_lists * d.cand_lists;
             cand_off += d.cand_cap;
             d.tile_count = (u32)((t.n + EXCP_TILE - 1) / EXCP_TILE);
@@ -429,7 +475,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     if (count) {
         if (hipMemcpyAsync(c->desc_all, c->h_desc, sizeof(TDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
         launch_zero_u32((u32 *)c->st_all, (u64)count * sizeof(TState) / 4, s);
         launch_zero_u32(c->cand_ctr_all, (u64)count * 512, s);
     }
@@ -449,10 +495,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         p.ntensors = g.count; p.ntiles = g.ntiles;
         u64 largest = 0;
         for (u32 q = 0; q < g.count; ++q) largest = std::max<u64>(largest, tensors[g.first + q].n);
-        p.wide = largest >= (1ull << 28) ? 2u : ((flags & 0x30u) != 0 ? 1u : 0u);
-#ifdef EXCP_TUNING
-        w.tune_wgs = (flags >> 24) & 0xffu;
-#endif
+        p.wide = largest >= c->wide_elems ? 2u : ((flags & 0x30u) != 0 ? 1u : 0u);
         { StageTimer t(c, ST_SAMPLE); launch_stats(w, p, 0, s); }
         { StageTimer t(c, ST_STATS); launch_stats(w, p, 1, s); }
         {
@@ -500,10 +543,10 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
     }
     if (count) {
         if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
-    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
-    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return enqueue_failed(c);
+    if (hipGetLastError() != hipSuccess) return enqueue_failed(c);
     c->pending = 1;
     c->pending_count = count;
     return EXCP_OK;
@@ -512,6 +555,7 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
 int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
     if (!c || count < 0 || (count && !blobs)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     for (int i = 0; i < count; ++i) {
         const excp_blob &b = blobs[i];
@@ -521,10 +565,11 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
         if (b.n && !b.W_prev_recon) return EXCP_E_ARG;
     }
     if (hipSetDevice(c->device) != hipSuccess) return EXCP_E_HIP;
-    std::vector<Group> groups;
+    std::vector<Group> &groups = c->groups;
+    std::vector<u32> &tb_offsets = c->tb_offsets;
+    groups.clear(); tb_offsets.clear();
     make_groups(count, c->max_group, kMaxGroupTensors, [&](u32 i) { return (u64)blobs[i].n; }, groups);
     u32 tb_off = 0;
-    std::vector<u32> tb_offsets;
     for (const Group &g : groups) {
         u32 tile = 0;
         tb_offsets.push_back(tb_off);
@@ -545,7 +590,7 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
     if (count) {
         if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
     for (size_t gi = 0; gi < groups.size(); ++gi) {
         const Group &g = groups[gi];
@@ -564,10 +609,10 @@ int excp_decompress_tensors(excp_ctx *c, int count, const excp_blob *blobs) {
     }
     if (count) {
         if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
-    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
-    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return enqueue_failed(c);
+    if (hipGetLastError() != hipSuccess) return enqueue_failed(c);
     c->pending = 2;
     c->pending_count = count;
     return EXCP_OK;
@@ -579,6 +624,7 @@ uint64_t excp_head_bytes(int nbits) { return (nbits < 2 || nbits > 8) ? 0 : EXCP
 int excp_export_dense(excp_ctx *c, int count, const excp_dense_export *items) {
     if (!c || count < 0 || (count && !items)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     for (int i = 0; i < count; ++i) {
         const excp_dense_export &e = items[i];
@@ -598,6 +644,7 @@ int excp_export_dense(excp_ctx *c, int count, const excp_dense_export *items) {
 int excp_decompress_dense(excp_ctx *c, int count, const excp_dense_blob *items) {
     if (!c || count < 0 || (count && !items)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     for (int i = 0; i < count; ++i) {
         const excp_dense_blob &e = items[i];
@@ -620,6 +667,7 @@ int excp_decompress_dense(excp_ctx *c, int count, const excp_dense_blob *items) 
 int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
     if (!c || count < 0 || (count && !chains)) return EXCP_E_ARG;
     if (c->pending) return EXCP_E_STATE;
+    if (c->broken) return EXCP_E_HIP;
     if ((u32)count > kMaxBatchTensors) return EXCP_E_ARG;
     u64 total_descs = 0;
     for (int i = 0; i < count; ++i) {
@@ -638,8 +686,8 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
     // Groups: at most kMaxGroupTensors descriptors (one per tensor and checkpoint) and as many
     // descriptor tiles as the per-tile count tables hold (EXCP_MAX_CHAIN times a group's tiles, so
     // any tensor the context accepts fits with its whole chain).
-    struct CGroup { u32 first, count, first_desc, ndescs, ntiles, tb_desc, tb_chain; };
-    std::vector<CGroup> groups;
+    std::vector<CGroup> &groups = c->cgroups;
+    groups.clear();
     u32 tb_off = 0, desc_off = 0;
     for (u32 i = 0; i < (u32)count;) {
         CGroup g{i, 0, desc_off, 0, 0, 0, 0};
@@ -683,7 +731,7 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
         if (hipMemcpyAsync(c->ddesc_all, c->h_ddesc, sizeof(DDesc) * desc_off, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipMemcpyAsync(c->cdesc_all, c->h_cdesc, sizeof(CDesc) * count, hipMemcpyHostToDevice, s) != hipSuccess ||
             hipMemcpyAsync(c->tile_begin_all, c->h_tile_begin, sizeof(u32) * tb_off, hipMemcpyHostToDevice, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
     for (const CGroup &g : groups) {
         Workspace w = c->w;
@@ -715,10 +763,10 @@ int excp_reconstruct_chain(excp_ctx *c, int count, const excp_chain *chains) {
     }
     if (count) {
         if (hipMemcpyAsync(c->h_rec, c->w.rec_dev, sizeof(HostRec) * count, hipMemcpyDeviceToHost, s) != hipSuccess)
-            return EXCP_E_HIP;
+            return enqueue_failed(c);
     }
-    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return EXCP_E_HIP;
-    if (hipGetLastError() != hipSuccess) return EXCP_E_HIP;
+    if (hipMemcpyAsync(c->h_err, c->w.err_flag, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return enqueue_failed(c);
+    if (hipGetLastError() != hipSuccess) return enqueue_failed(c);
     c->pending = 2;
     c->pending_count = count;
     return EXCP_OK;
@@ -771,7 +819,9 @@ int excp_compress_step(excp_ctx *c, const void *W_prev_recon, const void *W_t, c
     int rc = excp_compress_tensors(c, 1, &t, alpha, beta, nbits, lloyd_iters, flags);
     if (rc != EXCP_OK) return rc;
     excp_stats st;
+    memset(&st, 0, sizeof(st));
     rc = excp_collect(c, &st);
+    if (rc == EXCP_E_HIP || rc == EXCP_E_STATE) return rc;      // nothing was collected: the outputs stay untouched
     if (blob_bytes) *blob_bytes = st.blob_bytes;
     if (stats) *stats = st;
     return rc;

@@ -17,12 +17,6 @@
 
 namespace {
 
-#ifdef EXCP_TUNING
-#define TUNE(bit) ((g.flags >> (bit)) & 1u)
-#else
-#define TUNE(bit) 0u
-#endif
-
 constexpr u32 SUB = 2048;          // elements per sub-tile
 constexpr int NBATCH = 8;          // 64-element batches per wave and sub-tile
 constexpr u32 BO_WORDS = SUB / 64; // M_o words kept per sub-tile

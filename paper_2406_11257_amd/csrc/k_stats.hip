@@ -18,12 +18,6 @@
 
 namespace {
 
-#ifdef EXCP_TUNING
-#define TUNE(bit) ((g.flags >> (bit)) & 1u)
-#else
-#define TUNE(bit) 0u
-#endif
-
 constexpr u32 MED_SAMPLE = 8192;      // sample size (and the size up to which a tensor is simply sorted)
 constexpr u32 MED_HALF_WIDTH = 192;   // bracket = sample ranks 4096 -+ 192 (about 4.2 sigma of the sample rank)
 constexpr u32 CAND_PER_WAVE = 1024;
@@ -286,7 +280,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
                 }
             }
         }
-        if (!TUNE(18) && __any(worst >= 0x7f800000u)) {
+        if (__any(worst >= 0x7f800000u)) {
             // rare: something is not finite; it is reported and keeps out of the sum
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -297,7 +291,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
         }
         const u32 natoms = W16 ? S.natoms : 0u;
         const u32 ak0 = S.atom_key[0], ak1 = S.atom_key[1], ak2 = S.atom_key[2], ak3 = S.atom_key[3];
-        if (pending && !TUNE(16)) {
+        if (pending) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 clt += __popcll(ballot64(key[j] < klo));
@@ -317,7 +311,7 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_stats_stream(Workspace w, Grou
             }
             if (wcount > CAND_PER_WAVE) flush_cand(t);        // room for another 1024 is kept
         }
-        if (!TUNE(17)) {
+        {
             // exact sum of |m|: in-window values are whole multiples of 2^(B-149) below 2^48 units,
             // so this lane's sixteen add exactly in fp64.
             const u32 thr_lo = B ? ((B + 1u) << 23) : 0u, span = ((B + 25u) << 23) - thr_lo;
