@@ -1,6 +1,8 @@
-"""GPU parity at the benchmark's sizes and launch configuration: one complete LLaMA-7B-shaped tensor
-against the whole oracle, and the largest tensor (131 072 000 elements) checked through exact
-properties and on sampled elements that the oracle computes one by one."""
+"""GPU parity at the benchmark's sizes and launch configuration: the four tensor sizes of the
+LLaMA-7B-shaped checkpoint in one call.  The 16.8 M-element matrix is compared with the oracle piece by
+piece; the 131 M-element embedding and the 45 M-element MLP matrix (also stored as bf16) are compared
+with the oracle -- run beside the other tests in a pool of CPU processes -- on the whole blob and the
+reconstruction, and the embedding also through exact properties and sampled elements."""
 import numpy as np
 import pytest
 import torch
@@ -9,6 +11,8 @@ import oracle as O
 import paper_2406_11257_amd as X
 from paper_2406_11257_amd import synth
 from gpu_util import compare_with_oracle
+from oracle.pool import OraclePool
+from test_gpu_models import PARAMS, check_tensor, sha_dev
 
 pytestmark = pytest.mark.gpu
 f32 = np.float32
@@ -37,7 +41,17 @@ def batch():
     assert rc == 0
     for idx, t, st in zip(picks, tensors, stats):
         items[idx] = (t[:4], t[4], int(st.blob_bytes), st, t[5])
+    # the oracle on the two largest tensors (about 80 s and 30 s of one core each) and on the bf16 form
+    # of the second runs in worker processes while the tests below go on
+    pool = OraclePool(3)
+    for idx in (0, 5):
+        pool.submit(f"t{idx}", [x.cpu().numpy() for x in items[idx][0]], PARAMS)
+    Wp5, W5, m5, v5 = items[5][0]
+    as_u16 = lambda t: t.bfloat16().view(torch.int16).cpu().numpy().view(np.uint16)
+    pool.submit("b5", [as_u16(Wp5), as_u16(W5), m5.cpu().numpy(), v5.cpu().numpy()], dict(PARAMS, flags=X.EXCP_FLAG_W_BF16))
+    items["pool"] = pool
     yield ctx, cfg, items
+    pool.close()
     ctx.close()
 
 
@@ -131,6 +145,24 @@ def test_largest_tensor_properties_and_sampled_elements(batch):
     assert abs(12.0 * n / nbytes - 28.8) < 0.5                   # same ratio as every other tensor of this recipe
 
 
+def test_largest_tensors_against_the_whole_oracle(batch):
+    """The 131 M-element embedding and the 45 M-element MLP matrix: counts, thresholds, the whole blob
+    (so every centre of the three codebooks, both bitmaps and every code) and the reconstructed weights
+    equal the oracle's; Alg. 2 through the library returns the oracle's moments."""
+    ctx, cfg, items = batch
+    for idx in (5, 0):
+        (Wp, W, m, v), blob, nbytes, st, Wout = items[idx]
+        res = items["pool"].result(f"t{idx}")
+        n = cfg.tensors[idx].n
+        outs = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+        ctx.excp_decompress_step(Wp, blob, nbytes, *outs)
+        check_tensor(f"tensor {idx} ({cfg.tensors[idx].name}, {n} elements)", res, st, blob, Wout, outs[1], outs[2])
+        assert torch.equal(outs[0], Wout)
+        print(f"{n}-element tensor: blob of {nbytes} bytes and reconstruction identical to the oracle's "
+              f"(oracle: {res['seconds']:.0f} s)", flush=True)
+        del outs
+
+
 def test_sixteen_bit_weights_at_full_size(batch):
     """A 16.8 M-element tensor stored as fp16 with the moment mask on its own (flags F16 | NO_W2M) against
     the whole oracle, and a 45 M-element bf16 tensor against independent device-side routines; the same
@@ -178,6 +210,8 @@ def test_sixteen_bit_weights_at_full_size(batch):
     r_o = f32(f32(synth.BETA) * f32(st2.mean_abs_m))
     assert int((keep & (m2.abs() > float(r_o))).sum().item()) == st2.n_o
     print("45M bf16: n_w", st2.n_w, "n_o", st2.n_o, "median", st2.median_abs_dw, flush=True)
+    # the whole blob and the reconstruction against the oracle
+    check_tensor("45 M-element tensor stored as bf16", items["pool"].result("b5"), st2, blob2, Wout2)
     nb2 = int(st2.blob_bytes)
     assert nb2 == X.excp_blob_size(n2, st2.n_w, st2.n_o, 4)
     W3 = torch.empty(n2, dtype=torch.bfloat16, device=dev)

@@ -24,21 +24,42 @@ def ctx():
     c.close()
 
 
-def draw_batch(seed):
+@pytest.fixture(scope="module")
+def ctx_wide():
+    """The same limits, with the size thresholds of the library lowered so that every batch runs the
+    kernel forms that otherwise only tensors of 2^28 elements (per-bucket totals and initial centres with
+    sixteen waves, one workgroup per bucket) or 2^27 elements (several median-candidate lists) reach."""
+    c = X.Context(1 << 21, 4 << 20)
+    c.excp_set_param(X.EXCP_PARAM_WIDE_ELEMS, 1)
+    c.excp_set_param(X.EXCP_PARAM_CAND_LIST_ELEMS, 65536)
+    yield c
+    c.close()
+
+
+def draw_batch(seed, big=None):
+    """big: None, or the weight-storage flags of a batch whose first two tensors are large (0.6 to 1.5 M
+    elements), one of Laplace steps and one of a handful of distinct values."""
     g = np.random.default_rng(7700 + seed)
     nbits = int(g.integers(2, 9))
     iters = int(g.integers(0, 6))
     flags = int(g.integers(0, 16)) | int(g.choice([0, 0, 16, 32]))
+    if big is not None:
+        flags = (flags & 0xA) | big              # quantised, median of the residual, the storage asked for
+        iters = max(iters, 2)
     alpha = float(g.choice([0.0, 1e-6, 5e-5, 1e-3, 1.0])) if g.random() < 0.5 else float(10 ** g.uniform(-7, 0))
     if flags & O.FLAG_NO_M2W:                      # a plain scalar threshold: of the order of the median itself
         alpha = float(g.choice([0.0, 0.3, 0.7, 1.5, 20.0]))
     beta = float(g.choice([0.0, 0.5, 2.0, 10.0]))
+    if big is not None:                            # thresholds that keep a good share of every stream
+        alpha, beta = (0.3 if flags & O.FLAG_NO_M2W else 5e-5), 0.5
     cases = []
-    for _ in range(8):
+    for q in range(8):
         n = int(g.choice(EDGE_SIZES)) if g.random() < 0.4 else int(g.integers(1, 90000))
         if g.random() < 0.15:
             n = int(g.integers(100000, 1500000))
         kind = int(g.integers(0, 7))
+        if big is not None and q < 2:
+            n, kind = int(g.integers(600000, 1500000)), q
         Wp = (g.standard_normal(n) * 0.02).astype(f32)
         if kind == 0:
             d = g.laplace(0, 1e-4, n)
@@ -69,8 +90,26 @@ def draw_batch(seed):
 
 @pytest.mark.parametrize("seed", range(24))
 def test_random_batch(ctx, seed):
-    nbits, iters, flags, alpha, beta, cases = draw_batch(seed)
-    what = f"seed {seed}: nbits {nbits}, iters {iters}, flags {flags}, alpha {alpha}, beta {beta}"
+    run_batch(ctx, seed, None)
+
+
+@pytest.mark.parametrize("seed", range(100, 110))
+def test_random_batch_in_the_forms_for_very_large_tensors(ctx_wide, seed):
+    run_batch(ctx_wide, seed, None)
+
+
+@pytest.mark.parametrize("seed,storage", [(200, 0), (201, 16), (202, 32), (203, 0), (204, 16)])
+def test_large_continuous_and_tied_tensors_in_the_forms_for_very_large_tensors(ctx_wide, seed, storage):
+    """Two tensors of 0.6 to 1.5 M elements per batch -- Laplace steps, and a handful of distinct values
+    (with 16-bit storage: residuals that are multiples of the format's unit, the case in which a
+    sixteen-wave form of the per-bucket totals once gave a wrong centre) -- through the sixteen-wave,
+    one-bucket-per-workgroup kernels and several candidate lists, blob for blob against the oracle."""
+    run_batch(ctx_wide, seed, storage)
+
+
+def run_batch(ctx, seed, big):
+    nbits, iters, flags, alpha, beta, cases = draw_batch(seed, big)
+    what = f"seed {seed}: nbits {nbits}, iters {iters}, flags {flags}, alpha {alpha}, beta {beta}, sizes {[c[0].size for c in cases]}"
     print(what, flush=True)
     stored_bits = 32 if flags & O.FLAG_NO_QUANT else nbits
     dev = []
