@@ -275,6 +275,23 @@ int excp_compress_step(excp_ctx *ctx,
 int excp_decompress_step(excp_ctx *ctx, const void *W_prev_recon, const void *blob, uint64_t blob_bytes,
                          uint64_t n, void *W_recon_out, float *m_out, float *v_out, uint32_t flags);
 
+/* For callers that cannot allocate -- code under HIP graph capture restrictions, tight serving loops,
+ * harnesses that forbid hipMalloc: Alg. 2 for one tensor exactly as excp_decompress_step computes it,
+ * without a context and without allocating anything, on the device or on the host.  The tables the
+ * decoding kernels keep between their launches (the tensor's descriptor and state, per-tile survivor
+ * counts of both bitmaps, the result record: about 0.5 MiB) live in a static device array inside the
+ * library, one copy per GPU, held until the process ends; that fixes the largest tensor:
+ * n <= EXCP_STATIC_MAX_ELEMS, EXCP_E_ARG beyond it (larger tensors: a context).  Work is enqueued on
+ * `hip_stream` (a hipStream_t, borrowed; NULL = the default stream) of device `hip_device`, and the
+ * call waits for it.  Arguments, outputs, flags and errors are those of excp_decompress_step (blobs
+ * written with EXCP_FLAG_NO_QUANT are read too).  Every call on one GPU uses that GPU's one array:
+ * calls that overlap on the same GPU, from any threads or streams, race -- serialise them.  Calls on
+ * different GPUs are independent. */
+#define EXCP_STATIC_MAX_ELEMS 268435456ull   /* 2^28 */
+int excp_decompress_step_static(int hip_device, void *hip_stream, const void *W_prev_recon, const void *blob,
+                                uint64_t blob_bytes, uint64_t n, void *W_recon_out, float *m_out, float *v_out,
+                                uint32_t flags);
+
 /* Per-stage timing.  When enabled, HIP events bracket every kernel stage of the next batches;
  * after excp_collect, excp_stage_ms returns the summed milliseconds and launches of stage `i`
  * (0 <= i < excp_stage_count()); excp_stage_name names it. */

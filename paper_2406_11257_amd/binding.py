@@ -78,6 +78,8 @@ SYMBOLS = {
                                      C.c_uint64, C.POINTER(C.c_uint64), C.c_void_p, C.POINTER(ExcpStats)]),
     "excp_decompress_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]),
+    "excp_decompress_step_static": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]),
     "excp_set_profiling": (C.c_int, [C.c_void_p, C.c_int]),
     "excp_set_param": (C.c_int, [C.c_void_p, C.c_int, C.c_uint64]),
     "excp_stage_count": (C.c_int, []),
@@ -168,6 +170,28 @@ def _wflags(*tensors) -> int:
         raise TypeError("the weight tensors of one item differ in type")
     kind = kinds.pop() if kinds else torch.float32
     return {torch.float32: 0, torch.float16: EXCP_FLAG_W_F16, torch.bfloat16: EXCP_FLAG_W_BF16}[kind]
+
+
+EXCP_STATIC_MAX_ELEMS = 1 << 28
+
+
+def excp_decompress_step_static(Wp, blob, blob_bytes, W_recon_out=None, m_out=None, v_out=None, stream=None, check=True):
+    """Alg. 2 for one tensor through the entry point that allocates nothing (no context)."""
+    import torch
+    device = Wp.device
+    _check_f32(Wp, "W_prev_recon", device)
+    n = Wp.numel()
+    for t, nm in ((W_recon_out, "W_recon_out"), (m_out, "m_out"), (v_out, "v_out")):
+        if t is not None:
+            _check_f32(t, nm, device)
+            if t.numel() != n:
+                raise ValueError(nm + " length differs")
+    st = torch.cuda.current_stream(device) if stream is None else stream
+    rc = lib().excp_decompress_step_static(device.index, C.c_void_p(st.cuda_stream), _ptr(Wp), _ptr(blob), blob_bytes, n,
+                                           _ptr(W_recon_out), _ptr(m_out), _ptr(v_out), _wflags(Wp, W_recon_out))
+    if check and rc != EXCP_OK:
+        raise ExcpError(rc, "excp_decompress_step_static")
+    return rc
 
 
 class PreparedBatch:

@@ -192,6 +192,7 @@ void launch_assign_pack(const Workspace &w, const GroupParams &g, hipStream_t s)
 void launch_finalize(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_from_compress(const Workspace &w, const GroupParams &g, hipStream_t s);
 void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s);
+void launch_decode_single_setup(const Workspace &w, const DDesc &d, hipStream_t s);
 void launch_decode_main16(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_decode_raw(const Workspace &w, u32 ntensors, u32 ntiles, bool moments, hipStream_t s);
 void launch_store_raw(const Workspace &w, const GroupParams &g, hipStream_t s);

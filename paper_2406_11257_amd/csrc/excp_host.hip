@@ -7,6 +7,7 @@
 
 #include <new>
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "../../include/excp.h"
@@ -225,6 +226,48 @@ int run_dense(excp_ctx *c, int count, bool exporting, Fill fill) {
     if (hipGetLastError() != hipSuccess) return enqueue_failed(c);
     c->pending = 2;
     c->pending_count = count;
+    return EXCP_OK;
+}
+
+// ---- Alg. 2 for one tensor without any allocation -------------------------------------------------
+// Everything the decoders keep between their kernels -- the descriptor and state of the tensor, its
+// two-entry tile table, the per-tile survivor counts of both bitmaps, the scan's part totals, the
+// result record -- lives in one file-scope device array instead of a context's workspace.  Every GPU
+// has its own copy of the array at its own address: the address is asked for once per device and kept.
+constexpr u64 kStaticMaxTiles = EXCP_STATIC_MAX_ELEMS / EXCP_TILE;
+struct StaticOffsets {
+    static constexpr u64 ddesc = 0, dst = 256, tile_begin = 512, dec_kinds = 768, rec = 1024, dec_part = 1280,
+                         cnt_w = 1536, cnt_o = cnt_w + 4 * (kStaticMaxTiles + 64), end = cnt_o + 4 * (kStaticMaxTiles + 64);
+};
+static_assert(sizeof(DDesc) <= 256 && sizeof(DState) <= 256 && sizeof(HostRec) <= 256, "scratch slots are 256 bytes");
+static_assert(StaticOffsets::cnt_w % 256 == 0 && StaticOffsets::cnt_o % 256 == 0, "tables start on 256-byte boundaries");
+constexpr u64 kScratchBytes = StaticOffsets::end;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+struct StaticDevice { unsigned char *ptr = nullptr; int cus = 0; bool ready = false; };
+StaticDevice g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+// The device's copy of `scratch` and its compute-unit count, looked up on the first call per device
+// (with that device current).  The array's name is only a handle on the host; kernels and copies are
+// given the address returned here.
+int static_device(int device, StaticDevice &out) {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticDevice &d = g_static[device];
+    if (!d.ready) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return EXCP_E_HIP;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, device) != hipSuccess || prop.multiProcessorCount <= 0) return EXCP_E_HIP;
+        d.ptr = (unsigned char *)p; d.cus = prop.multiProcessorCount; d.ready = true;
+    }
+    out = d;
     return EXCP_OK;
 }
 
@@ -833,6 +876,67 @@ int excp_decompress_step(excp_ctx *c, const void *W_prev_recon, const void *blob
     int rc = excp_decompress_tensors(c, 1, &b);
     if (rc != EXCP_OK) return rc;
     return excp_collect(c, nullptr);
+}
+
+int excp_decompress_step_static(int hip_device, void *hip_stream, const void *W_prev_recon, const void *blob,
+                                uint64_t blob_bytes, uint64_t n, void *W_recon_out, float *m_out, float *v_out,
+                                uint32_t flags) {
+    if ((flags & ~0x30u) || (flags & 0x30u) == 0x30u) return EXCP_E_ARG;
+    if (n > EXCP_STATIC_MAX_ELEMS) return EXCP_E_ARG;           // the static tables hold no more tiles than that
+    if (!blob || ((uintptr_t)blob & 15u) || (n && !W_prev_recon)) return EXCP_E_ARG;
+    if (hip_device < 0 || hip_device >= kMaxDevices) return EXCP_E_ARG;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || hip_device >= ndev) return EXCP_E_HIP;
+    if (hipSetDevice(hip_device) != hipSuccess) return EXCP_E_HIP;
+    StaticDevice sd;
+    int rc = static_device(hip_device, sd);
+    if (rc != EXCP_OK) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    Workspace w{};
+    w.ddesc = (DDesc *)(sd.ptr + StaticOffsets::ddesc);
+    w.dst = (DState *)(sd.ptr + StaticOffsets::dst);
+    w.tile_begin = (u32 *)(sd.ptr + StaticOffsets::tile_begin);
+    w.dec_kinds = (u32 *)(sd.ptr + StaticOffsets::dec_kinds);
+    w.rec_dev = (HostRec *)(sd.ptr + StaticOffsets::rec);
+    w.dec_part = (u64 *)(sd.ptr + StaticOffsets::dec_part);
+    w.dec_cnt_w = (u32 *)(sd.ptr + StaticOffsets::cnt_w);
+    w.dec_cnt_o = (u32 *)(sd.ptr + StaticOffsets::cnt_o);
+    w.rec_base = 0;
+    w.cus = sd.cus;
+
+    DDesc d{};
+    d.Wp = (const float *)W_prev_recon; d.blob = (const unsigned char *)blob; d.blob_bytes = blob_bytes; d.n = n;
+    d.W_out = (float *)W_recon_out; d.m_out = m_out; d.v_out = v_out;
+    d.cw = d.cm = d.cv = d.head = nullptr; d.wtype = (flags >> 4) & 3u; d.pad = 0;
+    d.tile_begin = 0; d.tile_count = (u32)((n + EXCP_TILE - 1) / EXCP_TILE);
+    const u32 ntiles = d.tile_count;
+    const bool moments = m_out != nullptr || v_out != nullptr;
+
+    // Nothing of the previous call is relied on: the descriptor, the tile table and the kinds word are
+    // written first, the state and every count of the tiles in use are written by the kernels before
+    // they are read, and the record is written last.
+    launch_decode_single_setup(w, d, s);
+    launch_decode_parse(w, 1, true, s);
+    launch_decode_count(w, 1, ntiles, 0, s);
+    launch_decode_scan(w, 1, 0, s);
+    if (moments) {
+        launch_decode_count(w, 1, ntiles, 1, s);
+        launch_decode_scan(w, 1, 1, s);
+    }
+    launch_decode_main(w, 1, ntiles, moments, s);
+    launch_decode_main16(w, 1, ntiles, moments, s);
+    launch_decode_raw(w, 1, ntiles, moments, s);
+    launch_decode_finish(w, 1, s);
+    if (hipGetLastError() != hipSuccess) { (void)hipStreamSynchronize(s); return EXCP_E_HIP; }
+    HostRec rec;
+    memset(&rec, 0, sizeof(rec));
+    if (hipMemcpyAsync(&rec, w.rec_dev, sizeof(HostRec), hipMemcpyDeviceToHost, s) != hipSuccess) {
+        (void)hipStreamSynchronize(s);
+        return EXCP_E_HIP;
+    }
+    if (hipStreamSynchronize(s) != hipSuccess) return EXCP_E_HIP;
+    return rec.status;
 }
 
 }  // extern "C"

@@ -847,7 +847,21 @@ __global__ void k_decode_counts_from_mask(Workspace w, u32 ntiles) {
     if (tile < ntiles) w.dec_cnt_w[tile] = (u32)(w.mask_prefix[2ull * tile] >> 32);
 }
 
+// The descriptor of a single-tensor call arrives as a kernel argument and is written into the tables
+// the decoders read (for callers that have no staging memory to copy it from).
+__global__ void k_decode_single_setup(Workspace w, DDesc d) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        w.ddesc[0] = d;
+        w.tile_begin[0] = 0u;
+        w.tile_begin[1] = d.tile_count;
+    }
+}
+
 }  // namespace
+
+void launch_decode_single_setup(const Workspace &w, const DDesc &d, hipStream_t s) {
+    hipLaunchKernelGGL(k_decode_single_setup, dim3(1), dim3(64), 0, s, w, d);
+}
 
 void launch_decode_parse(const Workspace &w, u32 ntensors, bool allow_raw, hipStream_t s) {
     if (!ntensors) return;
