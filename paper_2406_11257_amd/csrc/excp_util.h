@@ -67,6 +67,7 @@ __device__ __forceinline__ u32 find_owner(const u32 *__restrict__ begin, u32 cou
 // Pointers read from descriptor tables are generic to the compiler; these casts state that they
 // point to global memory, which turns flat loads/stores into global ones with immediate offsets.
 #define EXCP_GLOBAL __attribute__((address_space(1)))
+#define EXCP_CONSTANT __attribute__((address_space(4)))      // global memory that the kernel at hand only reads
 template <class T>
 __device__ __forceinline__ const EXCP_GLOBAL T *gptr(const T *p) { return (const EXCP_GLOBAL T *)(uintptr_t)p; }
 template <class T>

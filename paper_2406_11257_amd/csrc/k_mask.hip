@@ -2,208 +2,214 @@
 // the survivors.
 //
 // Pass A (k_mask_slots) reads W_prev, W_t, m and v once.  Work unit: a sub-tile of 2048 elements
-// (half a 4096-element tile): 4 waves x 8 batches of 64, so that one wave ballot is one word of the
-// keep bitmap.  It writes the keep bitmap, the sub-tile's survivor counts, and the survivors
-// themselves -- compacted in index order, together with their M_o bits -- into the sub-tile's own
-// slot of a scratch area.  No workgroup waits for another: where a survivor finally goes depends on
-// the counts of all earlier sub-tiles, and that is left to a scan (k_mask_scan, one workgroup per
-// tensor over its sub-tile counts) and to pass B (k_mask_gather), which copies every slot to its
-// place in the dense survivor arrays; k_mask_bitmap_o then assembles bitmap_o from the sub-tiles'
-// local bit streams.  The extra copy costs 8 bytes per survivor; it replaces a chained scan whose
-// waits cost more than that.
-#include <type_traits>
-
+// (half a 4096-element tile), owned by one wave, which writes the keep bitmap, the sub-tile's
+// survivor counts, and the survivors themselves -- in index order, together with their M_o bits --
+// into the sub-tile's own slot of a scratch area.  No wave waits for another: where a survivor
+// finally goes depends on the counts of all earlier sub-tiles, and that is left to a scan
+// (k_mask_scan over the sub-tile counts of every tensor) and to pass B (k_mask_gather), which copies
+// every slot to its place in the dense survivor arrays; k_mask_bitmap_o then assembles bitmap_o from
+// the sub-tiles' local bit streams.  The extra copy costs 8 bytes per survivor; it replaces a chained
+// scan whose waits cost more than that.
 #include "excp_util.h"
 
 namespace {
 
 constexpr u32 SUB = 2048;          // elements per sub-tile
-constexpr int NBATCH = 8;          // 64-element batches per wave and sub-tile
+constexpr u32 QUARTER = 512;       // elements a wave holds at once: 8 batches of 64
+constexpr int NBATCH = 8;          // 64-element batches per quarter
 constexpr u32 BO_WORDS = SUB / 64; // M_o words kept per sub-tile
 
+// The bits of one quarter as they arrive (weights as stored: fp32 bit patterns, or 16-bit values).
 struct Regs {
-    float w[NBATCH], p[NBATCH], m[NBATCH], v[NBATCH];
+    u32 w[NBATCH], p[NBATCH];
+    float m[NBATCH], v[NBATCH];
 };
 
-// sub-tile s of the group -> (tensor, first element); slots live in the partition arrays, which are
-// free until the codebook stage
-//
-// NW2M (Table "vit", no weights-to-momentum check): M_o(i) = |m_i| > r_o for every element, kept
-// weight or not.  The moment survivors are then compacted from the elements themselves, and the
-// sub-tile's M_o words are indexed by element.
-// W16: the two weight arrays hold 16-bit values (fp16 or bf16 by the flags), widened as they arrive.
-template <bool NW2M, bool W16>
-__global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, GroupParams g) {
-    __shared__ float l_w[SUB], l_m[SUB], l_v[SUB];      // compacted survivors of one sub-tile
-    __shared__ u32 s_w[4], s_o[4];
-    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u64 lt_mask = lanemask_lt();
-    const u32 nsub = 2u * g.ntiles;
-    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
+// What a wave needs to know about the sub-tile it works on (all of it the same in every lane).
+struct SubTile {
+    u64 n, base;                   // elements of the tensor; first element of the sub-tile inside it
+    float t_w, r_o;                // the tensor's thresholds
+    float T_keep, T_drop;          // t_w^2 with the estimate's guard band on either side
+    bool T_ok;                     // t_w^2 is a positive normal number: the estimate may be used at all
+    EXCP_GLOBAL float *sw, *sm, *sv;   // the sub-tile's slot in the three survivor areas
+    u64 *bm;                       // the tensor's keep bitmap (inside its blob)
+    u64 *bo;                       // the sub-tile's 32 local M_o words
+};
 
-    auto issue_loads = [&](u32 sub, Regs &R) {
-        if (sub >= nsub) return;
-        const u32 tile = sub >> 1;
-        const u32 t = find_owner(s_tiles, g.ntensors, tile);
-        const TDesc &D = w.desc[t];
-        const u64 n = D.n;
-        const u64 base = (u64)(tile - s_tiles[t]) * EXCP_TILE + (u64)(sub & 1u) * SUB;
-        const bool bf = W16 && excp_wtype(g.flags) == 2u;
-        if (base + SUB <= n) {
-            // full sub-tile: one address per array and lane, the batches are immediate offsets
-            const u64 first = base + (u64)(wave * (SUB / 4) + lane);
-            const EXCP_GLOBAL float *gW = gptr(D.W) + first, *gP = gptr(D.Wp) + first;
-            const EXCP_GLOBAL unsigned short *hW = gptr((const unsigned short *)D.W) + first;
-            const EXCP_GLOBAL unsigned short *hP = gptr((const unsigned short *)D.Wp) + first;
-            const EXCP_GLOBAL float *gM = gptr(D.m) + first, *gV = gptr(D.v) + first;
+// Loads of one quarter (512 elements starting at element `first` of the tensor) that lies wholly
+// inside the tensor: one base per array, the batches are immediate offsets.
+template <bool W16>
+__device__ __forceinline__ void load_quarter(Regs &R, const TDesc &D, u64 first, u32 lane) {
+    const EXCP_GLOBAL float *gM = gptr(D.m) + first, *gV = gptr(D.v) + first;
+    if (W16) {
+        const EXCP_GLOBAL unsigned short *hW = gptr((const unsigned short *)D.W) + first;
+        const EXCP_GLOBAL unsigned short *hP = gptr((const unsigned short *)D.Wp) + first;
 #pragma unroll
-            for (int j = 0; j < NBATCH; ++j) {
-                if (W16) { R.w[j] = w16_widen(hW[j * 64], bf); R.p[j] = w16_widen(hP[j * 64], bf); }
-                else { R.w[j] = gW[j * 64]; R.p[j] = gP[j * 64]; }
-                R.m[j] = gM[j * 64]; R.v[j] = gV[j * 64];
-            }
+        for (int j = 0; j < NBATCH; ++j) { R.w[j] = hW[j * 64 + lane]; R.p[j] = hP[j * 64 + lane]; }
+    } else {
+        const EXCP_GLOBAL u32 *gW = gptr((const u32 *)D.W) + first, *gP = gptr((const u32 *)D.Wp) + first;
+#pragma unroll
+        for (int j = 0; j < NBATCH; ++j) { R.w[j] = gW[j * 64 + lane]; R.p[j] = gP[j * 64 + lane]; }
+    }
+#pragma unroll
+    for (int j = 0; j < NBATCH; ++j) { R.m[j] = gM[j * 64 + lane]; R.v[j] = gV[j * 64 + lane]; }
+}
+
+// The same for a quarter of which only `rem` elements exist (a tensor's ragged end; rem may be 0).
+template <bool W16>
+__device__ __forceinline__ void load_quarter_ragged(Regs &R, const TDesc &D, u64 first, u32 rem, u32 lane) {
+#pragma unroll
+    for (int j = 0; j < NBATCH; ++j) {
+        const u32 e = (u32)j * 64u + lane;
+        const bool ok = e < rem;
+        const u64 idx = first + e;
+        R.w[j] = ok ? (W16 ? (u32)((const unsigned short *)D.W)[idx] : ((const u32 *)D.W)[idx]) : 0u;
+        R.p[j] = ok ? (W16 ? (u32)((const unsigned short *)D.Wp)[idx] : ((const u32 *)D.Wp)[idx]) : 0u;
+        R.m[j] = ok ? D.m[idx] : 0.f;
+        R.v[j] = ok ? D.v[idx] : 1.f;
+    }
+}
+
+// Quarter r (0..3) of a sub-tile: decisions, bitmap words, survivors to their ranks.  All lanes of the
+// wave are active throughout: every decision is first a wave-wide bit mask (the ballot of one
+// comparison), the masks are combined as 64-bit integers, and only the final masks become lane
+// predicates again.  rem = elements of the quarter that exist (FULL: all 512).
+// cw_run / co_run / nf_run: kept residuals, kept moments and non-finite v of the sub-tile so far.
+template <bool NW2M, bool W16, bool FULL>
+__device__ __forceinline__ void mask_quarter(const Regs &R, const SubTile &S, u32 r, u32 rem, u32 flags, u32 *my_bo,
+                                             u32 lane, u32 &cw_run, u32 &co_run, u32 &nf_run) {
+    const bool bf = W16 && excp_wtype(flags) == 2u;
+    u32 w_lo = 0, w_hi = 0, o_lo = 0, o_hi = 0;          // lane j: the j-th bitmap word of this quarter
+#pragma unroll
+    for (int j = 0; j < NBATCH; ++j) {
+        // lanes whose element exists (all of them, except at a tensor's ragged end)
+        const u32 left = FULL ? 64u : (rem > (u32)j * 64u ? rem - (u32)j * 64u : 0u);
+        const u64 valid = left >= 64u ? ~0ull : ((1ull << left) - 1ull);
+        const float wv = W16 ? w16_widen(R.w[j], bf) : u2f(R.w[j]);
+        const float pv = W16 ? w16_widen(R.p[j], bf) : u2f(R.p[j]);
+        const float d = wv - pv;                          // the residual
+        const float ad = fabsf(d), vv = R.v[j], mv = R.m[j];
+        u64 bw;
+        if (flags & 2u) {
+            bw = ballot64(ad > S.t_w);                    // ablation: the same scalar threshold for every element
         } else {
-#pragma unroll
-            for (int j = 0; j < NBATCH; ++j) {
-                const u64 idx = base + (u64)((wave * NBATCH + j) * 64 + lane);
-                const bool ok = idx < n;
-                R.w[j] = ok ? load_weight(D.W, idx, W16 ? excp_wtype(g.flags) : 0u) : 0.f;
-                R.p[j] = ok ? load_weight(D.Wp, idx, W16 ? excp_wtype(g.flags) : 0u) : 0.f;
-                R.m[j] = ok ? D.m[idx] : 0.f;
-                R.v[j] = ok ? D.v[idx] : 1.f;
-            }
-        }
-    };
-
-    auto compute = [&](u32 sub, Regs &R, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;
-        const u32 tile = sub >> 1;
-        const u32 t = find_owner(s_tiles, g.ntensors, tile);
-        const TDesc &D = w.desc[t];
-        const u64 n = D.n;
-        const u32 first_sub = 2u * s_tiles[t];
-        const u64 base = (u64)(sub - first_sub) * SUB;
-        const float t_w = w.st[t].t_w, r_o = w.st[t].r_o;
-        const u32 rem = FULL ? SUB : (u32)(n > base ? n - base : 0);      // valid elements here
-        u64 bw[NBATCH];
-        u32 nf = 0, cw = 0;
-#pragma unroll
-        for (int j = 0; j < NBATCH; ++j) {
-            const u32 e = (wave * NBATCH + j) * 64 + lane;
-            const bool ok = FULL || e < rem;
-            R.w[j] = R.w[j] - R.p[j];                     // the residual
-            // |d| > t_w / sqrt(v) with correctly rounded sqrt and divide, decided by a cheap estimate
-            // when the estimate is not within 1e-5 of |d| (its own error is below 1e-6) and by the
-            // exact expression otherwise, so the result is always that of the exact expression.
-            // The estimate is trusted only for positive normal v and a positive normal estimate.
-            const float ad = fabsf(R.w[j]);
-            const float ra = t_w * __builtin_amdgcn_rsqf(R.v[j]);
-            const bool sure_keep = ad > ra * 1.00001f, sure_drop = ad < ra * 0.99999f;
-            const bool amb = !(sure_keep || sure_drop) || !__builtin_amdgcn_classf(R.v[j], 0x100) ||
-                             !__builtin_amdgcn_classf(ra, 0x100);
-            bool kw = sure_keep;
-            if (g.flags & 2u) {
-                kw = ad > t_w;                            // ablation: the same scalar threshold for every element
-            } else if (__any(amb)) {
+            // (d^2 may underflow where d^2 v does not: every factor and product must be a positive normal number)
+            const float dd = ad * ad, x = dd * vv;
+            const u64 b_keep = ballot64(x > S.T_keep), b_drop = ballot64(x < S.T_drop);
+            const u64 b_trust = ballot64(__builtin_amdgcn_classf(vv, 0x100)) & ballot64(__builtin_amdgcn_classf(dd, 0x100)) &
+                                ballot64(__builtin_amdgcn_classf(x, 0x100));
+            const u64 amb = S.T_ok ? (~(b_keep | b_drop) | ~b_trust) : ~0ull;
+            bw = b_keep;
+            if (amb & valid) {
                 // sqrtf and '/' are the correctly rounded forms (the build passes
                 // -fhip-fp32-correctly-rounded-divide-sqrt); __fsqrt_rn is NOT on this target
-                if (amb) kw = ad > t_w / sqrtf(R.v[j]);
+                const u64 b_exact = ballot64(ad > S.t_w / sqrtf(vv));
+                bw = (b_keep & ~amb) | (b_exact & amb);
             }
-            kw = ok && kw;
-            nf += ((f2u(R.v[j]) & 0x7f800000u) == 0x7f800000u);
-            bw[j] = ballot64(kw);
-            cw += __popcll(bw[j]);
         }
-        // keep bitmap of the residual: one ballot per 64 elements
-        {
-            u64 *bm = (u64 *)(D.blob + EXCP_HEADER + excp_books_bytes((u32)g.nbits));
-            const u64 nwords = excp_words(n);
-            u64 mine = 0;
-#pragma unroll
-            for (int j = 0; j < NBATCH; ++j) if (lane == (u32)j) mine = bw[j];
-            const u64 word = (base >> 6) + wave * NBATCH + lane;
-            // words past the last element carry an all-zero ballot: that is the 16-byte padding
-            if (lane < NBATCH && word < nwords + (nwords & 1ull)) bm[word] = mine;
+        bw &= valid;
+        nf_run += (u32)__popcll(ballot64((f2u(vv) & 0x7f800000u) == 0x7f800000u) & valid);
+        const u64 bo = ballot64(fabsf(mv) > S.r_o) & (NW2M ? valid : bw);
+        if (lane == (u32)j) { w_lo = (u32)bw; w_hi = (u32)(bw >> 32); }
+        const u32 rk = cw_run + __builtin_amdgcn_mbcnt_hi((u32)(bw >> 32), __builtin_amdgcn_mbcnt_lo((u32)bw, 0u));
+        if (__builtin_amdgcn_inverse_ballot_w64(bw)) S.sw[rk] = d;
+        if (__builtin_amdgcn_inverse_ballot_w64(bo)) {
+            const u32 ro = co_run + __builtin_amdgcn_mbcnt_hi((u32)(bo >> 32), __builtin_amdgcn_mbcnt_lo((u32)bo, 0u));
+            S.sm[ro] = mv; S.sv[ro] = vv;
+            if (!NW2M) atomicOr(&my_bo[rk >> 5], 1u << (rk & 31u));
         }
-        nf = wave_sum_u32(nf);
-        if (lane == 0) {
-            s_w[wave] = cw;
-            if (nf) atomicAdd(&w.st[t].nonfinite, (u64)nf);
-        }
-        __syncthreads();
-        const u32 tw = s_w[0] + s_w[1] + s_w[2] + s_w[3];
-        // compact the residual survivors (index order) in LDS, each with its M_o flag
-        u32 pw = 0;
-        for (u32 q = 0; q < wave; ++q) pw += s_w[q];
-#pragma unroll
-        for (int j = 0; j < NBATCH; ++j) {
-            const u64 mw = bw[j];
-            const bool kw = (mw >> lane) & 1ull;
-            const u32 rk = pw + __popcll(mw & lt_mask);
-            if (kw) {
-                l_w[rk] = R.w[j];
-                if (!NW2M) { l_m[rk] = R.m[j]; l_v[rk] = R.v[j]; }
-            }
-            pw += __popcll(mw);
-        }
-        __syncthreads();
-        // second compaction, over the survivors: those whose moments are kept (M_o).  Survivor p
-        // is handled by thread p % 256; a ballot over 64 consecutive survivors is one M_o word.
-        const u64 slot = D.elem_off + base;
-        EXCP_GLOBAL float *sw = gptr(w.pw) + slot, *sm = gptr(w.pm) + slot, *sv = gptr(w.pv) + slot;
-        float mm[NBATCH], vv2[NBATCH]; u64 bo[NBATCH]; u32 co = 0;
-#pragma unroll
-        for (int j = 0; j < NBATCH; ++j) {
-            const u32 p = (wave * NBATCH + j) * 64 + lane;       // survivor position in the sub-tile
-            const bool in = p < tw;
-            if (in) sw[p] = l_w[p];
-            if (NW2M) {
-                // p is also this lane's element of batch j
-                mm[j] = R.m[j]; vv2[j] = R.v[j];
-                bo[j] = ballot64((FULL || p < rem) && fabsf(mm[j]) > r_o);
-            } else {
-                mm[j] = in ? l_m[p] : 0.f;
-                vv2[j] = in ? l_v[p] : 0.f;
-                bo[j] = ballot64(in && fabsf(mm[j]) > r_o);
-            }
-            co += __popcll(bo[j]);
-        }
-        if (lane < NBATCH) {
-            u64 mine = 0;
-#pragma unroll
-            for (int j = 0; j < NBATCH; ++j) if (lane == (u32)j) mine = bo[j];
-            const u32 wordi = wave * NBATCH + lane;
-            if (NW2M || wordi < ((tw + 63u) >> 6)) w.mask_bo[(u64)sub * BO_WORDS + wordi] = mine;
-        }
-        if (lane == 0) s_o[wave] = co;
-        __syncthreads();
-        const u32 to = s_o[0] + s_o[1] + s_o[2] + s_o[3];
-        if (tid == 0) w.tile_status[sub] = ((u64)tw << 32) | (u64)to;
-        u32 po = 0;
-        for (u32 q = 0; q < wave; ++q) po += s_o[q];
-#pragma unroll
-        for (int j = 0; j < NBATCH; ++j) {
-            const u64 mo = bo[j];
-            if ((mo >> lane) & 1ull) {
-                const u32 ro = po + __popcll(mo & lt_mask);
-                sm[ro] = mm[j]; sv[ro] = vv2[j];
-            }
-            po += __popcll(mo);
-        }
-        __syncthreads();
-    };
+        if (NW2M && lane == (u32)j) { o_lo = (u32)bo; o_hi = (u32)(bo >> 32); }
+        cw_run += (u32)__popcll(bw);
+        co_run += (u32)__popcll(bo);
+    }
+    // the quarter's eight words of the keep bitmap; words past the last element carry an all-zero
+    // ballot: that is the section's 16-byte padding
+    const u64 nwords = excp_words(S.n), word = ((S.base + (u64)r * QUARTER) >> 6) + lane;
+    if (lane < (u32)NBATCH && (FULL || word < nwords + (nwords & 1ull))) S.bm[word] = (u64)w_lo | ((u64)w_hi << 32);
+    if (NW2M && lane < (u32)NBATCH) S.bo[r * NBATCH + lane] = (u64)o_lo | ((u64)o_hi << 32);
+}
 
-    auto sub_is_full = [&](u32 sub) -> bool {
-        const u32 tile = sub >> 1;
-        const u32 t = find_owner(s_tiles, g.ntensors, tile);
-        const u64 base = (u64)(tile - s_tiles[t]) * EXCP_TILE + (u64)(sub & 1u) * SUB;
-        return base + SUB <= w.desc[t].n;
-    };
-    Regs A;
-    for (u32 sub = blockIdx.x; sub < nsub; sub += gridDim.x) {
-        issue_loads(sub, A);
-        if (sub_is_full(sub)) compute(sub, A, std::true_type{}); else compute(sub, A, std::false_type{});
+// Pass A.  A wave owns whole sub-tiles (a contiguous range of the group's sub-tile list) and walks each
+// in four quarters of 512 elements; lane l of batch j holds element 64 j + l, so a wave ballot is one
+// word of a bitmap.  Nothing is shared between waves: no barrier after the tile table is loaded.
+// While one quarter is worked on the next is already on its way from memory (two register sets).
+//
+// Per element: the residual; the keep decision |d| > t_w / sqrt(v) with correctly rounded sqrt and
+// divide -- taken from the estimate d^2 v against t_w^2 when that is not within 1e-5 of the boundary
+// (the estimate's own error is below 3e-7) and from the exact expression otherwise, so it is always
+// that of the exact expression; the M_o decision.  Survivors go straight to their rank in the
+// sub-tile's slot (ballot + lane count); the M_o bit of a kept residual is ORed into the wave's own
+// LDS words at the residual's rank.
+//
+// NW2M (Table "vit", no weights-to-momentum check): M_o(i) = |m_i| > r_o for every element, kept
+// weight or not; the sub-tile's M_o words are then indexed by element and are the ballots themselves.
+// W16: the two weight arrays hold 16-bit values (fp16 or bf16 by the flags), widened as they are used.
+template <bool NW2M, bool W16>
+__global__ __launch_bounds__(EXCP_THREADS, 5) void k_mask_slots(Workspace w, GroupParams g) {
+    __shared__ u32 s_bo[EXCP_THREADS / 64][SUB / 32];      // per wave: M_o bits of its sub-tile's kept residuals, by rank
+    __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
+    const u32 lane = threadIdx.x & 63u;
+    const u32 wave = (u32)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const u32 nsub = 2u * g.ntiles;
+    load_tile_table(s_tiles, w.tile_begin, g.ntensors);
+    const u32 nwaves = gridDim.x * (EXCP_THREADS / 64), wid = blockIdx.x * (EXCP_THREADS / 64) + wave;
+    const u32 sub_lo = (u32)(((u64)wid * nsub) / nwaves), sub_hi = (u32)(((u64)(wid + 1u) * nsub) / nwaves);
+    if (sub_lo >= sub_hi) return;
+    u32 *my_bo = s_bo[wave];
+    my_bo[lane] = 0u;
+    u32 t = 0, first_sub = 0, end_sub = 0;                // the tensor in hand, its first sub-tile, one past its last
+    Regs A, B;
+    for (u32 sub = sub_lo; sub < sub_hi; ++sub) {
+        if (sub >= end_sub) {                             // (looked up again only when a tensor's sub-tiles run out)
+            t = (u32)__builtin_amdgcn_readfirstlane((int)find_owner(s_tiles, g.ntensors, sub >> 1));
+            first_sub = (u32)__builtin_amdgcn_readfirstlane((int)(2u * s_tiles[t]));
+            end_sub = (u32)__builtin_amdgcn_readfirstlane((int)(2u * s_tiles[t + 1u]));
+        }
+        // The tensor's description and thresholds are not written by this kernel: read as constant
+        // memory they come through the scalar unit, which global memory that the kernel also
+        // stores to may not.
+        const EXCP_CONSTANT TDesc *Dc = (const EXCP_CONSTANT TDesc *)(uintptr_t)(w.desc + t);
+        const EXCP_CONSTANT TState *St = (const EXCP_CONSTANT TState *)(uintptr_t)(w.st + t);
+        TDesc D;
+        D.Wp = Dc->Wp; D.W = Dc->W; D.m = Dc->m; D.v = Dc->v; D.n = Dc->n; D.blob = Dc->blob; D.elem_off = Dc->elem_off;
+        SubTile S;
+        S.n = D.n; S.base = (u64)(sub - first_sub) * SUB;
+        S.t_w = St->t_w; S.r_o = St->r_o;
+        const float T = S.t_w * S.t_w;
+        S.T_keep = T * 1.00001f; S.T_drop = T * 0.99999f; S.T_ok = __builtin_amdgcn_classf(T, 0x100);
+        const u64 slot = D.elem_off + S.base;
+        S.sw = gptr(w.pw) + slot; S.sm = gptr(w.pm) + slot; S.sv = gptr(w.pv) + slot;
+        S.bm = (u64 *)(D.blob + EXCP_HEADER + excp_books_bytes((u32)g.nbits));
+        S.bo = w.mask_bo + (u64)sub * BO_WORDS;
+        u32 cw_run = 0, co_run = 0, nf_run = 0;
+        if (S.base + SUB <= S.n) {
+            load_quarter<W16>(A, D, S.base, lane);
+            load_quarter<W16>(B, D, S.base + QUARTER, lane);
+            mask_quarter<NW2M, W16, true>(A, S, 0u, QUARTER, g.flags, my_bo, lane, cw_run, co_run, nf_run);
+            load_quarter<W16>(A, D, S.base + 2u * QUARTER, lane);
+            mask_quarter<NW2M, W16, true>(B, S, 1u, QUARTER, g.flags, my_bo, lane, cw_run, co_run, nf_run);
+            load_quarter<W16>(B, D, S.base + 3u * QUARTER, lane);
+            mask_quarter<NW2M, W16, true>(A, S, 2u, QUARTER, g.flags, my_bo, lane, cw_run, co_run, nf_run);
+            mask_quarter<NW2M, W16, true>(B, S, 3u, QUARTER, g.flags, my_bo, lane, cw_run, co_run, nf_run);
+        } else {
+#pragma unroll 1
+            for (u32 r = 0; r < 4u; ++r) {
+                const u64 first = S.base + (u64)r * QUARTER;
+                const u32 rem = S.n > first ? (S.n - first < (u64)QUARTER ? (u32)(S.n - first) : QUARTER) : 0u;
+                load_quarter_ragged<W16>(A, D, first, rem, lane);
+                mask_quarter<NW2M, W16, false>(A, S, r, rem, g.flags, my_bo, lane, cw_run, co_run, nf_run);
+            }
+        }
+        // the sub-tile is complete: its M_o words (by survivor rank) and its counts
+        if (!NW2M) {
+            const u64 word = (u64)my_bo[2u * (lane & 31u)] | ((u64)my_bo[2u * (lane & 31u) + 1u] << 32);
+            if (lane < ((cw_run + 63u) >> 6)) S.bo[lane] = word;
+            my_bo[lane] = 0u;
+        }
+        if (lane == 0u) {
+            w.tile_status[sub] = ((u64)cw_run << 32) | (u64)co_run;
+            if (nf_run) atomicAdd(&w.st[t].nonfinite, (u64)nf_run);
+        }
     }
 }
 
