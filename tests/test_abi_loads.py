@@ -49,3 +49,26 @@ def test_argument_errors_need_no_gpu():
     assert L.excp_compress_tensors(None, 0, None, 5e-5, 2.0, 4, 10, 0) == X.EXCP_E_ARG
     assert L.excp_create(None, 0, None, 1, 1) == X.EXCP_E_ARG
     assert L.excp_reconstruct_chain(None, 0, None) == X.EXCP_E_ARG
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library is built once more with its HOST code under AddressSanitizer and UBSan (the device
+    code as always), and a small C program walks every host path that needs no GPU work -- size
+    functions, names, argument and call-order checks of every entry point -- against it.  Any
+    sanitizer report, or a failed check, fails the test."""
+    import subprocess
+    from paper_2406_11257_amd import build
+    srcs = [os.path.join(build.CSRC, f) for f in os.listdir(build.CSRC)] + [os.path.join(ROOT, "include", "excp.h")]
+    if not os.path.exists(build.LIB_SAN) or os.path.getmtime(build.LIB_SAN) < max(os.path.getmtime(s) for s in srcs):
+        build.build_library(verbose=False, host_sanitizers=True)
+    clang = os.path.join(os.path.dirname(os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")), "..", "llvm", "bin", "clang")
+    exe = str(tmp_path / "abi_host_check")
+    pkg = os.path.dirname(build.LIB_SAN)
+    subprocess.run([clang, "-fsanitize=address,undefined", "-fno-omit-frame-pointer", "-g",
+                    os.path.join(ROOT, "tests", "abi_host_check.c"), "-L" + pkg, "-lexcp_hostsan",
+                    "-Wl,-rpath," + pkg, "-o", exe], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1",
+               HIP_VISIBLE_DEVICES="", ROCR_VISIBLE_DEVICES="")     # host paths only: no device is touched
+    r = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip().endswith("ok"), r.stdout + r.stderr
+    assert "Sanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr
