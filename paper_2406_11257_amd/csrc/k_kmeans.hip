@@ -1217,7 +1217,7 @@ void launch_km_classify(const Workspace &w, const GroupParams &g, int iteration,
 
 void launch_km_iter(const Workspace &w, const GroupParams &g, int iteration, hipStream_t s) {
     if (!g.ntensors) return;
-    hipLaunchKernelGGL(k_km_iter, dim3(excp_grid(w, 10)), dim3(EXCP_THREADS), 0, s, w, g, (u32)(iteration & 1));
+    hipLaunchKernelGGL(k_km_iter, dim3(excp_grid(w, 20)), dim3(EXCP_THREADS), 0, s, w, g, (u32)(iteration & 1));
 }
 
 void launch_km_update(const Workspace &w, const GroupParams &g, hipStream_t s) {
