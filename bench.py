@@ -352,6 +352,8 @@ def main():
     if cid == 3 and args.weights == "f32":
         del dec, chains
         others = other_configs(ctx, wl, params, traffic)
+        # (the 16-bit runs wrote their blobs where the fp32 ones were: one untimed step puts those back)
+        _, stats, _ = time_compress(ctx, wl, params, 1, 0, False)
 
     # ---- Alg. 2 with all three outputs (overwrites the m and v inputs: nothing needs them any more) ----
     dec3 = ctx.prepare_decompress([(wl.view(0, i), tensors[i][4], int(stats[i].blob_bytes), spec.n,
