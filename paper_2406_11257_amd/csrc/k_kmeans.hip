@@ -13,9 +13,11 @@
 // The same buckets give the initial centres (order statistics of rank ((2k+1) len)/(2K)) with a
 // radix select inside one bucket per rank.
 //
-// All sums are exact: a value is mant * 2^(pos-149); mantissas are added as integers in windows of
-// 40 binary orders and filed into signed 64-bit bins 8 binary orders apart (the representation of
-// the exact sum of |m| in the statistics pass, here with sign).  A centre is therefore
+// All sums are exact: a value is mant * 2^(pos-149); values that are neighbours in magnitude (inside
+// a window of 24 binary orders) are whole multiples of one unit, small enough that sixteen of them add
+// exactly in fp64; those partial sums go on as integers and end in signed 64-bit bins 8 binary orders
+// apart (the representation of the exact sum of |m| in the statistics pass, here with sign); a value
+// outside the window is filed into the bins by itself.  A centre is therefore
 // fp32(round-once-fp64(exact sum) / count), independent of the order in which values were met, so
 // integer atomics may be used freely and the partition need not be stable.
 //
@@ -113,6 +115,40 @@ __device__ __forceinline__ void wave_exact_add(const float (&x)[N], const bool (
             }
         }
     }
+}
+
+// Adds v * 2^(bitpos - 149) to a set of signed bins (bin g has weight 2^(8g - 149)), with integer atomics.
+__device__ __forceinline__ void file_i64(u64 *bins, long long v, u32 bitpos) {
+    const bool neg = v < 0;
+    const u64 mag = neg ? (u64)0 - (u64)v : (u64)v;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const u64 piece = (mag >> (32 * q)) & 0xffffffffull;
+        const u32 p = bitpos + 32u * q;
+        const u64 d = piece << (p & 7u);
+        if (piece) atomicAdd(&bins[p >> 3], neg ? (u64)0 - d : d);
+    }
+}
+
+// Exact summation of values that are neighbours in magnitude.  A value inside the window of 24 bit
+// positions [B, B + 24) is a whole multiple of the unit 2^(B-149) below 2^47 units, so up to sixteen of
+// them add exactly in fp64, whatever their signs; such a partial sum is then split into two integers
+// -- units below 2^32, and signed multiples of 2^32 units -- that go on in 64-bit integer counters.
+struct WindowSum {
+    double part = 0.0;             // at most sixteen values since the last fold
+    long long lo = 0, hi = 0;      // sum = (lo + 2^32 hi) units
+    __device__ __forceinline__ void fold(u32 B) {
+        const double units = ldexp(part, 149 - (int)B);                  // an integer, |units| < 2^51
+        const double h = floor(units * 2.3283064365386963e-10);          // floor(units / 2^32), |h| < 2^19
+        lo += (long long)(u32)(units - h * 4294967296.0);
+        hi += (long long)(int)h;
+        part = 0.0;
+    }
+};
+// magnitudes (bit patterns without the sign) inside the window: lo <= pattern < lo + span
+__device__ __forceinline__ void window_range(u32 B, u32 &lo, u32 &span) {
+    lo = B ? ((B + 1u) << 23) : 0u;
+    span = ((B + 25u) << 23) - lo;
 }
 
 // Signed bins -> the exact sum rounded once (to nearest, ties to even) to fp64.
@@ -482,10 +518,10 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
 // ---------------------------------------------------------------- P4: exact totals per bucket
 // One workgroup per four buckets of a stream (per bucket in the sixteen-wave form); its waves share every bucket,
 // so that one very large bucket (tied values) does not leave a single wave working alone.  Values of a bucket
-// are neighbours in value, hence in exponent: a window of 40 bit positions placed from the first
-// values met holds practically all of them; inside it a lane adds shifted mantissas as integers
-// (low and high 32-bit halves in separate 64-bit counters, magnitudes of all values and of the
-// negative ones) with no cross-lane traffic; the rest (rare) is filed one by one.
+// are neighbours in value, hence in exponent: a window of 24 bit positions placed from the first
+// values met holds practically all of them; inside it a lane adds sixteen values at a time exactly in
+// fp64 and keeps the running total in two integer counters, with no cross-lane traffic; the rest
+// (rare) is filed one by one.
 // (sixteen for 16-bit weights, whose residuals are heavily tied, and for groups with a tensor so large
 // that its buckets alone are millions of values; four otherwise, which is faster when the buckets are
 // small and even)
@@ -526,37 +562,36 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
             const u32 e = mb >> 23;
             pm = wave_max_u32((e ? e : 1u) - 1u);
         }
-        const u32 B = pm + 4u > 39u ? pm + 4u - 39u : 0u;
-        u64 aL = 0, aH = 0, nL = 0, nH = 0;
+        const u32 B = pm + 4u > 23u ? pm + 4u - 23u : 0u;
+        u32 thr_lo, span;
+        window_range(B, thr_lo, span);
+        WindowSum S;
         u32 kmin = 0xffffffffu, kmax = 0;
         // Tied data (the sixteen-wave form): a large bucket is mostly one value.  The wave takes its
         // first value as that one and only counts its repetitions; count times value joins the sums
         // at the end.
         u32 dom = 0xffffffffu, ndom = 0;                   // bit pattern of the repeated value; this lane's count
         if (BS_WAVES == 16u) {
-            const u32 first = f2u(part[p0]), fe = (first & 0x7fffffffu) >> 23;
-            if (((fe ? fe : 1u) - 1u) - B < 40u && (first & 0x7fffffffu)) dom = first;     // inside the window, not zero
+            const u32 head = f2u(part[p0]);
+            if ((head & 0x7fffffffu) - thr_lo < span && (head & 0x7fffffffu)) dom = head;     // inside the window, not zero
         }
         auto take = [&](float xv) {
-            const u32 u = f2u(xv), mb = u & 0x7fffffffu, e = mb >> 23;
+            const u32 u = f2u(xv), mb = u & 0x7fffffffu;
             if (BS_WAVES == 16u && u == dom) { ++ndom; return; }
             const u32 k = key_of(xv);
             kmin = min(kmin, k); kmax = max(kmax, k);
-            const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
-            const u32 pos = (e ? e : 1u) - 1u;
-            const bool neg = u >> 31;
-            if (pos - B < 40u) {
-                const u64 term = (u64)mant << (pos - B);
-                const u32 tl = (u32)term, th = (u32)(term >> 32);
-                aL += tl; aH += th;
-                nL += neg ? tl : 0u; nH += neg ? th : 0u;
-            } else if (mant) {
+            if (mb - thr_lo < span) {
+                S.part += (double)xv;
+            } else if (mb) {
+                const u32 e = mb >> 23;
+                const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+                const u32 pos = (e ? e : 1u) - 1u;
                 const u64 d = (u64)mant << (pos & 7u);
-                atomicAdd(&mybins[pos >> 3], neg ? (u64)0 - d : d);
+                atomicAdd(&mybins[pos >> 3], (u >> 31) ? (u64)0 - d : d);
             }
         };
         // four 16-byte loads in flight per lane: the share of a wave in a large bucket is a chain of
-        // round trips otherwise
+        // round trips otherwise.  Sixteen values per round: one fold of the fp64 partial sum.
         u32 p = p0;
         for (; p + 1024u <= p1; p += 1024u) {
             f4u q[4];
@@ -564,8 +599,9 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
             for (u32 r = 0; r < 4; ++r) q[r] = *(const EXCP_GLOBAL f4u *)(part + p + r * 256u + lane * 4u);
 #pragma unroll
             for (u32 r = 0; r < 4; ++r) { take(q[r].x); take(q[r].y); take(q[r].z); take(q[r].w); }
+            S.fold(B);
         }
-        for (; p < p1; p += 256u) {
+        for (; p < p1; p += 256u) {                       // (at most four rounds of four values)
             const u32 i = p + lane * 4u;
             if (p + 256u <= p1) {
                 const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
@@ -575,19 +611,17 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
                 for (u32 e = 0; e < 4; ++e) if (i + e < p1) take(part[i + e]);
             }
         }
+        S.fold(B);
         if (BS_WAVES == 16u && ndom) {
             const u32 mb = dom & 0x7fffffffu, e = mb >> 23;
             const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
-            const u64 term = (u64)mant << (((e ? e : 1u) - 1u) - B);
-            const u64 tl = (term & 0xffffffffull) * ndom, th = (term >> 32) * ndom;      // a lane sees < 2^20 values
-            aL += tl; aH += th;
-            if (dom >> 31) { nL += tl; nH += th; }
+            const u64 term = (u64)mant << (((e ? e : 1u) - 1u) - B);                      // below 2^47 units
+            const long long tl = (long long)((term & 0xffffffffull) * ndom), th = (long long)((term >> 32) * ndom);   // a lane sees < 2^20 values
+            if (dom >> 31) { S.lo -= tl; S.hi -= th; } else { S.lo += tl; S.hi += th; }
             const u32 k = key_of(u2f(dom));
             kmin = min(kmin, k); kmax = max(kmax, k);
         }
-        // wave totals: magnitudes of all values (+) and twice those of the negative ones (-)
-        aL = wave_sum_u64(aL); aH = wave_sum_u64(aH);
-        nL = wave_sum_u64(nL); nH = wave_sum_u64(nH);
+        const long long tL = (long long)wave_sum_u64((u64)S.lo), tH = (long long)wave_sum_u64((u64)S.hi);
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) {
             kmin = min(kmin, (u32)__shfl_xor(kmin, m, WAVE));
@@ -595,19 +629,7 @@ __global__ __launch_bounds__(BS_WAVES * 64) void k_km_bucket_stats(Workspace w, 
         }
         if (lane == 0) {
             atomicMin(&s_min[j], kmin); atomicMax(&s_max[j], kmax);
-#pragma unroll
-            for (int sgn = 0; sgn < 2; ++sgn) {
-                const u64 L = sgn ? nL : aL, H = sgn ? nH : aH;
-                const u64 lo64 = L + (H << 32);
-                const u64 hi64 = (H >> 32) + (lo64 < L ? 1ull : 0ull);
-                const u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
-#pragma unroll
-                for (int q = 0; q < 3; ++q) {
-                    const u32 p = B + 32u * q;
-                    const u64 d = piece[q] << (p & 7u);
-                    if (piece[q]) atomicAdd(&mybins[p >> 3], sgn ? (u64)0 - 2ull * d : d);
-                }
-            }
+            file_i64(mybins, tL, B); file_i64(mybins, tH, B + 32u);
         }
     }
     __syncthreads();
@@ -875,8 +897,13 @@ __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupP
         const u32 c_lo = I.range & 255u, c_hi = I.range >> 8;
         u64 *acc = w.km_acc + (u64)I.sidx * EXCP_MAX_K * (EXCP_ABSM_BINS + 1);
         if (c_hi - c_lo <= 2u) {
-            // ---- one or two borders inside the item (the usual case): per-lane integer totals of
-            // all values and of the values at or above each border; cluster totals are differences.
+            // ---- one or two borders inside the item (the usual case): per-lane totals of all values and
+            // of the values at or above each border; cluster totals are differences.
+            // A value inside the window of 24 bit positions [B, B + 24) is a whole multiple of the unit
+            // 2^(B-149) below 2^47 units, so a lane adds sixteen of them (one round of loads) exactly in
+            // fp64, whatever their signs; the round's sum is then split into two integers (units below
+            // 2^32, and signed multiples of 2^32) that go on in integer counters.  Values outside the
+            // window (rare: a bucket's values are neighbours) are filed one by one.
             const u32 cut1 = w.seg[I.sidx].cut[c_lo + 1];
             const u32 cut2 = (c_hi - c_lo == 2u) ? w.seg[I.sidx].cut[c_lo + 2] : 0xffffffffu;
             const EXCP_GLOBAL float *part = gptr(seg_part(w, I.sidx));
@@ -890,32 +917,29 @@ __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupP
                 const u32 e = mb >> 23;
                 pm = wave_max_u32((e ? e : 1u) - 1u);
             }
-            const u32 B = pm + 4u > 39u ? pm + 4u - 39u : 0u;
-            // [0] all values, [1] values at or above border 1, [2] at or above border 2;
-            // a = magnitudes, n = magnitudes of the negative ones
-            u64 aL[3] = {0, 0, 0}, aH[3] = {0, 0, 0}, nL[3] = {0, 0, 0}, nH[3] = {0, 0, 0};
+            const u32 B = pm + 4u > 23u ? pm + 4u - 23u : 0u;       // the window's top: 4 binary orders above the first values
+            u32 thr_lo, span;
+            window_range(B, thr_lo, span);
+            WindowSum S[3];                                // [0] all values, [1] values at or above border 1, [2] at or above border 2
             u32 cnt1 = 0, cnt2 = 0;
             auto take = [&](float xv) {
-                const u32 u = f2u(xv), mb = u & 0x7fffffffu, e = mb >> 23;
+                const u32 u = f2u(xv), mb = u & 0x7fffffffu;
                 const u32 key = key_of(xv);
-                const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
-                const u32 pos = (e ? e : 1u) - 1u;
-                const bool neg = u >> 31;
                 const bool up1 = key >= cut1, up2 = key >= cut2;
                 cnt1 += up1; cnt2 += up2;
-                if (pos - B < 40u) {
-                    const u64 term = (u64)mant << (pos - B);
-                    const u32 tl = (u32)term, th = (u32)(term >> 32);
-                    const u32 ntl = neg ? tl : 0u, nth = neg ? th : 0u;
-                    aL[0] += tl; aH[0] += th; nL[0] += ntl; nH[0] += nth;
-                    aL[1] += up1 ? tl : 0u; aH[1] += up1 ? th : 0u; nL[1] += up1 ? ntl : 0u; nH[1] += up1 ? nth : 0u;
-                    aL[2] += up2 ? tl : 0u; aH[2] += up2 ? th : 0u; nL[2] += up2 ? ntl : 0u; nH[2] += up2 ? nth : 0u;
-                } else if (mant) {
-                    const u64 d = (u64)mant << (pos & 7u);
+                if (mb - thr_lo < span) {
+                    const double xd = (double)xv;
+                    S[0].part += xd; S[1].part += up1 ? xd : 0.0; S[2].part += up2 ? xd : 0.0;
+                } else if (mb) {
+                    const u32 e = mb >> 23;
+                    const u32 mant = (mb & 0x7fffffu) | (e ? 0x800000u : 0u);
+                    const u32 pos = (e ? e : 1u) - 1u;
+                    const u64 dd = (u64)mant << (pos & 7u);
                     const u32 cl = c_lo + (up1 ? 1u : 0u) + (up2 ? 1u : 0u);
-                    atomicAdd(&acc[(u64)cl * (EXCP_ABSM_BINS + 1) + (pos >> 3)], neg ? (u64)0 - d : d);
+                    atomicAdd(&acc[(u64)cl * (EXCP_ABSM_BINS + 1) + (pos >> 3)], (u >> 31) ? (u64)0 - dd : dd);
                 }
             };
+            auto flush = [&]() { S[0].fold(B); S[1].fold(B); S[2].fold(B); };     // after at most sixteen values
             // four 16-byte loads in flight per lane
             constexpr u32 LOADS = 4;
             u32 p = p0;
@@ -925,8 +949,9 @@ __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupP
                 for (u32 j = 0; j < LOADS; ++j) q[j] = *(const EXCP_GLOBAL f4u *)(part + p + j * 256u + lane * 4u);
 #pragma unroll
                 for (u32 j = 0; j < LOADS; ++j) { take(q[j].x); take(q[j].y); take(q[j].z); take(q[j].w); }
+                flush();
             }
-            for (; p < p1; p += 256u) {
+            for (u32 n4 = 0; p < p1; p += 256u) {
                 const u32 i = p + lane * 4u;
                 if (p + 256u <= p1) {
                     const f4u q = *(const EXCP_GLOBAL f4u *)(part + i);
@@ -935,12 +960,12 @@ __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupP
 #pragma unroll
                     for (u32 e = 0; e < 4; ++e) if (i + e < p1) take(part[i + e]);
                 }
+                if (++n4 == 4u) { flush(); n4 = 0; }
             }
+            flush();
+            long long tL[3], tH[3];
 #pragma unroll
-            for (int s3 = 0; s3 < 3; ++s3) {
-                aL[s3] = wave_sum_u64(aL[s3]); aH[s3] = wave_sum_u64(aH[s3]);
-                nL[s3] = wave_sum_u64(nL[s3]); nH[s3] = wave_sum_u64(nH[s3]);
-            }
+            for (int s3 = 0; s3 < 3; ++s3) { tL[s3] = (long long)wave_sum_u64((u64)S[s3].lo); tH[s3] = (long long)wave_sum_u64((u64)S[s3].hi); }
             cnt1 = wave_sum_u32(cnt1); cnt2 = wave_sum_u32(cnt2);
             if (lane == 0) {
                 // cluster c_lo + j receives set j minus set j + 1
@@ -949,12 +974,8 @@ __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupP
                 for (u32 j = 0; j < 3; ++j) {
                     if (c_lo + j > c_hi) break;
                     u64 *dst = acc + (u64)(c_lo + j) * (EXCP_ABSM_BINS + 1);
-                    file_total(dst, aL[j], aH[j], B, false, 1u);
-                    file_total(dst, nL[j], nH[j], B, true, 2u);
-                    if (j < 2 && c_lo + j < c_hi) {
-                        file_total(dst, aL[j + 1], aH[j + 1], B, true, 1u);
-                        file_total(dst, nL[j + 1], nH[j + 1], B, false, 2u);
-                    }
+                    file_i64(dst, tL[j], B); file_i64(dst, tH[j], B + 32u);
+                    if (j < 2 && c_lo + j < c_hi) { file_i64(dst, -tL[j + 1], B); file_i64(dst, -tH[j + 1], B + 32u); }
                     const u32 nxt = (c_lo + j < c_hi) ? cnt[j + 1] : 0u;
                     if (cnt[j] - nxt) atomicAdd(&dst[EXCP_ABSM_BINS], (u64)(cnt[j] - nxt));
                 }
