@@ -334,21 +334,23 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_count(Workspace w, Group
     if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
     u32 sidx = 0xffffffffu, s_end = 0;
+    u64 len = 0;                                   // of the stream in hand: fetched when the stream changes, not per chunk
+    u32 chunk0 = 0;
+    const EXCP_GLOBAL float *data = nullptr;
     for (u32 c = lo; c < hi; ++c) {
         if (sidx == 0xffffffffu || c >= s_end) {
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
+            len = w.seg[sidx].len; chunk0 = w.seg[sidx].chunk_begin; data = gptr(seg_data(w, sidx));
             for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
         }
         hist[tid] = 0;
         __syncthreads();
-        const SegState &S = w.seg[sidx];
-        const u64 len = S.len;
-        const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u64 base = (u64)(c - chunk0) * EXCP_CHUNK;
         const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
         float v[PER_THREAD];
-        load_chunk(gptr(seg_data(w, sidx)) + base, clen, v);
+        load_chunk(data + base, clen, v);
 #pragma unroll
         for (u32 it = 0; it < PER_THREAD; ++it)
             if (clen == EXCP_CHUNK || chunk_elem(it) < clen) atomicAdd(&hist[bucket_of(v[it], map)], 1u);
@@ -456,24 +458,26 @@ __global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, Gro
     if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
     u32 sidx = 0xffffffffu, s_end = 0;
+    u64 len = 0;                                   // of the stream in hand: fetched when the stream changes, not per chunk
+    u32 chunk0 = 0;
+    const EXCP_GLOBAL float *data = nullptr;
+    float *__restrict__ part = nullptr;
     for (u32 c = lo; c < hi; ++c) {
         if (sidx == 0xffffffffu || c >= s_end) {
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
+            len = w.seg[sidx].len; chunk0 = w.seg[sidx].chunk_begin; data = gptr(seg_data(w, sidx)); part = seg_part(w, sidx);
             for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
         }
         hist[tid] = 0; fill[tid] = 0;
         goff[tid] = w.km_cnt[(u64)c * NBKT + tid];
         __syncthreads();
-        const SegState &S = w.seg[sidx];
-        float *__restrict__ part = seg_part(w, sidx);
-        const u64 len = S.len;
-        const u64 base = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u64 base = (u64)(c - chunk0) * EXCP_CHUNK;
         const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
         float v[PER_THREAD];
         u32 bk4[PER_THREAD / 4];                   // four bucket numbers per word
-        load_chunk(gptr(seg_data(w, sidx)) + base, clen, v);
+        load_chunk(data + base, clen, v);
 #pragma unroll
         for (u32 it = 0; it < PER_THREAD; ++it) {
             const u32 bb = bucket_of(v[it], map);
@@ -1041,13 +1045,54 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_update(Workspace w, GroupPa
     move_centres(w, g, sidx, nullptr);
 }
 
+// The codes of a thread's 32 values of a whole chunk, ORed into the chunk's bit stream in LDS; returns
+// the thread's share of the objective.  The four values of a group go through the bisection over the
+// cut keys side by side, so that four table reads are in flight at every step instead of one.
+__device__ __forceinline__ double assign_whole_chunk(const float (&v)[PER_THREAD], const u32 *s_cut, const float *s_C, u32 kp2,
+                                                     u32 nbits, u32 *s_pack) {
+    double obj = 0.0;
+    u32 tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));                  // bit positions are worked out where they are used, not kept from chunk to chunk
+#pragma unroll
+    for (u32 q = 0; q < PER_THREAD / 4; ++q) {
+        u32 key[4], pick[4];
+#pragma unroll
+        for (u32 j = 0; j < 4; ++j) { key[j] = key_of(v[4 * q + j]); pick[j] = 0; }
+        for (u32 step = kp2 >> 1; step >= 1; step >>= 1) {      // number of cut keys <= key, as centre_by_cuts
+            u32 c[4];
+#pragma unroll
+            for (u32 j = 0; j < 4; ++j) c[j] = s_cut[pick[j] + step];
+#pragma unroll
+            for (u32 j = 0; j < 4; ++j) pick[j] = c[j] <= key[j] ? pick[j] + step : pick[j];
+        }
+        float cen[4];
+#pragma unroll
+        for (u32 j = 0; j < 4; ++j) cen[j] = s_C[pick[j]];
+        u32 field = 0;                             // the codes of four consecutive values, nbits each
+#pragma unroll
+        for (u32 j = 0; j < 4; ++j) {
+            float x = v[4 * q + j];
+            asm volatile("" : "+v"(x));            // widened here, not when the value arrived (thirty-two doubles would not fit)
+            const double d = (double)x - (double)cen[j];
+            obj += d * d;
+            field |= (1u + pick[j]) << (nbits * j);
+        }
+        // into the chunk's bit stream at bit (first element) * nbits: at most two 32-bit words
+        const u32 bitpos = (q * EXCP_THREADS + tid) * 4u * nbits, wi = bitpos >> 5, sh = bitpos & 31u;
+        atomicOr(&s_pack[wi], field << sh);
+        if (sh && (field >> (32u - sh))) atomicOr(&s_pack[wi + 1], field >> (32u - sh));
+        __builtin_amdgcn_sched_barrier(0);         // one group at a time: nothing of the next is started early
+    }
+    return obj;
+}
+
 // ---------------------------------------------------------------- final assignment + packing
 // A chunk's codes are ORed, four at a time, into the chunk's bit stream in LDS and leave as whole
 // 64-bit words.
 __global__ __launch_bounds__(EXCP_THREADS, 5) void k_assign_pack(Workspace w, GroupParams g) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
-    __shared__ u32 s_pack[EXCP_CHUNK * 8 / 32 + 2];      // the chunk's packed codes (up to 8 bits each)
+    __shared__ u32 s_pack2[2][EXCP_CHUNK * 8 / 32 + 2];  // a chunk's packed codes (up to 8 bits each); chunks alternate between the two
     __shared__ double s_red[EXCP_THREADS / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 total = *w.chunk_total;
@@ -1061,48 +1106,66 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_assign_pack(Workspace w, Gr
     const u32 words_per_chunk = EXCP_CHUNK * nbits / 64u;
 
     u32 sidx = 0xffffffffu, s_end = 0;
+    u64 len = 0, nwords = 0;                       // of the stream in hand: fetched when the stream changes, not per chunk
+    u32 chunk0 = 0;
+    const EXCP_GLOBAL float *data = nullptr;
+    u64 *out = nullptr;
+    double obj = 0.0;                              // this thread's share of the objective over the chunks of the stream in hand
+    // The workgroup's total for the stream goes into the entry of the last of its chunks (the others hold 0).
+    auto close_stream = [&](u32 last_chunk) {
+#pragma unroll
+        for (int mm = 32; mm >= 1; mm >>= 1) obj += shfl_xor_f64(obj, mm);
+        if (lane == 0) s_red[wave] = obj;
+        __syncthreads();
+        if (tid == 0) w.part_obj[last_chunk] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        obj = 0.0;
+    };
     for (u32 c = lo; c < hi; ++c) {
+        u32 *s_pack = s_pack2[c & 1u];
         if (sidx == 0xffffffffu || c >= s_end) {
+            if (sidx != 0xffffffffu) close_stream(c - 1u);
             __syncthreads();
             sidx = find_owner(w.seg_chunk_begin, nseg, c);
             s_end = w.seg_chunk_begin[sidx + 1];
+            const u32 t = sidx / 3u, which = sidx % 3u;
+            const TState &T = w.st[t];
+            len = w.seg[sidx].len; chunk0 = w.seg[sidx].chunk_begin; data = gptr(seg_data(w, sidx));
+            nwords = excp_words(len * nbits);
+            out = (u64 *)(w.desc[t].blob + (which == 0 ? T.off_cw : (which == 1 ? T.off_cm : T.off_cv)));
             for (u32 k = tid; k < (u32)K; k += EXCP_THREADS) s_C[k] = w.seg[sidx].C[k];
             __syncthreads();
             compute_cut_keys(s_C, K, s_cut);       // the final centres' cut keys
             __syncthreads();
         }
-        const SegState &S = w.seg[sidx];
-        const u32 t = sidx / 3u, which = sidx % 3u;
-        const TState &T = w.st[t];
-        const u64 len = S.len;
-        const u64 ebase = (u64)(c - S.chunk_begin) * EXCP_CHUNK;
+        const u64 ebase = (u64)(c - chunk0) * EXCP_CHUNK;
         const u32 clen = (len - ebase) < EXCP_CHUNK ? (u32)(len - ebase) : EXCP_CHUNK;
-        const u64 nwords = excp_words(len * nbits);
-        u64 *out = (u64 *)(w.desc[t].blob + (which == 0 ? T.off_cw : (which == 1 ? T.off_cm : T.off_cv)));
-        const u64 wbase = (u64)(c - S.chunk_begin) * words_per_chunk;
-        double obj = 0.0;
+        const u64 wbase = (u64)(c - chunk0) * words_per_chunk;
         float v[PER_THREAD];
-        load_chunk(gptr(seg_data(w, sidx)) + ebase, clen, v);
+        load_chunk(data + ebase, clen, v);
         for (u32 i = tid; i < 2u * words_per_chunk + 2u; i += EXCP_THREADS) s_pack[i] = 0;
         __syncthreads();
+        if (clen == EXCP_CHUNK) {
+            obj += assign_whole_chunk(v, s_cut, s_C, kp2, nbits, s_pack);
+        } else {
+            // a stream's ragged last chunk: value by value
 #pragma unroll
-        for (u32 q = 0; q < PER_THREAD / 4; ++q) {
-            u32 field = 0;                         // the codes of four consecutive values, nbits each
+            for (u32 q = 0; q < PER_THREAD / 4; ++q) {
+                u32 field = 0;
 #pragma unroll
-            for (u32 j = 0; j < 4; ++j) {
-                const u32 it = 4 * q + j;
-                if (clen == EXCP_CHUNK || chunk_elem(it) < clen) {
-                    const u32 pick = centre_by_cuts(s_cut, kp2, key_of(v[it]));
-                    const double d = (double)v[it] - (double)s_C[pick];
-                    obj += d * d;
-                    field |= (1u + pick) << (nbits * j);
+                for (u32 j = 0; j < 4; ++j) {
+                    const u32 it = 4 * q + j;
+                    if (chunk_elem(it) < clen) {
+                        const u32 pick = centre_by_cuts(s_cut, kp2, key_of(v[it]));
+                        const double d = (double)v[it] - (double)s_C[pick];
+                        obj += d * d;
+                        field |= (1u + pick) << (nbits * j);
+                    }
                 }
-            }
-            // into the chunk's bit stream at bit (first element) * nbits: at most two 32-bit words
-            const u32 bitpos = chunk_elem(4 * q) * nbits, wi = bitpos >> 5, sh = bitpos & 31u;
-            if (field) {
-                atomicOr(&s_pack[wi], field << sh);
-                if (sh && (field >> (32u - sh))) atomicOr(&s_pack[wi + 1], field >> (32u - sh));
+                const u32 bitpos = chunk_elem(4 * q) * nbits, wi = bitpos >> 5, sh = bitpos & 31u;
+                if (field) {
+                    atomicOr(&s_pack[wi], field << sh);
+                    if (sh && (field >> (32u - sh))) atomicOr(&s_pack[wi + 1], field >> (32u - sh));
+                }
             }
         }
         __syncthreads();
@@ -1112,13 +1175,11 @@ __global__ __launch_bounds__(EXCP_THREADS, 5) void k_assign_pack(Workspace w, Gr
             out[wg] = (u64)s_pack[2 * wl] | ((u64)s_pack[2 * wl + 1] << 32);
             if (wg == nwords - 1 && (nwords & 1ull)) out[nwords] = 0ull;     // 16-byte padding
         }
-#pragma unroll
-        for (int mm = 32; mm >= 1; mm >>= 1) obj += shfl_xor_f64(obj, mm);
-        if (lane == 0) s_red[wave] = obj;
-        __syncthreads();
-        if (tid == 0) w.part_obj[c] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-        __syncthreads();
+        if (tid == 0) w.part_obj[c] = 0.0;
+        // (no barrier here: the next chunk uses the other buffer, and this one is zeroed again only after
+        // the two barriers of that chunk)
     }
+    close_stream(hi - 1u);
 }
 
 // ---------------------------------------------------------------- no quantisation: the streams as they are
