@@ -9,6 +9,10 @@ __device__ __forceinline__ float u2f(u32 x) { return __uint_as_float(x); }
 
 __device__ __forceinline__ u64 ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & 63u; }
+// number of set bits of a wave-wide mask that belong to lanes below the calling one
+__device__ __forceinline__ u32 lanes_below(unsigned long long m) {
+    return __builtin_amdgcn_mbcnt_hi((u32)(m >> 32), __builtin_amdgcn_mbcnt_lo((u32)m, 0u));
+}
 __device__ __forceinline__ u64 lanemask_lt() { return (1ull << lane_id()) - 1ull; }
 
 __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {

@@ -446,76 +446,198 @@ __global__ __launch_bounds__(1024) void k_km_scan_apply(Workspace w, GroupParams
 }
 
 // ---------------------------------------------------------------- P3: scatter into buckets
-__global__ __launch_bounds__(EXCP_THREADS, 3) void k_km_scatter(Workspace w, GroupParams g) {
-    __shared__ u32 map[EXCP_KM_MAP_WORDS];
-    __shared__ u32 hist[NBKT], loff[NBKT], goff[NBKT], fill[NBKT];
-    __shared__ float sval[EXCP_CHUNK];
-    __shared__ unsigned char sbkt[EXCP_CHUNK];
-    const u32 tid = threadIdx.x;
+// A workgroup takes a contiguous range of chunks; inside one stream the runs that consecutive chunks
+// contribute to a bucket are neighbours in memory, so the workgroup keeps, per bucket, a ring of up to
+// 128 values in LDS and writes a bucket's values as whole, aligned 128-byte lines (partial lines reach
+// memory at a fraction of the rate of whole ones: a run of about 32 values that starts anywhere costs
+// twice a run that starts on a line).  Partial lines are written only where a workgroup's range or a
+// stream begins or ends.  Values arrive 8192 at a time (eight per thread): a value takes the next place
+// of its bucket's ring (one LDS atomic on a counter that also carries the ring's read position); then
+// thread b looks at bucket b and lists the lines that are complete; then groups of eight lanes write
+// the listed lines, sixteen bytes per lane.  A value's ring index is its place inside its memory line,
+// so a whole line is one aligned quarter of the ring.  When more values arrive for a bucket in one step
+// than its ring holds (tied data: one bucket takes most of a stream), those beyond the ring go straight
+// to their places in memory -- consecutive arrivals, consecutive addresses -- and the ring is emptied.
+// The order of values inside a bucket is that of arrival, which no reader of a bucket depends on
+// (its sum, count, extremes and order statistics are those of a multiset).
+constexpr u32 SC_THREADS = 1024, SC_STEP = 8192, SC_PER = SC_STEP / SC_THREADS, SC_RING = 128, SC_LIST = 1536;
+
+__global__ __launch_bounds__(SC_THREADS, 1) void k_km_scatter(Workspace w, GroupParams g) {
+    __shared__ __attribute__((aligned(16))) float ring[NBKT][SC_RING];
+    __shared__ u32 cells[EXCP_KM_CELLS / 4u];
+    __shared__ u32 ctr[NBKT];                            // (ring index of the oldest value) << 16 | values waiting
+    __shared__ u32 gpos[NBKT];                           // place of the oldest value in the bucket-ordered array
+    __shared__ __attribute__((aligned(8))) u32 list[2 * SC_LIST];   // lines to write: (bucket | ring index << 8 | count << 16), place
+    __shared__ u32 nlist;
+    const u32 tid = threadIdx.x, grp = tid >> 3, gl = tid & 7u;    // groups of eight lanes write a line each
     const u32 total = *w.chunk_total;
     const u32 G = gridDim.x, bid = blockIdx.x;
     const u32 lo = (u32)(((u64)bid * total) / G), hi = (u32)(((u64)(bid + 1) * total) / G);
     if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
-    u32 sidx = 0xffffffffu, s_end = 0;
-    u64 len = 0;                                   // of the stream in hand: fetched when the stream changes, not per chunk
-    u32 chunk0 = 0;
-    const EXCP_GLOBAL float *data = nullptr;
-    float *__restrict__ part = nullptr;
-    for (u32 c = lo; c < hi; ++c) {
-        if (sidx == 0xffffffffu || c >= s_end) {
-            __syncthreads();
-            sidx = find_owner(w.seg_chunk_begin, nseg, c);
-            s_end = w.seg_chunk_begin[sidx + 1];
-            len = w.seg[sidx].len; chunk0 = w.seg[sidx].chunk_begin; data = gptr(seg_data(w, sidx)); part = seg_part(w, sidx);
-            for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
-        }
-        hist[tid] = 0; fill[tid] = 0;
-        goff[tid] = w.km_cnt[(u64)c * NBKT + tid];
+    if (tid == 0) nlist = 0;
+
+    for (u32 c = lo; c < hi;) {
+        // the chunks [c, c_end) of this workgroup that belong to one stream
         __syncthreads();
-        const u64 base = (u64)(c - chunk0) * EXCP_CHUNK;
-        const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
-        float v[PER_THREAD];
-        u32 bk4[PER_THREAD / 4];                   // four bucket numbers per word
-        load_chunk(data + base, clen, v);
-#pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            const u32 bb = bucket_of(v[it], map);
-            if ((it & 3u) == 0u) bk4[it >> 2] = bb; else bk4[it >> 2] |= bb << (8u * (it & 3u));
-            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) atomicAdd(&hist[bb], 1u);
+        const u32 sidx = find_owner(w.seg_chunk_begin, nseg, c);
+        const u32 c_end = min(hi, w.seg_chunk_begin[sidx + 1]);
+        const u64 len = w.seg[sidx].len;
+        const u32 chunk0 = w.seg[sidx].chunk_begin;
+        const EXCP_GLOBAL float *data = gptr(seg_data(w, sidx));
+        EXCP_GLOBAL float *part = gptr(seg_part(w, sidx));
+        const u32 misalign = (u32)(((uintptr_t)seg_part(w, sidx) >> 2) & 31u);   // (place + misalign) % 32 == 0: a line starts
+        // the value -> bucket table stays in global memory (4 KB, read through the vector cache): the LDS unit
+        // is what this kernel is short of
+        const u32 *mp = w.km_split + (u64)sidx * EXCP_KM_MAP_WORDS;
+        const u32 neg_min = mp[0], neg_sh = mp[1], pos_min = mp[2], pos_sh = mp[3];
+        for (u32 i = tid; i < EXCP_KM_CELLS / 4u; i += SC_THREADS) cells[i] = mp[4u + i];
+        const unsigned char *cellmap = (const unsigned char *)cells;
+        auto bucket = [&](float x) -> u32 {
+            const u32 bits = f2u(x), a = bits & 0x7fffffffu;
+            const bool neg = bits >> 31;
+            const u32 amin = neg ? neg_min : pos_min, sh = neg ? neg_sh : pos_sh;
+            const u32 cc = min((max(a, amin) - amin) >> sh, HALF_CELLS - 1u);
+            return cellmap[neg ? (cc ^ (HALF_CELLS - 1u)) : (cc | HALF_CELLS)];
+        };
+        if (tid < NBKT) {
+            // a ring index is the value's place inside its line, so that whole lines sit in one quarter of the ring
+            const u32 gp = w.km_cnt[(u64)c * NBKT + tid];
+            gpos[tid] = gp;
+            ctr[tid] = ((gp + misalign) & 31u) << 16;
         }
+        const u64 e_begin = (u64)(c - chunk0) * EXCP_CHUNK;
+        const u64 e_stop = min(len, (u64)(c_end - chunk0) * EXCP_CHUNK);
         __syncthreads();
-        // exclusive scan of the 256 bucket counts
-        {
-            u32 mine = hist[tid];
-            loff[tid] = mine;
-            __syncthreads();
-            for (u32 off = 1; off < NBKT; off <<= 1) {
-                u32 a = (tid >= off) ? loff[tid - off] : 0u;
-                __syncthreads();
-                loff[tid] += a;
-                __syncthreads();
+
+        // thread b: which lines of bucket b can be written now (at the end of the range: everything)
+        auto plan = [&](bool final) {
+            if (tid >= NBKT) return;                    // (whole waves)
+            const u32 b = tid;
+            const u32 cv = ctr[b];
+            const u32 arrived = cv & 0xffffu;           // since the last look: more than the ring holds if the bucket is crowded
+            const bool over = arrived > SC_RING;        // the values beyond the ring went straight to their places
+            const bool all = final || over;
+            const u32 f0 = min(arrived, SC_RING), h0 = cv >> 16, gp0 = gpos[b];
+            // what leaves: the values up to the next line start, then whole lines, and (all) the rest
+            const u32 mis = (gp0 + misalign) & 31u;
+            u32 f = f0, head_cnt = 0;
+            if (f && mis && (f >= 32u - mis || all)) { head_cnt = min(32u - mis, f); f -= head_cnt; }
+            const bool aligned = ((gp0 + head_cnt + misalign) & 31u) == 0u;
+            const u32 nfull = aligned ? f >> 5 : 0u;
+            f -= nfull << 5;
+            const u32 tail_cnt = (aligned && all) ? f : 0u;
+            f -= tail_cnt;
+            const u32 ne = (head_cnt ? 1u : 0u) + nfull + (tail_cnt ? 1u : 0u);
+            const u32 gone = f0 - f;
+            if (over) {                                 // the ring is empty and starts again behind everything that arrived
+                gpos[b] = gp0 + arrived;
+                ctr[b] = ((gp0 + arrived + misalign) & 31u) << 16;
+            } else {
+                ctr[b] = (((h0 + gone) & (SC_RING - 1u)) << 16) | f; gpos[b] = gp0 + gone;
             }
-            u32 incl = loff[tid];
-            __syncthreads();
-            loff[tid] = incl - mine;
-            __syncthreads();
-        }
-#pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it) {
-            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) {
-                const u32 bb = (bk4[it >> 2] >> (8u * (it & 3u))) & 255u;
-                const u32 pos = loff[bb] + atomicAdd(&fill[bb], 1u);
-                sval[pos] = v[it];
-                sbkt[pos] = (unsigned char)bb;
+            // places in the list: one atomic per wave, the lanes' shares by counting the set bits below them
+            const u64 b0 = ballot64(ne & 1u), b1 = ballot64(ne & 2u), b2 = ballot64(ne & 4u);
+            const u32 wave_total = (u32)__popcll(b0) + 2u * (u32)__popcll(b1) + 4u * (u32)__popcll(b2);
+            if (wave_total) {
+                u32 base = 0;
+                if ((tid & 63u) == 0u) base = atomicAdd(&nlist, wave_total);
+                base = (u32)__builtin_amdgcn_readfirstlane((int)base);
+                u32 at = base + lanes_below(b0) + 2u * lanes_below(b1) + 4u * lanes_below(b2);
+                u32 h = h0, gp = gp0;
+                auto emit = [&](u32 cnt) {
+                    list[2u * at] = b | (h << 8) | (cnt << 16); list[2u * at + 1u] = gp; ++at;
+                    h = (h + cnt) & (SC_RING - 1u); gp += cnt;
+                };
+                if (head_cnt) emit(head_cnt);
+                for (u32 k = 0; k < nfull; ++k) emit(32u);
+                if (tail_cnt) emit(tail_cnt);
             }
+        };
+        // groups of eight lanes write the listed lines, four values per lane
+        auto write_lines = [&]() {
+            const u32 n = nlist;
+            constexpr u32 GROUPS = SC_THREADS / 8u;
+            for (u32 i = grp; i < n; i += GROUPS) {
+                const u64 ev = *(const u64 *)&list[2u * i];
+                const u32 e0 = (u32)ev, b = e0 & 255u, off = (e0 >> 8) & 255u, cnt = e0 >> 16, gp = (u32)(ev >> 32);
+                if (cnt == 32u) {                       // a whole line: it sits in one half of the ring, and on a line in memory
+                    typedef float f4a __attribute__((ext_vector_type(4)));      // 16-byte aligned on both sides
+                    const f4a x = *(const f4a *)&ring[b][off + 4u * gl];
+                    *(EXCP_GLOBAL f4a *)(part + (u64)gp + 4u * gl) = x;
+                } else {
+#pragma unroll
+                    for (u32 k = 0; k < 4; ++k) {
+                        const u32 idx = 4u * gl + k;
+                        if (idx < cnt) part[(u64)gp + idx] = ring[b][(off + idx) & (SC_RING - 1u)];
+                    }
+                }
+            }
+        };
+
+        float nx[SC_PER];
+        auto load_step = [&](u64 e, float (&v)[SC_PER]) {
+            const u32 nval = (e_stop - e) < (u64)SC_STEP ? (u32)(e_stop - e) : SC_STEP;
+            if (nval == SC_STEP) {
+#pragma unroll
+                for (u32 q = 0; q < SC_PER / 4; ++q) {
+                    const f4u x = *(const EXCP_GLOBAL f4u *)(data + e + (q * SC_THREADS + tid) * 4u);
+                    v[4 * q] = x.x; v[4 * q + 1] = x.y; v[4 * q + 2] = x.z; v[4 * q + 3] = x.w;
+                }
+            } else {
+#pragma unroll
+                for (u32 j = 0; j < SC_PER; ++j) {
+                    const u32 el = ((j >> 2) * SC_THREADS + tid) * 4u + (j & 3u);
+                    v[j] = el < nval ? data[e + el] : 0.f;
+                }
+            }
+        };
+        if (e_begin < e_stop) load_step(e_begin, nx);
+        for (u64 e = e_begin; e < e_stop; e += SC_STEP) {
+            const u32 nval = (e_stop - e) < (u64)SC_STEP ? (u32)(e_stop - e) : SC_STEP;
+            float v[SC_PER];
+#pragma unroll
+            for (u32 j = 0; j < SC_PER; ++j) v[j] = nx[j];
+            if (e + SC_STEP < e_stop) load_step(e + SC_STEP, nx);      // the next step's values are on their way
+            u32 bb[SC_PER], cv[SC_PER];
+#pragma unroll
+            for (u32 j = 0; j < SC_PER; ++j) bb[j] = bucket(v[j]);
+            if (tid == 0) nlist = 0;
+            // a value takes the next place of its bucket: in the ring, or, when more than the ring holds have
+            // arrived since the bucket was last looked at (tied data: one bucket takes most of a stream),
+            // straight in the bucket-ordered array
+            if (nval == SC_STEP) {
+#pragma unroll
+                for (u32 j = 0; j < SC_PER; ++j) cv[j] = atomicAdd(&ctr[bb[j]], 1u);
+#pragma unroll
+                for (u32 j = 0; j < SC_PER; ++j) {
+                    const u32 pos = cv[j] & 0xffffu;
+                    if (pos < SC_RING) ring[bb[j]][((cv[j] >> 16) + pos) & (SC_RING - 1u)] = v[j];
+                    else part[(u64)gpos[bb[j]] + pos] = v[j];
+                }
+            } else {
+#pragma unroll
+                for (u32 j = 0; j < SC_PER; ++j) {
+                    if (((j >> 2) * SC_THREADS + tid) * 4u + (j & 3u) < nval) {
+                        const u32 c1 = atomicAdd(&ctr[bb[j]], 1u), pos = c1 & 0xffffu;
+                        if (pos < SC_RING) ring[bb[j]][((c1 >> 16) + pos) & (SC_RING - 1u)] = v[j];
+                        else part[(u64)gpos[bb[j]] + pos] = v[j];
+                    }
+                }
+            }
+            __syncthreads();
+            plan(false);
+            __syncthreads();
+            write_lines();
+            __syncthreads();
         }
+        // the end of the stream or of this workgroup's range: what is left goes out as it is
+        if (tid == 0) nlist = 0;
         __syncthreads();
-        for (u32 p = tid; p < clen; p += EXCP_THREADS) {
-            u32 bb = sbkt[p];
-            part[(u64)goff[bb] + (p - loff[bb])] = sval[p];
-        }
+        plan(true);
         __syncthreads();
+        write_lines();
+        c = c_end;
     }
 }
 
@@ -1275,7 +1397,7 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
             hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(NBKT), 0, s, w, g);
             hipLaunchKernelGGL(k_km_scan_apply, dim3(nseg * SCAN_PARTS), dim3(1024), 0, s, w, g);
             break;
-        case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 96)), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 3: hipLaunchKernelGGL(k_km_scatter, dim3(excp_grid(w, 1)), dim3(SC_THREADS), 0, s, w, g); break;
         case 4:
             if (g.wide == 2u) hipLaunchKernelGGL((k_km_bucket_stats<16, 1>), dim3(nseg * NBKT), dim3(1024), 0, s, w, g);
             else if (g.wide) hipLaunchKernelGGL((k_km_bucket_stats<16, 4>), dim3(nseg * (NBKT / 4)), dim3(1024), 0, s, w, g);
