@@ -1175,29 +1175,32 @@ __device__ __forceinline__ double assign_whole_chunk(const float (&v)[PER_THREAD
     double obj = 0.0;
     u32 tid = threadIdx.x;
     asm volatile("" : "+v"(tid));                  // bit positions are worked out where they are used, not kept from chunk to chunk
+    const unsigned char *cut_b = (const unsigned char *)s_cut, *cen_b = (const unsigned char *)s_C;
 #pragma unroll
     for (u32 q = 0; q < PER_THREAD / 4; ++q) {
-        u32 key[4], pick[4];
+        u32 key[4], p4[4];                         // p4: four times the number of cut keys <= key found so far (a byte offset)
 #pragma unroll
-        for (u32 j = 0; j < 4; ++j) { key[j] = key_of(v[4 * q + j]); pick[j] = 0; }
-        for (u32 step = kp2 >> 1; step >= 1; step >>= 1) {      // number of cut keys <= key, as centre_by_cuts
-            u32 c[4];
+        for (u32 j = 0; j < 4; ++j) { key[j] = key_of(v[4 * q + j]); p4[j] = 0; }
+        for (u32 step4 = kp2 << 1; step4 >= 4u; step4 >>= 1) {  // as centre_by_cuts, on byte offsets
+            u32 a[4], c[4];
 #pragma unroll
-            for (u32 j = 0; j < 4; ++j) c[j] = s_cut[pick[j] + step];
+            for (u32 j = 0; j < 4; ++j) { a[j] = p4[j] + step4; c[j] = *(const u32 *)(cut_b + a[j]); }
 #pragma unroll
-            for (u32 j = 0; j < 4; ++j) pick[j] = c[j] <= key[j] ? pick[j] + step : pick[j];
+            for (u32 j = 0; j < 4; ++j) p4[j] = c[j] <= key[j] ? a[j] : p4[j];
         }
         float cen[4];
 #pragma unroll
-        for (u32 j = 0; j < 4; ++j) cen[j] = s_C[pick[j]];
-        u32 field = 0;                             // the codes of four consecutive values, nbits each
+        for (u32 j = 0; j < 4; ++j) cen[j] = *(const float *)(cen_b + p4[j]);
+        // the codes (index + 1) of four consecutive values, nbits each: p4 + 4 is four times the code
+        u32 field = (p4[0] + 4u) >> 2;
+#pragma unroll
+        for (u32 j = 1; j < 4; ++j) field |= (p4[j] + 4u) << (nbits * j - 2u);
 #pragma unroll
         for (u32 j = 0; j < 4; ++j) {
             float x = v[4 * q + j];
             asm volatile("" : "+v"(x));            // widened here, not when the value arrived (thirty-two doubles would not fit)
             const double d = (double)x - (double)cen[j];
             obj += d * d;
-            field |= (1u + pick[j]) << (nbits * j);
         }
         // into the chunk's bit stream at bit (first element) * nbits: at most two 32-bit words
         const u32 bitpos = (q * EXCP_THREADS + tid) * 4u * nbits, wi = bitpos >> 5, sh = bitpos & 31u;
