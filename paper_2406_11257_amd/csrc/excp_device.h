@@ -9,6 +9,7 @@
 
 #define EXCP_TILE        4096u     // elements per tile of the full-tensor passes (256 threads x 16)
 #define EXCP_CHUNK       8192u     // survivors per chunk of the survivor passes
+#define EXCP_SUPER_CHUNKS 16u      // chunks per unit of the bucket counts (and of the scatter's workgroup ranges)
 #define EXCP_THREADS     256
 #define EXCP_ABSM_BINS   40        // u64 accumulators, 8 binary exponents apart, for the exact sum of |m|
 #define EXCP_MAX_K       255

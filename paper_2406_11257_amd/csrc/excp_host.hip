@@ -553,13 +553,17 @@ int excp_compress_tensors(excp_ctx *c, int count, const excp_tensor *tensors, fl
         }
         { StageTimer t(c, ST_MASK_COMPACT); launch_mask_compact(w, p, 0, s); }
         { StageTimer t(c, ST_MASK_SCAN); launch_mask_compact(w, p, 1, s); }
-        { StageTimer t(c, ST_MASK_GATHER); launch_mask_compact(w, p, 2, s); }
         { StageTimer t(c, ST_LAYOUT); launch_layout(w, p, s); }
+        if (!raw) {
+            // the value -> bucket maps come from the slots, and the count table is cleared, before the pass
+            // that makes the dense survivor arrays: that pass also takes the bucket counts
+            { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
+            { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }
+        }
+        { StageTimer t(c, ST_MASK_GATHER); launch_mask_compact(w, p, 2, s); }
         if (raw) {
             StageTimer t(c, ST_ASSIGN_PACK); launch_store_raw(w, p, s);
         } else {
-            { StageTimer t(c, ST_KM_SAMPLE); launch_km_partition(w, p, 0, s); }
-            { StageTimer t(c, ST_KM_COUNT); launch_km_partition(w, p, 1, s); }
             { StageTimer t(c, ST_KM_SCAN); launch_km_partition(w, p, 2, s); }
             { StageTimer t(c, ST_KM_SCATTER); launch_km_partition(w, p, 3, s); }
             { StageTimer t(c, ST_KM_BUCKET_STATS); launch_km_partition(w, p, 4, s); }

@@ -127,6 +127,23 @@ __device__ __forceinline__ void load_tile_table(u32 *dst, const u32 *__restrict_
     __syncthreads();
 }
 
+// ---- value -> bucket map of the codebook stage (built by k_km_sample)
+constexpr u32 HALF_CELLS = EXCP_KM_CELLS / 2;
+
+// Value -> cell, monotone in the value: negative values fill cells 2047 down to 0 as their
+// magnitude grows, positive ones 2048 up to 4095.  map[0..3] = offset and shift of the negative
+// side, offset and shift of the positive side; magnitudes beyond the sampled range clamp.
+__device__ __forceinline__ u32 cell_of(float x, const u32 *map) {
+    const u32 bits = f2u(x), a = bits & 0x7fffffffu;
+    const bool neg = bits >> 31;
+    const u32 amin = neg ? map[0] : map[2], sh = neg ? map[1] : map[3];
+    const u32 c = min((max(a, amin) - amin) >> sh, HALF_CELLS - 1u);
+    return neg ? (c ^ (HALF_CELLS - 1u)) : (c | HALF_CELLS);
+}
+__device__ __forceinline__ u32 bucket_of(float x, const u32 *map) {
+    return ((const unsigned char *)(map + 4))[cell_of(x, map)];
+}
+
 // Order-preserving map of fp32 bit patterns to unsigned keys (and back).
 __device__ __forceinline__ u32 key_of(float x) {
     u32 u = f2u(x);

@@ -45,22 +45,6 @@ __device__ __forceinline__ float *seg_part(const Workspace &w, u32 sidx) {
 // Four consecutive floats at an address that is only known to be 4-byte aligned.
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
-constexpr u32 HALF_CELLS = EXCP_KM_CELLS / 2;
-
-// Value -> cell, monotone in the value: negative values fill cells 2047 down to 0 as their
-// magnitude grows, positive ones 2048 up to 4095.  map[0..3] = offset and shift of the negative
-// side, offset and shift of the positive side; magnitudes beyond the sampled range clamp.
-__device__ __forceinline__ u32 cell_of(float x, const u32 *map) {
-    const u32 bits = f2u(x), a = bits & 0x7fffffffu;
-    const bool neg = bits >> 31;
-    const u32 amin = neg ? map[0] : map[2], sh = neg ? map[1] : map[3];
-    const u32 c = min((max(a, amin) - amin) >> sh, HALF_CELLS - 1u);
-    return neg ? (c ^ (HALF_CELLS - 1u)) : (c | HALF_CELLS);
-}
-__device__ __forceinline__ u32 bucket_of(float x, const u32 *map) {
-    return ((const unsigned char *)(map + 4))[cell_of(x, map)];
-}
-
 // ---------------------------------------------------------------- exact signed accumulation
 // Adds the values x[j] (j < N) with sel[j] set, for the whole wave, to a set of signed bins through
 // add(bin, delta): sum_g bins[g] * 2^(8g-149) grows by exactly the sum of the selected values.
@@ -220,17 +204,54 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_sample(Workspace w, GroupPa
     const u32 sidx = blockIdx.x, tid = threadIdx.x;
     const u64 len = w.seg[sidx].len;
     if (len == 0) return;
-    const float *__restrict__ x = seg_data(w, sidx);
+    // The stream is read where the mask pass left it, in the sub-tile slots (the dense copy is made
+    // afterwards, by the pass that also counts the buckets this map defines): survivor p of the stream
+    // sits in the sub-tile whose scanned count is the last one <= p.  Eight searches go side by side.
+    const u32 ts = sidx / 3u, which = sidx % 3u;
+    const u32 sub_first = 2u * w.tile_begin[ts], sub_end = 2u * w.tile_begin[ts + 1u];
+    const u64 *pre = w.mask_prefix;
+    const float *__restrict__ slots = (which == 0 ? w.pw : (which == 1 ? w.pm : w.pv)) + w.desc[ts].elem_off;
     const u32 ns = len < SAMPLE ? (u32)len : SAMPLE;
     if (tid < 4) s_ext[tid] = (tid & 1u) ? 0u : 0xffffffffu;
     for (u32 c = tid; c < EXCP_KM_CELLS; c += EXCP_THREADS) cnt[c] = 0;
     __syncthreads();
     u32 mn[2] = {0xffffffffu, 0xffffffffu}, mx[2] = {0u, 0u};
-    for (u32 i = tid; i < ns; i += EXCP_THREADS) {
-        const float v = x[((u64)i * len) / ns];
-        smp[i] = v;
-        const u32 bits = f2u(v), a = bits & 0x7fffffffu, sg = bits >> 31;
-        if (sg) { mn[0] = min(mn[0], a); mx[0] = max(mx[0], a); } else { mn[1] = min(mn[1], a); mx[1] = max(mx[1], a); }
+    for (u32 i0 = tid; i0 < ns; i0 += 8u * EXCP_THREADS) {
+        u32 pos[8], lo[8], hi[8];
+#pragma unroll
+        for (u32 k = 0; k < 8; ++k) {
+            const u32 i = min(i0 + k * EXCP_THREADS, ns - 1u);
+            pos[k] = (u32)(((u64)i * len) / ns);
+            lo[k] = sub_first; hi[k] = sub_end;         // invariant: prefix(lo) <= pos < prefix(hi)
+        }
+        bool more = true;
+        while (more) {
+            more = false;
+            u32 mid[8];
+            u64 pv[8];
+#pragma unroll
+            for (u32 k = 0; k < 8; ++k) { mid[k] = (lo[k] + hi[k]) >> 1; pv[k] = pre[mid[k]]; }
+#pragma unroll
+            for (u32 k = 0; k < 8; ++k) {
+                if (hi[k] - lo[k] > 1u) {
+                    const u32 at = which == 0 ? (u32)(pv[k] >> 32) : (u32)pv[k];
+                    if (at <= pos[k]) lo[k] = mid[k]; else hi[k] = mid[k];
+                    more = more || hi[k] - lo[k] > 1u;
+                }
+            }
+        }
+#pragma unroll
+        for (u32 k = 0; k < 8; ++k) {
+            const u32 i = i0 + k * EXCP_THREADS;
+            if (i < ns) {
+                const u64 pl = pre[lo[k]];
+                const u32 at = which == 0 ? (u32)(pl >> 32) : (u32)pl;
+                const float v = slots[(u64)(lo[k] - sub_first) * 2048u + (pos[k] - at)];
+                smp[i] = v;
+                const u32 bits = f2u(v), a = bits & 0x7fffffffu, sg = bits >> 31;
+                if (sg) { mn[0] = min(mn[0], a); mx[0] = max(mx[0], a); } else { mn[1] = min(mn[1], a); mx[1] = max(mx[1], a); }
+            }
+        }
     }
 #pragma unroll
     for (int sg = 0; sg < 2; ++sg) {
@@ -323,41 +344,12 @@ __device__ __forceinline__ void load_chunk(const EXCP_GLOBAL float *gx, u32 clen
 }
 __device__ __forceinline__ u32 chunk_elem(u32 it) { return ((it >> 2) * EXCP_THREADS + threadIdx.x) * 4u + (it & 3u); }
 
-// ---------------------------------------------------------------- P1: per-chunk bucket counts
-__global__ __launch_bounds__(EXCP_THREADS, 5) void k_km_count(Workspace w, GroupParams g) {
-    __shared__ u32 map[EXCP_KM_MAP_WORDS];
-    __shared__ u32 hist[NBKT];
-    const u32 tid = threadIdx.x;
-    const u32 total = *w.chunk_total;
-    const u32 G = gridDim.x, b = blockIdx.x;
-    const u32 lo = (u32)(((u64)b * total) / G), hi = (u32)(((u64)(b + 1) * total) / G);
-    if (lo >= hi) return;
-    const u32 nseg = 3u * g.ntensors;
-    u32 sidx = 0xffffffffu, s_end = 0;
-    u64 len = 0;                                   // of the stream in hand: fetched when the stream changes, not per chunk
-    u32 chunk0 = 0;
-    const EXCP_GLOBAL float *data = nullptr;
-    for (u32 c = lo; c < hi; ++c) {
-        if (sidx == 0xffffffffu || c >= s_end) {
-            __syncthreads();
-            sidx = find_owner(w.seg_chunk_begin, nseg, c);
-            s_end = w.seg_chunk_begin[sidx + 1];
-            len = w.seg[sidx].len; chunk0 = w.seg[sidx].chunk_begin; data = gptr(seg_data(w, sidx));
-            for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) map[i] = w.km_split[(u64)sidx * EXCP_KM_MAP_WORDS + i];
-        }
-        hist[tid] = 0;
-        __syncthreads();
-        const u64 base = (u64)(c - chunk0) * EXCP_CHUNK;
-        const u32 clen = (len - base) < EXCP_CHUNK ? (u32)(len - base) : EXCP_CHUNK;
-        float v[PER_THREAD];
-        load_chunk(data + base, clen, v);
-#pragma unroll
-        for (u32 it = 0; it < PER_THREAD; ++it)
-            if (clen == EXCP_CHUNK || chunk_elem(it) < clen) atomicAdd(&hist[bucket_of(v[it], map)], 1u);
-        __syncthreads();
-        w.km_cnt[(u64)c * NBKT + tid] = hist[tid];
-        __syncthreads();
-    }
+// ---------------------------------------------------------------- P1: bucket counts
+// Taken by the pass that makes the dense survivor arrays (k_mask_gather), per 16 chunks of a stream, into
+// the row of the first of them; the table is cleared here before that pass.
+__global__ __launch_bounds__(EXCP_THREADS) void k_km_clear_counts(Workspace w, GroupParams g) {
+    const u64 words = (u64)*w.chunk_total * NBKT;
+    for (u64 i = (u64)blockIdx.x * EXCP_THREADS + threadIdx.x; i < words; i += (u64)gridDim.x * EXCP_THREADS) w.km_cnt[i] = 0;
 }
 
 // ---------------------------------------------------------------- P2: offsets of every (chunk, bucket)
@@ -472,9 +464,16 @@ __global__ __launch_bounds__(SC_THREADS, 1) void k_km_scatter(Workspace w, Group
     const u32 tid = threadIdx.x, grp = tid >> 3, gl = tid & 7u;    // groups of eight lanes write a line each
     const u32 total = *w.chunk_total;
     const u32 G = gridDim.x, bid = blockIdx.x;
-    const u32 lo = (u32)(((u64)bid * total) / G), hi = (u32)(((u64)(bid + 1) * total) / G);
-    if (lo >= hi) return;
     const u32 nseg = 3u * g.ntensors;
+    // Equal shares of the chunk list, their ends moved back to where the bucket counts were taken: the first
+    // of every 16 chunks of a stream (the counts of a unit sit in that chunk's row, the rows between are zero).
+    auto snapped = [&](u32 c) -> u32 {
+        if (c >= total) return total;
+        const u32 c0 = w.seg_chunk_begin[find_owner(w.seg_chunk_begin, nseg, c)];
+        return c0 + ((c - c0) & ~(EXCP_SUPER_CHUNKS - 1u));
+    };
+    const u32 lo = snapped((u32)(((u64)bid * total) / G)), hi = snapped((u32)(((u64)(bid + 1) * total) / G));
+    if (lo >= hi) return;
     if (tid == 0) nlist = 0;
 
     for (u32 c = lo; c < hi;) {
@@ -1394,7 +1393,7 @@ void launch_km_partition(const Workspace &w, const GroupParams &g, int phase, hi
     const u32 nseg = 3 * g.ntensors;
     switch (phase) {
         case 0: hipLaunchKernelGGL(k_km_sample, dim3(nseg), dim3(EXCP_THREADS), 0, s, w, g); break;
-        case 1: hipLaunchKernelGGL(k_km_count, dim3(excp_grid(w, 30)), dim3(EXCP_THREADS), 0, s, w, g); break;
+        case 1: hipLaunchKernelGGL(k_km_clear_counts, dim3(excp_grid(w, 8)), dim3(EXCP_THREADS), 0, s, w, g); break;
         case 2:
             hipLaunchKernelGGL(k_km_scan_parts, dim3(nseg * SCAN_PARTS), dim3(1024), 0, s, w, g);
             hipLaunchKernelGGL(k_km_scan, dim3(nseg), dim3(NBKT), 0, s, w, g);

@@ -302,19 +302,54 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_scan(Workspace w, GroupPa
     }
 }
 
-// Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays.  A workgroup takes 32
-// consecutive sub-tiles; their counts, prefixes and tensor data are fetched once, side by side,
-// into LDS, so that a wave's copies do not wait behind a chain of dependent look-ups.
+// Pass B: one wave per sub-tile copies the slot to its place in the dense survivor arrays.  A workgroup takes a
+// contiguous range of batches of 32 consecutive sub-tiles; a batch's counts, prefixes and tensor data are
+// fetched once, side by side, into LDS, so that a wave's copies do not wait behind a chain of dependent
+// look-ups.
+// The same pass counts, for the value partition of the codebook stage, how many of the values it moves
+// fall into each of the 256 value buckets (the map k_km_sample made from the slots): the values are in
+// registers here, and a pass of its own would read them all again.  Counts are kept per 16 chunks
+// (131 072 positions) of a stream, in the row of the first of those chunks; the scatter's workgroups
+// begin only at such positions.  A workgroup adds up in LDS as long as its batches stay inside one tensor
+// and one such unit per stream, and hands the sums over when that changes.
 constexpr u32 GATHER_SUBS = 32;
+constexpr u32 SUPER_SHIFT = 17;                          // log2 of the positions per counted unit
+static_assert((1u << SUPER_SHIFT) == EXCP_SUPER_CHUNKS * EXCP_CHUNK, "counted unit = EXCP_SUPER_CHUNKS chunks");
 
 __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, GroupParams g) {
     __shared__ u32 s_tiles[EXCP_MAX_GROUP_TENSORS + 1];
     __shared__ u32 s_tw[GATHER_SUBS], s_to[GATHER_SUBS], s_pw[GATHER_SUBS], s_po[GATHER_SUBS], s_t[GATHER_SUBS];
     __shared__ u64 s_slot[GATHER_SUBS], s_eoff[GATHER_SUBS];
+    __shared__ u32 s_map[3][EXCP_KM_MAP_WORDS];
+    __shared__ u32 s_hist[3][2][256];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 nsub = 2u * g.ntiles;
+    const bool counting = (g.flags & 4u) == 0u;          // (no codebooks without quantisation)
     load_tile_table(s_tiles, w.tile_begin, g.ntensors);
-    for (u32 sub0 = blockIdx.x * GATHER_SUBS; sub0 < nsub; sub0 += gridDim.x * GATHER_SUBS) {
+    const u32 nbatch = (nsub + GATHER_SUBS - 1u) / GATHER_SUBS;
+    const u32 b_lo = (u32)(((u64)blockIdx.x * nbatch) / gridDim.x), b_hi = (u32)(((u64)(blockIdx.x + 1u) * nbatch) / gridDim.x);
+    for (u32 i = tid; i < 3u * 2u * 256u; i += EXCP_THREADS) (&s_hist[0][0][0])[i] = 0;
+    u32 cur_t = 0xffffffffu, cur_sc[3] = {0u, 0u, 0u};   // what the LDS counts belong to
+    bool live[3] = {false, false, false};                // the stream has a place in the chunk list (its tensor did not fail)
+    // hands the counts over: thread b adds bucket b of both units of the three streams
+    auto flush = [&]() {
+        __syncthreads();
+        if (cur_t != 0xffffffffu) {
+#pragma unroll
+            for (u32 k = 0; k < 3; ++k) {
+                if (!live[k]) continue;
+                const u32 row0 = w.seg[3u * cur_t + k].chunk_begin + cur_sc[k] * EXCP_SUPER_CHUNKS;
+#pragma unroll
+                for (u32 u = 0; u < 2; ++u) {
+                    const u32 h = s_hist[k][u][tid];
+                    if (h) { atomicAdd(&w.km_cnt[(u64)(row0 + u * EXCP_SUPER_CHUNKS) * 256u + tid], h); s_hist[k][u][tid] = 0; }
+                }
+            }
+        }
+        __syncthreads();
+    };
+    for (u32 batch = b_lo; batch < b_hi; ++batch) {
+        const u32 sub0 = batch * GATHER_SUBS;
         __syncthreads();
         if (tid < GATHER_SUBS) {
             const u32 sub = sub0 + tid;
@@ -331,7 +366,32 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
             s_tw[tid] = tw; s_to[tid] = to;
         }
         __syncthreads();
-        for (u32 j = wave; j < GATHER_SUBS; j += 4) {
+        const u32 nvalid = min(GATHER_SUBS, nsub - sub0);
+        const u32 t0 = s_t[0];
+        const bool one_tensor = t0 == s_t[nvalid - 1u];
+        if (counting) {
+            if (one_tensor) {
+                const u32 sc[3] = {s_pw[0] >> SUPER_SHIFT, s_po[0] >> SUPER_SHIFT, s_po[0] >> SUPER_SHIFT};
+                if (t0 != cur_t || sc[0] != cur_sc[0] || sc[1] != cur_sc[1]) {
+                    flush();
+                    if (t0 != cur_t) {
+#pragma unroll
+                        for (u32 k = 0; k < 3; ++k) {
+                            live[k] = w.seg[3u * t0 + k].len != 0;
+                            if (live[k])
+                                for (u32 i = tid; i < EXCP_KM_MAP_WORDS; i += EXCP_THREADS) s_map[k][i] = w.km_split[(u64)(3u * t0 + k) * EXCP_KM_MAP_WORDS + i];
+                        }
+                    }
+                    cur_t = t0; cur_sc[0] = sc[0]; cur_sc[1] = sc[1]; cur_sc[2] = sc[2];
+                    __syncthreads();
+                }
+            } else if (cur_t != 0xffffffffu) {
+                flush();
+                cur_t = 0xffffffffu;
+            }
+        }
+        const bool in_lds = counting && one_tensor;
+        for (u32 j = wave; j < nvalid; j += 4) {
             const u32 tw = s_tw[j], to = s_to[j];
             if (tw == 0 && to == 0) continue;
             const u32 pw = s_pw[j], po = s_po[j];
@@ -340,19 +400,47 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
             EXCP_GLOBAL float *xw = gptr(w.xw) + eoff + pw;
             EXCP_GLOBAL float *xm = gptr(w.xm) + eoff + po;
             EXCP_GLOBAL float *xv = gptr(w.xv) + eoff + po;
+            // counts of a batch that holds the end of one tensor and the start of the next (rare) go straight to
+            // the table, with that tensor's maps read where they are
+            const u32 tj = s_t[j];
+            auto count = [&](u32 k, float x, u32 place) {
+                if (in_lds) {
+                    if (live[k]) atomicAdd(&s_hist[k][(place >> SUPER_SHIFT) != cur_sc[k] ? 1u : 0u][bucket_of(x, s_map[k])], 1u);
+                } else if (counting && w.seg[3u * tj + k].len != 0) {
+                    const u32 row = w.seg[3u * tj + k].chunk_begin + (place >> SUPER_SHIFT) * EXCP_SUPER_CHUNKS;
+                    atomicAdd(&w.km_cnt[(u64)row * 256u + bucket_of(x, w.km_split + (u64)(3u * tj + k) * EXCP_KM_MAP_WORDS)], 1u);
+                }
+            };
             {
                 // the first batch of all three runs in flight together (usually there is no second)
                 float qw[12], qm[4], qv[4];
                 load_batch<12>(qw, sw, tw, 0, lane); load_batch<4>(qm, sm, to, 0, lane); load_batch<4>(qv, sv, to, 0, lane);
                 store_batch<12>(xw, qw, tw, 0, lane); store_batch<4>(xm, qm, to, 0, lane); store_batch<4>(xv, qv, to, 0, lane);
-                for (u32 b0 = 768u; b0 < tw; b0 += 768u) { load_batch<12>(qw, sw, tw, b0, lane); store_batch<12>(xw, qw, tw, b0, lane); }
+                if (counting) {
+#pragma unroll
+                    for (u32 k = 0; k < 12; ++k) { const u32 i = k * 64u + lane; if (i < tw) count(0, qw[k], pw + i); }
+#pragma unroll
+                    for (u32 k = 0; k < 4; ++k) { const u32 i = k * 64u + lane; if (i < to) { count(1, qm[k], po + i); count(2, qv[k], po + i); } }
+                }
+                for (u32 b0 = 768u; b0 < tw; b0 += 768u) {
+                    load_batch<12>(qw, sw, tw, b0, lane); store_batch<12>(xw, qw, tw, b0, lane);
+                    if (counting) {
+#pragma unroll
+                        for (u32 k = 0; k < 12; ++k) { const u32 i = b0 + k * 64u + lane; if (i < tw) count(0, qw[k], pw + i); }
+                    }
+                }
                 for (u32 b0 = 256u; b0 < to; b0 += 256u) {
                     load_batch<4>(qm, sm, to, b0, lane); load_batch<4>(qv, sv, to, b0, lane);
                     store_batch<4>(xm, qm, to, b0, lane); store_batch<4>(xv, qv, to, b0, lane);
+                    if (counting) {
+#pragma unroll
+                        for (u32 k = 0; k < 4; ++k) { const u32 i = b0 + k * 64u + lane; if (i < to) { count(1, qm[k], po + i); count(2, qv[k], po + i); } }
+                    }
                 }
             }
         }
     }
+    if (counting) flush();
 }
 
 // bitmap_o (the M_o bits of the survivors, in survivor order) from the sub-tiles' local bit
