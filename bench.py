@@ -33,8 +33,7 @@ def stage_bytes_per_param(p_w, p_o, nbits, iters, wb=4.0):
     return {
         "stats_stream": 2.0 * wb + 4.0,                    # read W_prev, W, m
         "mask_slots": 2.0 * wb + 8.0 + 0.125 + 4.0 * s,    # read all four arrays; write keep bitmap + survivor slots
-        "mask_gather": 8.0 * s + 0.25 * p_w,               # slots -> dense survivor arrays; local M_o bits -> bitmap_o
-        "km_count": 4.0 * s,                               # read the survivors, count per bucket
+        "mask_gather": 8.0 * s + 0.25 * p_w,               # slots -> dense survivor arrays (counting the value buckets on the way); local M_o bits -> bitmap_o
         "km_scatter": 8.0 * s,                             # read the survivors, write them bucket by bucket
         "km_bucket_stats": 4.0 * s,                        # read the partitioned survivors once
         "assign_pack": 4.0 * s + s * nbits / 8.0,          # read survivors, write codes
@@ -55,7 +54,7 @@ def stage_kernels(weights):
     w16 = weights != "f32"
     return {"stats_stream": "k_stats_stream<true>" if w16 else "k_stats_stream<false>",
             "mask_slots": "k_mask_slots<false,true>" if w16 else "k_mask_slots<false,false>",
-            "mask_gather": "k_mask_gather", "km_count": "k_km_count", "km_scatter": "k_km_scatter",
+            "mask_gather": "k_mask_gather", "km_scatter": "k_km_scatter",
             "km_bucket_stats": "k_km_bucket_stats<16u,4u>" if w16 else "k_km_bucket_stats<4u,4u>",
             "assign_pack": "k_assign_pack", "decode_main": "k_decode_main16<false>" if w16 else "k_decode_main<false>"}
 

@@ -391,6 +391,12 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
             }
         }
         const bool in_lds = counting && one_tensor;
+        u32 par[3][4] = {};                              // the maps' four parameters, out of LDS once per batch
+        if (in_lds) {
+#pragma unroll
+            for (u32 k = 0; k < 3; ++k)
+                if (live[k]) { par[k][0] = s_map[k][0]; par[k][1] = s_map[k][1]; par[k][2] = s_map[k][2]; par[k][3] = s_map[k][3]; }
+        }
         for (u32 j = wave; j < nvalid; j += 4) {
             const u32 tw = s_tw[j], to = s_to[j];
             if (tw == 0 && to == 0) continue;
@@ -400,15 +406,30 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_mask_gather(Workspace w, Group
             EXCP_GLOBAL float *xw = gptr(w.xw) + eoff + pw;
             EXCP_GLOBAL float *xm = gptr(w.xm) + eoff + po;
             EXCP_GLOBAL float *xv = gptr(w.xv) + eoff + po;
-            // counts of a batch that holds the end of one tensor and the start of the next (rare) go straight to
-            // the table, with that tensor's maps read where they are
+            // counts of a batch that holds the end of one tensor and the start of the next (small tensors) go
+            // straight to the table, with that tensor's maps read where they are: what a stream needs for
+            // that is fetched once per sub-tile
             const u32 tj = s_t[j];
+            u32 g_row[3] = {0u, 0u, 0u}, g_par[3][4] = {};
+            bool g_live[3] = {false, false, false};
+            const EXCP_GLOBAL unsigned char *g_cells[3] = {nullptr, nullptr, nullptr};
+            if (counting && !in_lds) {
+#pragma unroll
+                for (u32 k = 0; k < 3; ++k) {
+                    const u32 sg = 3u * tj + k;
+                    g_live[k] = w.seg[sg].len != 0;
+                    g_row[k] = w.seg[sg].chunk_begin;
+                    const u32 *mp = w.km_split + (u64)sg * EXCP_KM_MAP_WORDS;
+                    if (g_live[k]) { g_par[k][0] = mp[0]; g_par[k][1] = mp[1]; g_par[k][2] = mp[2]; g_par[k][3] = mp[3]; }
+                    g_cells[k] = gptr((const unsigned char *)(mp + 4));
+                }
+            }
             auto count = [&](u32 k, float x, u32 place) {
                 if (in_lds) {
-                    if (live[k]) atomicAdd(&s_hist[k][(place >> SUPER_SHIFT) != cur_sc[k] ? 1u : 0u][bucket_of(x, s_map[k])], 1u);
-                } else if (counting && w.seg[3u * tj + k].len != 0) {
-                    const u32 row = w.seg[3u * tj + k].chunk_begin + (place >> SUPER_SHIFT) * EXCP_SUPER_CHUNKS;
-                    atomicAdd(&w.km_cnt[(u64)row * 256u + bucket_of(x, w.km_split + (u64)(3u * tj + k) * EXCP_KM_MAP_WORDS)], 1u);
+                    if (live[k]) atomicAdd(&s_hist[k][(place >> SUPER_SHIFT) != cur_sc[k] ? 1u : 0u][((const unsigned char *)(s_map[k] + 4))[cell_of(x, par[k])]], 1u);
+                } else if (g_live[k]) {
+                    const u32 row = g_row[k] + (place >> SUPER_SHIFT) * EXCP_SUPER_CHUNKS;
+                    atomicAdd(&w.km_cnt[(u64)row * 256u + g_cells[k][cell_of(x, g_par[k])]], 1u);
                 }
             };
             {
