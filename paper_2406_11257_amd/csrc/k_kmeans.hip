@@ -992,20 +992,6 @@ __global__ __launch_bounds__(EXCP_THREADS) void k_km_classify(Workspace w, Group
 // centres.  Sums are gathered in LDS per item and flushed with a few integer atomics.
 constexpr u32 ITEM_R = 8;      // centres per item held in LDS; wider ranges go straight to global memory
 
-// Files an integer total (low / high 32-bit halves summed separately in L and H, unit 2^(B-149))
-// into signed bins with global atomics, added or subtracted `times` times.
-__device__ __forceinline__ void file_total(u64 *bins, u64 L, u64 H, u32 B, bool subtract, u32 times) {
-    const u64 lo64 = L + (H << 32);
-    const u64 hi64 = (H >> 32) + (lo64 < L ? 1ull : 0ull);
-    const u64 piece[3] = {lo64 & 0xffffffffull, lo64 >> 32, hi64};
-#pragma unroll
-    for (int q = 0; q < 3; ++q) {
-        const u32 p = B + 32u * q;
-        const u64 d = (piece[q] << (p & 7u)) * times;
-        if (piece[q]) atomicAdd(&bins[p >> 3], subtract ? (u64)0 - d : d);
-    }
-}
-
 __global__ __launch_bounds__(EXCP_THREADS, 4) void k_km_iter(Workspace w, GroupParams g, u32 parity) {
     __shared__ float s_C[EXCP_MAX_K + 1];
     __shared__ u32 s_cut[EXCP_MAX_K + 1];
